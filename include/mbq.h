@@ -1,0 +1,148 @@
+/*
+ * mbq - token-routed any-precision linear layer (MoBiQuant inference hot path)
+ * for AMD MI355X (gfx950).  C ABI of libmbq.so.
+ *
+ * The layer:  a weight matrix W (N output features x K input features) is stored
+ * once as four 2-bit slices produced by recursive residual quantisation (paper
+ * Sec. 4.1, Eq. 2; quantiser and scale refinement of App. B).  At run time a
+ * per-token router picks a precision index p in {0,1,2,3} (2, 4, 6 or 8 bits) and
+ * the token's output row is its activation row times the weight rebuilt from
+ * slices 0..p only (Sec. 4.1 Eq. 3, Sec. 4.2 Eq. 6).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name ends in _host.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no state
+ *     between calls (apart from the tuning knobs below) and never synchronises:
+ *     all work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream).  Outputs are valid once the stream reaches that point.
+ *   - Every entry point returns an mbq_status.  On failure nothing has been
+ *     enqueued and mbq_last_error() describes the cause (thread-local string).
+ *   - bf16 values are passed as uint16_t bit patterns.
+ *   - Only the paper's default configuration is supported: group size 128 along K,
+ *     four slices of two bits (App. C.1).  K must be a multiple of 128.
+ *
+ * Packed weight blob (written by mbq_encode, read by every other call)
+ *   Let NT = ceil(N/16), KB = ceil(K/256); rows and columns beyond N, K are padded
+ *   with code 0 and scale 0.  The blob is, in this order,
+ *     codes : uint32 [4 slices][NT][KB][64 lanes][4 dwords]      (1 KiB per tile)
+ *     meta  : float  [NT][2*KB groups][16 rows][2]  = {s0, z0}    (128 B per tile-group)
+ *   A code tile holds 16 rows x 256 columns of one slice.  For weight (n, k):
+ *     r = k mod 256, d = r / 64, step = (r mod 64) / 32, kq = (r mod 32) / 8, s = r mod 8,
+ *     lane = 16*kq + (n mod 16), dword d of that lane,
+ *     bit  = (16*(s&1) + 4*(s>>1) + 2*step + (2 - 2*slice)) mod 32   (2-bit field).
+ *   (Slice e is stored rotated left by 2-2e bits so that the four slices of one
+ *   weight line up as one byte after a common rotation; the decode kernel reads a
+ *   tile with one 128-bit load per lane and feeds it to 16x16x32 MFMAs without
+ *   transposition.)  s0 is the base-slice scale, z0 its continuous zero point;
+ *   slice e uses s0 / 4^e and, for e >= 1, zero point 2.
+ */
+#ifndef MBQ_H_
+#define MBQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mbq_status {
+  MBQ_OK = 0,
+  MBQ_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad enum value          */
+  MBQ_ERR_BAD_SHAPE = 2,   /* K not a multiple of 128, size overflow, P != 4       */
+  MBQ_ERR_WORKSPACE = 3,   /* workspace smaller than mbq_*_workspace_bytes()       */
+  MBQ_ERR_HIP = 4          /* a HIP call or kernel launch failed                   */
+} mbq_status;
+
+/* Which kernel family mbq_linear uses. AUTO picks by token count. */
+typedef enum mbq_algo {
+  MBQ_ALGO_AUTO = 0,
+  MBQ_ALGO_SIMPLE = 1, /* one thread per output, fp64 accumulate: slow checker path   */
+  MBQ_ALGO_DECODE = 2, /* bandwidth-bound per-slice MFMA GEMV, T <= 64               */
+  MBQ_ALGO_PREFILL = 3 /* merged-code bf16 MFMA tiled GEMM, any T                     */
+} mbq_algo;
+
+#define MBQ_N_PRECISIONS 4
+#define MBQ_GROUP 128
+
+const char* mbq_version(void);
+const char* mbq_last_error(void);
+
+/* Bytes of the packed weight blob for an N x K matrix (0 if the shape is invalid). */
+size_t mbq_blob_bytes(int64_t N, int64_t K);
+
+/* Workspace sizes (bytes) for mbq_route / mbq_linear at the given sizes. */
+size_t mbq_route_workspace_bytes(int64_t T, int64_t K);
+size_t mbq_linear_workspace_bytes(int64_t T, int64_t N, int64_t K);
+
+/*
+ * mbq_encode - recursive residual quantisation of W into the packed blob.
+ * Sec. 4.1 Eq. 2 with the floor-aligned quantiser, scale refinement s_{e+1} = s_e/4
+ * and centred residual zero point of App. B.  Per (row, group of 128): s0 =
+ * (max-min)/4 and z0 = -min/s0 in fp32 (range floored at 2^-16 of the group's
+ * magnitude and at 2^-100); codes from the fp64 recursion
+ *   c_e = clamp(floor(R/s_e + z_e), 0, 3),  R <- R - s_e (c_e - z_e + 0.5).
+ *   W    : fp32 [N][K] row-major (read)
+ *   blob : mbq_blob_bytes(N, K) bytes, 256-byte aligned (written, fully)
+ */
+mbq_status mbq_encode(const float* W, int64_t N, int64_t K, void* blob, void* stream);
+
+/*
+ * mbq_unpack - blob -> canonical arrays, for inspection and tests.
+ *   codes : uint8 [4][N][K], one code (0..3) per byte          (may be NULL)
+ *   scale : fp32 [N][K/128]  base-slice scale s0               (may be NULL)
+ *   zero  : fp32 [N][K/128]  base-slice zero point z0          (may be NULL)
+ */
+mbq_status mbq_unpack(const void* blob, int64_t N, int64_t K, uint8_t* codes, float* scale,
+                      float* zero, void* stream);
+
+/*
+ * mbq_dequant - weight at precision index p (Sec. 4.1 Eq. 3):
+ *   What[n][k] = (s0/4^p) * (I_p - 4^p z0 + 0.5),  I_p = sum_{e<=p} c_e 4^{p-e},
+ * evaluated in fp64 and rounded once to fp32.  What : fp32 [N][K].
+ */
+mbq_status mbq_dequant(const void* blob, int64_t N, int64_t K, int p, float* What, void* stream);
+
+/*
+ * mbq_route - router scores, precision choice and token permutation
+ * (Sec. 4.2 Eq. 4 read as one linear map to P = 4 logits; Sec. 4.3 challenge 3).
+ *   logits[i][q] = sum_k X[i][k] * Wr[q][k] + br[q]   accumulated in fp64
+ *   prec[i]      = argmax_q logits[i][q], first maximum on ties
+ *   perm/offsets = stable grouping of token ids by ascending prec:
+ *                  tokens of precision q are perm[offsets[q] .. offsets[q+1]-1]
+ *   X      : bf16 [T][K]           Wr : fp32 [P][K]        br : fp32 [P]
+ *   prec   : int32 [T] (out)       perm : int32 [T] (out)  offsets : int32 [P+1] (out)
+ *   logits : fp64 [T][P] (out, may be NULL)
+ *   ws     : at least mbq_route_workspace_bytes(T, K) bytes, 256-byte aligned
+ * T = 0 is legal (offsets are zero-filled).
+ */
+mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
+                     int P, int32_t* prec, int32_t* perm, int32_t* offsets, double* logits,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * mbq_linear - routed output (Sec. 4.2 Eq. 6 with the prefix mask of slices 0..p_i):
+ *   Y[i][n] = sum_k X[i][k] * What^(prec[i])[n][k],  fp32 accumulate, fp32 output,
+ * reading for each token only the slices its precision needs.
+ *   X    : bf16 [T][K]            blob : packed weights of an N x K matrix
+ *   prec, perm, offsets : as written by mbq_route (must be mutually consistent)
+ *   Y    : fp32 [T][N] in ORIGINAL token order (written for every token)
+ *   ws   : at least mbq_linear_workspace_bytes(T, N, K) bytes, 256-byte aligned
+ *   algo : an mbq_algo value
+ * T = 0 is legal (no-op).
+ */
+mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
+                      const int32_t* prec, const int32_t* perm, const int32_t* offsets, float* Y,
+                      void* ws, size_t ws_bytes, int algo, void* stream);
+
+/*
+ * Launch-shape knobs for experiments (process-global, not thread-safe; 0 = default).
+ *   knob 0: waves per workgroup of the decode kernel (4, 8 or 16)
+ *   knob 1: K-split (workgroups along K) of the decode kernel, 0 = automatic
+ */
+mbq_status mbq_set_knob(int knob, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MBQ_H_ */

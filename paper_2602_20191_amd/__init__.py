@@ -1,0 +1,164 @@
+"""Thin Python binding over libmbq.so (C ABI in include/mbq.h).
+
+Argument marshalling only: every step of the path (encode, route, bucket, linear)
+runs in the HIP kernels of the library.  torch is used for device memory and the
+current stream, nothing else.  There is no CPU fallback: if the shared library is
+missing, every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmbq.so")
+
+ALGO_AUTO, ALGO_SIMPLE, ALGO_DECODE, ALGO_PREFILL = 0, 1, 2, 3
+N_PRECISIONS = 4
+GROUP = 128
+
+EXPORTS = (
+    "mbq_version", "mbq_last_error", "mbq_blob_bytes", "mbq_route_workspace_bytes",
+    "mbq_linear_workspace_bytes", "mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route",
+    "mbq_linear", "mbq_set_knob",
+)
+
+_lib = None
+
+
+class MbqError(RuntimeError):
+    pass
+
+
+def load() -> ctypes.CDLL:
+    """Loads libmbq.so (built by ``python -m paper_2602_20191_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MbqError(f"{LIB_PATH} not found: build it with `python -m paper_2602_20191_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    c_i64, c_sz, c_p, c_int = ctypes.c_int64, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int
+    lib.mbq_version.restype = ctypes.c_char_p
+    lib.mbq_last_error.restype = ctypes.c_char_p
+    lib.mbq_blob_bytes.restype = c_sz
+    lib.mbq_blob_bytes.argtypes = [c_i64, c_i64]
+    lib.mbq_route_workspace_bytes.restype = c_sz
+    lib.mbq_route_workspace_bytes.argtypes = [c_i64, c_i64]
+    lib.mbq_linear_workspace_bytes.restype = c_sz
+    lib.mbq_linear_workspace_bytes.argtypes = [c_i64, c_i64, c_i64]
+    lib.mbq_encode.argtypes = [c_p, c_i64, c_i64, c_p, c_p]
+    lib.mbq_unpack.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_p, c_p]
+    lib.mbq_dequant.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p]
+    lib.mbq_route.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
+    lib.mbq_linear.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
+    lib.mbq_set_knob.argtypes = [c_int, c_int]
+    for name in ("mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route", "mbq_linear", "mbq_set_knob"):
+        getattr(lib, name).restype = c_int
+    _lib = lib
+    return lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise MbqError(f"{what} failed with status {status}: {load().mbq_last_error().decode()}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise MbqError("tensors handed to libmbq must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def version() -> str:
+    return load().mbq_version().decode()
+
+
+def set_knob(knob: int, value: int) -> None:
+    _check(load().mbq_set_knob(knob, value), "mbq_set_knob")
+
+
+def blob_bytes(N: int, K: int) -> int:
+    n = load().mbq_blob_bytes(N, K)
+    if n == 0:
+        raise MbqError(f"invalid shape: {load().mbq_last_error().decode()}")
+    return n
+
+
+def mbq_encode(W: torch.Tensor, blob: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """W fp32 [N, K] on the device -> packed blob (uint8 tensor)."""
+    assert W.dtype == torch.float32 and W.dim() == 2
+    N, K = W.shape
+    if blob is None:
+        blob = torch.empty(blob_bytes(N, K), dtype=torch.uint8, device=W.device)
+    _check(load().mbq_encode(_ptr(W), N, K, _ptr(blob), _stream()), "mbq_encode")
+    return blob
+
+
+def mbq_unpack(blob: torch.Tensor, N: int, K: int) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """blob -> (codes uint8 [4, N, K], s0 fp32 [N, K/128], z0 fp32 [N, K/128])."""
+    codes = torch.empty((4, N, K), dtype=torch.uint8, device=blob.device)
+    s0 = torch.empty((N, K // GROUP), dtype=torch.float32, device=blob.device)
+    z0 = torch.empty((N, K // GROUP), dtype=torch.float32, device=blob.device)
+    _check(load().mbq_unpack(_ptr(blob), N, K, _ptr(codes), _ptr(s0), _ptr(z0), _stream()), "mbq_unpack")
+    return codes, s0, z0
+
+
+def mbq_dequant(blob: torch.Tensor, N: int, K: int, p: int) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.float32, device=blob.device)
+    _check(load().mbq_dequant(_ptr(blob), N, K, p, _ptr(out), _stream()), "mbq_dequant")
+    return out
+
+
+def route_workspace(T: int, K: int, device) -> torch.Tensor:
+    return torch.empty(load().mbq_route_workspace_bytes(T, K), dtype=torch.uint8, device=device)
+
+
+def linear_workspace(T: int, N: int, K: int, device) -> torch.Tensor:
+    return torch.empty(load().mbq_linear_workspace_bytes(T, N, K), dtype=torch.uint8, device=device)
+
+
+def mbq_route(X: torch.Tensor, Wr: torch.Tensor, br: torch.Tensor, want_logits: bool = False,
+              out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+              ws: Optional[torch.Tensor] = None):
+    """X bf16 [T, K], Wr fp32 [4, K], br fp32 [4] -> (prec, perm, offsets[, logits fp64])."""
+    assert X.dtype == torch.bfloat16 and Wr.dtype == torch.float32 and br.dtype == torch.float32
+    T, K = X.shape
+    P = Wr.shape[0]
+    dev = X.device
+    if out is None:
+        prec = torch.empty(T, dtype=torch.int32, device=dev)
+        perm = torch.empty(T, dtype=torch.int32, device=dev)
+        offsets = torch.empty(P + 1, dtype=torch.int32, device=dev)
+    else:
+        prec, perm, offsets = out
+    logits = torch.empty((T, P), dtype=torch.float64, device=dev) if want_logits else None
+    if ws is None:
+        ws = route_workspace(T, K, dev)
+    _check(load().mbq_route(_ptr(X), T, K, _ptr(Wr), _ptr(br), P, _ptr(prec), _ptr(perm), _ptr(offsets),
+                            _ptr(logits), _ptr(ws), ws.numel(), _stream()), "mbq_route")
+    return (prec, perm, offsets, logits) if want_logits else (prec, perm, offsets)
+
+
+def mbq_linear(X: torch.Tensor, blob: torch.Tensor, N: int, K: int, prec: torch.Tensor, perm: torch.Tensor,
+               offsets: torch.Tensor, Y: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+               algo: int = ALGO_AUTO) -> torch.Tensor:
+    """Routed output Y fp32 [T, N] in original token order."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.shape[1] == K
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, N), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = linear_workspace(T, N, K, X.device)
+    _check(load().mbq_linear(_ptr(X), T, _ptr(blob), N, K, _ptr(prec), _ptr(perm), _ptr(offsets), _ptr(Y),
+                             _ptr(ws), ws.numel(), algo, _stream()), "mbq_linear")
+    return Y

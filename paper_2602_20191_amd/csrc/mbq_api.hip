@@ -1,0 +1,186 @@
+// C-ABI entry points of libmbq.so: argument checks, shape arithmetic, dispatch.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "mbq_common.h"
+
+namespace mbq {
+
+static thread_local char g_error[512] = "";
+static int g_knobs[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+}
+
+mbq_status hip_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return MBQ_OK;
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return MBQ_ERR_HIP;
+}
+
+int knob(int index) { return (index >= 0 && index < 8) ? g_knobs[index] : 0; }
+
+bool make_shape(int64_t N, int64_t K, Shape* out) {
+  if (N <= 0 || K <= 0) {
+    set_error("N and K must be positive (N=%lld, K=%lld)", (long long)N, (long long)K);
+    return false;
+  }
+  if (K % kGroup != 0) {
+    set_error("K=%lld is not a multiple of the group size %d", (long long)K, kGroup);
+    return false;
+  }
+  if (N > (int64_t)1 << 24 || K > (int64_t)1 << 24 || N * K > (int64_t)1 << 36) {
+    set_error("shape %lld x %lld is too large", (long long)N, (long long)K);
+    return false;
+  }
+  Shape s;
+  s.N = N;
+  s.K = K;
+  s.NT = (int)((N + kTileN - 1) / kTileN);
+  s.KB = (int)((K + kTileK - 1) / kTileK);
+  s.G = (int)(K / kGroup);
+  s.slice_words = (size_t)s.NT * s.KB * kTileWords;
+  s.meta_offset = (size_t)kSlices * s.slice_words * 4;
+  s.bytes = s.meta_offset + (size_t)s.NT * (2 * s.KB) * kTileN * 8;
+  *out = s;
+  return true;
+}
+
+static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+}  // namespace mbq
+
+using namespace mbq;
+
+extern "C" {
+
+const char* mbq_version(void) { return "mbq 0.1 (gfx950)"; }
+
+const char* mbq_last_error(void) { return g_error; }
+
+size_t mbq_blob_bytes(int64_t N, int64_t K) {
+  Shape sh;
+  return make_shape(N, K, &sh) ? sh.bytes : 0;
+}
+
+size_t mbq_route_workspace_bytes(int64_t T, int64_t K) {
+  (void)T;
+  (void)K;
+  return 256;
+}
+
+size_t mbq_linear_workspace_bytes(int64_t T, int64_t N, int64_t K) {
+  Shape sh;
+  if (T < 0 || !make_shape(N, K, &sh)) return 0;
+  size_t a = decode_workspace_bytes(T, sh);
+  size_t b = prefill_workspace_bytes(T, sh);
+  return (a > b ? a : b) + 256;
+}
+
+mbq_status mbq_set_knob(int k, int value) {
+  if (k < 0 || k >= 8) {
+    set_error("unknown knob %d", k);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  g_knobs[k] = value;
+  return MBQ_OK;
+}
+
+mbq_status mbq_encode(const float* W, int64_t N, int64_t K, void* blob, void* stream) {
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!W || !blob || !aligned(blob, 256) || !aligned(W, 16)) {
+    set_error("mbq_encode: W must be 16-byte and blob 256-byte aligned and non-null");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_encode(W, sh, blob, (hipStream_t)stream);
+}
+
+mbq_status mbq_unpack(const void* blob, int64_t N, int64_t K, uint8_t* codes, float* scale, float* zero,
+                      void* stream) {
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!blob || !aligned(blob, 256)) {
+    set_error("mbq_unpack: blob must be non-null and 256-byte aligned");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_unpack(blob, sh, codes, scale, zero, (hipStream_t)stream);
+}
+
+mbq_status mbq_dequant(const void* blob, int64_t N, int64_t K, int p, float* What, void* stream) {
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!blob || !What || !aligned(blob, 256) || p < 0 || p >= MBQ_N_PRECISIONS) {
+    set_error("mbq_dequant: null/misaligned pointer or precision index %d outside 0..3", p);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_dequant(blob, sh, p, What, (hipStream_t)stream);
+}
+
+mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br, int P,
+                     int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
+                     size_t ws_bytes, void* stream) {
+  if (P != MBQ_N_PRECISIONS) {
+    set_error("mbq_route: P=%d, only %d precisions are supported", P, MBQ_N_PRECISIONS);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (T < 0 || K <= 0 || K % kGroup != 0 || T > (int64_t)1 << 24 || K > (int64_t)1 << 24) {
+    set_error("mbq_route: bad sizes T=%lld K=%lld", (long long)T, (long long)K);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (!offsets || (T > 0 && (!X || !Wr || !br || !prec || !perm)) || !aligned(X, 16) || !aligned(Wr, 16)) {
+    set_error("mbq_route: null or misaligned pointer (X and Wr need 16-byte alignment)");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws) {
+    set_error("mbq_route: workspace too small (%zu < %zu)", ws_bytes, mbq_route_workspace_bytes(T, K));
+    return MBQ_ERR_WORKSPACE;
+  }
+  return launch_route(X, T, K, Wr, br, prec, perm, offsets, logits, ws, (hipStream_t)stream);
+}
+
+mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
+                      const int32_t* prec, const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
+                      size_t ws_bytes, int algo, void* stream) {
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (T < 0 || T > (int64_t)1 << 24) {
+    set_error("mbq_linear: bad token count %lld", (long long)T);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (algo < MBQ_ALGO_AUTO || algo > MBQ_ALGO_PREFILL) {
+    set_error("mbq_linear: unknown algo %d", algo);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (T == 0) return MBQ_OK;
+  if (!X || !blob || !prec || !perm || !offsets || !Y || !aligned(blob, 256) || !aligned(X, 16)) {
+    set_error("mbq_linear: null or misaligned pointer (X 16-byte, blob 256-byte alignment)");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (!ws || !aligned(ws, 256) || ws_bytes < mbq_linear_workspace_bytes(T, N, K)) {
+    set_error("mbq_linear: workspace too small or misaligned (%zu < %zu)", ws_bytes,
+              mbq_linear_workspace_bytes(T, N, K));
+    return MBQ_ERR_WORKSPACE;
+  }
+  if (algo == MBQ_ALGO_AUTO) algo = (T <= 16) ? MBQ_ALGO_DECODE : MBQ_ALGO_PREFILL;
+  if (algo == MBQ_ALGO_DECODE && T > kMaxDecodeTokens) {
+    set_error("mbq_linear: the decode kernel handles at most %d tokens (T=%lld)", kMaxDecodeTokens,
+              (long long)T);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  switch (algo) {
+    case MBQ_ALGO_SIMPLE:
+      return launch_linear_simple(X, T, blob, sh, prec, Y, s);
+    case MBQ_ALGO_DECODE:
+      return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
+    default:
+      return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s);
+  }
+}
+
+}  // extern "C"

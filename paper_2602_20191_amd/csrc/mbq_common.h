@@ -1,0 +1,75 @@
+// Internal definitions shared by the translation units of libmbq.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mbq.h"
+
+namespace mbq {
+
+constexpr int kGroup = 128;    // input features per quantisation group (paper App. C.1)
+constexpr int kSlices = 4;     // E, number of 2-bit slices (paper Sec. 4.1 default)
+constexpr int kTileN = 16;     // rows of one code tile
+constexpr int kTileK = 256;    // columns of one code tile
+constexpr int kTileWords = 256;  // uint32 words of one code tile of one slice (64 lanes x 4)
+constexpr int kMaxDecodeTokens = 64;
+constexpr int kMaxKSplit = 8;
+
+// Geometry of the packed blob of an N x K matrix.
+struct Shape {
+  int64_t N, K;
+  int NT;               // row tiles, ceil(N / 16)
+  int KB;               // column tiles, ceil(K / 256)
+  int G;                // real groups per row, K / 128
+  size_t slice_words;   // uint32 words of one slice = NT * KB * 256
+  size_t meta_offset;   // byte offset of the {s0, z0} section
+  size_t bytes;         // total blob bytes
+};
+
+bool make_shape(int64_t N, int64_t K, Shape* out);  // false (and error set) if invalid
+void set_error(const char* fmt, ...);
+mbq_status hip_status(hipError_t e, const char* what);
+int knob(int index);
+
+// ---- blob addressing (device + host) -------------------------------------------
+// Word index, inside one slice, of the dword holding weight (n, k).
+__host__ __device__ inline size_t code_word(int NT, int KB, int64_t n, int64_t k) {
+  const int r = (int)(k & 255);
+  const int d = r >> 6;
+  const int kq = (r & 31) >> 3;
+  const int lane = 16 * kq + (int)(n & 15);
+  return ((size_t)(n >> 4) * KB + (size_t)(k >> 8)) * kTileWords + (size_t)lane * 4 + d;
+}
+// Bit position of the 2-bit field of weight column k in slice e's (rotated) dword.
+__host__ __device__ inline int code_bit(int e, int64_t k) {
+  const int r = (int)(k & 255);
+  const int step = (r & 63) >> 5;
+  const int s = r & 7;
+  return (16 * (s & 1) + 4 * (s >> 1) + 2 * step + 2 - 2 * e) & 31;
+}
+// Index of the float2 {s0, z0} of (row n, group g) inside the meta section.
+__host__ __device__ inline size_t meta_index(int KB, int64_t n, int g) {
+  return ((size_t)(n >> 4) * (2 * KB) + g) * kTileN + (size_t)(n & 15);
+}
+
+// ---- kernels' host launchers (each enqueues on `stream`, returns a status) ------
+mbq_status launch_encode(const float* W, const Shape& sh, void* blob, hipStream_t stream);
+mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* codes, float* scale, float* zero,
+                         hipStream_t stream);
+mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream);
+mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
+                        int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
+                        hipStream_t stream);
+mbq_status launch_linear_simple(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
+                                const int32_t* prec, float* Y, hipStream_t stream);
+mbq_status launch_linear_decode(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
+                                const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
+                                hipStream_t stream);
+mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
+                                 const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
+                                 hipStream_t stream);
+size_t decode_workspace_bytes(int64_t T, const Shape& sh);
+size_t prefill_workspace_bytes(int64_t T, const Shape& sh);
+
+}  // namespace mbq

@@ -1,0 +1,163 @@
+// Offline side of the layer: recursive residual quantisation into the packed blob
+// (paper Sec. 4.1 Eq. 2, quantiser and scale refinement of App. B), and the inverse
+// helpers that turn the blob back into canonical arrays.
+//
+// This translation unit is compiled with -ffp-contract=off: the code recursion is
+// specified operation by operation in fp64 and must not be fused.
+#include "mbq_common.h"
+
+namespace mbq {
+
+// One workgroup of 256 threads encodes one code tile (16 rows x 256 columns = two
+// groups per row).  Thread (lane, d) owns dword d of lane `lane`: row nn = lane%16,
+// columns 64*d + 32*step + 8*kq + s for step in {0,1}, s in 0..7 (kq = lane/16).
+__global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ W, int64_t N, int64_t K,
+                                                     int NT, int KB, uint32_t* __restrict__ codes,
+                                                     size_t slice_words, float2* __restrict__ meta) {
+#pragma clang fp contract(off)
+  const int nt = blockIdx.x;
+  const int kb = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int lane = tid >> 2;
+  const int d = tid & 3;
+  const int nn = lane & 15;
+  const int kq = lane >> 4;
+  const int64_t n = (int64_t)nt * kTileN + nn;
+  const int64_t kbase = (int64_t)kb * kTileK + 64 * d + 8 * kq;
+  const int h = d >> 1;  // group of this thread inside the tile
+  const int64_t g = 2 * (int64_t)kb + h;
+  const bool real = (n < N) && (g * kGroup < K);
+
+  float w[16];
+#pragma unroll
+  for (int step = 0; step < 2; ++step) {
+    if (real) {
+      const float4* src = reinterpret_cast<const float4*>(W + n * K + kbase + 32 * step);
+      float4 a = src[0], b = src[1];
+      w[8 * step + 0] = a.x; w[8 * step + 1] = a.y; w[8 * step + 2] = a.z; w[8 * step + 3] = a.w;
+      w[8 * step + 4] = b.x; w[8 * step + 5] = b.y; w[8 * step + 6] = b.z; w[8 * step + 7] = b.w;
+    } else {
+#pragma unroll
+      for (int s = 0; s < 8; ++s) w[8 * step + s] = 0.f;
+    }
+  }
+  float lo = w[0], hi = w[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) {
+    lo = fminf(lo, w[i]);
+    hi = fmaxf(hi, w[i]);
+  }
+  // a (row, group) is spread over 8 threads: d in {2h, 2h+1} x kq in 0..3
+  __shared__ float s_lo[16][2][8];
+  __shared__ float s_hi[16][2][8];
+  s_lo[nn][h][(d & 1) * 4 + kq] = lo;
+  s_hi[nn][h][(d & 1) * 4 + kq] = hi;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    lo = fminf(lo, s_lo[nn][h][i]);
+    hi = fmaxf(hi, s_hi[nn][h][i]);
+  }
+  // base-slice fit: four floor-aligned bins tile [lo, hi]
+  float rng = hi - lo;
+  const float mag = fmaxf(fabsf(lo), fabsf(hi));
+  const float floor_rng = fmaxf(mag * 0x1p-16f, 0x1p-100f);
+  rng = fmaxf(rng, floor_rng);
+  const float s0 = rng * 0.25f;
+  const float z0 = (float)((double)(-lo) / (double)s0);  // equals the IEEE fp32 quotient
+
+  uint32_t word[kSlices] = {0u, 0u, 0u, 0u};
+  if (real) {
+    const double s0d = (double)s0, z0d = (double)z0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int step = i >> 3, s = i & 7;
+      const int field = 16 * (s & 1) + 4 * (s >> 1) + 2 * step;
+      double R = (double)w[i];
+      double se = s0d;
+#pragma unroll
+      for (int e = 0; e < kSlices; ++e) {
+        const double ze = (e == 0) ? z0d : 2.0;
+        double q = floor(R / se + ze);
+        q = fmin(fmax(q, 0.0), 3.0);
+        R = R - se * ((q - ze) + 0.5);
+        word[e] |= (uint32_t)q << ((field + 2 - 2 * e) & 31);
+        se = se * 0.25;
+      }
+    }
+  }
+  const size_t widx = ((size_t)nt * KB + kb) * kTileWords + (size_t)lane * 4 + d;
+#pragma unroll
+  for (int e = 0; e < kSlices; ++e) codes[e * slice_words + widx] = word[e];
+  if ((d & 1) == 0 && kq == 0) {
+    float2 m;
+    m.x = real ? s0 : 0.f;
+    m.y = real ? z0 : 0.f;
+    meta[meta_index(KB, n, (int)g)] = m;
+  }
+}
+
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ codes, size_t slice_words,
+                                                     const float2* __restrict__ meta, int64_t N, int64_t K,
+                                                     int NT, int KB, uint8_t* __restrict__ out_codes,
+                                                     float* __restrict__ scale, float* __restrict__ zero) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= N * K) return;
+  const int64_t n = idx / K, k = idx % K;
+  if (out_codes) {
+    const size_t w = code_word(NT, KB, n, k);
+#pragma unroll
+    for (int e = 0; e < kSlices; ++e)
+      out_codes[(size_t)e * N * K + idx] = (uint8_t)((codes[e * slice_words + w] >> code_bit(e, k)) & 3u);
+  }
+  if ((k % kGroup) == 0) {
+    const int g = (int)(k / kGroup);
+    const float2 m = meta[meta_index(KB, n, g)];
+    if (scale) scale[n * (K / kGroup) + g] = m.x;
+    if (zero) zero[n * (K / kGroup) + g] = m.y;
+  }
+}
+
+__global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict__ codes, size_t slice_words,
+                                                      const float2* __restrict__ meta, int64_t N, int64_t K,
+                                                      int NT, int KB, int p, float* __restrict__ What) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= N * K) return;
+  const int64_t n = idx / K, k = idx % K;
+  const size_t w = code_word(NT, KB, n, k);
+  int I = 0;
+  for (int e = 0; e <= p; ++e) I = I * 4 + (int)((codes[e * slice_words + w] >> code_bit(e, k)) & 3u);
+  const float2 m = meta[meta_index(KB, n, (int)(k / kGroup))];
+  const double pw = (double)(1 << (2 * p));
+  What[idx] = (float)(((double)m.x / pw) * (((double)I - pw * (double)m.y) + 0.5));
+}
+
+mbq_status launch_encode(const float* W, const Shape& sh, void* blob, hipStream_t stream) {
+  uint32_t* codes = reinterpret_cast<uint32_t*>(blob);
+  float2* meta = reinterpret_cast<float2*>(reinterpret_cast<char*>(blob) + sh.meta_offset);
+  dim3 grid(sh.NT, sh.KB);
+  hipLaunchKernelGGL(encode_kernel, grid, dim3(256), 0, stream, W, sh.N, sh.K, sh.NT, sh.KB, codes,
+                     sh.slice_words, meta);
+  return hip_status(hipGetLastError(), "encode_kernel launch");
+}
+
+mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* out_codes, float* scale, float* zero,
+                         hipStream_t stream) {
+  const uint32_t* codes = reinterpret_cast<const uint32_t*>(blob);
+  const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
+  const int64_t total = sh.N * sh.K;
+  hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes,
+                     sh.slice_words, meta, sh.N, sh.K, sh.NT, sh.KB, out_codes, scale, zero);
+  return hip_status(hipGetLastError(), "unpack_kernel launch");
+}
+
+mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream) {
+  const uint32_t* codes = reinterpret_cast<const uint32_t*>(blob);
+  const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
+  const int64_t total = sh.N * sh.K;
+  hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes,
+                     sh.slice_words, meta, sh.N, sh.K, sh.NT, sh.KB, p, What);
+  return hip_status(hipGetLastError(), "dequant_kernel launch");
+}
+
+}  // namespace mbq

@@ -1,0 +1,75 @@
+"""CPU-side checks of the boundary: the shared library loads and exports every symbol
+the header declares; shape arithmetic needs no GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mbq.h")
+LIB = os.path.join(ROOT, "paper_2602_20191_amd", "libmbq.so")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mbq_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import paper_2602_20191_amd.build as b
+
+        b.build()
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_entry_points():
+    names = declared_symbols()
+    for must in ("mbq_encode", "mbq_route", "mbq_linear", "mbq_unpack", "mbq_dequant", "mbq_blob_bytes"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_binding_lists_the_same_symbols():
+    import paper_2602_20191_amd as pkg
+
+    assert sorted(pkg.EXPORTS) == declared_symbols()
+
+
+def test_shape_arithmetic_matches_the_documented_blob_format(lib):
+    import oracle as O
+
+    lib.mbq_blob_bytes.restype = ctypes.c_size_t
+    lib.mbq_blob_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+    lib.mbq_last_error.restype = ctypes.c_char_p
+    for N, K in [(16, 256), (21, 384), (3, 128), (4096, 4096), (11008, 4096), (8192, 28672)]:
+        assert lib.mbq_blob_bytes(N, K) == O.blob_bytes(N, K)
+    assert lib.mbq_blob_bytes(16, 100) == 0          # K not a multiple of the group size
+    assert b"multiple" in lib.mbq_last_error()
+    assert lib.mbq_blob_bytes(0, 128) == 0
+    assert lib.mbq_blob_bytes(-1, 128) == 0
+
+
+def test_argument_errors_are_reported_without_a_gpu(lib):
+    lib.mbq_linear.restype = ctypes.c_int
+    lib.mbq_linear.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                               ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    lib.mbq_route.restype = ctypes.c_int
+    lib.mbq_route.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                              ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    # bad shape, bad algo, null pointers, unsupported precision count: all refused before any launch
+    assert lib.mbq_linear(None, 4, None, 16, 100, None, None, None, None, None, 0, 0, None) == 2
+    assert lib.mbq_linear(None, 4, None, 16, 128, None, None, None, None, None, 0, 9, None) == 1
+    assert lib.mbq_linear(None, 4, None, 16, 128, None, None, None, None, None, 0, 0, None) == 1
+    assert lib.mbq_linear(None, 0, None, 16, 128, None, None, None, None, None, 0, 0, None) == 0   # T = 0: no-op
+    assert lib.mbq_route(None, 4, 128, None, None, 3, None, None, None, None, None, 0, None) == 2
+    assert lib.mbq_route(None, 4, 128, None, None, 4, None, None, None, None, None, 0, None) == 1

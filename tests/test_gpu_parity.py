@@ -1,0 +1,165 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same
+seeded inputs, at sizes the oracle finishes in seconds.  Codes, blob bytes, routing and
+permutation are compared bit for bit; outputs within the floating-point bar."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import (assert_output_close, check_bucket, compare_routing, dev, dev_bf16)
+from workloads import CONFIGS, f32_to_bf16_bits, make_case, make_weight
+
+pytestmark = pytest.mark.gpu
+
+
+def tokens(T, K, seed, scale_channels=True):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, K)).astype(np.float32)
+    if scale_channels and K >= 256:
+        x[:, rng.choice(K, size=max(1, K // 100), replace=False)] *= 20.0
+    return f32_to_bf16_bits(x)
+
+
+# ----------------------------------------------------------------------------- encode
+@pytest.mark.parametrize("N,K", [(16, 256), (3, 128), (40, 384), (130, 1280), (2048, 2048)])
+def test_encode_blob_is_bit_exact(mbq, N, K):
+    print(f"[case] encode N={N} K={K}", flush=True)
+    W = make_weight(N, K, [7, N, K], 4.0)
+    if N >= 40:
+        W[1, :128] = 0.0                # an all-zero group
+        W[2, 128:256] = 0.3125          # a constant group
+    codes, s0, z0 = O.encode(W)
+    blob = mbq.mbq_encode(dev(W))
+    torch.cuda.synchronize()
+    got = blob.cpu().numpy()
+    want = O.pack_blob(codes, s0, z0)
+    assert got.size == want.size
+    assert np.array_equal(got, want)
+    c, s, z = mbq.mbq_unpack(blob, N, K)
+    assert np.array_equal(c.cpu().numpy(), codes)
+    assert np.array_equal(s.cpu().numpy(), s0) and np.array_equal(z.cpu().numpy(), z0)
+    for p in range(4):
+        What = mbq.mbq_dequant(blob, N, K, p).cpu().numpy().astype(np.float64)
+        ref = O.dequant(codes, s0, z0, p)
+        np.testing.assert_allclose(What, ref, rtol=2e-7, atol=1e-12)
+
+
+# ------------------------------------------------------------------------------ route
+@pytest.mark.parametrize("T,K", [(0, 256), (1, 128), (5, 384), (32, 2048), (64, 4096), (65, 1024),
+                                 (1023, 256), (1024, 256), (1025, 256), (4100, 512)])
+def test_route_and_bucket_are_bit_exact(mbq, T, K):
+    print(f"[case] route T={T} K={K}", flush=True)
+    rng = np.random.default_rng([T, K])
+    xb = tokens(T, K, [T, K, 1])
+    Wr = (rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32)
+    br = np.array([0.3, 0.1, -0.1, -0.4], dtype=np.float32)
+    S, prec_ref, gap = O.route(xb, Wr, br)
+    prec, perm, offsets, logits = mbq.mbq_route(dev_bf16(xb).reshape(T, K), dev(Wr), dev(br), want_logits=True)
+    torch.cuda.synchronize()
+    prec, perm, offsets = prec.cpu().numpy(), perm.cpu().numpy(), offsets.cpu().numpy()
+    if T:
+        np.testing.assert_allclose(logits.cpu().numpy(), S, rtol=0, atol=1e-10)
+    compare_routing(prec, prec_ref, gap, f"route T={T} K={K}")
+    check_bucket(prec, perm, offsets)          # permutation of the GPU's own choices: unique answer
+    assert offsets[4] == T
+
+
+def test_route_ties_and_single_bucket(mbq):
+    T, K = 70, 256
+    xb = tokens(T, K, 3)
+    Wr = np.zeros((4, K), dtype=np.float32)
+    br = np.zeros(4, dtype=np.float32)            # every logit ties: first index wins
+    prec, perm, offsets = mbq.mbq_route(dev_bf16(xb), dev(Wr), dev(br))
+    assert prec.cpu().numpy().tolist() == [0] * T
+    assert offsets.cpu().numpy().tolist() == [0, T, T, T, T]
+    assert perm.cpu().numpy().tolist() == list(range(T))
+    br[2] = 1.0
+    prec, perm, offsets = mbq.mbq_route(dev_bf16(xb), dev(Wr), dev(br))
+    assert prec.cpu().numpy().tolist() == [2] * T
+    assert offsets.cpu().numpy().tolist() == [0, 0, 0, T, T]
+
+
+# ----------------------------------------------------------------------------- linear
+def run_linear(mbq, W, xb, prec, algo):
+    N, K = W.shape
+    T = xb.shape[0]
+    blob = mbq.mbq_encode(dev(W))
+    perm, offsets = O.bucket(prec)
+    Y = mbq.mbq_linear(dev_bf16(xb).reshape(T, K), blob, N, K, dev(prec.astype(np.int32)), dev(perm),
+                       dev(offsets), algo=algo)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy()
+
+
+ALGOS = {"simple": 1, "decode": 2, "prefill": 3}
+
+
+@pytest.mark.parametrize("algo", ["simple", "decode", "prefill"])
+@pytest.mark.parametrize("N,K,T", [(16, 256, 1), (40, 384, 5), (130, 1280, 16), (272, 512, 33), (64, 2048, 64)])
+def test_linear_small_shapes(mbq, algo, N, K, T):
+    print(f"[case] linear {algo} N={N} K={K} T={T}", flush=True)
+    W = make_weight(N, K, [11, N, K], 4.0)
+    xb = tokens(T, K, [N, K, T])
+    prec = np.random.default_rng([N, T]).integers(0, 4, size=T).astype(np.int32)
+    codes, s0, z0 = O.encode(W)
+    Yref = O.linear(xb, codes, s0, z0, prec)
+    Y = run_linear(mbq, W, xb, prec, ALGOS[algo])
+    assert_output_close(Y, Yref, f"{algo} N={N} K={K} T={T}")
+
+
+@pytest.mark.parametrize("algo", ["decode", "prefill"])
+@pytest.mark.parametrize("p", [0, 1, 2, 3])
+def test_linear_single_precision_is_a_dense_gemm(mbq, algo, p):
+    """All tokens at one precision: three empty buckets; equals X What^T (dense library matmul)."""
+    N, K, T = 96, 768, 16 if algo == "decode" else 150
+    print(f"[case] linear {algo} uniform p={p}", flush=True)
+    W = make_weight(N, K, [13, p], 4.0)
+    xb = tokens(T, K, [p, 5])
+    prec = np.full(T, p, dtype=np.int32)
+    codes, s0, z0 = O.encode(W)
+    dense = torch.from_numpy(O.bf16_bits_to_f64(xb)) @ torch.from_numpy(O.dequant_merged(codes, s0, z0, p)).T
+    Y = run_linear(mbq, W, xb, prec, ALGOS[algo])
+    assert_output_close(Y, dense.numpy(), f"{algo} uniform p={p}")
+
+
+def test_linear_zero_tokens_and_bad_arguments(mbq):
+    N, K = 32, 256
+    W = make_weight(N, K, [17], 4.0)
+    blob = mbq.mbq_encode(dev(W))
+    empty = torch.empty((0, K), dtype=torch.bfloat16, device="cuda")
+    z32 = torch.zeros(0, dtype=torch.int32, device="cuda")
+    off = torch.zeros(5, dtype=torch.int32, device="cuda")
+    Y = mbq.mbq_linear(empty, blob, N, K, z32, z32, off)
+    assert Y.shape == (0, N)
+    xb = tokens(70, K, 1)
+    prec = np.zeros(70, dtype=np.int32)
+    perm, offsets = O.bucket(prec)
+    with pytest.raises(mbq.MbqError):       # the decode kernel refuses more than 64 tokens
+        mbq.mbq_linear(dev_bf16(xb), blob, N, K, dev(prec), dev(perm), dev(offsets), algo=2)
+    with pytest.raises(mbq.MbqError):       # workspace too small
+        mbq.mbq_linear(dev_bf16(xb), blob, N, K, dev(prec), dev(perm), dev(offsets),
+                       ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+
+
+def test_config0_end_to_end(mbq):
+    """BASELINE config 0: 2048 x 2048, 32 tokens, {40,30,20,10}% mix; full comparison, every kernel."""
+    cfg = CONFIGS[0]
+    case = make_case(cfg, 0, 32)
+    W, xb, Wr, br = case["W"], case["X"], case["Wr"], case["br"]
+    N, K = W.shape
+    codes, s0, z0 = O.encode(W)
+    S, prec_ref, gap = O.route(xb, Wr, br)
+    X = dev_bf16(xb)
+    blob = mbq.mbq_encode(dev(W))
+    assert np.array_equal(blob.cpu().numpy(), O.pack_blob(codes, s0, z0))
+    prec, perm, offsets = mbq.mbq_route(X, dev(Wr), dev(br))
+    compare_routing(prec.cpu().numpy(), prec_ref, gap, "config 0")
+    check_bucket(prec.cpu().numpy(), perm.cpu().numpy(), offsets.cpu().numpy())
+    Yref = O.linear(xb, codes, s0, z0, prec.cpu().numpy())
+    for name, algo in ALGOS.items():
+        Y = mbq.mbq_linear(X, blob, N, K, prec, perm, offsets, algo=algo)
+        assert_output_close(Y.cpu().numpy(), Yref, f"config 0 {name}")
+    # the layer fed with the oracle's routing as well
+    perm_ref, off_ref = O.bucket(prec_ref)
+    Y = mbq.mbq_linear(X, blob, N, K, dev(prec_ref), dev(perm_ref), dev(off_ref))
+    assert_output_close(Y.cpu().numpy(), O.linear(xb, codes, s0, z0, prec_ref), "config 0 oracle routing")
