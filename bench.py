@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed mixed-bit linear hot path on one MI355X.
+
+Workload (default): BASELINE config 1 - the seven linears of a Llama-2-7B-shaped decoder
+block (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), each with its own
+router, one decode batch of bf16 tokens with 1% outlier channels, uniform precision mix.
+A *step* is one pass of the whole hot path (mbq_route then mbq_linear) over all seven
+linears for one batch.  Weights, activations and router parameters are resident in HBM
+before the timed region; three distinct copies of the packed block (> 600 MB) are
+rotated so that no step finds its weights in the 256 MB last-level cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+RING = 3                        # distinct packed copies of the block rotated across steps
+
+
+def algorithmic_bytes(N, K, T, pmax):
+    """Bytes one routed-linear call has to move: slices 0..pmax actually read, the
+    fp32 scale / zero point pairs, the activations, the outputs."""
+    return (pmax + 1) * N * K // 4 + N * K // 16 + 2 * T * K + 4 * T * N
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--batch", type=int, default=16, help="decode batch (tokens per step): 1, 4 or 16")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the batch-1/4 and prefill side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2602_20191_amd as mbq
+    from workloads import CONFIGS, make_case
+
+    mbq.load()          # no fallback: raises if libmbq.so is missing
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[1]
+    T = args.batch
+
+    # ------------------------------------------------------------------ inputs in HBM
+    t0 = time.time()
+    layers = []
+    for li, spec in enumerate(cfg.linears):
+        case = make_case(cfg, li, T)
+        Wd = torch.from_numpy(case["W"]).to(dev)
+        blob = mbq.mbq_encode(Wd)
+        torch.cuda.synchronize()
+        del Wd
+        blobs = [blob] + [blob.clone() for _ in range(RING - 1)]
+        X = torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev)
+        layer = dict(
+            spec=spec, X=X, Wr=torch.from_numpy(case["Wr"]).to(dev), br=torch.from_numpy(case["br"]).to(dev),
+            blobs=blobs, x_bits=case["X"], Wr_h=case["Wr"], br_h=case["br"],
+            prec=torch.empty(T, dtype=torch.int32, device=dev), perm=torch.empty(T, dtype=torch.int32, device=dev),
+            offsets=torch.empty(5, dtype=torch.int32, device=dev),
+            Y=torch.empty((T, spec.N), dtype=torch.float32, device=dev),
+            ws_r=mbq.route_workspace(T, spec.K, dev), ws_l=mbq.linear_workspace(T, spec.N, spec.K, dev))
+        layers.append(layer)
+    print(f"[bench] inputs ready in {time.time() - t0:.1f}s "
+          f"({sum(l['blobs'][0].numel() for l in layers) * RING / 1e6:.0f} MB of packed weights)", file=sys.stderr)
+
+    def step(ring_slot: int) -> None:
+        for l in layers:
+            mbq.mbq_route(l["X"], l["Wr"], l["br"], out=(l["prec"], l["perm"], l["offsets"]), ws=l["ws_r"])
+            mbq.mbq_linear(l["X"], l["blobs"][ring_slot], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
+                           l["offsets"], Y=l["Y"], ws=l["ws_l"])
+
+    # ------------------------------------------------------------- launch mechanism
+    launch = "eager"
+    graphs = None
+    step(0)
+    torch.cuda.synchronize()
+    if not args.no_graph:
+        try:
+            graphs = []
+            for slot in range(RING):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    step(slot)
+                graphs.append(g)
+            launch = "hipgraph"
+        except Exception as exc:  # capture not available: time eager launches instead
+            print(f"[bench] graph capture failed ({exc}); falling back to eager launches", file=sys.stderr)
+            graphs = None
+            torch.cuda.synchronize()
+
+    def run(i: int) -> None:
+        if graphs is not None:
+            graphs[i % RING].replay()
+        else:
+            step(i % RING)
+
+    for i in range(args.warmup):
+        run(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_start = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        run(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    ms_per_step = wall_ms / args.steps
+    ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
+
+    # realised routing (device results of the last step)
+    mixes, step_bytes, pmaxes = [], 0, []
+    for l in layers:
+        p = l["prec"].cpu().numpy()
+        pmax = int(p.max())
+        pmaxes.append(pmax)
+        mixes.append(np.bincount(p, minlength=4).tolist())
+        step_bytes += algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax) + 16 * l["spec"].K
+    avg_bits = float(np.mean([2 * (q + 1) for m in mixes for q in range(4) for _ in range(m[q])]))
+
+    # ------------------------------------- dominant kernel: per-launch duration (HIP events)
+    # mbq_linear alone, back to back over the rotating weight copies, on the same stream.
+    reps = max(20, min(200, args.steps))
+    kernel_us, kernel_bytes = [], []
+    for l, pmax in zip(layers, pmaxes):
+        for i in range(5):
+            mbq.mbq_linear(l["X"], l["blobs"][i % RING], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
+                           l["offsets"], Y=l["Y"], ws=l["ws_l"])
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(reps):
+            mbq.mbq_linear(l["X"], l["blobs"][i % RING], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
+                           l["offsets"], Y=l["Y"], ws=l["ws_l"])
+        b.record()
+        torch.cuda.synchronize()
+        kernel_us.append(a.elapsed_time(b) * 1e3 / reps)
+        kernel_bytes.append(algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax))
+    avg_launch_us = float(np.mean(kernel_us))
+    avg_launch_bytes = float(np.mean(kernel_bytes))
+    achieved = avg_launch_bytes / (avg_launch_us * 1e-6) / 1e9
+
+    out = {
+        "metric": "decode tokens/s of the routed mixed-bit linear path (route + linear, 7 linears of a Llama-2-7B block)",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"BASELINE configs[1]: Llama-2-7B-shaped decoder block, 7 routed linears, decode batch {T}, "
+                        "group 128, 2-bit base + three 2-bit residual slices, uniform precision mix, 1% outlier channels",
+            "batch": T, "launch": launch, "weight_ring_copies": RING,
+            "precision_mix_per_linear": mixes, "avg_bits": avg_bits,
+        },
+        "hbm_gbps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "event_ms_per_step": ev_ms_per_step,
+        "roofline": {
+            "bound": "hbm", "kernel": "mbq::decode_kernel (mbq_linear, T <= 16)",
+            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": None,
+            "avg_launch_us": avg_launch_us, "avg_launch_bytes": avg_launch_bytes,
+            "per_linear_us": {l["spec"].name: round(u, 2) for l, u in zip(layers, kernel_us)},
+            "per_linear_gbps": {l["spec"].name: round(bts / (u * 1e-6) / 1e9, 1)
+                                for l, u, bts in zip(layers, kernel_us, kernel_bytes)},
+        },
+    }
+
+    # ------------------------------------------------------------------ CPU baseline
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, layers, T)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(cfg, layers, T):
+    """The oracle as it stands, timed on the host: full routing, and the routed linear on
+    the first 256 output rows of each linear, extrapolated linearly to all rows."""
+    import oracle as O
+    from workloads import make_weight
+
+    try:
+        from threadpoolctl import threadpool_info
+
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sample_rows = 256
+    total = 0.0
+    for li, l in enumerate(layers):
+        spec = l["spec"]
+        rows = np.arange(min(sample_rows, spec.N))
+        W = make_weight(spec.N, spec.K, [cfg.seed, li], cfg.weight_df, rows=rows)
+        codes, s0, z0 = O.encode(W)                      # offline step: not timed
+        t0 = time.perf_counter()
+        S, prec, gap = O.route(l["x_bits"], l["Wr_h"], l["br_h"])
+        perm, offsets = O.bucket(prec)
+        t1 = time.perf_counter()
+        O.linear(l["x_bits"], codes, s0, z0, prec)
+        t2 = time.perf_counter()
+        total += (t1 - t0) + (t2 - t1) * (spec.N / len(rows))
+    return {"value": T / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"routing in full; linear on the first {sample_rows} output rows of each of the 7 linears, "
+                      f"time scaled by N/{sample_rows} (numpy fp64, dequantise-then-matmul)"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
