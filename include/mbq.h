@@ -138,7 +138,9 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
 /*
  * Launch-shape knobs for experiments (process-global, not thread-safe; 0 = default).
  *   knob 0: waves per workgroup of the decode kernel (4, 8 or 16)
- *   knob 1: K-split (workgroups along K) of the decode kernel, 0 = automatic
+ *   knob 1: K-split (workgroups along K) of the multi-tile decode kernel, 0 = automatic
+ *   knob 2: workgroups per compute unit of the single-tile decode kernel, 0 = automatic
+ *   knob 3: 1 = route T <= 16 through the multi-tile decode kernel as well
  */
 mbq_status mbq_set_knob(int knob, int value);
 

@@ -20,6 +20,7 @@ SOURCES = [
     ("mbq_route.hip", ["-ffp-contract=off"]),
     ("mbq_linear_simple.hip", []),
     ("mbq_linear_decode.hip", []),
+    ("mbq_linear_decode16.hip", []),
     ("mbq_linear_prefill.hip", []),
 ]
 

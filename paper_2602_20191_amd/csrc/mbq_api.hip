@@ -177,6 +177,7 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
     case MBQ_ALGO_SIMPLE:
       return launch_linear_simple(X, T, blob, sh, prec, Y, s);
     case MBQ_ALGO_DECODE:
+      if (T <= 16 && knob(3) == 0) return launch_linear_decode16(X, T, blob, sh, prec, Y, s);
       return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
     default:
       return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s);
