@@ -4,21 +4,24 @@
 // shared-scale structure of App. B (s_e = s0/4^e, z_e = 2 for e >= 1); only slices
 // 0..max_i p_i are fetched (Sec. 4.3, on-demand slice access).
 //
-// Work split: a workgroup of WAVES wavefronts owns 16-row code tiles nt = blockIdx.x,
-// blockIdx.x + gridDim.x, ...; wavefront w owns the 256-column blocks kb = w, w + WAVES, ...
-// When the row fits (KB <= WAVES) the wavefront's activation fragments and their group
-// sums stay in registers for the whole kernel and only packed weights stream from HBM,
-// the next tile's loads being issued before the current tile is consumed.
+// Work split: a workgroup of WAVES wavefronts owns the 16-row code tiles nt = blockIdx.x,
+// blockIdx.x + gridDim.x, ...  The K axis is cut into chunks of WAVES 256-column blocks;
+// inside a chunk wavefront w owns block chunk*WAVES + w, keeps its activation fragments in
+// registers (and their group sums in LDS) and streams only packed weights from HBM while it
+// walks over the workgroup's tiles, always fetching the next tile before consuming the
+// current one.  Partial tiles of different chunks are summed in LDS.
 //
 // Per tile and slice a lane issues ONE 128-bit load (64 two-bit codes).  A dword becomes
 // MFMA B operands with a rotate and an and-or per pair of codes: the 2-bit field is OR-ed
 // into the mantissa of a bf16 power of two chosen per slice and field position so that the
 // operand equals  beta + c / 4^e  exactly (e.g. 32 + c/4).  Tokens are the 16 rows of the
 // v_mfma_f32_16x16x32_bf16 A operand, read straight from X in original token order.  All
-// slices of a group chain into one accumulator; the accumulator after slice p is kept, so a
-// row of precision p simply selects snapshot p.  The known offsets (beta times the group
-// sums of x, delivered in accumulator layout by MFMAs against an all-ones operand), the zero
-// points and the group scale are applied once per group of 128 columns in fp32.
+// slices of a group chain into one accumulator; a row of precision p keeps the value the
+// accumulator had after slice p.  The known offsets (beta times the group sums of x, which
+// MFMAs against an all-ones operand deliver in accumulator layout), the zero points and the
+// group scale are applied once per group of 128 columns in fp32.
+#include <type_traits>
+
 #include "mbq_common.h"
 
 namespace mbq {
@@ -27,6 +30,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace d16 {
+
+constexpr int kMaxTilesMulti = 32;  // tiles per workgroup whose partial sums fit the LDS budget
 
 __device__ inline floatx4 mfma(const uint4& a, const uint4& b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
@@ -42,38 +47,49 @@ __device__ inline uint32_t rotr(uint32_t w) {
 // bf16 pairs of 2^5, 2^3, 2^1, 2^-1
 constexpr uint32_t kPow5 = 0x42004200u, kPow3 = 0x41004100u, kPow1 = 0x40004000u, kPowM1 = 0x3F003F00u;
 
+// (t & mask) | bias in one VALU op.  The compiler splits this into v_and + v_or when the
+// operands are literals (a VOP3 instruction cannot carry a literal on gfx9), so the mask is
+// pinned to a scalar register and the bias to a vector register.
+__device__ inline uint32_t and_or(uint32_t t, uint32_t mask, uint32_t bias) {
+  uint32_t d;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(t), "s"(mask), "v"(bias));
+  return d;
+}
+
 // B operands (a-step, b-step) of the two k-steps held by one dword of slice E.
 // The unrotated field of (step, slot s = 2j + h) sits at bit 16h + 4j + 2 step; slice E is
 // stored rotated left by 2 - 2E.  Slice 0 is consumed one field position up (no rotation
 // for j = 0); its bias exponents are lowered accordingly.  Operand values:
-//   slice 0: 32 + c, 8 + c     slice 1: 32 + c/4, 8 + c/4
-//   slice 2: 8 + c/16, 2 + c/16   slice 3: 2 + c/64, 0.5 + c/64
+//   slice 0: 32 + c, 8 + c          slice 1: 32 + c/4, 8 + c/4
+//   slice 2: 8 + c/16, 2 + c/16     slice 3: 2 + c/64, 0.5 + c/64
+// `bias` holds the four bf16-pair constants 2^5, 2^3, 2^1, 2^-1 in vector registers.
 template <int E>
-__device__ inline void unpack_dword(uint32_t w, uint4& Ba, uint4& Bb) {
+__device__ inline void unpack_dword(uint32_t w, const uint32_t bias[4], uint4& Ba, uint4& Bb) {
   constexpr int rho = (2 - 2 * E) & 31;
   constexpr int a0 = (E == 0) ? 2 : 0;
   constexpr uint32_t ma = 0x00030003u << a0;
   constexpr uint32_t mb = 0x000C000Cu << a0;
-  constexpr uint32_t ba = (E <= 1) ? kPow5 : (E == 2 ? kPow3 : kPow1);
-  constexpr uint32_t bb = (E <= 1) ? kPow3 : (E == 2 ? kPow1 : kPowM1);
+  const uint32_t ba = bias[(E <= 1) ? 0 : (E == 2 ? 1 : 2)];
+  const uint32_t bb = bias[(E <= 1) ? 1 : (E == 2 ? 2 : 3)];
   const uint32_t t0 = rotr<(0 + rho - a0) & 31>(w);
   const uint32_t t1 = rotr<(4 + rho - a0) & 31>(w);
   const uint32_t t2 = rotr<(8 + rho - a0) & 31>(w);
   const uint32_t t3 = rotr<(12 + rho - a0) & 31>(w);
-  Ba.x = (t0 & ma) | ba; Bb.x = (t0 & mb) | bb;
-  Ba.y = (t1 & ma) | ba; Bb.y = (t1 & mb) | bb;
-  Ba.z = (t2 & ma) | ba; Bb.z = (t2 & mb) | bb;
-  Ba.w = (t3 & ma) | ba; Bb.w = (t3 & mb) | bb;
+  Ba.x = and_or(t0, ma, ba); Bb.x = and_or(t0, mb, bb);
+  Ba.y = and_or(t1, ma, ba); Bb.y = and_or(t1, mb, bb);
+  Ba.z = and_or(t2, ma, ba); Bb.z = and_or(t2, mb, bb);
+  Ba.w = and_or(t3, ma, ba); Bb.w = and_or(t3, mb, bb);
 }
 
 // D += X_group * slice-E operands of the two dwords (w_lo, w_hi) of one group.
 template <int E>
-__device__ inline floatx4 slice_group(const uint4 A[4], uint32_t w_lo, uint32_t w_hi, floatx4 D) {
+__device__ inline floatx4 slice_group(const uint4 A[4], const uint32_t bias[4], uint32_t w_lo, uint32_t w_hi,
+                                       floatx4 D) {
   uint4 Ba, Bb;
-  unpack_dword<E>(w_lo, Ba, Bb);
+  unpack_dword<E>(w_lo, bias, Ba, Bb);
   D = mfma(A[0], Ba, D);
   D = mfma(A[1], Bb, D);
-  unpack_dword<E>(w_hi, Ba, Bb);
+  unpack_dword<E>(w_hi, bias, Ba, Bb);
   D = mfma(A[2], Ba, D);
   D = mfma(A[3], Bb, D);
   return D;
@@ -86,174 +102,190 @@ struct Item {
 
 }  // namespace d16
 
-template <int WAVES, bool STATIONARY>
+// MULTI: the K axis needs more than one chunk (KB > WAVES); partial tiles go through LDS.
+template <int WAVES, bool MULTI>
 __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
     const uint16_t* __restrict__ X, int T, int64_t K, const uint4* __restrict__ codes, size_t slice_vec,
     const float2* __restrict__ meta, int64_t N, int NT, int KB, const int32_t* __restrict__ prec,
-    float* __restrict__ Y, int dbg) {
+    float* __restrict__ Y) {
   using namespace d16;
-  if (dbg & 16) return;
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps tile addresses scalar
   const int m = lane & 15;   // token row of A / weight row of B / output column
   const int kq = lane >> 4;  // k quarter of a k-step; output rows 4 kq .. 4 kq + 3
-
-  // 16 wavefronts that also reload activations per block have no registers left for a second
-  // set of weight fragments: they fetch the next block after finishing the current one.
-  constexpr bool kPrefetch = STATIONARY || WAVES < 16;
-  const int phases = STATIONARY ? 1 : (KB + WAVES - 1) / WAVES;
+  const int chunks = MULTI ? (KB + WAVES - 1) / WAVES : 1;
   const int my_tiles = (NT - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
-  const int n_items = my_tiles * phases;
+
+  __shared__ float red[2][WAVES][64][4];                   // per-wavefront partial tiles, double buffered
+  __shared__ floatx4 cst[WAVES][4][64];                    // per wavefront: C1[2], SS[2] of its current block
+  __shared__ float part[MULTI ? kMaxTilesMulti : 1][256];  // sums over chunks
 
   // ---- loads that depend on nothing: precisions first, then activations, slice 0 ----
-  const int pl = (dbg & 8) ? ((lane < T) ? 3 : -1) : (lane < T) ? prec[lane] : -1;
+  const int pl = (lane < T) ? prec[lane] : -1;
   const uint16_t* xrow = (m < T) ? (X + (int64_t)m * K) : nullptr;
   uint4 xa[8];
   auto load_x = [&](int kb) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int64_t k = (int64_t)kb * kTileK + 32 * j + 8 * kq;
-      xa[j] = (xrow != nullptr && k < K && !(dbg & 4)) ? *reinterpret_cast<const uint4*>(xrow + k) : uint4{0u, 0u, 0u, 0u};
+      xa[j] = (xrow != nullptr && k < K) ? *reinterpret_cast<const uint4*>(xrow + k) : uint4{0u, 0u, 0u, 0u};
     }
   };
-  auto tile_of = [&](int it) { return (int)blockIdx.x + (it / phases) * (int)gridDim.x; };
-  auto block_of = [&](int it) { return (it % phases) * WAVES + wave; };
-  auto load_slice0 = [&](int nt, int kb, Item& I) {
+  auto load_base = [&](int nt, int kb, Item& I) {
     const size_t tile = ((size_t)nt * KB + kb) * 64 + lane;
     I.w[0] = codes[tile];
     I.mt[0] = meta[((size_t)nt * (2 * KB) + 2 * kb) * kTileN + m];
     I.mt[1] = meta[((size_t)nt * (2 * KB) + 2 * kb + 1) * kTileN + m];
   };
-  int pmax = 0;
-  auto load_rest = [&](int nt, int kb, Item& I) {
-    const size_t tile = ((size_t)nt * KB + kb) * 64 + lane;
-    if (pmax >= 1) I.w[1] = codes[slice_vec + tile];
-    if (pmax >= 2) I.w[2] = codes[2 * slice_vec + tile];
-    if (pmax >= 3) I.w[3] = codes[3 * slice_vec + tile];
-  };
-
   Item cur, nxt;
-  if (n_items > 0 && block_of(0) < KB) {
-    load_x(block_of(0));
-    load_slice0(tile_of(0), block_of(0), cur);
+  if (!MULTI && my_tiles > 0 && wave < KB) {
+    load_x(wave);
+    load_base((int)blockIdx.x, wave, cur);
   }
 
-  // ---- routing facts (first dependent step): highest precision present, per-row constants ----
-  pmax = (__ballot(pl == 3) != 0ull) ? 3 : (__ballot(pl == 2) != 0ull) ? 2 : (__ballot(pl == 1) != 0ull) ? 1 : 0;
-  if (n_items > 0 && block_of(0) < KB) load_rest(tile_of(0), block_of(0), cur);
-
+  // ---- routing facts (the only dependent step): highest precision present, per-row constants ----
+  const int pmax =
+      (__ballot(pl == 3) != 0ull) ? 3 : (__ballot(pl == 2) != 0ull) ? 2 : (__ballot(pl == 1) != 0ull) ? 1 : 0;
   int prow[4];
-  float coefA[4], coefB[4], coefS[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = __shfl(pl, 4 * kq + i, 64);
-    prow[i] = p;
-    // offsets accumulated by snapshot p: sum of the operand biases of slices 0..p
-    coefA[i] = (p >= 3) ? 74.f : (p == 2) ? 72.f : (p == 1) ? 64.f : 32.f;
-    coefB[i] = (p >= 3) ? 18.5f : (p == 2) ? 18.f : (p == 1) ? 16.f : 8.f;
-    // residual zero points: sum_{1 <= e <= p} 4^-e (2 - 0.5), and the base slice's -0.5
-    const float q = (p >= 3) ? 0.328125f : (p == 2) ? 0.3125f : (p == 1) ? 0.25f : 0.f;
-    coefS[i] = 1.5f * q - 0.5f;
-  }
+  for (int i = 0; i < 4; ++i) prow[i] = __shfl(pl, 4 * kq + i, 64);
 
+  uint32_t bias[4] = {kPow5, kPow3, kPow1, kPowM1};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(bias[i]));  // keep them resident in vector registers
   const uint4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
-  floatx4 C1[2], SS[2];  // per group of the current k-block: offset term and sum of x, per output row
-  auto group_sums = [&]() {
+
+  // The body is instantiated per highest precision so that every load count is static: the
+  // hardware wait counters can then let the next tile's loads stay in flight.
+  auto body = [&](auto pm_tag) {
+    constexpr int PM = decltype(pm_tag)::value;
+    auto load_rest = [&](int nt, int kb, Item& I) {
+      const size_t tile = ((size_t)nt * KB + kb) * 64 + lane;
+      if constexpr (PM >= 1) I.w[1] = codes[slice_vec + tile];
+      if constexpr (PM >= 2) I.w[2] = codes[2 * slice_vec + tile];
+      if constexpr (PM >= 3) I.w[3] = codes[3 * slice_vec + tile];
+    };
+    int step_count = 0;
+#pragma unroll 1
+    for (int chunk = 0; chunk < chunks; ++chunk) {
+      const int kb = chunk * WAVES + wave;
+      const bool active = (kb < KB) && my_tiles > 0;
+      if (active) {
+        if (MULTI) {
+          load_x(kb);
+          load_base((int)blockIdx.x, kb, cur);
+        }
+        load_rest((int)blockIdx.x, kb, cur);
+        // group sums of this block's activations, in accumulator layout, and the offset term
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      floatx4 Sa = mfma(xa[4 * h + 0], ones, zero4);
-      Sa = mfma(xa[4 * h + 2], ones, Sa);
-      floatx4 Sb = mfma(xa[4 * h + 1], ones, zero4);
-      Sb = mfma(xa[4 * h + 3], ones, Sb);
+        for (int h = 0; h < 2; ++h) {
+          floatx4 Sa = mfma(xa[4 * h + 0], ones, zero4);
+          Sa = mfma(xa[4 * h + 2], ones, Sa);
+          floatx4 Sb = mfma(xa[4 * h + 1], ones, zero4);
+          Sb = mfma(xa[4 * h + 3], ones, Sb);
+          floatx4 c1, ss;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        SS[h][i] = Sa[i] + Sb[i];
-        C1[h][i] = coefA[i] * Sa[i] + coefB[i] * Sb[i] + coefS[i] * SS[h][i];
+          for (int i = 0; i < 4; ++i) {
+            const int p = prow[i];
+            // offsets accumulated up to slice p: sums of the operand biases of slices 0..p
+            const float coefA = (p >= 3) ? 74.f : (p == 2) ? 72.f : (p == 1) ? 64.f : 32.f;
+            const float coefB = (p >= 3) ? 18.5f : (p == 2) ? 18.f : (p == 1) ? 16.f : 8.f;
+            // residual zero points: sum_{1 <= e <= p} 4^-e (2 - 0.5), and the base slice's -0.5
+            const float q = (p >= 3) ? 0.328125f : (p == 2) ? 0.3125f : (p == 1) ? 0.25f : 0.f;
+            ss[i] = Sa[i] + Sb[i];
+            c1[i] = coefA * Sa[i] + coefB * Sb[i] + (1.5f * q - 0.5f) * ss[i];
+          }
+          cst[wave][h][lane] = c1;
+          cst[wave][2 + h][lane] = ss;
+        }
+      }
+      // one step: fetch tile ti+1 into `n`, consume tile ti from `c`, reduce and store
+      auto step = [&](int ti, Item& c, Item& n) {
+        const int nt = (int)blockIdx.x + ti * (int)gridDim.x;
+        floatx4 acc = zero4;
+        if (active) {
+          const int tn = (int)blockIdx.x + min(ti + 1, my_tiles - 1) * (int)gridDim.x;
+          load_base(tn, kb, n);
+          load_rest(tn, kb, n);
+          // the two groups of the block run as two independent accumulator chains
+          floatx4 D[2], v[2];
+          D[0] = slice_group<0>(&xa[0], bias, c.w[0].x, c.w[0].y, zero4);
+          D[1] = slice_group<0>(&xa[4], bias, c.w[0].z, c.w[0].w, zero4);
+          v[0] = D[0];
+          v[1] = D[1];
+          if constexpr (PM >= 1) {
+            D[0] = slice_group<1>(&xa[0], bias, c.w[1].x, c.w[1].y, D[0]);
+            D[1] = slice_group<1>(&xa[4], bias, c.w[1].z, c.w[1].w, D[1]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 1) ? D[h][i] : v[h][i];
+          }
+          if constexpr (PM >= 2) {
+            D[0] = slice_group<2>(&xa[0], bias, c.w[2].x, c.w[2].y, D[0]);
+            D[1] = slice_group<2>(&xa[4], bias, c.w[2].z, c.w[2].w, D[1]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 2) ? D[h][i] : v[h][i];
+          }
+          if constexpr (PM >= 3) {
+            D[0] = slice_group<3>(&xa[0], bias, c.w[3].x, c.w[3].y, D[0]);
+            D[1] = slice_group<3>(&xa[4], bias, c.w[3].z, c.w[3].w, D[1]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 3) ? D[h][i] : v[h][i];
+          }
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const float s0 = c.mt[h].x, s0z0 = c.mt[h].x * c.mt[h].y;
+            const floatx4 c1 = cst[wave][h][lane];
+            const floatx4 ss = cst[wave][2 + h][lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] += s0 * (v[h][i] - c1[i]) - s0z0 * ss[i];
+          }
+        }
+        // sum the wavefronts' partial tiles; rows leave in original token order
+        const int buf = step_count & 1;
+        ++step_count;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[buf][wave][lane][i] = acc[i];
+        __syncthreads();
+        if (threadIdx.x < 256) {
+          const int r = threadIdx.x >> 4, cc = threadIdx.x & 15;
+          const int64_t col = (int64_t)nt * kTileN + cc;
+          float sum = 0.f;
+#pragma unroll
+          for (int wv = 0; wv < WAVES; ++wv) sum += red[buf][wv][16 * (r >> 2) + cc][r & 3];
+          if (MULTI) {
+            if (chunk > 0) sum += part[ti][threadIdx.x];
+            if (chunk + 1 < chunks) part[ti][threadIdx.x] = sum;
+          }
+          if (chunk + 1 == chunks && r < T && col < N) Y[(int64_t)r * N + col] = sum;
+        }
+      };
+#pragma unroll 1
+      for (int ti = 0; ti < my_tiles; ti += 2) {
+        step(ti, cur, nxt);
+        if (ti + 1 < my_tiles) step(ti + 1, nxt, cur);
       }
     }
   };
-  if (STATIONARY && n_items > 0 && block_of(0) < KB) group_sums();
-
-  __shared__ float red[2][WAVES][64][4];
-  floatx4 acc = zero4;
-  for (int it = 0; it < n_items; ++it) {
-    const int nt = tile_of(it), kb = block_of(it);
-    const bool active = kb < KB;
-    const bool has_next = it + 1 < n_items;
-    const bool next_active = has_next && block_of(it + 1) < KB;
-    if (kPrefetch && next_active) {
-      load_slice0(tile_of(it + 1), block_of(it + 1), nxt);
-      load_rest(tile_of(it + 1), block_of(it + 1), nxt);
-    }
-    if (active && (dbg & 1)) {
-      acc[0] += __uint_as_float((cur.w[0].x ^ cur.w[1].y ^ cur.w[2].z ^ cur.w[3].w) & 0x3FFFFFu) + cur.mt[0].x + cur.mt[1].y;
-    } else if (active) {
-      if (!STATIONARY) {
-        if (it > 0) load_x(kb);
-        group_sums();
-      }
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const uint4* A = &xa[4 * h];
-        const uint32_t l0 = h ? cur.w[0].z : cur.w[0].x, h0 = h ? cur.w[0].w : cur.w[0].y;
-        // all slices chain into one accumulator; a row keeps the value after its last slice
-        floatx4 D = slice_group<0>(A, l0, h0, zero4);
-        floatx4 v = D;
-        if (pmax >= 1) {
-          D = slice_group<1>(A, h ? cur.w[1].z : cur.w[1].x, h ? cur.w[1].w : cur.w[1].y, D);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = (prow[i] >= 1) ? D[i] : v[i];
-        }
-        if (pmax >= 2) {
-          D = slice_group<2>(A, h ? cur.w[2].z : cur.w[2].x, h ? cur.w[2].w : cur.w[2].y, D);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = (prow[i] >= 2) ? D[i] : v[i];
-        }
-        if (pmax >= 3) {
-          D = slice_group<3>(A, h ? cur.w[3].z : cur.w[3].x, h ? cur.w[3].w : cur.w[3].y, D);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = (prow[i] >= 3) ? D[i] : v[i];
-        }
-        const float s0 = cur.mt[h].x, s0z0 = cur.mt[h].x * cur.mt[h].y;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] += s0 * (v[i] - C1[h][i]) - s0z0 * SS[h][i];
-      }
-    }
-    if ((it % phases) == phases - 1 && (!(dbg & 2) || it == n_items - 1)) {
-      // all column blocks of tile nt are done: sum the wavefronts, store rows in token order
-      const int buf = (it / phases) & 1;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) red[buf][wave][lane][i] = acc[i];
-      acc = zero4;
-      __syncthreads();
-      if (threadIdx.x < 256) {
-        const int r = threadIdx.x >> 4, c = threadIdx.x & 15;
-        const int64_t n = (int64_t)nt * kTileN + c;
-        if (r < T && n < N) {
-          float sum = 0.f;
-#pragma unroll
-          for (int wv = 0; wv < WAVES; ++wv) sum += red[buf][wv][16 * (r >> 2) + c][r & 3];
-          Y[(int64_t)r * N + n] = sum;
-        }
-      }
-    }
-    if (next_active) {
-      if (kPrefetch) {
-        cur = nxt;
-      } else {
-        load_slice0(tile_of(it + 1), block_of(it + 1), cur);
-        load_rest(tile_of(it + 1), block_of(it + 1), cur);
-      }
-    }
+  switch (pmax) {
+    case 0: body(std::integral_constant<int, 0>{}); break;
+    case 1: body(std::integral_constant<int, 1>{}); break;
+    case 2: body(std::integral_constant<int, 2>{}); break;
+    default: body(std::integral_constant<int, 3>{}); break;
   }
 }
 
-template <int WAVES, bool STATIONARY>
+template <int WAVES, bool MULTI>
 static void launch_decode16(int grid, hipStream_t stream, const uint16_t* X, int T, const Shape& sh,
                             const uint4* codes, const float2* meta, const int32_t* prec, float* Y) {
-  hipLaunchKernelGGL((decode16_kernel<WAVES, STATIONARY>), dim3(grid), dim3(WAVES * 64), 0, stream, X, T, sh.K,
-                     codes, sh.slice_words / 4, meta, sh.N, sh.NT, sh.KB, prec, Y, knob(4));
+  hipLaunchKernelGGL((decode16_kernel<WAVES, MULTI>), dim3(grid), dim3(WAVES * 64), 0, stream, X, T, sh.K, codes,
+                     sh.slice_words / 4, meta, sh.N, sh.NT, sh.KB, prec, Y);
 }
 
 static int compute_units() {
@@ -275,15 +307,18 @@ mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob
   const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
   int waves = knob(0);
   if (waves != 4 && waves != 8 && waves != 16) waves = (sh.KB <= 4) ? 4 : (sh.KB <= 8 ? 8 : 16);
-  const bool stationary = sh.KB <= waves;
+  const bool multi = sh.KB > waves;
   int per_cu = knob(2);
   if (per_cu <= 0) per_cu = 16 / waves;  // 16 wavefronts per compute unit
   int grid = compute_units() * per_cu;
   if (grid > sh.NT) grid = sh.NT;
-#define MBQ_D16(WV)                                                                        \
-  if (waves == WV) {                                                                       \
-    if (stationary) launch_decode16<WV, true>(grid, stream, X, (int)T, sh, codes, meta, prec, Y);  \
-    else launch_decode16<WV, false>(grid, stream, X, (int)T, sh, codes, meta, prec, Y);    \
+  // with several K chunks the per-tile partial sums live in LDS: bound the tiles per workgroup
+  if (multi && (sh.NT + grid - 1) / grid > d16::kMaxTilesMulti)
+    grid = (sh.NT + d16::kMaxTilesMulti - 1) / d16::kMaxTilesMulti;
+#define MBQ_D16(WV)                                                                          \
+  if (waves == WV) {                                                                         \
+    if (multi) launch_decode16<WV, true>(grid, stream, X, (int)T, sh, codes, meta, prec, Y);  \
+    else launch_decode16<WV, false>(grid, stream, X, (int)T, sh, codes, meta, prec, Y);       \
   }
   MBQ_D16(4) MBQ_D16(8) MBQ_D16(16)
 #undef MBQ_D16
