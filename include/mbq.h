@@ -113,7 +113,10 @@ mbq_status mbq_dequant(const void* blob, int64_t N, int64_t K, int p, float* Wha
  *   X      : bf16 [T][K]           Wr : fp32 [P][K]        br : fp32 [P]
  *   prec   : int32 [T] (out)       perm : int32 [T] (out)  offsets : int32 [P+1] (out)
  *   logits : fp64 [T][P] (out, may be NULL)
- *   ws     : at least mbq_route_workspace_bytes(T, K) bytes, 256-byte aligned
+ *   ws     : at least mbq_route_workspace_bytes(T, K) bytes, 256-byte aligned.  It holds a
+ *            ticket counter: the bytes must be ZERO before the first call that uses this
+ *            workspace; every call leaves them zero again.  Calls sharing one workspace
+ *            must not overlap in time.
  * T = 0 is legal (offsets are zero-filled).
  */
 mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,

@@ -120,7 +120,8 @@ def mbq_dequant(blob: torch.Tensor, N: int, K: int, p: int) -> torch.Tensor:
 
 
 def route_workspace(T: int, K: int, device) -> torch.Tensor:
-    return torch.empty(load().mbq_route_workspace_bytes(T, K), dtype=torch.uint8, device=device)
+    # zero-filled: mbq_route keeps a ticket counter there (see include/mbq.h)
+    return torch.zeros(load().mbq_route_workspace_bytes(T, K), dtype=torch.uint8, device=device)
 
 
 def linear_workspace(T: int, N: int, K: int, device) -> torch.Tensor:

@@ -9,16 +9,81 @@ constexpr int kP = MBQ_N_PRECISIONS;
 __device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 
-// One workgroup of 256 threads scores TPW consecutive tokens.  The K axis is split
-// over the threads in chunks of 8 columns; each thread keeps 4 x TPW fp64 partial
-// sums (bf16 x fp32 products are exact in fp64), which are then reduced over the
-// wavefront with DPP-free shuffles and over the four wavefronts through LDS.
+// Stable counting sort of token ids by precision by ONE workgroup of NW wavefronts
+// (Sec. 4.3, token permutation).  Counting and ranking use wavefront ballots: a lane's rank
+// inside its wavefront is the population count of the ballot below its lane.
+template <int NW>
+__device__ inline void bucket_by_workgroup(const int32_t* prec, int64_t T,
+                                           int32_t* __restrict__ perm, int32_t* __restrict__ offsets) {
+  __shared__ int s_wave[NW][kP];  // per-wavefront counts of the current pass
+  __shared__ int s_run[kP];       // running write position of each precision
+  constexpr int NT = NW * 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+
+  // pass 1: totals
+  int cnt[kP] = {0, 0, 0, 0};
+  for (int64_t base = 0; base < T; base += NT) {
+    const int64_t i = base + tid;
+    const int p = (i < T) ? prec[i] : -1;
+#pragma unroll
+    for (int q = 0; q < kP; ++q) cnt[q] += __popcll(__ballot(p == q));
+  }
+  if (lane == 0)
+#pragma unroll
+    for (int q = 0; q < kP; ++q) s_wave[wave][q] = cnt[q];
+  __syncthreads();
+  if (tid == 0) {
+    int pos = 0;
+    for (int q = 0; q < kP; ++q) {
+      int c = 0;
+      for (int w = 0; w < NW; ++w) c += s_wave[w][q];
+      s_run[q] = pos;
+      offsets[q] = pos;
+      pos += c;
+    }
+    offsets[kP] = pos;
+  }
+  __syncthreads();
+
+  // pass 2: stable placement, NT tokens at a time in token order
+  for (int64_t base = 0; base < T; base += NT) {
+    const int64_t i = base + tid;
+    const int p = (i < T) ? prec[i] : -1;
+    int rank_in_wave = 0;
+#pragma unroll
+    for (int q = 0; q < kP; ++q) {
+      const uint64_t b = __ballot(p == q);
+      if (p == q) rank_in_wave = __popcll(b & below);
+      if (lane == 0) s_wave[wave][q] = __popcll(b);
+    }
+    __syncthreads();
+    if (p >= 0) {
+      int pos = s_run[p] + rank_in_wave;
+      for (int w = 0; w < wave; ++w) pos += s_wave[w][p];
+      perm[pos] = (int32_t)i;
+    }
+    __syncthreads();
+    if (tid < kP) {
+      int c = 0;
+      for (int w = 0; w < NW; ++w) c += s_wave[w][tid];
+      s_run[tid] += c;
+    }
+    __syncthreads();
+  }
+}
+
+// One workgroup of 256 threads scores TPW consecutive tokens (Sec. 4.2 Eq. 4).  The K axis
+// is split over the threads in chunks of 8 columns; each thread keeps 4 x TPW fp64 partial
+// sums (bf16 x fp32 products are exact in fp64), reduced over the wavefront with shuffles and
+// over the four wavefronts through LDS.  The workgroup that finishes last (a ticket counter in
+// the workspace, left at zero again) then buckets all tokens, so routing is one launch.
 template <int TPW>
-__global__ __launch_bounds__(256) void route_logits_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
-                                                           const float* __restrict__ Wr,
-                                                           const float* __restrict__ br,
-                                                           int32_t* __restrict__ prec,
-                                                           double* __restrict__ logits) {
+__global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
+                                                    const float* __restrict__ Wr, const float* __restrict__ br,
+                                                    int32_t* prec, int32_t* __restrict__ perm,
+                                                    int32_t* __restrict__ offsets, double* __restrict__ logits,
+                                                    unsigned int* __restrict__ ticket) {
   const int64_t tok0 = (int64_t)blockIdx.x * TPW;
   const int tid = threadIdx.x;
   double acc[TPW][kP];
@@ -50,6 +115,7 @@ __global__ __launch_bounds__(256) void route_logits_kernel(const uint16_t* __res
     }
   }
   __shared__ double red[4][TPW][kP];
+  __shared__ unsigned int s_ticket;
   const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
   for (int t = 0; t < TPW; ++t)
@@ -74,89 +140,40 @@ __global__ __launch_bounds__(256) void route_logits_kernel(const uint16_t* __res
       }
     }
     prec[tok0 + tid] = arg;
+    __threadfence();  // publish this workgroup's choices before taking a ticket
   }
+  __syncthreads();
+  if (tid == 0) s_ticket = atomicAdd(ticket, 1u);
+  __syncthreads();
+  if (s_ticket != gridDim.x - 1) return;
+  // last workgroup: every token's precision is visible now
+  __threadfence();
+  bucket_by_workgroup<4>(prec, T, perm, offsets);
+  if (tid == 0) *ticket = 0u;  // leave the counter ready for the next call
 }
 
-// Stable counting sort of token ids by precision, one workgroup of 1024 threads.
-// Counting and ranking use wavefront ballots: a lane's rank inside its wavefront is
-// the population count of the ballot below its lane.
-__global__ __launch_bounds__(1024) void bucket_kernel(const int32_t* __restrict__ prec, int64_t T,
-                                                      int32_t* __restrict__ perm,
-                                                      int32_t* __restrict__ offsets) {
-  __shared__ int s_wave[16][kP];   // per-wavefront counts of the current pass
-  __shared__ int s_run[kP];        // running write position of each precision
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-
-  // pass 1: totals
-  int cnt[kP] = {0, 0, 0, 0};
-  for (int64_t base = 0; base < T; base += 1024) {
-    const int64_t i = base + tid;
-    const int p = (i < T) ? prec[i] : -1;
-#pragma unroll
-    for (int q = 0; q < kP; ++q) cnt[q] += __popcll(__ballot(p == q));
-  }
-  if (lane == 0)
-#pragma unroll
-    for (int q = 0; q < kP; ++q) s_wave[wave][q] = cnt[q];
-  __syncthreads();
-  if (tid == 0) {
-    int pos = 0;
-    for (int q = 0; q < kP; ++q) {
-      int c = 0;
-      for (int w = 0; w < 16; ++w) c += s_wave[w][q];
-      s_run[q] = pos;
-      offsets[q] = pos;
-      pos += c;
-    }
-    offsets[kP] = pos;
-  }
-  __syncthreads();
-
-  // pass 2: stable placement, 1024 tokens at a time in token order
-  for (int64_t base = 0; base < T; base += 1024) {
-    const int64_t i = base + tid;
-    const int p = (i < T) ? prec[i] : -1;
-    int rank_in_wave = 0;
-#pragma unroll
-    for (int q = 0; q < kP; ++q) {
-      const uint64_t b = __ballot(p == q);
-      if (p == q) rank_in_wave = __popcll(b & below);
-      if (lane == 0) s_wave[wave][q] = __popcll(b);
-    }
-    __syncthreads();
-    if (p >= 0) {
-      int pos = s_run[p] + rank_in_wave;
-      for (int w = 0; w < wave; ++w) pos += s_wave[w][p];
-      perm[pos] = (int32_t)i;
-    }
-    __syncthreads();
-    if (tid < kP) {
-      int c = 0;
-      for (int w = 0; w < 16; ++w) c += s_wave[w][tid];
-      s_run[tid] += c;
-    }
-    __syncthreads();
-  }
+// T = 0: only the (all-zero) offsets have to be written.
+__global__ __launch_bounds__(64) void bucket_kernel(const int32_t* __restrict__ prec, int64_t T,
+                                                    int32_t* __restrict__ perm, int32_t* __restrict__ offsets) {
+  bucket_by_workgroup<1>(prec, T, perm, offsets);
 }
 
 mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
                         int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
                         hipStream_t stream) {
-  (void)ws;
-  if (T > 0) {
-    if (T <= 64) {
-      hipLaunchKernelGGL(route_logits_kernel<1>, dim3((unsigned)T), dim3(256), 0, stream, X, T, K, Wr, br, prec,
-                         logits);
-    } else {
-      hipLaunchKernelGGL(route_logits_kernel<4>, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, stream, X, T, K,
-                         Wr, br, prec, logits);
-    }
-    mbq_status st = hip_status(hipGetLastError(), "route_logits_kernel launch");
-    if (st != MBQ_OK) return st;
+  unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
+  if (T == 0) {
+    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(64), 0, stream, prec, T, perm, offsets);
+    return hip_status(hipGetLastError(), "bucket_kernel launch");
   }
-  hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(1024), 0, stream, prec, T, perm, offsets);
-  return hip_status(hipGetLastError(), "bucket_kernel launch");
+  if (T <= 256) {
+    hipLaunchKernelGGL(route_kernel<1>, dim3((unsigned)T), dim3(256), 0, stream, X, T, K, Wr, br, prec, perm,
+                       offsets, logits, ticket);
+  } else {
+    hipLaunchKernelGGL(route_kernel<4>, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, stream, X, T, K, Wr, br,
+                       prec, perm, offsets, logits, ticket);
+  }
+  return hip_status(hipGetLastError(), "route_kernel launch");
 }
 
 }  // namespace mbq
