@@ -181,7 +181,7 @@ def main() -> int:
         "hbm_gbps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "event_ms_per_step": ev_ms_per_step,
         "roofline": {
-            "bound": "hbm", "kernel": "mbq::decode_kernel (mbq_linear, T <= 16)",
+            "bound": "hbm", "kernel": "mbq::decode16_kernel / mbq::decode_kernel (mbq_linear, one token tile)",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
             "traffic": None,
             "avg_launch_us": avg_launch_us, "avg_launch_bytes": avg_launch_bytes,
@@ -191,11 +191,97 @@ def main() -> int:
         },
     }
 
+    if not args.no_extra:
+        out["extra"] = extra_measurements(mbq, torch, dev, cfg, layers, T)
+
     # ------------------------------------------------------------------ CPU baseline
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layers, T)
     print(json.dumps(out))
     return 0
+
+
+def extra_measurements(mbq, torch, dev, cfg, layers, T_main):
+    """Side figures, each timed with HIP events over eager back-to-back launches:
+    the same block at the other decode batches of the config, and one prefill linear
+    (BASELINE configs[2], gate projection, 2048 tokens) as TFLOP/s."""
+    from workloads import CONFIGS, make_case
+
+    extra = {}
+    for T in cfg.token_counts:
+        if T == T_main:
+            continue
+        bufs = []
+        for li, l in enumerate(layers):
+            case = make_case(cfg, li, T, with_weight=False)
+            spec = l["spec"]
+            bufs.append(dict(
+                X=torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev),
+                prec=torch.empty(T, dtype=torch.int32, device=dev), perm=torch.empty(T, dtype=torch.int32, device=dev),
+                offsets=torch.empty(5, dtype=torch.int32, device=dev),
+                Y=torch.empty((T, spec.N), dtype=torch.float32, device=dev)))
+
+        def one(slot):
+            for l, b in zip(layers, bufs):
+                mbq.mbq_route(b["X"], l["Wr"], l["br"], out=(b["prec"], b["perm"], b["offsets"]), ws=l["ws_r"])
+                mbq.mbq_linear(b["X"], l["blobs"][slot], l["spec"].N, l["spec"].K, b["prec"], b["perm"],
+                               b["offsets"], Y=b["Y"], ws=l["ws_l"])
+
+        one(0)
+        torch.cuda.synchronize()
+        graphs = []
+        try:
+            for slot in range(RING):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    one(slot)
+                graphs.append(g)
+        except Exception:
+            graphs = []
+        n = 60
+        for i in range(6):
+            graphs[i % RING].replay() if graphs else one(i % RING)
+        a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n):
+            graphs[i % RING].replay() if graphs else one(i % RING)
+        b2.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b2) / n
+        byts = 0
+        for l, b in zip(layers, bufs):
+            pmax = int(b["prec"].max().item())
+            byts += algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax) + 16 * l["spec"].K
+        extra[f"decode_batch_{T}"] = {"ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
+                                      "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9}
+    # one prefill linear
+    pcfg = CONFIGS[2]
+    T = pcfg.token_counts[0]
+    case = make_case(pcfg, 0, T)
+    spec = pcfg.linears[0]
+    Wd = torch.from_numpy(case["W"]).to(dev)
+    blob = mbq.mbq_encode(Wd)
+    del Wd
+    X = torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev)
+    Wr, br = torch.from_numpy(case["Wr"]).to(dev), torch.from_numpy(case["br"]).to(dev)
+    prec, perm, offsets = mbq.mbq_route(X, Wr, br)
+    Y = torch.empty((T, spec.N), dtype=torch.float32, device=dev)
+    ws = mbq.linear_workspace(T, spec.N, spec.K, dev)
+    for _ in range(2):
+        mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
+    a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = 10
+    a.record()
+    for _ in range(n):
+        mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
+    b2.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b2) / n
+    tf = 2.0 * T * spec.N * spec.K / (ms * 1e-3) / 1e12
+    extra["prefill_gate_2048tok"] = {"workload": "BASELINE configs[2] gate 11008x4096, 2048 tokens, {50,30,15,5}% mix + 2% outlier tokens",
+                                     "ms": ms, "tflops": tf, "mfma_bf16_peak_tflops": 2500.0, "frac": tf / 2500.0,
+                                     "mix": np.bincount(prec.cpu().numpy(), minlength=4).tolist()}
+    return extra
 
 
 def cpu_baseline(cfg, layers, T):
