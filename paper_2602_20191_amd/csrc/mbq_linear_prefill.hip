@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void prefill_sx_kernel(const uint16_t* __restr
   if (item < T * G && sub == 0) Sx[item] = s;
 }
 
-__global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
+__global__ __launch_bounds__(256, 2) void prefill_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
                                                       const uint2* __restrict__ codes, size_t slice_vec2,
                                                       const float2* __restrict__ meta, int64_t N, int KB,
                                                       const int32_t* __restrict__ perm,
@@ -119,12 +119,15 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
   // ---- global -> register staging ----
   // A: thread loads rows (tid/16) + 16 i, columns 8 (tid%16) .. +7
   const int a_col = 8 * (tid & 15);
-  const uint16_t* a_src[8];
+  // row offsets in units of 8 bf16 (16 bytes); ~0u marks a padding row
+  uint32_t a_src[8];
+  const uint32_t k8 = (uint32_t)(K >> 3);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int r = (tid >> 4) + 16 * i;
-    a_src[i] = (r < rows) ? (X + (int64_t)perm[row0 + r] * K + a_col) : nullptr;
+    a_src[i] = (r < rows) ? ((uint32_t)perm[row0 + r] * k8 + (uint32_t)(tid & 15)) : ~0u;
   }
+  const uint4* X4 = reinterpret_cast<const uint4*>(X);
   // B: thread handles code tiles ntile0 + wave + 4 i (i = 0, 1), lane `lane`
   uint4 a_reg[8];
   uint2 b_reg[2][4];
@@ -132,7 +135,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
   auto load_step = [&](int g) {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      a_reg[i] = a_src[i] ? *reinterpret_cast<const uint4*>(a_src[i] + (int64_t)g * kGroup) : uint4{0u, 0u, 0u, 0u};
+      a_reg[i] = (a_src[i] != ~0u) ? X4[(size_t)a_src[i] + (size_t)g * (kGroup / 8)] : uint4{0u, 0u, 0u, 0u};
     const int kb = g >> 1, h = g & 1;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -184,35 +187,30 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     __syncthreads();
     if (g + 1 < G) load_step(g + 1);
 
-    // ---- 128 x 128 x 128 on the matrix cores: each wavefront 64 x 64 ----
-    floatx16 part[2][2];
+    // ---- 128 x 128 x 128 on the matrix cores: each wavefront 64 x 64, one 32-column half at
+    // a time so that only two fresh 32 x 32 accumulators are live ----
+    const float half_step = 0.5f * (float)(1 << (2 * (3 - p)));
 #pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      uint4 af[2], bf[2];
+    for (int b = 0; b < 2; ++b) {
+      floatx16 part[2];
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
-        af[a] = *reinterpret_cast<const uint4*>(&sA[64 * wm + 32 * a + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
+      for (int kk = 0; kk < kBK / 16; ++kk) {
+        const uint4 bf = *reinterpret_cast<const uint4*>(&sB[64 * wn + 32 * b + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-        bf[b] = *reinterpret_cast<const uint4*>(&sB[64 * wn + 32 * b + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
+        for (int a = 0; a < 2; ++a) {
+          const uint4 af =
+              *reinterpret_cast<const uint4*>(&sA[64 * wm + 32 * a + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
           if (kk == 0) {
             floatx16 z;
 #pragma unroll
             for (int i = 0; i < 16; ++i) z[i] = 0.f;
-            part[a][b] = mfma32(af[a], bf[b], z);
+            part[a] = mfma32(af, bf, z);
           } else {
-            part[a][b] = mfma32(af[a], bf[b], part[a][b]);
+            part[a] = mfma32(af, bf, part[a]);
           }
         }
-    }
-    // ---- group epilogue: scale and zero point in fp32 ----
-    const float half_step = 0.5f * (float)(1 << (2 * (3 - p)));
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
+      }
+      // group epilogue: scale and zero point in fp32
       const int64_t n = (int64_t)blockIdx.x * kBN + 64 * wn + 32 * b + (lane & 31);
       float s3 = 0.f, c = 0.f;
       if (n < (int64_t)NT * kTileN) {
@@ -225,7 +223,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int r = 64 * wm + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-          acc[a][b][i] += s3 * (part[a][b][i] + c * sSx[r]);
+          acc[a][b][i] += s3 * (part[a][i] + c * sSx[r]);
         }
     }
     __syncthreads();
