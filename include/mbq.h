@@ -143,6 +143,7 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
  *   knob 0: waves per workgroup of the decode kernel (4, 8 or 16)
  *   knob 1: K-split (workgroups along K) of the multi-tile decode kernel, 0 = automatic
  *   knob 2: workgroups per compute unit of the single-tile decode kernel, 0 = automatic
+ *   knob 5: prefill tile rows / 64 (2 or 4), 0 = automatic
  *   knob 3: T <= 16 kernel choice: 0 automatic, 1 multi-tile kernel, 2 single-tile kernel
  */
 mbq_status mbq_set_knob(int knob, int value);

@@ -166,7 +166,7 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
               mbq_linear_workspace_bytes(T, N, K));
     return MBQ_ERR_WORKSPACE;
   }
-  if (algo == MBQ_ALGO_AUTO) algo = (T <= 16) ? MBQ_ALGO_DECODE : MBQ_ALGO_PREFILL;
+  if (algo == MBQ_ALGO_AUTO) algo = (T <= kMaxDecodeTokens) ? MBQ_ALGO_DECODE : MBQ_ALGO_PREFILL;
   if (algo == MBQ_ALGO_DECODE && T > kMaxDecodeTokens) {
     set_error("mbq_linear: the decode kernel handles at most %d tokens (T=%lld)", kMaxDecodeTokens,
               (long long)T);

@@ -13,6 +13,8 @@
 // K step = one group of 128.  Codes are merged with a rotate + and-or per slice (the
 // blob stores slice e rotated so that the four fields of one weight line up as one
 // byte), converted with v_cvt_f32_ubyte and written to LDS as bf16.
+#include <type_traits>
+
 #include "mbq_common.h"
 
 namespace mbq {
@@ -20,8 +22,7 @@ namespace mbq {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128, kBN = 128, kBK = 128;
-constexpr int kLdsStride = kBK + 8;  // bf16 elements per LDS row (272 bytes): conflict-free 128-bit rows
+constexpr int kBN = 128, kBK = 128;
 
 __device__ inline floatx16 mfma32(const uint4& a, const uint4& b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
@@ -79,25 +80,39 @@ __global__ __launch_bounds__(256) void prefill_sx_kernel(const uint16_t* __restr
   if (item < T * G && sub == 0) Sx[item] = s;
 }
 
-__global__ __launch_bounds__(256, 2) void prefill_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
-                                                      const uint2* __restrict__ codes, size_t slice_vec2,
-                                                      const float2* __restrict__ meta, int64_t N, int KB,
-                                                      const int32_t* __restrict__ perm,
-                                                      const int32_t* __restrict__ offsets,
-                                                      const float* __restrict__ Sx, float* __restrict__ Y) {
-  // ---- which (precision bucket, 128-row tile) is this workgroup's ----
+// WM = wavefront rows of the workgroup: tile = (64 WM) tokens x 128 outputs, 128 WM threads,
+// each wavefront a 64 x 64 sub-tile.  WM = 2: 128-token tiles, two workgroups per compute unit;
+// WM = 4: 256-token tiles (the unpacked weight tile feeds twice as many tokens), one workgroup
+// of eight wavefronts per compute unit.
+//
+// The K loop advances in half groups of 64 columns through two LDS buffers: while the matrix
+// cores consume half-step h from one buffer, the same wavefronts unpack half-step h+1 into the
+// other and the global loads of half-step h+2 are in flight; one barrier per half-step.
+constexpr int kHalfK = 64;
+constexpr int kHalfStride = kHalfK + 8;  // bf16 per LDS row (144 bytes): conflict-free 128-bit row reads
+
+template <int WM>
+__global__ __launch_bounds__(WM * 128, WM == 2 ? 2 : 1) void prefill_kernel(
+    const uint16_t* __restrict__ X, int64_t T, int64_t K, const uint32_t* __restrict__ codes, size_t slice_words,
+    const float2* __restrict__ meta, int64_t N, int KB, const int32_t* __restrict__ perm,
+    const int32_t* __restrict__ offsets, const float* __restrict__ Sx, float* __restrict__ Y) {
+  constexpr int BM = 64 * WM;
+  constexpr int THREADS = 128 * WM;
+  constexpr int A_ITERS = BM * 8 / THREADS;  // 128-bit loads of a half-step of the A tile per thread (= 4)
+  constexpr int B_ITERS = 512 / THREADS;     // (code tile, lane) dwords of a half-step of the B tile per thread
+  // ---- which (precision bucket, BM-row tile) is this workgroup's ----
   int ty = blockIdx.y, p = -1, row0 = 0, rows = 0;
   {
     int lo = offsets[0];
 #pragma unroll
     for (int q = 0; q < MBQ_N_PRECISIONS; ++q) {
       const int hi = offsets[q + 1];
-      const int tiles = (hi - lo + kBM - 1) / kBM;
+      const int tiles = (hi - lo + BM - 1) / BM;
       if (p < 0) {
         if (ty < tiles) {
           p = q;
-          row0 = lo + ty * kBM;
-          rows = min(kBM, hi - row0);
+          row0 = lo + ty * BM;
+          rows = min(BM, hi - row0);
         } else {
           ty -= tiles;
         }
@@ -107,126 +122,152 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const uint16_t* __restr
   }
   if (p < 0) return;
   const int G = (int)(K / kGroup);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int H = 2 * G;  // half-steps
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
+  const bool wave_has_rows = 64 * wm < rows;       // a wavefront whose 64 rows are all padding skips the MFMAs
   const int ntile0 = blockIdx.x * (kBN / kTileN);  // first 16-row code tile of this workgroup
   const int NT = (int)((N + kTileN - 1) / kTileN);
 
-  __shared__ __attribute__((aligned(16))) uint16_t sA[kBM][kLdsStride];
-  __shared__ __attribute__((aligned(16))) uint16_t sB[kBN][kLdsStride];
-  __shared__ __attribute__((aligned(16))) float sSx[kBM];
+  __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM][kHalfStride];
+  __shared__ __attribute__((aligned(16))) uint16_t sB[2][kBN][kHalfStride];
+  __shared__ __attribute__((aligned(16))) float sSx[2][BM];
 
-  // ---- global -> register staging ----
-  // A: thread loads rows (tid/16) + 16 i, columns 8 (tid%16) .. +7
-  const int a_col = 8 * (tid & 15);
-  // row offsets in units of 8 bf16 (16 bytes); ~0u marks a padding row
-  uint32_t a_src[8];
+  // ---- global -> register staging of one half-step ----
+  // A: thread loads rows (tid/8) + (THREADS/8) i, columns 8 (tid%8) .. +7 of the 64-column half
+  const int a_col = 8 * (tid & 7);
+  uint32_t a_src[A_ITERS];  // row offsets in units of 8 bf16 (16 bytes); ~0u marks a padding row
   const uint32_t k8 = (uint32_t)(K >> 3);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = (tid >> 4) + 16 * i;
-    a_src[i] = (r < rows) ? ((uint32_t)perm[row0 + r] * k8 + (uint32_t)(tid & 15)) : ~0u;
+  for (int i = 0; i < A_ITERS; ++i) {
+    const int r = (tid >> 3) + (THREADS / 8) * i;
+    a_src[i] = (r < rows) ? ((uint32_t)perm[row0 + r] * k8 + (uint32_t)(tid & 7)) : ~0u;
   }
   const uint4* X4 = reinterpret_cast<const uint4*>(X);
-  // B: thread handles code tiles ntile0 + wave + 4 i (i = 0, 1), lane `lane`
-  uint4 a_reg[8];
-  uint2 b_reg[2][4];
+  uint4 a_reg[A_ITERS];
+  uint32_t b_reg[B_ITERS][4];
   float sx_reg = 0.f;
-  auto load_step = [&](int g) {
+  auto load_half = [&](int h) {
+    const int g = h >> 1, dd = h & 1;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      a_reg[i] = (a_src[i] != ~0u) ? X4[(size_t)a_src[i] + (size_t)g * (kGroup / 8)] : uint4{0u, 0u, 0u, 0u};
-    const int kb = g >> 1, h = g & 1;
+    for (int i = 0; i < A_ITERS; ++i)
+      a_reg[i] = (a_src[i] != ~0u) ? X4[(size_t)a_src[i] + (size_t)h * (kHalfK / 8)] : uint4{0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int nt = ntile0 + wave + 4 * i;
-      const size_t v = (((size_t)nt * KB + kb) * 64 + lane) * 2 + h;
+    for (int i = 0; i < B_ITERS; ++i) {
+      const int nt = ntile0 + wave + 2 * WM * i;
+      const size_t v = (((size_t)nt * KB + (g >> 1)) * 64 + lane) * 4 + 2 * (g & 1) + dd;
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        b_reg[i][e] = (nt < NT && e <= p) ? codes[e * slice_vec2 + v] : uint2{0u, 0u};
+      for (int e = 0; e < 4; ++e) b_reg[i][e] = (nt < NT && e <= p) ? codes[e * slice_words + v] : 0u;
     }
-    if (tid < kBM) sx_reg = (tid < rows) ? Sx[(int64_t)(row0 + tid) * G + g] : 0.f;
+    if (dd == 0 && tid < BM) sx_reg = (tid < rows) ? Sx[(int64_t)(row0 + tid) * G + g] : 0.f;
+  };
+  // registers -> LDS buffer h & 1 (A as is, B merged and converted to exact bf16 integers)
+  auto store_half = [&](int h) {
+    const int buf = h & 1;
+#pragma unroll
+    for (int i = 0; i < A_ITERS; ++i)
+      *reinterpret_cast<uint4*>(&sA[buf][(tid >> 3) + (THREADS / 8) * i][a_col]) = a_reg[i];
+#pragma unroll
+    for (int i = 0; i < B_ITERS; ++i) {
+      const int nl = 16 * (wave + 2 * WM * i) + (lane & 15);
+      const int kq = lane >> 4;
+      uint32_t mg[4];
+      merge_dword(b_reg[i], p, mg);
+#pragma unroll
+      for (int step = 0; step < 2; ++step) {
+        uint4 v;
+        v.x = bf16_pair_from_bytes<0>(mg[step]);
+        v.y = bf16_pair_from_bytes<0>(mg[step + 2]);
+        v.z = bf16_pair_from_bytes<1>(mg[step]);
+        v.w = bf16_pair_from_bytes<1>(mg[step + 2]);
+        *reinterpret_cast<uint4*>(&sB[buf][nl][32 * step + 8 * kq]) = v;
+      }
+    }
+    if ((h & 1) == 0 && tid < BM) sSx[(h >> 1) & 1][tid] = sx_reg;
   };
 
-  floatx16 acc[2][2];
+  floatx16 acc[2][2], part[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+  const float half_step = 0.5f * (float)(1 << (2 * (3 - p)));
 
-  load_step(0);
-  for (int g = 0; g < G; ++g) {
-    // ---- registers -> LDS (A as is, B merged and converted to bf16) ----
+  // one half-step: stage h+1, fetch h+2, multiply h; the first half of a group starts fresh
+  // partial accumulators (zero C operand), the second half ends with the group epilogue
+  auto half = [&](int h, auto first_tag, auto rows_tag) {
+    constexpr bool kFirst = decltype(first_tag)::value;
+    constexpr bool kHasRows = decltype(rows_tag)::value;
+    if (h + 1 < H) store_half(h + 1);
+    if (h + 2 < H) load_half(h + 2);
+    if (kHasRows) {
+      const int buf = h & 1;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<uint4*>(&sA[(tid >> 4) + 16 * i][a_col]) = a_reg[i];
+      for (int kk = 0; kk < kHalfK / 16; ++kk) {
+        uint4 af[2], bf[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int nl = 16 * (wave + 4 * i) + (lane & 15);
-      const int kq = lane >> 4;
+        for (int a = 0; a < 2; ++a)
+          af[a] = *reinterpret_cast<const uint4*>(&sA[buf][64 * wm + 32 * a + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
 #pragma unroll
-      for (int dd = 0; dd < 2; ++dd) {
-        const uint32_t w[4] = {dd ? b_reg[i][0].y : b_reg[i][0].x, dd ? b_reg[i][1].y : b_reg[i][1].x,
-                               dd ? b_reg[i][2].y : b_reg[i][2].x, dd ? b_reg[i][3].y : b_reg[i][3].x};
-        uint32_t mg[4];
-        merge_dword(w, p, mg);
+        for (int b = 0; b < 2; ++b)
+          bf[b] = *reinterpret_cast<const uint4*>(&sB[buf][64 * wn + 32 * b + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
 #pragma unroll
-        for (int step = 0; step < 2; ++step) {
-          uint4 v;
-          v.x = bf16_pair_from_bytes<0>(mg[step]);
-          v.y = bf16_pair_from_bytes<0>(mg[step + 2]);
-          v.z = bf16_pair_from_bytes<1>(mg[step]);
-          v.w = bf16_pair_from_bytes<1>(mg[step + 2]);
-          *reinterpret_cast<uint4*>(&sB[nl][64 * dd + 32 * step + 8 * kq]) = v;
-        }
-      }
-    }
-    if (tid < kBM) sSx[tid] = sx_reg;
-    __syncthreads();
-    if (g + 1 < G) load_step(g + 1);
-
-    // ---- 128 x 128 x 128 on the matrix cores: each wavefront 64 x 64, one 32-column half at
-    // a time so that only two fresh 32 x 32 accumulators are live ----
-    const float half_step = 0.5f * (float)(1 << (2 * (3 - p)));
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      floatx16 part[2];
+          for (int b = 0; b < 2; ++b) {
+            if (kFirst && kk == 0) {
+              floatx16 z;
 #pragma unroll
-      for (int kk = 0; kk < kBK / 16; ++kk) {
-        const uint4 bf = *reinterpret_cast<const uint4*>(&sB[64 * wn + 32 * b + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-          const uint4 af =
-              *reinterpret_cast<const uint4*>(&sA[64 * wm + 32 * a + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
-          if (kk == 0) {
-            floatx16 z;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) z[i] = 0.f;
-            part[a] = mfma32(af, bf, z);
-          } else {
-            part[a] = mfma32(af, bf, part[a]);
+              for (int i = 0; i < 16; ++i) z[i] = 0.f;
+              part[a][b] = mfma32(af[a], bf[b], z);
+            } else {
+              part[a][b] = mfma32(af[a], bf[b], part[a][b]);
+            }
           }
+      }
+      if (!kFirst) {
+        // group finished: scale and zero point in fp32
+        const int g = h >> 1;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int64_t n = (int64_t)blockIdx.x * kBN + 64 * wn + 32 * b + (lane & 31);
+          float s3 = 0.f, c = 0.f;
+          if (n < (int64_t)NT * kTileN) {
+            const float2 mt = meta[((size_t)(n >> 4) * (2 * KB) + g) * kTileN + (n & 15)];
+            s3 = mt.x * (1.f / 64.f);
+            c = half_step - 64.f * mt.y;
+          }
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int r = 64 * wm + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+              acc[a][b][i] += s3 * (part[a][b][i] + c * sSx[g & 1][r]);
+            }
         }
       }
-      // group epilogue: scale and zero point in fp32
-      const int64_t n = (int64_t)blockIdx.x * kBN + 64 * wn + 32 * b + (lane & 31);
-      float s3 = 0.f, c = 0.f;
-      if (n < (int64_t)NT * kTileN) {
-        const float2 mt = meta[((size_t)(n >> 4) * (2 * KB) + g) * kTileN + (n & 15)];
-        s3 = mt.x * (1.f / 64.f);
-        c = half_step - 64.f * mt.y;
-      }
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = 64 * wm + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-          acc[a][b][i] += s3 * (part[a][i] + c * sSx[r]);
-        }
     }
     __syncthreads();
+  };
+
+  load_half(0);
+  store_half(0);
+  load_half(1);
+  __syncthreads();
+  // the row test is hoisted out of the K loop: a wavefront of padding rows only stages data
+  if (wave_has_rows) {
+    for (int g = 0; g < G; ++g) {
+      half(2 * g, std::true_type{}, std::true_type{});
+      half(2 * g + 1, std::false_type{}, std::true_type{});
+    }
+  } else {
+    for (int g = 0; g < G; ++g) {
+      half(2 * g, std::true_type{}, std::false_type{});
+      half(2 * g + 1, std::false_type{}, std::false_type{});
+    }
   }
 
   // ---- write the tile in original token order ----
@@ -251,7 +292,7 @@ size_t prefill_workspace_bytes(int64_t T, const Shape& sh) { return (size_t)T * 
 mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                  const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
                                  hipStream_t stream) {
-  const uint2* codes = reinterpret_cast<const uint2*>(blob);
+  const uint32_t* codes = reinterpret_cast<const uint32_t*>(blob);
   const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
   float* Sx = reinterpret_cast<float*>(ws);
   const int64_t items = T * sh.G * 16;
@@ -259,9 +300,17 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
                      perm, Sx);
   mbq_status st = hip_status(hipGetLastError(), "prefill_sx_kernel launch");
   if (st != MBQ_OK) return st;
-  dim3 grid((unsigned)((sh.N + kBN - 1) / kBN), (unsigned)(T / kBM + MBQ_N_PRECISIONS));
-  hipLaunchKernelGGL(prefill_kernel, grid, dim3(256), 0, stream, X, T, sh.K, codes, sh.slice_words / 2, meta,
-                     sh.N, sh.KB, perm, offsets, Sx, Y);
+  // 256-token tiles halve the unpack work per token once buckets are large enough to fill them
+  int wm = knob(5);
+  if (wm != 2 && wm != 4) wm = (T >= 1024) ? 4 : 2;
+  const int bm = 64 * wm;
+  dim3 grid((unsigned)((sh.N + kBN - 1) / kBN), (unsigned)(T / bm + MBQ_N_PRECISIONS));
+  if (wm == 4)
+    hipLaunchKernelGGL(prefill_kernel<4>, grid, dim3(512), 0, stream, X, T, sh.K, codes, sh.slice_words, meta,
+                       sh.N, sh.KB, perm, offsets, Sx, Y);
+  else
+    hipLaunchKernelGGL(prefill_kernel<2>, grid, dim3(256), 0, stream, X, T, sh.K, codes, sh.slice_words, meta,
+                       sh.N, sh.KB, perm, offsets, Sx, Y);
   return hip_status(hipGetLastError(), "prefill_kernel launch");
 }
 
