@@ -27,6 +27,10 @@ import numpy as np
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 RING = 3                        # distinct packed copies of the block rotated across steps
+# HBM bytes per mbq_linear launch at batch 16 (mean over the seven linears) from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of `bench.py --probe`, scaled by what the same counters read for a plain 256 MiB copy
+# (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/decode_linear_hbm_traffic_llama2_7b_batch16.txt
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 32.64e6}
 
 
 def algorithmic_bytes(N, K, T, pmax):
@@ -44,6 +48,9 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the batch-1/4 and prefill side measurements")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter probe for rocprofv3 --pmc: a plain 256 MiB device copy (known size, calibrates the "
+                         "counters) followed by a few mbq_linear launches per linear; prints nothing to time")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -82,6 +89,25 @@ def main() -> int:
         layers.append(layer)
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s "
           f"({sum(l['blobs'][0].numel() for l in layers) * RING / 1e6:.0f} MB of packed weights)", file=sys.stderr)
+
+    if args.probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)          # plain copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        for l in layers:
+            mbq.mbq_route(l["X"], l["Wr"], l["br"], out=(l["prec"], l["perm"], l["offsets"]), ws=l["ws_r"])
+            for i in range(RING):
+                mbq.mbq_linear(l["X"], l["blobs"][i], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
+                               l["offsets"], Y=l["Y"], ws=l["ws_l"])
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "done", "copy_bytes": 256 << 20,
+                          "linears": [[l["spec"].name, l["spec"].N, l["spec"].K, int(l["prec"].max().item())]
+                                      for l in layers]}))
+        return 0
 
     def step(ring_slot: int) -> None:
         for l in layers:
@@ -183,7 +209,7 @@ def main() -> int:
         "roofline": {
             "bound": "hbm", "kernel": "mbq::decode16_kernel / mbq::decode_kernel (mbq_linear, one token tile)",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(T),
             "avg_launch_us": avg_launch_us, "avg_launch_bytes": avg_launch_bytes,
             "per_linear_us": {l["spec"].name: round(u, 2) for l, u in zip(layers, kernel_us)},
             "per_linear_gbps": {l["spec"].name: round(bts / (u * 1e-6) / 1e9, 1)
