@@ -180,8 +180,9 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
       // One token tile: the register-stationary kernel wins when the row fits one chunk of
       // column blocks or a workgroup walks over several row tiles; short, wide matrices
       // (few tiles per compute unit, many chunks) keep every column block in flight instead.
-      if (T <= 16 && knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 1024))
-        return launch_linear_decode16(X, T, blob, sh, prec, Y, s);
+      // Several token tiles (17..64 tokens) run as one pass of that kernel per 16 sorted tokens.
+      if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 1024))
+        return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
       return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
     default:
       return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s);

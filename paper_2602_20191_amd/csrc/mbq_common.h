@@ -70,7 +70,7 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
                                  const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
                                  hipStream_t stream);
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
-                                  const int32_t* prec, float* Y, hipStream_t stream);
+                                  const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
 size_t decode_workspace_bytes(int64_t T, const Shape& sh);
 size_t prefill_workspace_bytes(int64_t T, const Shape& sh);
 

@@ -47,13 +47,24 @@ __device__ inline uint32_t rotr(uint32_t w) {
 // bf16 pairs of 2^5, 2^3, 2^1, 2^-1
 constexpr uint32_t kPow5 = 0x42004200u, kPow3 = 0x41004100u, kPow1 = 0x40004000u, kPowM1 = 0x3F003F00u;
 
-// (t & mask) | bias in one VALU op.  The compiler splits this into v_and + v_or when the
-// operands are literals (a VOP3 instruction cannot carry a literal on gfx9), so the mask is
-// pinned to a scalar register and the bias to a vector register.
-__device__ inline uint32_t and_or(uint32_t t, uint32_t mask, uint32_t bias) {
-  uint32_t d;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(t), "s"(mask), "v"(bias));
-  return d;
+// Unpack constants kept in registers.  (t & mask) | bias is one v_and_or_b32 only when neither
+// operand is a literal (a VOP3 instruction cannot carry one on gfx9), so the three field masks live
+// in scalar registers and the four bf16-pair biases 2^5, 2^3, 2^1, 2^-1 in vector registers; both are
+// made opaque to constant folding once, at kernel entry.
+struct UnpackConsts {
+  uint32_t mask[3];  // 0x00030003 << 0, 2, 4
+  uint32_t bias[4];
+};
+
+__device__ inline UnpackConsts make_unpack_consts() {
+  UnpackConsts c;
+  c.mask[0] = 0x00030003u; c.mask[1] = 0x000C000Cu; c.mask[2] = 0x00300030u;
+  c.bias[0] = kPow5; c.bias[1] = kPow3; c.bias[2] = kPow1; c.bias[3] = kPowM1;
+#pragma unroll
+  for (int i = 0; i < 3; ++i) asm volatile("" : "+s"(c.mask[i]));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(c.bias[i]));
+  return c;
 }
 
 // B operands (a-step, b-step) of the two k-steps held by one dword of slice E.
@@ -62,34 +73,33 @@ __device__ inline uint32_t and_or(uint32_t t, uint32_t mask, uint32_t bias) {
 // for j = 0); its bias exponents are lowered accordingly.  Operand values:
 //   slice 0: 32 + c, 8 + c          slice 1: 32 + c/4, 8 + c/4
 //   slice 2: 8 + c/16, 2 + c/16     slice 3: 2 + c/64, 0.5 + c/64
-// `bias` holds the four bf16-pair constants 2^5, 2^3, 2^1, 2^-1 in vector registers.
 template <int E>
-__device__ inline void unpack_dword(uint32_t w, const uint32_t bias[4], uint4& Ba, uint4& Bb) {
+__device__ inline void unpack_dword(uint32_t w, const UnpackConsts& uc, uint4& Ba, uint4& Bb) {
   constexpr int rho = (2 - 2 * E) & 31;
   constexpr int a0 = (E == 0) ? 2 : 0;
-  constexpr uint32_t ma = 0x00030003u << a0;
-  constexpr uint32_t mb = 0x000C000Cu << a0;
-  const uint32_t ba = bias[(E <= 1) ? 0 : (E == 2 ? 1 : 2)];
-  const uint32_t bb = bias[(E <= 1) ? 1 : (E == 2 ? 2 : 3)];
+  const uint32_t ma = uc.mask[(E == 0) ? 1 : 0];
+  const uint32_t mb = uc.mask[(E == 0) ? 2 : 1];
+  const uint32_t ba = uc.bias[(E <= 1) ? 0 : (E == 2 ? 1 : 2)];
+  const uint32_t bb = uc.bias[(E <= 1) ? 1 : (E == 2 ? 2 : 3)];
   const uint32_t t0 = rotr<(0 + rho - a0) & 31>(w);
   const uint32_t t1 = rotr<(4 + rho - a0) & 31>(w);
   const uint32_t t2 = rotr<(8 + rho - a0) & 31>(w);
   const uint32_t t3 = rotr<(12 + rho - a0) & 31>(w);
-  Ba.x = and_or(t0, ma, ba); Bb.x = and_or(t0, mb, bb);
-  Ba.y = and_or(t1, ma, ba); Bb.y = and_or(t1, mb, bb);
-  Ba.z = and_or(t2, ma, ba); Bb.z = and_or(t2, mb, bb);
-  Ba.w = and_or(t3, ma, ba); Bb.w = and_or(t3, mb, bb);
+  Ba.x = (t0 & ma) | ba; Bb.x = (t0 & mb) | bb;
+  Ba.y = (t1 & ma) | ba; Bb.y = (t1 & mb) | bb;
+  Ba.z = (t2 & ma) | ba; Bb.z = (t2 & mb) | bb;
+  Ba.w = (t3 & ma) | ba; Bb.w = (t3 & mb) | bb;
 }
 
 // D += X_group * slice-E operands of the two dwords (w_lo, w_hi) of one group.
 template <int E>
-__device__ inline floatx4 slice_group(const uint4 A[4], const uint32_t bias[4], uint32_t w_lo, uint32_t w_hi,
+__device__ inline floatx4 slice_group(const uint4 A[4], const UnpackConsts& uc, uint32_t w_lo, uint32_t w_hi,
                                        floatx4 D) {
   uint4 Ba, Bb;
-  unpack_dword<E>(w_lo, bias, Ba, Bb);
+  unpack_dword<E>(w_lo, uc, Ba, Bb);
   D = mfma(A[0], Ba, D);
   D = mfma(A[1], Bb, D);
-  unpack_dword<E>(w_hi, bias, Ba, Bb);
+  unpack_dword<E>(w_hi, uc, Ba, Bb);
   D = mfma(A[2], Ba, D);
   D = mfma(A[3], Bb, D);
   return D;
@@ -107,8 +117,12 @@ template <int WAVES, bool MULTI>
 __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
     const uint16_t* __restrict__ X, int T, int64_t K, const uint4* __restrict__ codes, size_t slice_vec,
     const float2* __restrict__ meta, int64_t N, int NT, int KB, const int32_t* __restrict__ prec,
-    float* __restrict__ Y) {
+    const int32_t* __restrict__ perm, float* __restrict__ Y) {
   using namespace d16;
+  // blockIdx.y = token tile: rows 16 y .. 16 y + 15 of the token order (of the precision-sorted
+  // order `perm` when there are several tiles, so that a tile reads only the slices it needs)
+  const int row0 = 16 * (int)blockIdx.y;
+  T = min(16, T - row0);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps tile addresses scalar
   const int m = lane & 15;   // token row of A / weight row of B / output column
@@ -121,8 +135,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   __shared__ float part[MULTI ? kMaxTilesMulti : 1][256];  // sums over chunks
 
   // ---- loads that depend on nothing: precisions first, then activations, slice 0 ----
-  const int pl = (lane < T) ? prec[lane] : -1;
-  const uint16_t* xrow = (m < T) ? (X + (int64_t)m * K) : nullptr;
+  const int my_token = (lane < T) ? (perm ? perm[row0 + lane] : row0 + lane) : -1;
+  const int pl = (lane < T) ? prec[my_token] : -1;
+  const int x_token = __shfl(my_token, m, 64);
+  const uint16_t* xrow = (m < T) ? (X + (int64_t)x_token * K) : nullptr;
   uint4 xa[8];
   auto load_x = [&](int kb) {
 #pragma unroll
@@ -149,10 +165,9 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   int prow[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) prow[i] = __shfl(pl, 4 * kq + i, 64);
+  const int y_token = __shfl(my_token, (int)(threadIdx.x >> 4) & 15, 64);  // output row of the reducing thread
 
-  uint32_t bias[4] = {kPow5, kPow3, kPow1, kPowM1};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(bias[i]));  // keep them resident in vector registers
+  const UnpackConsts uc = make_unpack_consts();
   const uint4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
@@ -210,29 +225,29 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
           load_rest(tn, kb, n);
           // the two groups of the block run as two independent accumulator chains
           floatx4 D[2], v[2];
-          D[0] = slice_group<0>(&xa[0], bias, c.w[0].x, c.w[0].y, zero4);
-          D[1] = slice_group<0>(&xa[4], bias, c.w[0].z, c.w[0].w, zero4);
+          D[0] = slice_group<0>(&xa[0], uc, c.w[0].x, c.w[0].y, zero4);
+          D[1] = slice_group<0>(&xa[4], uc, c.w[0].z, c.w[0].w, zero4);
           v[0] = D[0];
           v[1] = D[1];
           if constexpr (PM >= 1) {
-            D[0] = slice_group<1>(&xa[0], bias, c.w[1].x, c.w[1].y, D[0]);
-            D[1] = slice_group<1>(&xa[4], bias, c.w[1].z, c.w[1].w, D[1]);
+            D[0] = slice_group<1>(&xa[0], uc, c.w[1].x, c.w[1].y, D[0]);
+            D[1] = slice_group<1>(&xa[4], uc, c.w[1].z, c.w[1].w, D[1]);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
               for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 1) ? D[h][i] : v[h][i];
           }
           if constexpr (PM >= 2) {
-            D[0] = slice_group<2>(&xa[0], bias, c.w[2].x, c.w[2].y, D[0]);
-            D[1] = slice_group<2>(&xa[4], bias, c.w[2].z, c.w[2].w, D[1]);
+            D[0] = slice_group<2>(&xa[0], uc, c.w[2].x, c.w[2].y, D[0]);
+            D[1] = slice_group<2>(&xa[4], uc, c.w[2].z, c.w[2].w, D[1]);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
               for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 2) ? D[h][i] : v[h][i];
           }
           if constexpr (PM >= 3) {
-            D[0] = slice_group<3>(&xa[0], bias, c.w[3].x, c.w[3].y, D[0]);
-            D[1] = slice_group<3>(&xa[4], bias, c.w[3].z, c.w[3].w, D[1]);
+            D[0] = slice_group<3>(&xa[0], uc, c.w[3].x, c.w[3].y, D[0]);
+            D[1] = slice_group<3>(&xa[4], uc, c.w[3].z, c.w[3].w, D[1]);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -263,7 +278,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
             if (chunk > 0) sum += part[ti][threadIdx.x];
             if (chunk + 1 < chunks) part[ti][threadIdx.x] = sum;
           }
-          if (chunk + 1 == chunks && r < T && col < N) Y[(int64_t)r * N + col] = sum;
+          if (chunk + 1 == chunks && r < T && col < N) Y[(int64_t)y_token * N + col] = sum;
         }
       };
 #pragma unroll 1
@@ -283,9 +298,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
 
 template <int WAVES, bool MULTI>
 static void launch_decode16(int grid, hipStream_t stream, const uint16_t* X, int T, const Shape& sh,
-                            const uint4* codes, const float2* meta, const int32_t* prec, float* Y) {
-  hipLaunchKernelGGL((decode16_kernel<WAVES, MULTI>), dim3(grid), dim3(WAVES * 64), 0, stream, X, T, sh.K, codes,
-                     sh.slice_words / 4, meta, sh.N, sh.NT, sh.KB, prec, Y);
+                            const uint4* codes, const float2* meta, const int32_t* prec, const int32_t* perm,
+                            float* Y) {
+  hipLaunchKernelGGL((decode16_kernel<WAVES, MULTI>), dim3(grid, (T + 15) / 16), dim3(WAVES * 64), 0, stream, X, T,
+                     sh.K, codes, sh.slice_words / 4, meta, sh.N, sh.NT, sh.KB, prec, T > 16 ? perm : nullptr, Y);
 }
 
 static int compute_units() {
@@ -302,7 +318,7 @@ static int compute_units() {
 }
 
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
-                                  const int32_t* prec, float* Y, hipStream_t stream) {
+                                  const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream) {
   const uint4* codes = reinterpret_cast<const uint4*>(blob);
   const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
   int waves = knob(0);
@@ -310,15 +326,16 @@ mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob
   const bool multi = sh.KB > waves;
   int per_cu = knob(2);
   if (per_cu <= 0) per_cu = 16 / waves;  // 16 wavefronts per compute unit
-  int grid = compute_units() * per_cu;
+  const int token_tiles = (int)((T + 15) / 16);
+  int grid = (compute_units() * per_cu + token_tiles - 1) / token_tiles;  // workgroups per token tile
   if (grid > sh.NT) grid = sh.NT;
   // with several K chunks the per-tile partial sums live in LDS: bound the tiles per workgroup
   if (multi && (sh.NT + grid - 1) / grid > d16::kMaxTilesMulti)
     grid = (sh.NT + d16::kMaxTilesMulti - 1) / d16::kMaxTilesMulti;
 #define MBQ_D16(WV)                                                                          \
   if (waves == WV) {                                                                         \
-    if (multi) launch_decode16<WV, true>(grid, stream, X, (int)T, sh, codes, meta, prec, Y);  \
-    else launch_decode16<WV, false>(grid, stream, X, (int)T, sh, codes, meta, prec, Y);       \
+    if (multi) launch_decode16<WV, true>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);  \
+    else launch_decode16<WV, false>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);       \
   }
   MBQ_D16(4) MBQ_D16(8) MBQ_D16(16)
 #undef MBQ_D16

@@ -122,6 +122,24 @@ def test_linear_single_precision_is_a_dense_gemm(mbq, algo, p):
     assert_output_close(Y, dense.numpy(), f"{algo} uniform p={p}")
 
 
+@pytest.mark.parametrize("K", [768, 2048, 4096, 5120])
+@pytest.mark.parametrize("pmax", [0, 1, 2, 3])
+@pytest.mark.parametrize("T", [7, 16, 40])
+def test_decode_every_highest_precision(mbq, K, pmax, T):
+    """The decode kernels are specialised on the highest precision present and on the number of
+    column blocks (4, 8 or 16 wavefronts, one or several K chunks): cover every combination."""
+    N = 80
+    print(f"[case] decode pmax={pmax} K={K} T={T}", flush=True)
+    W = make_weight(N, K, [19, K], 4.0)
+    xb = tokens(T, K, [K, pmax, T])
+    prec = np.random.default_rng([K, pmax, T]).integers(0, pmax + 1, size=T).astype(np.int32)
+    prec[T // 2] = pmax
+    codes, s0, z0 = O.encode(W)
+    Yref = O.linear(xb, codes, s0, z0, prec)
+    Y = run_linear(mbq, W, xb, prec, ALGOS["decode"])
+    assert_output_close(Y, Yref, f"decode pmax={pmax} K={K} T={T}")
+
+
 def test_linear_zero_tokens_and_bad_arguments(mbq):
     N, K = 32, 256
     W = make_weight(N, K, [17], 4.0)
