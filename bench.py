@@ -48,9 +48,10 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the batch-1/4 and prefill side measurements")
-    ap.add_argument("--probe", action="store_true",
-                    help="counter probe for rocprofv3 --pmc: a plain 256 MiB device copy (known size, calibrates the "
-                         "counters) followed by a few mbq_linear launches per linear; prints nothing to time")
+    ap.add_argument("--probe", choices=["decode", "prefill"], default=None,
+                    help="counter probe for rocprofv3 --pmc, nothing is timed.  decode: a plain 256 MiB device copy "
+                         "(known size, calibrates the counters) then a few mbq_linear launches per linear of the "
+                         "block.  prefill: three mbq_linear launches of the BASELINE configs[2] gate linear")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -67,6 +68,21 @@ def main() -> int:
     dev = torch.device("cuda:0")
     cfg = CONFIGS[1]
     T = args.batch
+    if args.probe == "prefill":
+        pcfg = CONFIGS[2]
+        Tp, spec = pcfg.token_counts[0], pcfg.linears[0]
+        case = make_case(pcfg, 0, Tp)
+        blob = mbq.mbq_encode(torch.from_numpy(case["W"]).to(dev))
+        X = torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev)
+        prec, perm, offsets = mbq.mbq_route(X, torch.from_numpy(case["Wr"]).to(dev), torch.from_numpy(case["br"]).to(dev))
+        Y = torch.empty((Tp, spec.N), dtype=torch.float32, device=dev)
+        ws = mbq.linear_workspace(Tp, spec.N, spec.K, dev)
+        for _ in range(3):
+            mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "prefill", "N": spec.N, "K": spec.K, "T": Tp,
+                          "mix": np.bincount(prec.cpu().numpy(), minlength=4).tolist()}))
+        return 0
 
     # ------------------------------------------------------------------ inputs in HBM
     t0 = time.time()
@@ -90,7 +106,7 @@ def main() -> int:
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s "
           f"({sum(l['blobs'][0].numel() for l in layers) * RING / 1e6:.0f} MB of packed weights)", file=sys.stderr)
 
-    if args.probe:
+    if args.probe == "decode":
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         src.fill_(1)
