@@ -64,6 +64,7 @@ typedef enum mbq_algo {
 
 #define MBQ_N_PRECISIONS 4
 #define MBQ_GROUP 128
+#define MBQ_MAX_GROUP 4 /* most projections one mbq_*_group call takes */
 
 const char* mbq_version(void);
 const char* mbq_last_error(void);
@@ -124,6 +125,20 @@ mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, c
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * mbq_route_group - mbq_route for n_proj routers that read the SAME activations (the
+ * projections of a decoder block that share their input: q/k/v, gate/up), in one launch
+ * when T is small (Sec. 4.3, fused router launch for all projections of a layer).
+ * Results are those of n_proj separate mbq_route calls.
+ *   Wr_host, br_host, prec_host, perm_host, offsets_host : HOST arrays of n_proj DEVICE
+ *   pointers, each pointing to what the argument of the same name is in mbq_route; they are
+ *   read before the call returns.  1 <= n_proj <= MBQ_MAX_GROUP.  ws as in mbq_route.
+ */
+mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
+                           const float* const* Wr_host, const float* const* br_host, int P,
+                           int32_t* const* prec_host, int32_t* const* perm_host,
+                           int32_t* const* offsets_host, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * mbq_linear - routed output (Sec. 4.2 Eq. 6 with the prefix mask of slices 0..p_i):
  *   Y[i][n] = sum_k X[i][k] * What^(prec[i])[n][k],  fp32 accumulate, fp32 output,
  * reading for each token only the slices its precision needs.
@@ -145,6 +160,7 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
  *   knob 2: workgroups per compute unit of the single-tile decode kernel, 0 = automatic
  *   knob 5: prefill tile rows / 64 (2 or 4), 0 = automatic
  *   knob 3: T <= 16 kernel choice: 0 automatic, 1 multi-tile kernel, 2 single-tile kernel
+ *   knob 4: 1 = route small batches with the general kernel too
  */
 mbq_status mbq_set_knob(int knob, int value);
 

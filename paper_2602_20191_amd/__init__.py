@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Tuple
+from typing import List, Optional, Sequence, Tuple
 
 import torch
 
@@ -23,7 +23,7 @@ GROUP = 128
 EXPORTS = (
     "mbq_version", "mbq_last_error", "mbq_blob_bytes", "mbq_route_workspace_bytes",
     "mbq_linear_workspace_bytes", "mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route",
-    "mbq_linear", "mbq_set_knob",
+    "mbq_route_group", "mbq_linear", "mbq_set_knob",
 )
 
 _lib = None
@@ -54,9 +54,11 @@ def load() -> ctypes.CDLL:
     lib.mbq_unpack.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_p, c_p]
     lib.mbq_dequant.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p]
     lib.mbq_route.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
+    lib.mbq_route_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_sz, c_p]
     lib.mbq_linear.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_set_knob.argtypes = [c_int, c_int]
-    for name in ("mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route", "mbq_linear", "mbq_set_knob"):
+    for name in ("mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route", "mbq_route_group", "mbq_linear",
+                 "mbq_set_knob"):
         getattr(lib, name).restype = c_int
     _lib = lib
     return lib
@@ -148,6 +150,34 @@ def mbq_route(X: torch.Tensor, Wr: torch.Tensor, br: torch.Tensor, want_logits: 
     _check(load().mbq_route(_ptr(X), T, K, _ptr(Wr), _ptr(br), P, _ptr(prec), _ptr(perm), _ptr(offsets),
                             _ptr(logits), _ptr(ws), ws.numel(), _stream()), "mbq_route")
     return (prec, perm, offsets, logits) if want_logits else (prec, perm, offsets)
+
+
+def _ptr_array(tensors: Sequence[torch.Tensor]):
+    """Host array of device pointers (void* [n])."""
+    return (ctypes.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
+
+
+def mbq_route_group(X: torch.Tensor, Wr: Sequence[torch.Tensor], br: Sequence[torch.Tensor],
+                    out: Optional[Sequence[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]]] = None,
+                    ws: Optional[torch.Tensor] = None) -> List[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]]:
+    """Several routers over the same X bf16 [T, K] -> [(prec, perm, offsets)] per router."""
+    assert X.dtype == torch.bfloat16 and len(Wr) == len(br) and len(Wr) >= 1
+    T, K = X.shape
+    dev = X.device
+    n = len(Wr)
+    P = Wr[0].shape[0]
+    for w, b in zip(Wr, br):
+        assert w.dtype == torch.float32 and b.dtype == torch.float32 and tuple(w.shape) == (P, K)
+    if out is None:
+        out = [(torch.empty(T, dtype=torch.int32, device=dev), torch.empty(T, dtype=torch.int32, device=dev),
+                torch.empty(P + 1, dtype=torch.int32, device=dev)) for _ in range(n)]
+    if ws is None:
+        ws = route_workspace(T, K, dev)
+    _check(load().mbq_route_group(_ptr(X), T, K, n, _ptr_array(Wr), _ptr_array(br), P,
+                                  _ptr_array([o[0] for o in out]), _ptr_array([o[1] for o in out]),
+                                  _ptr_array([o[2] for o in out]), _ptr(ws), ws.numel(), _stream()),
+           "mbq_route_group")
+    return [tuple(o) for o in out]
 
 
 def mbq_linear(X: torch.Tensor, blob: torch.Tensor, N: int, K: int, prec: torch.Tensor, perm: torch.Tensor,

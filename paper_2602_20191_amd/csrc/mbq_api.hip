@@ -136,11 +136,46 @@ mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, c
     set_error("mbq_route: null or misaligned pointer (X and Wr need 16-byte alignment)");
     return MBQ_ERR_INVALID_ARG;
   }
-  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws) {
-    set_error("mbq_route: workspace too small (%zu < %zu)", ws_bytes, mbq_route_workspace_bytes(T, K));
+  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws || !aligned(ws, 8)) {
+    set_error("mbq_route: workspace too small or misaligned (%zu < %zu)", ws_bytes, mbq_route_workspace_bytes(T, K));
     return MBQ_ERR_WORKSPACE;
   }
   return launch_route(X, T, K, Wr, br, prec, perm, offsets, logits, ws, (hipStream_t)stream);
+}
+
+mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, const float* const* Wr_host,
+                           const float* const* br_host, int P, int32_t* const* prec_host,
+                           int32_t* const* perm_host, int32_t* const* offsets_host, void* ws, size_t ws_bytes,
+                           void* stream) {
+  if (P != MBQ_N_PRECISIONS) {
+    set_error("mbq_route_group: P=%d, only %d precisions are supported", P, MBQ_N_PRECISIONS);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (n_proj < 1 || n_proj > MBQ_MAX_GROUP) {
+    set_error("mbq_route_group: n_proj=%d outside 1..%d", n_proj, MBQ_MAX_GROUP);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (T < 0 || K <= 0 || K % kGroup != 0 || T > (int64_t)1 << 24 || K > (int64_t)1 << 24) {
+    set_error("mbq_route_group: bad sizes T=%lld K=%lld", (long long)T, (long long)K);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (!Wr_host || !br_host || !prec_host || !perm_host || !offsets_host || (T > 0 && (!X || !aligned(X, 16)))) {
+    set_error("mbq_route_group: null pointer array or null/misaligned X");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  for (int i = 0; i < n_proj; ++i)
+    if (!offsets_host[i] ||
+        (T > 0 && (!Wr_host[i] || !br_host[i] || !prec_host[i] || !perm_host[i] || !aligned(Wr_host[i], 16)))) {
+      set_error("mbq_route_group: null or misaligned pointer for projection %d", i);
+      return MBQ_ERR_INVALID_ARG;
+    }
+  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws || !aligned(ws, 256)) {
+    set_error("mbq_route_group: workspace too small or misaligned (%zu < %zu)", ws_bytes,
+              mbq_route_workspace_bytes(T, K));
+    return MBQ_ERR_WORKSPACE;
+  }
+  return launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr, ws,
+                            (hipStream_t)stream);
 }
 
 mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,

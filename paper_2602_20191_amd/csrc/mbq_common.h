@@ -61,6 +61,9 @@ mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What,
 mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
                         int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
                         hipStream_t stream);
+mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
+                              const float* const* br, int32_t* const* prec, int32_t* const* perm,
+                              int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream);
 mbq_status launch_linear_simple(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                 const int32_t* prec, float* Y, hipStream_t stream);
 mbq_status launch_linear_decode(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,

@@ -32,6 +32,8 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 namespace d16 {
 
 constexpr int kMaxTilesMulti = 32;  // tiles per workgroup whose partial sums fit the LDS budget
+constexpr int kStageStride = 272;   // bytes between token rows of the activation staging area (256 + 16: no bank conflicts)
+constexpr int kAreaBytes = 16 * kStageStride;  // >= 4 * 64 * 16 bytes of per-block constants
 
 __device__ inline floatx4 mfma(const uint4& a, const uint4& b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
@@ -131,20 +133,49 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   const int my_tiles = (NT - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
 
   __shared__ float red[2][WAVES][64][4];                   // per-wavefront partial tiles, double buffered
-  __shared__ floatx4 cst[WAVES][4][64];                    // per wavefront: C1[2], SS[2] of its current block
+  // Private to each wavefront: first the staging rows of its activation block (16 tokens x 128
+  // columns, row stride kStageStride bytes), afterwards C1[2], SS[2] of that block.
+  __shared__ __attribute__((aligned(16))) char area[WAVES][kAreaBytes];
   __shared__ float part[MULTI ? kMaxTilesMulti : 1][256];  // sums over chunks
+  char* const stage = area[wave];
+  floatx4* const cst = reinterpret_cast<floatx4*>(area[wave]);  // [4][64]
 
   // ---- loads that depend on nothing: precisions first, then activations, slice 0 ----
   const int my_token = (lane < T) ? (perm ? perm[row0 + lane] : row0 + lane) : -1;
   const int pl = (lane < T) ? prec[my_token] : -1;
-  const int x_token = __shfl(my_token, m, 64);
-  const uint16_t* xrow = (m < T) ? (X + (int64_t)x_token * K) : nullptr;
+  // Activations: a load instruction covers four token rows, a quarter wavefront reading 256
+  // contiguous bytes of each (whole cache lines); the MFMA A layout (token = lane % 16) is then
+  // produced by a round trip through the wavefront's LDS rows, one half block at a time (LDS
+  // operations of one wavefront execute in order; every access to the area uses one vector type).
   uint4 xa[8];
   auto load_x = [&](int kb) {
+    const int64_t k0 = (int64_t)kb * kTileK + 8 * m;  // K is a multiple of 128: a half block is all there or absent
+    const uint16_t* col = X + k0;
+    const int second = (k0 + 128 < K) ? 128 : 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int64_t k = (int64_t)kb * kTileK + 32 * j + 8 * kq;
-      xa[j] = (xrow != nullptr && k < K) ? *reinterpret_cast<const uint4*>(xrow + k) : uint4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < 4; ++i) {
+      const int tok = __shfl(my_token, 4 * i + kq, 64);
+      const uint16_t* src = col + (int64_t)max(tok, 0) * K;  // always a valid address
+      xa[i] = *reinterpret_cast<const uint4*>(src);
+      xa[4 + i] = *reinterpret_cast<const uint4*>(src + second);
+    }
+  };
+  // Rows past the last token and an absent second half block become zeros on the way through.
+  auto transpose_x = [&](int kb) {
+    const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+    const bool second = (int64_t)kb * kTileK + 128 < K;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool there = (4 * i + kq < T) && (h == 0 || second);
+        *reinterpret_cast<floatx4*>(stage + (4 * i + kq) * kStageStride + 16 * m) =
+            there ? __builtin_bit_cast(floatx4, xa[4 * h + i]) : zero;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        xa[4 * h + j] = __builtin_bit_cast(
+            uint4, *reinterpret_cast<const floatx4*>(stage + m * kStageStride + 64 * j + 16 * kq));
     }
   };
   auto load_base = [&](int nt, int kb, Item& I) {
@@ -192,6 +223,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
           load_base((int)blockIdx.x, kb, cur);
         }
         load_rest((int)blockIdx.x, kb, cur);
+        transpose_x(kb);
         // group sums of this block's activations, in accumulator layout, and the offset term
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -211,8 +243,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
             ss[i] = Sa[i] + Sb[i];
             c1[i] = coefA * Sa[i] + coefB * Sb[i] + (1.5f * q - 0.5f) * ss[i];
           }
-          cst[wave][h][lane] = c1;
-          cst[wave][2 + h][lane] = ss;
+          cst[h * 64 + lane] = c1;
+          cst[(2 + h) * 64 + lane] = ss;
         }
       }
       // one step: fetch tile ti+1 into `n`, consume tile ti from `c`, reduce and store
@@ -256,8 +288,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
             const float s0 = c.mt[h].x, s0z0 = c.mt[h].x * c.mt[h].y;
-            const floatx4 c1 = cst[wave][h][lane];
-            const floatx4 ss = cst[wave][2 + h][lane];
+            const floatx4 c1 = cst[h * 64 + lane];
+            const floatx4 ss = cst[(2 + h) * 64 + lane];
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] += s0 * (v[h][i] - c1[i]) - s0z0 * ss[i];
           }
@@ -322,10 +354,11 @@ mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob
   const uint4* codes = reinterpret_cast<const uint4*>(blob);
   const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
   int waves = knob(0);
-  if (waves != 4 && waves != 8 && waves != 16) waves = (sh.KB <= 4) ? 4 : (sh.KB <= 8 ? 8 : 16);
+  // eight wavefronts leave 256 registers each: room for the staged activations and both weight buffers
+  if (waves != 4 && waves != 8 && waves != 16) waves = (sh.KB <= 4) ? 4 : 8;
   const bool multi = sh.KB > waves;
   int per_cu = knob(2);
-  if (per_cu <= 0) per_cu = 16 / waves;  // 16 wavefronts per compute unit
+  if (per_cu <= 0) per_cu = (waves == 4) ? 2 : 1;  // resident workgroups per compute unit at these register counts
   const int token_tiles = (int)((T + 15) / 16);
   int grid = (compute_units() * per_cu + token_tiles - 1) / token_tiles;  // workgroups per token tile
   if (grid > sh.NT) grid = sh.NT;

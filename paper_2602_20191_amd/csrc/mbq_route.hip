@@ -152,16 +152,123 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   if (tid == 0) *ticket = 0u;  // leave the counter ready for the next call
 }
 
+// Small batches (T <= kSmallRouteTokens), one or several routers over the same activations
+// (the projections of a decoder block that share their input, Sec. 4.3, fused router launch).
+// blockIdx.x = token, blockIdx.y = router.  512 threads split the K axis in chunks of 8 columns,
+// two chunks in flight per thread.  Workgroups meet through ONE 64-bit atomic add per token: the
+// word carries 2 bits per token and an arrival count in its top byte, so the workgroup that
+// arrives last holds every token's precision in the returned value and buckets them with
+// wavefront ballots, without fences or a second pass over memory.  The word starts at zero and is
+// left at zero.
+constexpr int kSmallRouteTokens = 28;
+constexpr int kRouteGroupMax = MBQ_MAX_GROUP;
+
+struct RouteOut {
+  const float* Wr;
+  const float* br;
+  int32_t* prec;
+  int32_t* perm;
+  int32_t* offsets;
+  double* logits;
+};
+struct RouteGroup {
+  RouteOut r[kRouteGroupMax];
+};
+
+__global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
+                                                          RouteGroup group, unsigned long long* words) {
+  const RouteOut& out = group.r[blockIdx.y];
+  const int tok = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint16_t* x = X + (int64_t)tok * K;
+  const float* __restrict__ Wr = out.Wr;
+  double acc[kP] = {0.0, 0.0, 0.0, 0.0};
+  for (int64_t k = (int64_t)tid * 8; k < K; k += 2 * 4096) {
+    const bool two = k + 4096 < K;
+    const int64_t k2 = two ? k + 4096 : k;  // a valid address either way
+    const uint4 xa = *reinterpret_cast<const uint4*>(x + k);
+    const uint4 xb = *reinterpret_cast<const uint4*>(x + k2);
+    float4 wa[kP][2], wb[kP][2];
+#pragma unroll
+    for (int q = 0; q < kP; ++q) {
+      const float4* sa = reinterpret_cast<const float4*>(Wr + (int64_t)q * K + k);
+      const float4* sb = reinterpret_cast<const float4*>(Wr + (int64_t)q * K + k2);
+      wa[q][0] = sa[0]; wa[q][1] = sa[1];
+      wb[q][0] = sb[0]; wb[q][1] = sb[1];
+    }
+    auto add = [&](const uint4& xv, const float4 (&w)[kP][2]) {
+      const float xs[8] = {bf16_lo(xv.x), bf16_hi(xv.x), bf16_lo(xv.y), bf16_hi(xv.y),
+                           bf16_lo(xv.z), bf16_hi(xv.z), bf16_lo(xv.w), bf16_hi(xv.w)};
+#pragma unroll
+      for (int q = 0; q < kP; ++q) {
+        const float ws[8] = {w[q][0].x, w[q][0].y, w[q][0].z, w[q][0].w, w[q][1].x, w[q][1].y, w[q][1].z, w[q][1].w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[q] = fma((double)xs[j], (double)ws[j], acc[q]);
+      }
+    };
+    add(xa, wa);
+    if (two) add(xb, wb);
+  }
+  __shared__ double red[8][kP];
+#pragma unroll
+  for (int q = 0; q < kP; ++q) {
+    double v = acc[q];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+    if (lane == 0) red[wave][q] = v;
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  // lanes 0..3 finish one logit each; every lane then sees all four
+  double mine = 0.0;
+  if (lane < kP) {
+    mine = ((red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane])) +
+           ((red[4][lane] + red[5][lane]) + (red[6][lane] + red[7][lane])) + (double)out.br[lane];
+    if (out.logits) out.logits[(int64_t)tok * kP + lane] = mine;
+  }
+  double best = __shfl(mine, 0, 64);
+  int arg = 0;
+#pragma unroll
+  for (int q = 1; q < kP; ++q) {
+    const double s = __shfl(mine, q, 64);
+    if (s > best) {  // strict: the first maximum wins ties
+      best = s;
+      arg = q;
+    }
+  }
+  unsigned long long all = 0ull;
+  if (lane == 0) {
+    out.prec[tok] = arg;
+    const unsigned long long inc = ((unsigned long long)arg << (2 * tok)) + (1ull << 56);
+    all = atomicAdd(words + blockIdx.y, inc) + inc;
+  }
+  all = __shfl(all, 0, 64);
+  if ((int)(all >> 56) != T) return;
+  // last workgroup of this router: stable counting sort of the T tokens by precision
+  const int p = (lane < T) ? (int)((all >> (2 * lane)) & 3ull) : -1;
+  const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int start = 0, my_pos = 0;
+#pragma unroll
+  for (int q = 0; q < kP; ++q) {
+    const uint64_t b = __ballot(p == q);
+    if (p == q) my_pos = start + __popcll(b & below);
+    if (lane == q) out.offsets[q] = start;
+    start += __popcll(b);
+  }
+  if (lane == kP) out.offsets[kP] = start;
+  if (p >= 0) out.perm[my_pos] = lane;
+  if (lane == 0) words[blockIdx.y] = 0ull;  // ready for the next call
+}
+
 // T = 0: only the (all-zero) offsets have to be written.
 __global__ __launch_bounds__(64) void bucket_kernel(const int32_t* __restrict__ prec, int64_t T,
                                                     int32_t* __restrict__ perm, int32_t* __restrict__ offsets) {
   bucket_by_workgroup<1>(prec, T, perm, offsets);
 }
 
-mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
-                        int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
-                        hipStream_t stream) {
-  unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
+static mbq_status launch_route_one(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
+                                   int32_t* prec, int32_t* perm, int32_t* offsets, double* logits,
+                                   unsigned int* ticket, hipStream_t stream) {
   if (T == 0) {
     hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(64), 0, stream, prec, T, perm, offsets);
     return hip_status(hipGetLastError(), "bucket_kernel launch");
@@ -174,6 +281,38 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
                        prec, perm, offsets, logits, ticket);
   }
   return hip_status(hipGetLastError(), "route_kernel launch");
+}
+
+// Workspace: the ticket counter of the general kernels at byte 0, the per-router words of the
+// small-batch kernel from byte 64.
+mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
+                              const float* const* br, int32_t* const* prec, int32_t* const* perm,
+                              int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream) {
+  unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
+  if (T >= 1 && T <= kSmallRouteTokens && knob(4) != 1) {
+    RouteGroup g;
+    for (int i = 0; i < kRouteGroupMax; ++i) {
+      const int j = i < n ? i : 0;
+      g.r[i] = RouteOut{Wr[j], br[j], prec[j], perm[j], offsets[j], logits ? logits[j] : nullptr};
+    }
+    unsigned long long* words = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(ws) + 64);
+    hipLaunchKernelGGL(route_small_kernel, dim3((unsigned)T, (unsigned)n), dim3(512), 0, stream, X, (int)T, K, g,
+                       words);
+    return hip_status(hipGetLastError(), "route_small_kernel launch");
+  }
+  for (int i = 0; i < n; ++i) {
+    mbq_status st = launch_route_one(X, T, K, Wr[i], br[i], prec[i], perm[i], offsets[i],
+                                     logits ? logits[i] : nullptr, ticket, stream);
+    if (st != MBQ_OK) return st;
+  }
+  return MBQ_OK;
+}
+
+mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
+                        int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
+                        hipStream_t stream) {
+  double* const lg[1] = {logits};
+  return launch_route_group(X, T, K, 1, &Wr, &br, &prec, &perm, &offsets, logits ? lg : nullptr, ws, stream);
 }
 
 }  // namespace mbq

@@ -45,8 +45,9 @@ def test_encode_blob_is_bit_exact(mbq, N, K):
 
 
 # ------------------------------------------------------------------------------ route
-@pytest.mark.parametrize("T,K", [(0, 256), (1, 128), (5, 384), (32, 2048), (64, 4096), (65, 1024),
-                                 (1023, 256), (1024, 256), (1025, 256), (4100, 512)])
+@pytest.mark.parametrize("T,K", [(0, 256), (1, 128), (5, 384), (16, 4096), (16, 11008), (28, 8192), (29, 8320),
+                                 (32, 2048), (64, 4096), (65, 1024), (1023, 256), (1024, 256), (1025, 256),
+                                 (4100, 512)])
 def test_route_and_bucket_are_bit_exact(mbq, T, K):
     print(f"[case] route T={T} K={K}", flush=True)
     rng = np.random.default_rng([T, K])
@@ -62,6 +63,49 @@ def test_route_and_bucket_are_bit_exact(mbq, T, K):
     compare_routing(prec, prec_ref, gap, f"route T={T} K={K}")
     check_bucket(prec, perm, offsets)          # permutation of the GPU's own choices: unique answer
     assert offsets[4] == T
+
+
+@pytest.mark.parametrize("T,K,n", [(1, 4096, 3), (16, 4096, 3), (28, 1280, 4), (16, 11008, 1), (40, 512, 2),
+                                   (0, 256, 2)])
+def test_route_group_equals_separate_calls(mbq, T, K, n):
+    """Several routers over one X: against the oracle, and bit for bit against mbq_route; called
+    twice on one workspace (the arrival words must be left at zero)."""
+    print(f"[case] route group T={T} K={K} n={n}", flush=True)
+    rng = np.random.default_rng([T, K, n])
+    xb = tokens(T, K, [T, K, 2])
+    X = dev_bf16(xb).reshape(T, K)
+    Wrs = [(rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32) for _ in range(n)]
+    brs = [rng.normal(0, 0.2, size=4).astype(np.float32) for _ in range(n)]
+    ws = mbq.route_workspace(T, K, "cuda")
+    for _ in range(2):
+        outs = mbq.mbq_route_group(X, [dev(w) for w in Wrs], [dev(b) for b in brs], ws=ws)
+        torch.cuda.synchronize()
+        for i in range(n):
+            S, prec_ref, gap = O.route(xb, Wrs[i], brs[i])
+            prec, perm, offsets = (t.cpu().numpy() for t in outs[i])
+            compare_routing(prec, prec_ref, gap, f"group router {i}")
+            check_bucket(prec, perm, offsets)
+            single = mbq.mbq_route(X, dev(Wrs[i]), dev(brs[i]))
+            for a, b in zip(single, outs[i]):
+                assert torch.equal(a, b)
+    assert int(ws.cpu().numpy().astype(np.int64).sum()) == 0
+
+
+def test_route_small_and_general_kernels_agree(mbq):
+    T, K = 16, 4096
+    xb = tokens(T, K, 77)
+    rng = np.random.default_rng(77)
+    Wr = (rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32)
+    br = np.zeros(4, dtype=np.float32)
+    a = mbq.mbq_route(dev_bf16(xb), dev(Wr), dev(br), want_logits=True)
+    mbq.set_knob(4, 1)
+    try:
+        b = mbq.mbq_route(dev_bf16(xb), dev(Wr), dev(br), want_logits=True)
+    finally:
+        mbq.set_knob(4, 0)
+    for u, v in zip(a[:3], b[:3]):
+        assert torch.equal(u, v)
+    np.testing.assert_allclose(a[3].cpu().numpy(), b[3].cpu().numpy(), rtol=0, atol=1e-10)
 
 
 def test_route_ties_and_single_bucket(mbq):
