@@ -4,8 +4,10 @@
 Workload (default): BASELINE config 1 - the seven linears of a Llama-2-7B-shaped decoder
 block (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), each with its own
 router, one decode batch of bf16 tokens with 1% outlier channels, uniform precision mix.
-A *step* is one pass of the whole hot path (mbq_route then mbq_linear) over all seven
-linears for one batch.  Weights, activations and router parameters are resident in HBM
+A *step* is one pass of the whole hot path over all seven linears for one batch, as the four
+dependent stages of the block: {q, k, v} (one input), {o}, {gate, up} (one input), {down};
+each stage is one mbq_routed_linear_group call (route every projection's tokens, then the
+routed outputs).  Weights, activations and router parameters are resident in HBM
 before the timed region; three distinct copies of the packed block (> 600 MB) are
 rotated so that no step finds its weights in the 256 MB last-level cache.
 
@@ -27,6 +29,7 @@ import numpy as np
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 RING = 3                        # distinct packed copies of the block rotated across steps
+STAGES = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))   # projections that share their input
 # HBM bytes per mbq_linear launch at batch 16 (mean over the seven linears) from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of `bench.py --probe`, scaled by what the same counters read for a plain 256 MiB copy
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/decode_linear_hbm_traffic_llama2_7b_batch16.txt
@@ -103,6 +106,18 @@ def main() -> int:
             Y=torch.empty((T, spec.N), dtype=torch.float32, device=dev),
             ws_r=mbq.route_workspace(T, spec.K, dev), ws_l=mbq.linear_workspace(T, spec.N, spec.K, dev))
         layers.append(layer)
+    by_name = {l["spec"].name: l for l in layers}
+    stages = []
+    for names in STAGES:
+        ls = [by_name[n] for n in names]
+        for l in ls[1:]:                      # the stage's projections read the first one's activations
+            l["X"], l["x_bits"] = ls[0]["X"], ls[0]["x_bits"]
+        K = ls[0]["spec"].K
+        stages.append(dict(
+            names=names, layers=ls, X=ls[0]["X"], K=K, Ns=[l["spec"].N for l in ls],
+            Wr=[l["Wr"] for l in ls], br=[l["br"] for l in ls],
+            routing=[(l["prec"], l["perm"], l["offsets"]) for l in ls], Y=[l["Y"] for l in ls],
+            ws_r=mbq.route_workspace(T, K, dev), ws_l=mbq.linear_workspace(T, max(l["spec"].N for l in ls), K, dev)))
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s "
           f"({sum(l['blobs'][0].numel() for l in layers) * RING / 1e6:.0f} MB of packed weights)", file=sys.stderr)
 
@@ -114,22 +129,22 @@ def main() -> int:
         for _ in range(3):
             dst.copy_(src)          # plain copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
-        for l in layers:
-            mbq.mbq_route(l["X"], l["Wr"], l["br"], out=(l["prec"], l["perm"], l["offsets"]), ws=l["ws_r"])
+        for st in stages:
             for i in range(RING):
-                mbq.mbq_linear(l["X"], l["blobs"][i], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
-                               l["offsets"], Y=l["Y"], ws=l["ws_l"])
+                mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [l["blobs"][i] for l in st["layers"]],
+                                            st["Ns"], routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"],
+                                            ws_linear=st["ws_l"])
         torch.cuda.synchronize()
-        print(json.dumps({"probe": "done", "copy_bytes": 256 << 20,
-                          "linears": [[l["spec"].name, l["spec"].N, l["spec"].K, int(l["prec"].max().item())]
-                                      for l in layers]}))
+        print(json.dumps({"probe": "done", "copy_bytes": 256 << 20, "launches_per_stage": RING,
+                          "stages": [["+".join(st["names"]), st["Ns"], st["K"],
+                                      [int(l["prec"].max().item()) for l in st["layers"]]] for st in stages]}))
         return 0
 
     def step(ring_slot: int) -> None:
-        for l in layers:
-            mbq.mbq_route(l["X"], l["Wr"], l["br"], out=(l["prec"], l["perm"], l["offsets"]), ws=l["ws_r"])
-            mbq.mbq_linear(l["X"], l["blobs"][ring_slot], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
-                           l["offsets"], Y=l["Y"], ws=l["ws_l"])
+        for st in stages:
+            mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [l["blobs"][ring_slot] for l in st["layers"]],
+                                        st["Ns"], routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"],
+                                        ws_linear=st["ws_l"])
 
     # ------------------------------------------------------------- launch mechanism
     launch = "eager"
@@ -181,22 +196,43 @@ def main() -> int:
     avg_bits = float(np.mean([2 * (q + 1) for m in mixes for q in range(4) for _ in range(m[q])]))
 
     # ------------------------------------- dominant kernel: per-launch duration (HIP events)
-    # mbq_linear alone, back to back over the rotating weight copies, on the same stream.
-    reps = max(20, min(200, args.steps))
+    # The linear kernel of every stage alone (activations already prepared in the workspace by the
+    # stage call above; knob 6 = 1 makes mbq_linear_group launch only that kernel), 24 launches per
+    # HIP-graph replay over the rotating weight copies, timed with events on the launch stream.
+    per_graph = 24
     kernel_us, kernel_bytes = [], []
-    for l, pmax in zip(layers, pmaxes):
-        for i in range(5):
-            mbq.mbq_linear(l["X"], l["blobs"][i % RING], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
-                           l["offsets"], Y=l["Y"], ws=l["ws_l"])
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for i in range(reps):
-            mbq.mbq_linear(l["X"], l["blobs"][i % RING], l["spec"].N, l["spec"].K, l["prec"], l["perm"],
-                           l["offsets"], Y=l["Y"], ws=l["ws_l"])
-        b.record()
-        torch.cuda.synchronize()
-        kernel_us.append(a.elapsed_time(b) * 1e3 / reps)
-        kernel_bytes.append(algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax))
+    mbq.set_knob(6, 1)
+    try:
+        for st in stages:
+            def burst():
+                for i in range(per_graph):
+                    mbq.mbq_linear_group(st["X"], [l["blobs"][i % RING] for l in st["layers"]], st["Ns"], st["K"],
+                                         st["routing"], Y=st["Y"], ws=st["ws_l"])
+            burst()
+            torch.cuda.synchronize()
+            g = None
+            if not args.no_graph:
+                try:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        burst()
+                except Exception:
+                    g = None
+                    torch.cuda.synchronize()
+            reps = 8
+            (g.replay() if g is not None else burst())
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                (g.replay() if g is not None else burst())
+            b.record()
+            torch.cuda.synchronize()
+            kernel_us.append(a.elapsed_time(b) * 1e3 / (reps * per_graph))
+            kernel_bytes.append(sum(algorithmic_bytes(l["spec"].N, l["spec"].K, T, pm) - 2 * T * l["spec"].K
+                                    for l, pm in zip(st["layers"], [pmaxes[layers.index(l)] for l in st["layers"]]))
+                                + 2 * T * st["K"])
+    finally:
+        mbq.set_knob(6, 0)
     avg_launch_us = float(np.mean(kernel_us))
     avg_launch_bytes = float(np.mean(kernel_bytes))
     achieved = avg_launch_bytes / (avg_launch_us * 1e-6) / 1e9
@@ -218,23 +254,25 @@ def main() -> int:
             "workload": f"BASELINE configs[1]: Llama-2-7B-shaped decoder block, 7 routed linears, decode batch {T}, "
                         "group 128, 2-bit base + three 2-bit residual slices, uniform precision mix, 1% outlier channels",
             "batch": T, "launch": launch, "weight_ring_copies": RING,
+            "stages": ["+".join(n) for n in STAGES],
             "precision_mix_per_linear": mixes, "avg_bits": avg_bits,
         },
         "hbm_gbps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "event_ms_per_step": ev_ms_per_step,
         "roofline": {
-            "bound": "hbm", "kernel": "mbq::decode16_kernel / mbq::decode_kernel (mbq_linear, one token tile)",
+            "bound": "hbm", "kernel": "the linear kernel of each stage: mbq::decode_f4_kernel (q+k+v, o, gate+up), "
+                                      "mbq::decode_kernel (down)",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
             "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(T),
             "avg_launch_us": avg_launch_us, "avg_launch_bytes": avg_launch_bytes,
-            "per_linear_us": {l["spec"].name: round(u, 2) for l, u in zip(layers, kernel_us)},
-            "per_linear_gbps": {l["spec"].name: round(bts / (u * 1e-6) / 1e9, 1)
-                                for l, u, bts in zip(layers, kernel_us, kernel_bytes)},
+            "per_stage_us": {"+".join(st["names"]): round(u, 2) for st, u in zip(stages, kernel_us)},
+            "per_stage_gbps": {"+".join(st["names"]): round(bts / (u * 1e-6) / 1e9, 1)
+                               for st, u, bts in zip(stages, kernel_us, kernel_bytes)},
         },
     }
 
     if not args.no_extra:
-        out["extra"] = extra_measurements(mbq, torch, dev, cfg, layers, T)
+        out["extra"] = extra_measurements(mbq, torch, dev, cfg, layers, stages, T)
 
     # ------------------------------------------------------------------ CPU baseline
     if not args.no_cpu_baseline:
@@ -243,7 +281,7 @@ def main() -> int:
     return 0
 
 
-def extra_measurements(mbq, torch, dev, cfg, layers, T_main):
+def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
     """Side figures, each timed with HIP events over eager back-to-back launches:
     the same block at the other decode batches of the config, and one prefill linear
     (BASELINE configs[2], gate projection, 2048 tokens) as TFLOP/s."""
@@ -253,21 +291,22 @@ def extra_measurements(mbq, torch, dev, cfg, layers, T_main):
     for T in cfg.token_counts:
         if T == T_main:
             continue
-        bufs = []
+        bufs = {}
         for li, l in enumerate(layers):
             case = make_case(cfg, li, T, with_weight=False)
             spec = l["spec"]
-            bufs.append(dict(
+            bufs[spec.name] = dict(
                 X=torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev),
                 prec=torch.empty(T, dtype=torch.int32, device=dev), perm=torch.empty(T, dtype=torch.int32, device=dev),
                 offsets=torch.empty(5, dtype=torch.int32, device=dev),
-                Y=torch.empty((T, spec.N), dtype=torch.float32, device=dev)))
+                Y=torch.empty((T, spec.N), dtype=torch.float32, device=dev))
 
         def one(slot):
-            for l, b in zip(layers, bufs):
-                mbq.mbq_route(b["X"], l["Wr"], l["br"], out=(b["prec"], b["perm"], b["offsets"]), ws=l["ws_r"])
-                mbq.mbq_linear(b["X"], l["blobs"][slot], l["spec"].N, l["spec"].K, b["prec"], b["perm"],
-                               b["offsets"], Y=b["Y"], ws=l["ws_l"])
+            for st in stages:
+                bs = [bufs[n] for n in st["names"]]
+                mbq.mbq_routed_linear_group(bs[0]["X"], st["Wr"], st["br"], [l["blobs"][slot] for l in st["layers"]],
+                                            st["Ns"], routing=[(b["prec"], b["perm"], b["offsets"]) for b in bs],
+                                            Y=[b["Y"] for b in bs], ws_route=st["ws_r"], ws_linear=st["ws_l"])
 
         one(0)
         torch.cuda.synchronize()
@@ -291,7 +330,8 @@ def extra_measurements(mbq, torch, dev, cfg, layers, T_main):
         torch.cuda.synchronize()
         ms = a.elapsed_time(b2) / n
         byts = 0
-        for l, b in zip(layers, bufs):
+        for l in layers:
+            b = bufs[l["spec"].name]
             pmax = int(b["prec"].max().item())
             byts += algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax) + 16 * l["spec"].K
         extra[f"decode_batch_{T}"] = {"ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),

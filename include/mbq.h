@@ -154,13 +154,51 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
                       void* ws, size_t ws_bytes, int algo, void* stream);
 
 /*
+ * mbq_linear_group - mbq_linear for n_proj weight matrices with the same K that read the SAME
+ * activations (q/k/v, gate/up of a decoder block), each with its own routing; one launch and
+ * one pass over X when T <= 16 and K <= 4096 (Sec. 4.3, fused launch for the projections of a
+ * layer).  Results are those of n_proj separate mbq_linear calls.
+ *   blob_host, prec_host, perm_host, offsets_host, Y_host : HOST arrays of n_proj DEVICE
+ *   pointers (meaning as in mbq_linear); N_host : HOST array of the n_proj row counts.  The
+ *   arrays are read before the call returns.  1 <= n_proj <= MBQ_MAX_GROUP.
+ *   ws : at least max_i mbq_linear_workspace_bytes(T, N_host[i], K) bytes, 256-byte aligned
+ */
+mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
+                            const void* const* blob_host, const int64_t* N_host,
+                            const int32_t* const* prec_host, const int32_t* const* perm_host,
+                            const int32_t* const* offsets_host, float* const* Y_host, void* ws,
+                            size_t ws_bytes, int algo, void* stream);
+
+/*
+ * mbq_routed_linear_group - mbq_route_group followed by mbq_linear_group on the same
+ * projections: one decoder-block stage (route the tokens for q/k/v, or gate/up, or one
+ * projection alone, then compute their outputs).  Same results and the same outputs (prec,
+ * perm, offsets, Y) as the two calls; for T <= 16 and K <= 4096 the router launch also carries
+ * the decode kernel's activation preparation, so the stage is two launches.
+ *   ws_route  : as ws in mbq_route (zero before first use, left zero)
+ *   ws_linear : as ws in mbq_linear_group
+ * const int32_t* and int32_t* arrays: prec_host etc. are written by the routing step and read
+ * by the linear step.
+ */
+mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
+                                   const float* const* Wr_host, const float* const* br_host, int P,
+                                   const void* const* blob_host, const int64_t* N_host,
+                                   int32_t* const* prec_host, int32_t* const* perm_host,
+                                   int32_t* const* offsets_host, float* const* Y_host, void* ws_route,
+                                   size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
+                                   int algo, void* stream);
+
+/*
  * Launch-shape knobs for experiments (process-global, not thread-safe; 0 = default).
  *   knob 0: waves per workgroup of the decode kernel (4, 8 or 16)
  *   knob 1: K-split (workgroups along K) of the multi-tile decode kernel, 0 = automatic
  *   knob 2: workgroups per compute unit of the single-tile decode kernel, 0 = automatic
  *   knob 5: prefill tile rows / 64 (2 or 4), 0 = automatic
- *   knob 3: T <= 16 kernel choice: 0 automatic, 1 multi-tile kernel, 2 single-tile kernel
+ *   knob 3: decode kernel choice: 0 automatic, 1 multi-tile kernel, 2 single-matrix stationary kernel,
+ *           3 bf16-operand group kernel
  *   knob 4: 1 = route small batches with the general kernel too
+ *   knob 6: 1 = mbq_linear_group skips the activation preparation launch (the workspace must hold
+ *           the result of an earlier call on the same X): for timing the linear kernel alone
  */
 mbq_status mbq_set_knob(int knob, int value);
 

@@ -23,7 +23,7 @@ GROUP = 128
 EXPORTS = (
     "mbq_version", "mbq_last_error", "mbq_blob_bytes", "mbq_route_workspace_bytes",
     "mbq_linear_workspace_bytes", "mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route",
-    "mbq_route_group", "mbq_linear", "mbq_set_knob",
+    "mbq_route_group", "mbq_linear", "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob",
 )
 
 _lib = None
@@ -56,9 +56,12 @@ def load() -> ctypes.CDLL:
     lib.mbq_route.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
     lib.mbq_route_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_sz, c_p]
     lib.mbq_linear.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
+    lib.mbq_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
+    lib.mbq_routed_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_p,
+                                            c_p, c_sz, c_p, c_sz, c_int, c_p]
     lib.mbq_set_knob.argtypes = [c_int, c_int]
     for name in ("mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route", "mbq_route_group", "mbq_linear",
-                 "mbq_set_knob"):
+                 "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob"):
         getattr(lib, name).restype = c_int
     _lib = lib
     return lib
@@ -193,3 +196,53 @@ def mbq_linear(X: torch.Tensor, blob: torch.Tensor, N: int, K: int, prec: torch.
     _check(load().mbq_linear(_ptr(X), T, _ptr(blob), N, K, _ptr(prec), _ptr(perm), _ptr(offsets), _ptr(Y),
                              _ptr(ws), ws.numel(), algo, _stream()), "mbq_linear")
     return Y
+
+
+def mbq_linear_group(X: torch.Tensor, blobs: Sequence[torch.Tensor], Ns: Sequence[int], K: int,
+                     routing: Sequence[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]],
+                     Y: Optional[Sequence[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None,
+                     algo: int = ALGO_AUTO) -> List[torch.Tensor]:
+    """Routed outputs of several matrices over the same X; routing[i] = (prec, perm, offsets) of matrix i."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.shape[1] == K
+    assert len(blobs) == len(Ns) == len(routing) >= 1
+    T = X.shape[0]
+    if Y is None:
+        Y = [torch.empty((T, N), dtype=torch.float32, device=X.device) for N in Ns]
+    if ws is None:
+        ws = linear_workspace(T, max(Ns), K, X.device)
+    n_arr = (ctypes.c_int64 * len(Ns))(*[int(N) for N in Ns])
+    _check(load().mbq_linear_group(_ptr(X), T, K, len(Ns), _ptr_array(blobs), n_arr,
+                                   _ptr_array([r[0] for r in routing]), _ptr_array([r[1] for r in routing]),
+                                   _ptr_array([r[2] for r in routing]), _ptr_array(Y), _ptr(ws), ws.numel(), algo,
+                                   _stream()), "mbq_linear_group")
+    return list(Y)
+
+
+def mbq_routed_linear_group(X: torch.Tensor, Wr: Sequence[torch.Tensor], br: Sequence[torch.Tensor],
+                            blobs: Sequence[torch.Tensor], Ns: Sequence[int],
+                            routing: Optional[Sequence[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]]] = None,
+                            Y: Optional[Sequence[torch.Tensor]] = None, ws_route: Optional[torch.Tensor] = None,
+                            ws_linear: Optional[torch.Tensor] = None, algo: int = ALGO_AUTO):
+    """One stage: route X with every router, then the routed outputs.  -> (routing, Y) lists."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2
+    T, K = X.shape
+    n = len(Ns)
+    assert len(Wr) == len(br) == len(blobs) == n >= 1
+    P = Wr[0].shape[0]
+    dev = X.device
+    if routing is None:
+        routing = [(torch.empty(T, dtype=torch.int32, device=dev), torch.empty(T, dtype=torch.int32, device=dev),
+                    torch.empty(P + 1, dtype=torch.int32, device=dev)) for _ in range(n)]
+    if Y is None:
+        Y = [torch.empty((T, N), dtype=torch.float32, device=dev) for N in Ns]
+    if ws_route is None:
+        ws_route = route_workspace(T, K, dev)
+    if ws_linear is None:
+        ws_linear = linear_workspace(T, max(Ns), K, dev)
+    n_arr = (ctypes.c_int64 * n)(*[int(N) for N in Ns])
+    _check(load().mbq_routed_linear_group(
+        _ptr(X), T, K, n, _ptr_array(Wr), _ptr_array(br), P, _ptr_array(blobs), n_arr,
+        _ptr_array([r[0] for r in routing]), _ptr_array([r[1] for r in routing]),
+        _ptr_array([r[2] for r in routing]), _ptr_array(Y), _ptr(ws_route), ws_route.numel(), _ptr(ws_linear),
+        ws_linear.numel(), algo, _stream()), "mbq_routed_linear_group")
+    return [tuple(r) for r in routing], list(Y)

@@ -52,6 +52,34 @@ bool make_shape(int64_t N, int64_t K, Shape* out) {
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// algo is DECODE (T <= 64), PREFILL or SIMPLE here
+mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const Shape& sh, const int32_t* prec,
+                           const int32_t* perm, const int32_t* offsets, float* Y, void* ws, int algo,
+                           hipStream_t s) {
+  switch (algo) {
+    case MBQ_ALGO_SIMPLE:
+      return launch_linear_simple(X, T, blob, sh, prec, Y, s);
+    case MBQ_ALGO_DECODE:
+      // One token tile and at most 4096 columns: activations stay in registers while a workgroup
+      // walks over its row tiles.  Otherwise the register-stationary chunked kernel wins when a
+      // workgroup has many row tiles; short, wide matrices (few tiles per compute unit, many
+      // chunks) keep every column block in flight instead.  Several token tiles (17..64 tokens)
+      // run as one pass per 16 precision-sorted tokens.
+      if (knob(3) == 0 && decode_f4_supports(T, sh)) {
+        mbq_status st = launch_decode_f4_prep(X, T, sh.K, sh.KB, ws, s);
+        if (st != MBQ_OK) return st;
+        return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s);
+      }
+      if (knob(3) == 3 && decode_group_supports(T, sh))
+        return launch_linear_decode_group(X, T, 1, &blob, &sh, &prec, &Y, s);
+      if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 1024))
+        return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
+      return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
+    default:
+      return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s);
+  }
+}
+
 }  // namespace mbq
 
 using namespace mbq;
@@ -78,7 +106,10 @@ size_t mbq_linear_workspace_bytes(int64_t T, int64_t N, int64_t K) {
   if (T < 0 || !make_shape(N, K, &sh)) return 0;
   size_t a = decode_workspace_bytes(T, sh);
   size_t b = prefill_workspace_bytes(T, sh);
-  return (a > b ? a : b) + 256;
+  size_t c = decode_f4_workspace_bytes(T, sh);
+  if (b > a) a = b;
+  if (c > a) a = c;
+  return a + 256;
 }
 
 mbq_status mbq_set_knob(int k, int value) {
@@ -175,7 +206,40 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
     return MBQ_ERR_WORKSPACE;
   }
   return launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr, ws,
-                            (hipStream_t)stream);
+                            (hipStream_t)stream, nullptr, 0);
+}
+
+mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
+                                   const float* const* Wr_host, const float* const* br_host, int P,
+                                   const void* const* blob_host, const int64_t* N_host, int32_t* const* prec_host,
+                                   int32_t* const* perm_host, int32_t* const* offsets_host, float* const* Y_host,
+                                   void* ws_route, size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
+                                   int algo, void* stream) {
+  // the fused form: the router launch also prepares the activations of the decode kernel
+  if (algo == MBQ_ALGO_AUTO || algo == MBQ_ALGO_DECODE) {
+    Shape sh[MBQ_MAX_GROUP];
+    bool ok = n_proj >= 1 && n_proj <= MBQ_MAX_GROUP && N_host && blob_host && Y_host && P == MBQ_N_PRECISIONS &&
+              T >= 1 && K > 0 && K % kGroup == 0 && X && aligned(X, 16) && Wr_host && br_host && prec_host &&
+              perm_host && offsets_host && ws_route && aligned(ws_route, 256) &&
+              ws_route_bytes >= mbq_route_workspace_bytes(T, K) && ws_linear && aligned(ws_linear, 256);
+    for (int i = 0; ok && i < n_proj; ++i) {
+      ok = N_host[i] > 0 && make_shape(N_host[i], K, &sh[i]) && blob_host[i] && aligned(blob_host[i], 256) &&
+           Y_host[i] && Wr_host[i] && aligned(Wr_host[i], 16) && br_host[i] && prec_host[i] && perm_host[i] &&
+           offsets_host[i] && ws_linear_bytes >= mbq_linear_workspace_bytes(T, N_host[i], K);
+    }
+    if (ok && knob(3) == 0 && decode_f4_supports(T, sh[0]) && route_can_carry_prep(T)) {
+      mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
+                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB);
+      if (st != MBQ_OK) return st;
+      return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream);
+    }
+  }
+  // otherwise exactly the two calls (they check the arguments)
+  mbq_status st = mbq_route_group(X, T, K, n_proj, Wr_host, br_host, P, prec_host, perm_host, offsets_host,
+                                  ws_route, ws_route_bytes, stream);
+  if (st != MBQ_OK) return st;
+  return mbq_linear_group(X, T, K, n_proj, blob_host, N_host, prec_host, perm_host, offsets_host, Y_host, ws_linear,
+                          ws_linear_bytes, algo, stream);
 }
 
 mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
@@ -207,21 +271,72 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
               (long long)T);
     return MBQ_ERR_BAD_SHAPE;
   }
-  hipStream_t s = (hipStream_t)stream;
-  switch (algo) {
-    case MBQ_ALGO_SIMPLE:
-      return launch_linear_simple(X, T, blob, sh, prec, Y, s);
-    case MBQ_ALGO_DECODE:
-      // One token tile: the register-stationary kernel wins when the row fits one chunk of
-      // column blocks or a workgroup walks over several row tiles; short, wide matrices
-      // (few tiles per compute unit, many chunks) keep every column block in flight instead.
-      // Several token tiles (17..64 tokens) run as one pass of that kernel per 16 sorted tokens.
-      if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 1024))
-        return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
-      return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
-    default:
-      return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s);
+  return dispatch_linear(X, T, blob, sh, prec, perm, offsets, Y, ws, algo, (hipStream_t)stream);
+}
+
+mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, const void* const* blob_host,
+                            const int64_t* N_host, const int32_t* const* prec_host,
+                            const int32_t* const* perm_host, const int32_t* const* offsets_host,
+                            float* const* Y_host, void* ws, size_t ws_bytes, int algo, void* stream) {
+  if (n_proj < 1 || n_proj > MBQ_MAX_GROUP) {
+    set_error("mbq_linear_group: n_proj=%d outside 1..%d", n_proj, MBQ_MAX_GROUP);
+    return MBQ_ERR_INVALID_ARG;
   }
+  if (!blob_host || !N_host || !prec_host || !perm_host || !offsets_host || !Y_host) {
+    set_error("mbq_linear_group: null pointer array");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (T < 0 || T > (int64_t)1 << 24) {
+    set_error("mbq_linear_group: bad token count %lld", (long long)T);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (algo < MBQ_ALGO_AUTO || algo > MBQ_ALGO_PREFILL) {
+    set_error("mbq_linear_group: unknown algo %d", algo);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  Shape sh[MBQ_MAX_GROUP];
+  size_t need = 0;
+  for (int i = 0; i < n_proj; ++i) {
+    if (!make_shape(N_host[i], K, &sh[i])) return MBQ_ERR_BAD_SHAPE;
+    const size_t b = mbq_linear_workspace_bytes(T, N_host[i], K);
+    if (b > need) need = b;
+  }
+  if (T == 0) return MBQ_OK;
+  if (!X || !aligned(X, 16)) {
+    set_error("mbq_linear_group: null or misaligned X");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  for (int i = 0; i < n_proj; ++i)
+    if (!blob_host[i] || !prec_host[i] || !perm_host[i] || !offsets_host[i] || !Y_host[i] ||
+        !aligned(blob_host[i], 256)) {
+      set_error("mbq_linear_group: null or misaligned pointer for projection %d", i);
+      return MBQ_ERR_INVALID_ARG;
+    }
+  if (!ws || !aligned(ws, 256) || ws_bytes < need) {
+    set_error("mbq_linear_group: workspace too small or misaligned (%zu < %zu)", ws_bytes, need);
+    return MBQ_ERR_WORKSPACE;
+  }
+  if (algo == MBQ_ALGO_AUTO) algo = (T <= kMaxDecodeTokens) ? MBQ_ALGO_DECODE : MBQ_ALGO_PREFILL;
+  if (algo == MBQ_ALGO_DECODE && T > kMaxDecodeTokens) {
+    set_error("mbq_linear_group: the decode kernel handles at most %d tokens (T=%lld)", kMaxDecodeTokens,
+              (long long)T);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (algo == MBQ_ALGO_DECODE && knob(3) == 0 && decode_f4_supports(T, sh[0])) {
+    // knob 6 = 1 (measurement only): the workspace already holds the prepared activations
+    mbq_status st = knob(6) == 1 ? MBQ_OK : launch_decode_f4_prep(X, T, K, sh[0].KB, ws, s);
+    if (st != MBQ_OK) return st;
+    return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s);
+  }
+  if (algo == MBQ_ALGO_DECODE && knob(3) == 3 && decode_group_supports(T, sh[0]))
+    return launch_linear_decode_group(X, T, n_proj, blob_host, sh, prec_host, Y_host, s);
+  for (int i = 0; i < n_proj; ++i) {
+    mbq_status st =
+        dispatch_linear(X, T, blob_host[i], sh[i], prec_host[i], perm_host[i], offsets_host[i], Y_host[i], ws, algo, s);
+    if (st != MBQ_OK) return st;
+  }
+  return MBQ_OK;
 }
 
 }  // extern "C"

@@ -63,7 +63,9 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
                         hipStream_t stream);
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
-                              int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream);
+                              int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
+                              void* prep, int prep_blocks);
+bool route_can_carry_prep(int64_t T);
 mbq_status launch_linear_simple(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                 const int32_t* prec, float* Y, hipStream_t stream);
 mbq_status launch_linear_decode(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
@@ -74,6 +76,16 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
                                  hipStream_t stream);
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
+bool decode_group_supports(int64_t T, const Shape& sh);
+mbq_status launch_linear_decode_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
+                                      const Shape* shapes, const int32_t* const* prec, float* const* Y,
+                                      hipStream_t stream);
+bool decode_f4_supports(int64_t T, const Shape& sh);
+size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh);
+mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, hipStream_t stream);
+mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
+                                   const int32_t* const* prec, float* const* Y, const void* ws,
+                                   hipStream_t stream);
 size_t decode_workspace_bytes(int64_t T, const Shape& sh);
 size_t prefill_workspace_bytes(int64_t T, const Shape& sh);
 

@@ -1,0 +1,109 @@
+// Preparation of the activations for the FP4-operand decode kernel: bf16 -> three BF8 (E5M2)
+// pieces in MFMA A-operand order, group sums and per-block scale exponents.  Shared by the
+// stand-alone preparation kernel and by the router launch that carries it along.
+#pragma once
+
+#include "mbq_common.h"
+
+namespace mbq {
+namespace f4 {
+
+constexpr int kPieces = 3;
+// Prepared activations of one 256-column block: [2 groups][3 pieces][64 lanes] x 32 bytes, then
+// per group the 16 token sums (fp32), then the 16 scale exponents (int32).
+constexpr size_t kPrepVecPerBlock = 2 * kPieces * 64 * 2;  // uint4 units
+constexpr size_t kPrepBytesPerBlock = kPrepVecPerBlock * 16 + 2 * 16 * 4 + 16 * 4;
+
+// One wavefront per 256-column block: lane (m, qa) = (token, k sub-block of the MFMA A operand).
+// A lane's 32 bytes of one (group, piece) are the A operand registers of one MFMA: bytes
+// 16 c + 8 step + 4 h + j hold column 128 g + 64 (qa & 1) + 32 step + 8 (2 c + (qa >> 1)) + 2 j + h
+// of the block, which is where the FP4 operand built from lane group 2 c + (qa >> 1) of the packed
+// tile puts the matching weight.
+__device__ inline void prep_block(const uint16_t* __restrict__ X, int T, int64_t K, char* __restrict__ prep,
+                                  int kb, int lane) {
+  const int m = lane & 15, qa = lane >> 4;
+  char* base = prep + (size_t)kb * kPrepBytesPerBlock;
+  uint4* out = reinterpret_cast<uint4*>(base);
+  float* sums = reinterpret_cast<float*>(base + kPrepVecPerBlock * 16);
+  int* scl = reinterpret_cast<int*>(base + kPrepVecPerBlock * 16 + 2 * 16 * 4);
+
+  uint4 raw[2][2][2];  // [group][c][step]
+#pragma unroll
+  for (int g = 0; g < 2; ++g)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int step = 0; step < 2; ++step) {
+        const int64_t col = (int64_t)kb * kTileK + 128 * g + 64 * (qa & 1) + 32 * step + 8 * (2 * c + (qa >> 1));
+        raw[g][c][step] = (m < T && col < K) ? *reinterpret_cast<const uint4*>(X + (int64_t)m * K + col)
+                                             : uint4{0u, 0u, 0u, 0u};
+      }
+  // largest exponent of the token's block
+  uint32_t mx = 0u;
+#pragma unroll
+  for (int g = 0; g < 2; ++g)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int step = 0; step < 2; ++step) {
+        const uint32_t u[4] = {raw[g][c][step].x, raw[g][c][step].y, raw[g][c][step].z, raw[g][c][step].w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          mx = max(mx, u[t] & 0x7F800000u);
+          mx = max(mx, (u[t] << 16) & 0x7F800000u);
+        }
+      }
+  mx = max(mx, (uint32_t)__shfl_xor((int)mx, 16, 64));
+  mx = max(mx, (uint32_t)__shfl_xor((int)mx, 32, 64));
+  // scale the largest element into [2^14, 2^15): below the BF8 maximum 57344
+  int scale_byte = (int)(mx >> 23) - 14;  // = 127 + k, x = 2^k * scaled
+  scale_byte = min(max(scale_byte, 1), 254);
+  const int down = 127 - scale_byte;      // exponent of the factor applied to x
+  if (qa == 0) scl[m] = scale_byte;
+
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    float sum = 0.f;
+    int piece_regs[kPieces][8];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int step = 0; step < 2; ++step) {
+        const uint32_t u[4] = {raw[g][c][step].x, raw[g][c][step].y, raw[g][c][step].z, raw[g][c][step].w};
+        float v[2][4];  // [h][j]: column 2 j + h of the run
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[0][j] = __uint_as_float(u[j] << 16);
+          v[1][j] = __uint_as_float(u[j] & 0xFFFF0000u);
+          sum += v[0][j] + v[1][j];
+          v[0][j] = __builtin_ldexpf(v[0][j], down);
+          v[1][j] = __builtin_ldexpf(v[1][j], down);
+        }
+#pragma unroll
+        for (int piece = 0; piece < kPieces; ++piece)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            int packed = __builtin_amdgcn_cvt_pk_bf8_f32(v[h][0], v[h][1], 0, false);
+            packed = __builtin_amdgcn_cvt_pk_bf8_f32(v[h][2], v[h][3], packed, true);
+            piece_regs[piece][4 * c + 2 * step + h] = packed;
+            v[h][0] -= __builtin_amdgcn_cvt_f32_bf8(packed, 0);
+            v[h][1] -= __builtin_amdgcn_cvt_f32_bf8(packed, 1);
+            v[h][2] -= __builtin_amdgcn_cvt_f32_bf8(packed, 2);
+            v[h][3] -= __builtin_amdgcn_cvt_f32_bf8(packed, 3);
+          }
+      }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    if (qa == 0) sums[16 * g + m] = sum;
+#pragma unroll
+    for (int piece = 0; piece < kPieces; ++piece) {
+      uint4* dst = out + ((size_t)(g * kPieces + piece) * 64 + lane) * 2;
+      const int* r = piece_regs[piece];
+      dst[0] = uint4{(uint32_t)r[0], (uint32_t)r[1], (uint32_t)r[2], (uint32_t)r[3]};
+      dst[1] = uint4{(uint32_t)r[4], (uint32_t)r[5], (uint32_t)r[6], (uint32_t)r[7]};
+    }
+  }
+}
+
+}  // namespace f4
+}  // namespace mbq

@@ -1,0 +1,322 @@
+// Decode-side routed linear for one token tile (T <= 16), K <= 4096, and up to MBQ_MAX_GROUP
+// weight matrices that read the SAME activations: the 2-bit codes go to the matrix cores as FP4.
+//
+// Paper Sec. 4.2 Eq. 6 evaluated slice by slice, Y_i = sum_{e <= p_i} W_e^T X_i, with the
+// shared-scale structure of App. B (s_e = s0/4^e, z_e = 2 for e >= 1); a tile fetches only
+// slices 0..max_i p_i of its own matrix (Sec. 4.3, on-demand slice access), and the matrices of
+// one call share one launch and one pass over the activations (Sec. 4.3, fused launch for the
+// projections of a layer).
+//
+// Arithmetic.  A 2-bit code c zero-extended to four bits IS the FP4 (E2M1) number c/2, so a
+// packed dword turns into MFMA operands with a rotate and a mask per eight codes.  The bf16
+// activations are split once, by a small preparation kernel, into three BF8 (E5M2) pieces
+// x = x1 + x2 + x3 (each the round-to-nearest of what is left; 3 + 3 + 2 significant bits, so
+// the split is exact over 24 binades below the largest element of the token's 256-column block,
+// which a per-block power-of-two scale moves to the top of the BF8 range).  Every product
+// piece x code is exact and v_mfma_scale_f32_16x16x128_f8f6f4 accumulates in fp32.  Its
+// per-lane block scales do the rest of the bookkeeping at no cost:
+//   - the B scale of slice e is 2^(1-2e): the operand c/2 counts as c / 4^e;
+//   - the A scale byte of token i and slice e undoes the block scale when e <= p_i and is
+//     2^-127 otherwise, so one accumulator chain over the slices yields sum_{e<=p_i} for
+//     every token at once (the leak of a masked slice is below 2^-100 of the output).
+// With D that chain and Sx the group sum of x,
+//   y += s0 * (D + (0.5 - 1.5 q_p - z0) Sx),   q_p = sum_{1 <= e <= p} 4^-e.
+//
+// Work split: the 16-row code tiles of all matrices form one list; a workgroup of 8 wavefronts
+// owns tiles blockIdx.x, blockIdx.x + gridDim.x, ...  Wavefront w owns the 256-column blocks
+// w and w + 8 of every tile, keeps their activation pieces in registers for the whole kernel
+// and streams only packed weights, always fetching the next tile before consuming the current
+// one.  The load count per tile is fixed (a slice that the tile does not need is replaced by a
+// load of one fixed KiB that stays in the vector cache), so the hardware wait counters let the
+// next tile's loads stay in flight.
+#include "mbq_common.h"
+#include "mbq_f4_prep.h"
+
+namespace mbq {
+
+typedef int intx8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace f4 {
+
+
+struct Proj {
+  const uint4* codes;
+  const float2* meta;
+  const int32_t* prec;
+  float* Y;
+  size_t slice_vec;  // uint4 per slice
+  int64_t N;
+  int tile_begin;    // index of this matrix's first tile in the joint list
+  int pad;
+};
+struct Group {
+  Proj p[MBQ_MAX_GROUP];
+  int n;
+  int tiles;
+};
+
+template <int R>
+__device__ inline uint32_t rotr(uint32_t w) {
+  if constexpr (R == 0) return w;
+  return __builtin_amdgcn_alignbit(w, w, R);
+}
+
+// FP4 operand dwords of one packed dword of slice E: eight codes of k-step 0, eight of k-step 1.
+// The unrotated field of (step, slot s = 2j + h) sits at bit 16h + 4j + 2 step and slice E is
+// stored rotated left by 2 - 2E; nibble 4h + j of the result holds slot 2j + h.
+template <int E>
+__device__ inline void nibbles(uint32_t w, uint32_t mask, int& step0, int& step1) {
+  constexpr int r0 = (2 - 2 * E) & 31, r1 = (4 - 2 * E) & 31;
+  step0 = (int)(rotr<r0>(w) & mask);
+  step1 = (int)(rotr<r1>(w) & mask);
+}
+
+template <int E>
+__device__ inline floatx4 slice_group(const intx8* A, uint32_t w_lo, uint32_t w_hi, uint32_t mask, int sa, int sb,
+                                       floatx4 D) {
+  intx8 B = {0, 0, 0, 0, 0, 0, 0, 0};
+  int b0, b1, b2, b3;
+  nibbles<E>(w_lo, mask, b0, b1);
+  nibbles<E>(w_hi, mask, b2, b3);
+  B[0] = b0; B[1] = b1; B[2] = b2; B[3] = b3;
+#pragma unroll
+  for (int piece = 0; piece < kPieces; ++piece)
+    D = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A[piece], B, D, 1 /* A: BF8 */, 4 /* B: FP4 */, E, sa, E, sb);
+  return D;
+}
+
+struct Item {  // one 16 x 256 block: four slices and the {s0, z0} of its two groups
+  uint4 w[4];
+  float2 mt[2];
+};
+
+}  // namespace f4
+
+template <int kWaves, int CPW>
+__global__ __launch_bounds__(kWaves * 64) void decode_f4_kernel(const char* __restrict__ prep, int T, int KB,
+                                                                     const f4::Group g) {
+  using namespace f4;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 15;   // token row of A / weight row of B / output column
+  const int kq = lane >> 4;  // k sub-block; output rows 4 kq .. 4 kq + 3
+  const int my_tiles = (g.tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  if (my_tiles <= 0) return;
+
+  __shared__ float red[2][kWaves][64][4];  // per-wavefront partial tiles, double buffered
+
+  // ---- precisions of every matrix (the first loads issued: what depends on them waits least) ----
+  int pl[MBQ_MAX_GROUP];
+#pragma unroll
+  for (int j = 0; j < MBQ_MAX_GROUP; ++j) pl[j] = (j < g.n && lane < T) ? g.p[j].prec[lane] : -1;
+
+  // ---- prepared activations of this wavefront's blocks ----
+  // block c is wave + 8 c; a block past the end contributes zeros (its token scales are set to
+  // 2^-127 and its sums to zero) and its weight loads are pointed at block 0 of the tile.
+  intx8 xa[CPW][2][kPieces];
+  floatx4 sx[CPW][2];  // group sums of the tokens 4 kq .. 4 kq + 3
+  int tok_scale[CPW];
+  int kb_of[CPW];
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) {
+    const int kb = wave + kWaves * c;
+    const bool there = kb < KB;
+    kb_of[c] = there ? kb : 0;
+    const char* base = prep + (size_t)kb_of[c] * kPrepBytesPerBlock;
+    const uint4* src = reinterpret_cast<const uint4*>(base);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int piece = 0; piece < kPieces; ++piece) {
+        const uint4 lo = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2];
+        const uint4 hi = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2 + 1];
+        xa[c][h][piece] = intx8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+      }
+      const floatx4 s = *reinterpret_cast<const floatx4*>(base + kPrepVecPerBlock * 16 + (16 * h + 4 * kq) * 4);
+      sx[c][h] = there ? s : floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int sc = reinterpret_cast<const int*>(base + kPrepVecPerBlock * 16 + 2 * 16 * 4)[m];
+    tok_scale[c] = there ? sc : 0;
+  }
+
+  const uint4* dummy = reinterpret_cast<const uint4*>(prep);  // 1 KiB that stays in the vector cache
+  auto proj_of = [&](int t) {
+    int j = 0;
+#pragma unroll
+    for (int i = 1; i < MBQ_MAX_GROUP; ++i)
+      if (i < g.n && t >= g.p[i].tile_begin) j = i;
+    return j;
+  };
+  auto load_base = [&](int t, Item (&I)[CPW]) {
+    const Proj& P = g.p[proj_of(t)];
+    const int nt = t - P.tile_begin;
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      I[c].w[0] = P.codes[((size_t)nt * KB + kb_of[c]) * 64 + lane];
+      I[c].mt[0] = P.meta[((size_t)nt * (2 * KB) + 2 * kb_of[c]) * kTileN + m];
+      I[c].mt[1] = P.meta[((size_t)nt * (2 * KB) + 2 * kb_of[c] + 1) * kTileN + m];
+    }
+  };
+  auto load_rest = [&](int t, int pm, Item (&I)[CPW]) {
+    const Proj& P = g.p[proj_of(t)];
+    const int nt = t - P.tile_begin;
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      const size_t tile = ((size_t)nt * KB + kb_of[c]) * 64 + lane;
+#pragma unroll
+      for (int e = 1; e < 4; ++e) {
+        const uint4* src = (e <= pm) ? P.codes + ((size_t)e * P.slice_vec + tile) : dummy + lane;
+        I[c].w[e] = *src;
+      }
+    }
+  };
+  Item cur[CPW], nxt[CPW];
+  load_base((int)blockIdx.x, cur);
+
+  // ---- routing facts: highest precision present per matrix ----
+  int pmax[MBQ_MAX_GROUP];
+#pragma unroll
+  for (int j = 0; j < MBQ_MAX_GROUP; ++j)
+    pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
+  auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
+  load_rest((int)blockIdx.x, pmax_of(proj_of((int)blockIdx.x)), cur);
+
+  uint32_t nib_mask = 0x33333333u;
+  asm volatile("" : "+s"(nib_mask));  // keep the mask in a register: one v_and_b32 per operand dword
+  const int sb = 0x7A7C7E80;          // B scale bytes 2^(1-2e), e = 0..3
+  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+  // one step: fetch tile ti+1 into `nx`, consume tile ti from `cu`, reduce and store
+  auto step = [&](int ti, Item (&cu)[CPW], Item (&nx)[CPW]) {
+    const int t = (int)blockIdx.x + ti * (int)gridDim.x;
+    const int tn = (int)blockIdx.x + min(ti + 1, my_tiles - 1) * (int)gridDim.x;
+    load_base(tn, nx);
+    load_rest(tn, pmax_of(proj_of(tn)), nx);
+
+    const int j = proj_of(t);
+    const int pm = pmax_of(j);
+    const int plv = j == 0 ? pl[0] : j == 1 ? pl[1] : j == 2 ? pl[2] : pl[3];
+    // A scale bytes of this lane's token (row m of the A operand): slice e counts iff e <= its precision
+    const int pa = __shfl(plv, m, 64);
+    const uint32_t gate = (pa >= 3) ? 0xFFFFFFFFu : (pa == 2) ? 0x00FFFFFFu : (pa == 1) ? 0x0000FFFFu
+                          : (pa == 0) ? 0x000000FFu : 0u;
+    float kp[4];  // 0.5 - 1.5 q_p of the output rows 4 kq + i
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int p = __shfl(plv, 4 * kq + i, 64);
+      kp[i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
+    }
+    floatx4 acc = zero4;
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      const Item& I = cu[c];
+      const int sa = (int)(((uint32_t)tok_scale[c] * 0x01010101u) & gate);
+      // the two groups of the block run as two independent accumulator chains
+      floatx4 D0 = slice_group<0>(xa[c][0], I.w[0].x, I.w[0].y, nib_mask, sa, sb, zero4);
+      floatx4 D1 = slice_group<0>(xa[c][1], I.w[0].z, I.w[0].w, nib_mask, sa, sb, zero4);
+      if (pm >= 1) {
+        D0 = slice_group<1>(xa[c][0], I.w[1].x, I.w[1].y, nib_mask, sa, sb, D0);
+        D1 = slice_group<1>(xa[c][1], I.w[1].z, I.w[1].w, nib_mask, sa, sb, D1);
+      }
+      if (pm >= 2) {
+        D0 = slice_group<2>(xa[c][0], I.w[2].x, I.w[2].y, nib_mask, sa, sb, D0);
+        D1 = slice_group<2>(xa[c][1], I.w[2].z, I.w[2].w, nib_mask, sa, sb, D1);
+      }
+      if (pm >= 3) {
+        D0 = slice_group<3>(xa[c][0], I.w[3].x, I.w[3].y, nib_mask, sa, sb, D0);
+        D1 = slice_group<3>(xa[c][1], I.w[3].z, I.w[3].w, nib_mask, sa, sb, D1);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[i] += I.mt[0].x * (D0[i] + (kp[i] - I.mt[0].y) * sx[c][0][i]);
+        acc[i] += I.mt[1].x * (D1[i] + (kp[i] - I.mt[1].y) * sx[c][1][i]);
+      }
+    }
+    // sum the wavefronts' partial tiles; rows leave in token order
+    const int buf = ti & 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[buf][wave][lane][i] = acc[i];
+    __syncthreads();
+    if (threadIdx.x < 256) {
+      const Proj& P = g.p[j];
+      const int r = threadIdx.x >> 4, cc = threadIdx.x & 15;
+      const int64_t col = (int64_t)(t - P.tile_begin) * kTileN + cc;
+      float sum = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < kWaves; ++wv) sum += red[buf][wv][16 * (r >> 2) + cc][r & 3];
+      if (r < T && col < P.N) P.Y[(int64_t)r * P.N + col] = sum;
+    }
+  };
+#pragma unroll 1
+  for (int ti = 0; ti < my_tiles; ti += 2) {
+    step(ti, cur, nxt);
+    if (ti + 1 < my_tiles) step(ti + 1, nxt, cur);
+  }
+}
+
+static int f4_compute_units() {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cached = n;
+    else
+      cached = 256;
+  }
+  return cached;
+}
+
+bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16 && sh.KB <= 16; }
+
+size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh) {
+  return decode_f4_supports(T, sh) ? (size_t)sh.KB * f4::kPrepBytesPerBlock : 0;
+}
+
+__global__ __launch_bounds__(64) void decode_f4_prep_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
+                                                            char* __restrict__ prep) {
+  f4::prep_block(X, T, K, prep, (int)blockIdx.x, (int)threadIdx.x);
+}
+
+mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, hipStream_t stream) {
+  hipLaunchKernelGGL(decode_f4_prep_kernel, dim3(KB), dim3(64), 0, stream, X, (int)T, K, reinterpret_cast<char*>(ws));
+  return hip_status(hipGetLastError(), "decode_f4_prep_kernel launch");
+}
+
+// All matrices share K (the caller has checked); T <= 16, KB <= 16; ws holds the prepared activations.
+mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
+                                   const int32_t* const* prec, float* const* Y, const void* ws,
+                                   hipStream_t stream) {
+  f4::Group g;
+  int tiles = 0;
+  for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
+    const int j = i < n ? i : 0;
+    const Shape& sh = shapes[j];
+    g.p[i].codes = reinterpret_cast<const uint4*>(blobs[j]);
+    g.p[i].meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blobs[j]) + sh.meta_offset);
+    g.p[i].prec = prec[j];
+    g.p[i].Y = Y[j];
+    g.p[i].slice_vec = sh.slice_words / 4;
+    g.p[i].N = sh.N;
+    g.p[i].tile_begin = tiles;
+    g.p[i].pad = 0;
+    if (i < n) tiles += sh.NT;
+  }
+  g.n = n;
+  g.tiles = tiles;
+  const Shape& s0 = shapes[0];
+  int per_cu = knob(2) > 0 ? knob(2) : 1;
+  int grid = f4_compute_units() * per_cu;
+  if (grid > tiles) grid = tiles;
+  const char* prep = reinterpret_cast<const char*>(ws);
+  if (s0.KB <= 8)
+    hipLaunchKernelGGL((decode_f4_kernel<8, 1>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
+  else if (knob(0) == 16)
+    hipLaunchKernelGGL((decode_f4_kernel<16, 1>), dim3(grid), dim3(1024), 0, stream, prep, (int)T, s0.KB, g);
+  else
+    hipLaunchKernelGGL((decode_f4_kernel<8, 2>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
+  return hip_status(hipGetLastError(), "decode_f4_kernel launch");
+}
+
+}  // namespace mbq

@@ -1,6 +1,7 @@
 // Router scores + argmax (paper Sec. 4.2 Eq. 4, read as one linear map to four
 // logits) and the token permutation by precision (Sec. 4.3, challenge 3).
 #include "mbq_common.h"
+#include "mbq_f4_prep.h"
 
 namespace mbq {
 
@@ -175,11 +176,21 @@ struct RouteGroup {
   RouteOut r[kRouteGroupMax];
 };
 
+//
+// The launch can carry the activation preparation of the FP4-operand decode kernel along: plane
+// blockIdx.y == n_routers of the grid prepares 256-column block blockIdx.x with its first
+// wavefront (prep == nullptr: no such plane).
 __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
-                                                          RouteGroup group, unsigned long long* words) {
+                                                          RouteGroup group, int n_routers,
+                                                          unsigned long long* words, char* prep, int prep_blocks) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if ((int)blockIdx.y == n_routers) {
+    if ((int)blockIdx.x < prep_blocks && wave == 0) f4::prep_block(X, T, K, prep, (int)blockIdx.x, lane);
+    return;
+  }
+  if ((int)blockIdx.x >= T) return;
   const RouteOut& out = group.r[blockIdx.y];
   const int tok = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint16_t* x = X + (int64_t)tok * K;
   const float* __restrict__ Wr = out.Wr;
   double acc[kP] = {0.0, 0.0, 0.0, 0.0};
@@ -285,19 +296,25 @@ static mbq_status launch_route_one(const uint16_t* X, int64_t T, int64_t K, cons
 
 // Workspace: the ticket counter of the general kernels at byte 0, the per-router words of the
 // small-batch kernel from byte 64.
+bool route_can_carry_prep(int64_t T) { return T >= 1 && T <= kSmallRouteTokens && knob(4) != 1; }
+
+// prep != nullptr (only when route_can_carry_prep(T)): the launch also prepares the activations
+// of the FP4-operand decode kernel, prep_blocks 256-column blocks, into prep.
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
-                              int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream) {
+                              int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
+                              void* prep, int prep_blocks) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
-  if (T >= 1 && T <= kSmallRouteTokens && knob(4) != 1) {
+  if (route_can_carry_prep(T)) {
     RouteGroup g;
     for (int i = 0; i < kRouteGroupMax; ++i) {
       const int j = i < n ? i : 0;
       g.r[i] = RouteOut{Wr[j], br[j], prec[j], perm[j], offsets[j], logits ? logits[j] : nullptr};
     }
     unsigned long long* words = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(ws) + 64);
-    hipLaunchKernelGGL(route_small_kernel, dim3((unsigned)T, (unsigned)n), dim3(512), 0, stream, X, (int)T, K, g,
-                       words);
+    const unsigned gx = (prep && prep_blocks > (int)T) ? (unsigned)prep_blocks : (unsigned)T;
+    hipLaunchKernelGGL(route_small_kernel, dim3(gx, (unsigned)n + (prep ? 1u : 0u)), dim3(512), 0, stream, X, (int)T,
+                       K, g, n, words, reinterpret_cast<char*>(prep), prep ? prep_blocks : 0);
     return hip_status(hipGetLastError(), "route_small_kernel launch");
   }
   for (int i = 0; i < n; ++i) {
@@ -312,7 +329,8 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
                         int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
                         hipStream_t stream) {
   double* const lg[1] = {logits};
-  return launch_route_group(X, T, K, 1, &Wr, &br, &prec, &perm, &offsets, logits ? lg : nullptr, ws, stream);
+  return launch_route_group(X, T, K, 1, &Wr, &br, &prec, &perm, &offsets, logits ? lg : nullptr, ws, stream,
+                            nullptr, 0);
 }
 
 }  // namespace mbq

@@ -184,6 +184,65 @@ def test_decode_every_highest_precision(mbq, K, pmax, T):
     assert_output_close(Y, Yref, f"decode pmax={pmax} K={K} T={T}")
 
 
+@pytest.mark.parametrize("K,T,Ns", [(4096, 16, (96, 32, 130)), (4096, 1, (64, 64)), (2048, 7, (80, 48, 16, 33)),
+                                    (768, 16, (40,)), (3072, 5, (48, 96)), (5120, 16, (48, 32)), (1024, 40, (48, 32))])
+def test_linear_group_equals_separate_calls(mbq, K, T, Ns):
+    """Several matrices over one X, each with its own routing: against the oracle and bit for bit
+    against mbq_linear (the last two shapes take the per-matrix kernels inside the group call)."""
+    print(f"[case] linear group K={K} T={T} Ns={Ns}", flush=True)
+    xb = tokens(T, K, [K, T, 9])
+    X = dev_bf16(xb).reshape(T, K)
+    blobs, routing, refs = [], [], []
+    for i, N in enumerate(Ns):
+        W = make_weight(N, K, [23, N, K, i], 4.0)
+        codes, s0, z0 = O.encode(W)
+        rng = np.random.default_rng([K, T, i])
+        prec = rng.integers(0, (i % 4) + 1 if i else 4, size=T).astype(np.int32)   # different highest precisions
+        perm, offsets = O.bucket(prec)
+        blobs.append(mbq.mbq_encode(dev(W)))
+        routing.append((dev(prec), dev(perm), dev(offsets)))
+        refs.append(O.linear(xb, codes, s0, z0, prec))
+    Ys = mbq.mbq_linear_group(X, blobs, list(Ns), K, routing)
+    torch.cuda.synchronize()
+    for i, N in enumerate(Ns):
+        assert_output_close(Ys[i].cpu().numpy(), refs[i], f"group matrix {i}")
+        single = mbq.mbq_linear(X, blobs[i], N, K, *routing[i])
+        assert torch.equal(single, Ys[i])
+
+
+@pytest.mark.parametrize("K,T,Ns", [(4096, 16, (96, 32, 130)), (2048, 1, (64, 48)), (1280, 9, (40,)), (5120, 16, (48, 32)),
+                                    (1024, 40, (48, 32))])
+def test_routed_linear_stage_equals_route_then_linear(mbq, K, T, Ns):
+    """One block stage in one call: same routing and the same outputs, bit for bit, as mbq_route_group
+    followed by mbq_linear_group, and within tolerance of the oracle; run twice on the same workspaces."""
+    print(f"[case] stage K={K} T={T} Ns={Ns}", flush=True)
+    rng = np.random.default_rng([K, T, len(Ns)])
+    xb = tokens(T, K, [K, T, 31])
+    X = dev_bf16(xb).reshape(T, K)
+    Wrs = [(rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32) for _ in Ns]
+    brs = [rng.normal(0, 0.3, size=4).astype(np.float32) for _ in Ns]
+    Ws = [make_weight(N, K, [29, N, K, i], 4.0) for i, N in enumerate(Ns)]
+    blobs = [mbq.mbq_encode(dev(W)) for W in Ws]
+    ws_r = mbq.route_workspace(T, K, "cuda")
+    ws_l = mbq.linear_workspace(T, max(Ns), K, "cuda")
+    dWr, dbr = [dev(w) for w in Wrs], [dev(b) for b in brs]
+    for _ in range(2):
+        routing, Ys = mbq.mbq_routed_linear_group(X, dWr, dbr, blobs, list(Ns), ws_route=ws_r, ws_linear=ws_l)
+        torch.cuda.synchronize()
+        routing2 = mbq.mbq_route_group(X, dWr, dbr)
+        Ys2 = mbq.mbq_linear_group(X, blobs, list(Ns), K, routing2)
+        for i, N in enumerate(Ns):
+            for a, b in zip(routing[i], routing2[i]):
+                assert torch.equal(a, b)
+            assert torch.equal(Ys[i], Ys2[i])
+            S, prec_ref, gap = O.route(xb, Wrs[i], brs[i])
+            prec = routing[i][0].cpu().numpy()
+            compare_routing(prec, prec_ref, gap, f"stage router {i}")
+            check_bucket(prec, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
+            codes, s0, z0 = O.encode(Ws[i])
+            assert_output_close(Ys[i].cpu().numpy(), O.linear(xb, codes, s0, z0, prec), f"stage matrix {i}")
+
+
 def test_linear_zero_tokens_and_bad_arguments(mbq):
     N, K = 32, 256
     W = make_weight(N, K, [17], 4.0)
