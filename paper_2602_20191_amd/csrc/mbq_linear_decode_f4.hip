@@ -1,4 +1,4 @@
-// Decode-side routed linear for one token tile (T <= 16), K <= 4096, and up to MBQ_MAX_GROUP
+// Decode-side routed linear for one token tile (T <= 16) and up to MBQ_MAX_GROUP
 // weight matrices that read the SAME activations: the 2-bit codes go to the matrix cores as FP4.
 //
 // Paper Sec. 4.2 Eq. 6 evaluated slice by slice, Y_i = sum_{e <= p_i} W_e^T X_i, with the
@@ -255,6 +255,174 @@ __global__ __launch_bounds__(kWaves * 64) void decode_f4_kernel(const char* __re
   }
 }
 
+
+// K > 4096: the activation pieces no longer fit in registers next to two weight buffers, so
+// they are streamed like the weights (they stay in L2: 12 KiB per block against 4.3 KiB of packed
+// weights from HBM).  Wavefront w walks over blocks w, w + 8, ... of a tile and over the
+// workgroup's tiles as ONE sequence of (tile, block) items, always fetching the next item before
+// consuming the current one; its partial tile stays in registers until the tile's last block, then
+// the eight partial tiles are summed through LDS.
+namespace f4 {
+struct StreamItem {
+  intx8 xa[2][kPieces];
+  floatx4 sx[2];
+  int scale;
+  Item w;
+};
+}  // namespace f4
+
+__global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __restrict__ prep, int T, int KB,
+                                                               const f4::Group g) {
+  using namespace f4;
+  constexpr int kWaves = 8;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 15, kq = lane >> 4;
+  const int my_tiles = (g.tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  if (my_tiles <= 0) return;
+  const int nblk = (KB - wave + kWaves - 1) / kWaves;  // >= 2 here (KB > 16)
+
+  __shared__ float red[2][kWaves][64][4];
+
+  int pl[MBQ_MAX_GROUP];
+#pragma unroll
+  for (int j = 0; j < MBQ_MAX_GROUP; ++j) pl[j] = (j < g.n && lane < T) ? g.p[j].prec[lane] : -1;
+
+  const uint4* dummy = reinterpret_cast<const uint4*>(prep);
+  auto proj_of = [&](int t) {
+    int j = 0;
+#pragma unroll
+    for (int i = 1; i < MBQ_MAX_GROUP; ++i)
+      if (i < g.n && t >= g.p[i].tile_begin) j = i;
+    return j;
+  };
+  // everything of item (tile t, block kb) except slices 1..3
+  auto load_first = [&](int t, int kb, StreamItem& I) {
+    const char* base = prep + (size_t)kb * kPrepBytesPerBlock;
+    const uint4* src = reinterpret_cast<const uint4*>(base);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int piece = 0; piece < kPieces; ++piece) {
+        const uint4 lo = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2];
+        const uint4 hi = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2 + 1];
+        I.xa[h][piece] = intx8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+      }
+      I.sx[h] = *reinterpret_cast<const floatx4*>(base + kPrepVecPerBlock * 16 + (16 * h + 4 * kq) * 4);
+    }
+    I.scale = reinterpret_cast<const int*>(base + kPrepVecPerBlock * 16 + 2 * 16 * 4)[m];
+    const Proj& P = g.p[proj_of(t)];
+    const int nt = t - P.tile_begin;
+    I.w.w[0] = P.codes[((size_t)nt * KB + kb) * 64 + lane];
+    I.w.mt[0] = P.meta[((size_t)nt * (2 * KB) + 2 * kb) * kTileN + m];
+    I.w.mt[1] = P.meta[((size_t)nt * (2 * KB) + 2 * kb + 1) * kTileN + m];
+  };
+  auto load_rest = [&](int t, int kb, int pm, StreamItem& I) {
+    const Proj& P = g.p[proj_of(t)];
+    const int nt = t - P.tile_begin;
+    const size_t tile = ((size_t)nt * KB + kb) * 64 + lane;
+#pragma unroll
+    for (int e = 1; e < 4; ++e) {
+      const uint4* src = (e <= pm) ? P.codes + ((size_t)e * P.slice_vec + tile) : dummy + lane;
+      I.w.w[e] = *src;
+    }
+  };
+  StreamItem A, B;
+  load_first((int)blockIdx.x, wave, A);
+
+  int pmax[MBQ_MAX_GROUP];
+#pragma unroll
+  for (int j = 0; j < MBQ_MAX_GROUP; ++j)
+    pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
+  auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
+  load_rest((int)blockIdx.x, wave, pmax_of(proj_of((int)blockIdx.x)), A);
+
+  uint32_t nib_mask = 0x33333333u;
+  asm volatile("" : "+s"(nib_mask));
+  const int sb = 0x7A7C7E80;
+  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  floatx4 acc = zero4;
+
+  // item (ti, b): tile index in this workgroup's list, block index in this wavefront's list
+  auto item = [&](int ti, int b, StreamItem& cu, StreamItem& nx) {
+    // next item: same tile, next block; or first block of the next tile; the last item refetches itself
+    int tin = ti, bn = b + 1;
+    if (bn == nblk) {
+      bn = 0;
+      tin = ti + 1;
+    }
+    if (tin == my_tiles) {
+      tin = ti;
+      bn = b;
+    }
+    const int tn = (int)blockIdx.x + tin * (int)gridDim.x;
+    load_first(tn, wave + kWaves * bn, nx);
+    load_rest(tn, wave + kWaves * bn, pmax_of(proj_of(tn)), nx);
+
+    const int t = (int)blockIdx.x + ti * (int)gridDim.x;
+    const int j = proj_of(t);
+    const int pm = pmax_of(j);
+    const int plv = j == 0 ? pl[0] : j == 1 ? pl[1] : j == 2 ? pl[2] : pl[3];
+    const int pa = __shfl(plv, m, 64);
+    const uint32_t gate = (pa >= 3) ? 0xFFFFFFFFu : (pa == 2) ? 0x00FFFFFFu : (pa == 1) ? 0x0000FFFFu
+                          : (pa == 0) ? 0x000000FFu : 0u;
+    float kp[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int p = __shfl(plv, 4 * kq + i, 64);
+      kp[i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
+    }
+    const Item& I = cu.w;
+    const int sa = (int)(((uint32_t)cu.scale * 0x01010101u) & gate);
+    floatx4 D0 = slice_group<0>(cu.xa[0], I.w[0].x, I.w[0].y, nib_mask, sa, sb, zero4);
+    floatx4 D1 = slice_group<0>(cu.xa[1], I.w[0].z, I.w[0].w, nib_mask, sa, sb, zero4);
+    if (pm >= 1) {
+      D0 = slice_group<1>(cu.xa[0], I.w[1].x, I.w[1].y, nib_mask, sa, sb, D0);
+      D1 = slice_group<1>(cu.xa[1], I.w[1].z, I.w[1].w, nib_mask, sa, sb, D1);
+    }
+    if (pm >= 2) {
+      D0 = slice_group<2>(cu.xa[0], I.w[2].x, I.w[2].y, nib_mask, sa, sb, D0);
+      D1 = slice_group<2>(cu.xa[1], I.w[2].z, I.w[2].w, nib_mask, sa, sb, D1);
+    }
+    if (pm >= 3) {
+      D0 = slice_group<3>(cu.xa[0], I.w[3].x, I.w[3].y, nib_mask, sa, sb, D0);
+      D1 = slice_group<3>(cu.xa[1], I.w[3].z, I.w[3].w, nib_mask, sa, sb, D1);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[i] += I.mt[0].x * (D0[i] + (kp[i] - I.mt[0].y) * cu.sx[0][i]);
+      acc[i] += I.mt[1].x * (D1[i] + (kp[i] - I.mt[1].y) * cu.sx[1][i]);
+    }
+    if (b == nblk - 1) {  // the tile is complete in this wavefront
+      const int buf = ti & 1;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) red[buf][wave][lane][i] = acc[i];
+      acc = zero4;
+      __syncthreads();
+      if (threadIdx.x < 256) {
+        const Proj& P = g.p[j];
+        const int r = threadIdx.x >> 4, cc = threadIdx.x & 15;
+        const int64_t col = (int64_t)(t - P.tile_begin) * kTileN + cc;
+        float sum = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) sum += red[buf][wv][16 * (r >> 2) + cc][r & 3];
+        if (r < T && col < P.N) P.Y[(int64_t)r * P.N + col] = sum;
+      }
+    }
+  };
+  const int total = my_tiles * nblk;
+  int ti = 0, b = 0;
+#pragma unroll 1
+  for (int q = 0; q < total; q += 2) {
+    item(ti, b, A, B);
+    if (++b == nblk) { b = 0; ++ti; }
+    if (q + 1 < total) {
+      item(ti, b, B, A);
+      if (++b == nblk) { b = 0; ++ti; }
+    }
+  }
+}
+
 static int f4_compute_units() {
   static int cached = 0;
   if (cached == 0) {
@@ -268,7 +436,7 @@ static int f4_compute_units() {
   return cached;
 }
 
-bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16 && sh.KB <= 16; }
+bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16; }
 
 size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh) {
   return decode_f4_supports(T, sh) ? (size_t)sh.KB * f4::kPrepBytesPerBlock : 0;
@@ -284,7 +452,7 @@ mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB
   return hip_status(hipGetLastError(), "decode_f4_prep_kernel launch");
 }
 
-// All matrices share K (the caller has checked); T <= 16, KB <= 16; ws holds the prepared activations.
+// All matrices share K (the caller has checked); T <= 16; ws holds the prepared activations.
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
                                    const int32_t* const* prec, float* const* Y, const void* ws,
                                    hipStream_t stream) {
@@ -310,7 +478,9 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
   int grid = f4_compute_units() * per_cu;
   if (grid > tiles) grid = tiles;
   const char* prep = reinterpret_cast<const char*>(ws);
-  if (s0.KB <= 8)
+  if (s0.KB > 16)
+    hipLaunchKernelGGL(decode_f4_stream_kernel, dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
+  else if (s0.KB <= 8)
     hipLaunchKernelGGL((decode_f4_kernel<8, 1>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
   else if (knob(0) == 16)
     hipLaunchKernelGGL((decode_f4_kernel<16, 1>), dim3(grid), dim3(1024), 0, stream, prep, (int)T, s0.KB, g);

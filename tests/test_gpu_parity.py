@@ -166,7 +166,7 @@ def test_linear_single_precision_is_a_dense_gemm(mbq, algo, p):
     assert_output_close(Y, dense.numpy(), f"{algo} uniform p={p}")
 
 
-@pytest.mark.parametrize("K", [768, 2048, 4096, 5120])
+@pytest.mark.parametrize("K", [768, 2048, 4096, 5120, 11008])
 @pytest.mark.parametrize("pmax", [0, 1, 2, 3])
 @pytest.mark.parametrize("T", [7, 16, 40])
 def test_decode_every_highest_precision(mbq, K, pmax, T):
