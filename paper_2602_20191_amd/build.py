@@ -21,7 +21,6 @@ SOURCES = [
     ("mbq_linear_simple.hip", []),
     ("mbq_linear_decode.hip", []),
     ("mbq_linear_decode16.hip", []),
-    ("mbq_linear_decode_group.hip", []),
     ("mbq_linear_decode_f4.hip", []),
     ("mbq_linear_prefill.hip", []),
 ]

@@ -60,18 +60,15 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
     case MBQ_ALGO_SIMPLE:
       return launch_linear_simple(X, T, blob, sh, prec, Y, s);
     case MBQ_ALGO_DECODE:
-      // One token tile and at most 4096 columns: activations stay in registers while a workgroup
-      // walks over its row tiles.  Otherwise the register-stationary chunked kernel wins when a
-      // workgroup has many row tiles; short, wide matrices (few tiles per compute unit, many
-      // chunks) keep every column block in flight instead.  Several token tiles (17..64 tokens)
-      // run as one pass per 16 precision-sorted tokens.
+      // One token tile (T <= 16): the FP4-operand kernels (activation preparation, then the
+      // linear kernel).  17..64 tokens run the bf16-operand kernels, one pass per 16
+      // precision-sorted tokens: the register-stationary chunked kernel when K <= 4096 or a
+      // workgroup has many row tiles; short, wide matrices keep every column block in flight.
       if (knob(3) == 0 && decode_f4_supports(T, sh)) {
         mbq_status st = launch_decode_f4_prep(X, T, sh.K, sh.KB, ws, s);
         if (st != MBQ_OK) return st;
         return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s);
       }
-      if (knob(3) == 3 && decode_group_supports(T, sh))
-        return launch_linear_decode_group(X, T, 1, &blob, &sh, &prec, &Y, s);
       if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 1024))
         return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
       return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
@@ -329,8 +326,6 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     if (st != MBQ_OK) return st;
     return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s);
   }
-  if (algo == MBQ_ALGO_DECODE && knob(3) == 3 && decode_group_supports(T, sh[0]))
-    return launch_linear_decode_group(X, T, n_proj, blob_host, sh, prec_host, Y_host, s);
   for (int i = 0; i < n_proj; ++i) {
     mbq_status st =
         dispatch_linear(X, T, blob_host[i], sh[i], prec_host[i], perm_host[i], offsets_host[i], Y_host[i], ws, algo, s);

@@ -76,10 +76,6 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
                                  hipStream_t stream);
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
-bool decode_group_supports(int64_t T, const Shape& sh);
-mbq_status launch_linear_decode_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
-                                      const Shape* shapes, const int32_t* const* prec, float* const* Y,
-                                      hipStream_t stream);
 bool decode_f4_supports(int64_t T, const Shape& sh);
 size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh);
 mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, hipStream_t stream);

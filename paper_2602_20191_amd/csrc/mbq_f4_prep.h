@@ -19,10 +19,11 @@ constexpr size_t kPrepBytesPerBlock = kPrepVecPerBlock * 16 + 2 * 16 * 4 + 16 * 
 // 16 c + 8 step + 4 h + j hold column 128 g + 64 (qa & 1) + 32 step + 8 (2 c + (qa >> 1)) + 2 j + h
 // of the block, which is where the FP4 operand built from lane group 2 c + (qa >> 1) of the packed
 // tile puts the matching weight.
-__device__ inline void prep_block(const uint16_t* __restrict__ X, int T, int64_t K, char* __restrict__ prep,
-                                  int kb, int lane) {
+// `token` is the row of X that is row m = lane % 16 of the tile (-1: no token, zeros); `base` is where
+// the prepared block goes.
+__device__ inline void prep_block_rows(const uint16_t* __restrict__ X, int token, int64_t K, char* __restrict__ base,
+                                       int kb, int lane) {
   const int m = lane & 15, qa = lane >> 4;
-  char* base = prep + (size_t)kb * kPrepBytesPerBlock;
   uint4* out = reinterpret_cast<uint4*>(base);
   float* sums = reinterpret_cast<float*>(base + kPrepVecPerBlock * 16);
   int* scl = reinterpret_cast<int*>(base + kPrepVecPerBlock * 16 + 2 * 16 * 4);
@@ -35,8 +36,8 @@ __device__ inline void prep_block(const uint16_t* __restrict__ X, int T, int64_t
 #pragma unroll
       for (int step = 0; step < 2; ++step) {
         const int64_t col = (int64_t)kb * kTileK + 128 * g + 64 * (qa & 1) + 32 * step + 8 * (2 * c + (qa >> 1));
-        raw[g][c][step] = (m < T && col < K) ? *reinterpret_cast<const uint4*>(X + (int64_t)m * K + col)
-                                             : uint4{0u, 0u, 0u, 0u};
+        raw[g][c][step] = (token >= 0 && col < K) ? *reinterpret_cast<const uint4*>(X + (int64_t)token * K + col)
+                                                  : uint4{0u, 0u, 0u, 0u};
       }
   // largest exponent of the token's block
   uint32_t mx = 0u;
@@ -103,6 +104,13 @@ __device__ inline void prep_block(const uint16_t* __restrict__ X, int T, int64_t
       dst[1] = uint4{(uint32_t)r[4], (uint32_t)r[5], (uint32_t)r[6], (uint32_t)r[7]};
     }
   }
+}
+
+// One token tile in original order: row m is token m.
+__device__ inline void prep_block(const uint16_t* __restrict__ X, int T, int64_t K, char* __restrict__ prep,
+                                  int kb, int lane) {
+  const int m = lane & 15;
+  prep_block_rows(X, m < T ? m : -1, K, prep + (size_t)kb * kPrepBytesPerBlock, kb, lane);
 }
 
 }  // namespace f4

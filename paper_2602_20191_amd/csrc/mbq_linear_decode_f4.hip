@@ -437,7 +437,6 @@ static int f4_compute_units() {
 }
 
 bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16; }
-
 size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh) {
   return decode_f4_supports(T, sh) ? (size_t)sh.KB * f4::kPrepBytesPerBlock : 0;
 }
@@ -482,8 +481,6 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
     hipLaunchKernelGGL(decode_f4_stream_kernel, dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
   else if (s0.KB <= 8)
     hipLaunchKernelGGL((decode_f4_kernel<8, 1>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
-  else if (knob(0) == 16)
-    hipLaunchKernelGGL((decode_f4_kernel<16, 1>), dim3(grid), dim3(1024), 0, stream, prep, (int)T, s0.KB, g);
   else
     hipLaunchKernelGGL((decode_f4_kernel<8, 2>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
   return hip_status(hipGetLastError(), "decode_f4_kernel launch");
