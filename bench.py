@@ -30,10 +30,10 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 RING = 3                        # distinct packed copies of the block rotated across steps
 STAGES = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))   # projections that share their input
-# HBM bytes per mbq_linear launch at batch 16 (mean over the seven linears) from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs of `bench.py --probe`, scaled by what the same counters read for a plain 256 MiB copy
+# HBM bytes per linear-kernel launch at batch 16 (mean over the four stages) from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of `bench.py --probe decode`, scaled by what the same counters read for a plain 256 MiB copy
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/decode_linear_hbm_traffic_llama2_7b_batch16.txt
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 32.64e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 54.05e6}
 
 
 def algorithmic_bytes(N, K, T, pmax):
