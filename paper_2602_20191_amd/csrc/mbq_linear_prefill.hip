@@ -3,16 +3,27 @@
 // Paper Sec. 4.2 Eq. 6 in the merged-code form of App. B (truncating the merged
 // integer code is the coarser quantiser): for a token of precision p,
 //   Y[i][n] = sum_g (s0/64) * ( sum_{k in g} x_ik V_nk + (0.5 * 4^(3-p) - 64 z0) * Sx[i][g] )
-// with V = I_p * 4^(3-p) the 8-bit code whose unused low digits are zero (an integer
-// <= 255, exact in bf16) and Sx the group sums of x.  Tokens arrive sorted by
-// precision (Sec. 4.3, token permutation), so a 128-row M tile has one precision and
-// reads only slices 0..p.  The integer products are exact in the fp32 MFMA
-// accumulator; the group scale is applied to each 128-column partial in fp32.
+// with V = I_p * 4^(3-p) the 8-bit code whose unused low digits are zero and Sx the group
+// sums of x.  Tokens arrive sorted by precision (Sec. 4.3, token permutation), so a tile of
+// sorted rows has one precision and reads only slices 0..p.
 //
-// Workgroup: 256 threads = 2 x 2 wavefronts, tile 128 (tokens) x 128 (outputs),
-// K step = one group of 128.  Codes are merged with a rotate + and-or per slice (the
-// blob stores slice e rotated so that the four fields of one weight line up as one
-// byte), converted with v_cvt_f32_ubyte and written to LDS as bf16.
+// How the group scale reaches the matrix cores without a second accumulator set:
+//   s0 = m * 2^t with m in [1/2, 2) chosen so that the bf16 exponent below is even.  The MFMA
+//   B operand is the exact bf16 number (OFF + V) * 2^t (OFF = 256 for p <= 2, where V/2 sits in
+//   the seven mantissa bits under a per-row exponent byte; OFF = 0 for p = 3), so a group's
+//   products are already in units of 2^t and only the mantissa factor m is left.  The running
+//   accumulator R is kept in units of the CURRENT group's m:  R <- R * (m_prev / m_cur) at a
+//   group boundary (one multiply per element, ratio in (1/4, 4)), then the group's MFMAs
+//   accumulate straight into R.  After the last group R * m_last / 64 is the sum in true units.
+//   The zero-point / offset term  -sum_g s0 (OFF/64 - half/64 + z0) Sx[i][g]  is a rank-G update
+//   done at the end with fp32 MFMAs (32x32x2), so it costs no vector work in the K loop.
+//
+// Workgroup: 512 threads = 2 (tokens) x 4 (outputs) wavefronts, tile 256 sorted tokens x 256
+// outputs, K step 64 (half a group) through two LDS buffers; wavefront tile 128 x 64 as
+// 4 x 2 MFMAs of 32x32x16.  While the matrix cores consume step h, the same wavefronts unpack
+// step h+1 into the other buffer and the global loads of step h+2 are in flight.
+// A small pre-kernel gathers the activations into sorted order (so the main kernel streams
+// contiguous rows) and writes the group sums transposed ([group][sorted row]).
 #include <type_traits>
 
 #include "mbq_common.h"
@@ -21,296 +32,512 @@ namespace mbq {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBN = 128, kBK = 128;
+constexpr int kBM = 256, kBN = 256, kBK = 32;
+constexpr int kBRowBytes = 2 * kBK + 16;           // LDS row pitch of the weight tile (80 bytes): conflict-free
+constexpr int kBSlotBytes = kBN * kBRowBytes;      // 20 KiB per weight slot, ring of three
+constexpr int kBRingBytes = 3 * kBSlotBytes;
+constexpr int kARowBytes = 2 * kBK;                // activation rows are unpadded (64 bytes), chunks swizzled
+constexpr int kASlotBytes = kBM * kARowBytes;      // 16 KiB per activation slot, ring of five
+constexpr int kSmemBytes = kBRingBytes + 5 * kASlotBytes;
+constexpr int kPadRows = 256;       // spare sorted rows after the last token (tile loads stay in bounds)
 
-__device__ inline floatx16 mfma32(const uint4& a, const uint4& b, floatx16 c) {
+__device__ inline floatx16 mfma_bf16(const u32x4& a, const u32x4& b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
                                                  c, 0, 0, 0);
 }
 
-template <int R>
-__device__ inline uint32_t rotr_c(uint32_t w) {
-  if constexpr (R == 0) return w;
-  return __builtin_amdgcn_alignbit(w, w, R);
+__device__ inline uint32_t rotr32(uint32_t w, int r) {  // r in 0..31, compile-time after inlining
+  return (r & 31) == 0 ? w : __builtin_amdgcn_alignbit(w, w, r & 31);
+}
+__host__ __device__ constexpr uint32_t rotl_c(uint32_t m, int r) {
+  return ((r & 31) == 0) ? m : ((m << (r & 31)) | (m >> (32 - (r & 31))));
 }
 
-// bf16 pair {byte B0 of m, byte B0+2 of m} as exact small integers.
-template <int B0>
-__device__ inline uint32_t bf16_pair_from_bytes(uint32_t m) {
-  const float lo = (float)((m >> (8 * B0)) & 0xFFu);
-  const float hi = (float)((m >> (8 * (B0 + 2))) & 0xFFu);
-  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
-}
-
-// Merged bytes of the 16 weights of one dword position, slices 0..p.
-// out[r], r = 0..3: byte b holds the code of (step = r & 1, slot 4(b&1) + 2(r>>1) + (b>>1)).
-__device__ inline void merge_dword(const uint32_t w[4], int p, uint32_t out[4]) {
-  auto part = [&](uint32_t ws, uint32_t mask, uint32_t o[4]) {
-    o[0] |= rotr_c<28>(ws) & mask;
-    o[1] |= rotr_c<30>(ws) & mask;
-    o[2] |= ws & mask;
-    o[3] |= rotr_c<2>(ws) & mask;
-  };
-  out[0] = out[1] = out[2] = out[3] = 0u;
-  part(w[0], 0xC0C0C0C0u, out);
-  if (p >= 1) part(w[1], 0x30303030u, out);
-  if (p >= 2) part(w[2], 0x0C0C0C0Cu, out);
-  if (p >= 3) part(w[3], 0x03030303u, out);
-}
-
-// Group sums of the activations in sorted-row order: Sx[r][g] = sum_{k in g} X[perm[r]][k].
-__global__ __launch_bounds__(256) void prefill_sx_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
-                                                         const int32_t* __restrict__ perm,
-                                                         float* __restrict__ Sx) {
-  const int G = (int)(K / kGroup);
-  const int64_t item = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;  // (row, group)
-  const int sub = threadIdx.x & 15;
-  float s = 0.f;
-  if (item < T * G) {
-    const int64_t r = item / G;
-    const int g = (int)(item % G);
-    const uint4 v = *reinterpret_cast<const uint4*>(X + (int64_t)perm[r] * K + (int64_t)g * kGroup + 8 * sub);
+// ---- pre-kernel: Xs[r][:] = X[perm[r]][:], SxT[g][r] = sum_{k in g} X[perm[r]][k] ----------
+__global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
+                                                           const int32_t* __restrict__ perm,
+                                                           uint16_t* __restrict__ Xs, float* __restrict__ SxT,
+                                                           int64_t ldT) {
+  const int64_t r = blockIdx.x;
+  const uint4* src = reinterpret_cast<const uint4*>(X + (int64_t)perm[r] * K);
+  uint4* dst = reinterpret_cast<uint4*>(Xs + r * K);
+  const int chunks = (int)(K >> 3);  // a multiple of 16: groups of 16 lanes are whole
+  for (int c = threadIdx.x; c < chunks; c += 256) {
+    const uint4 v = src[c];
+    dst[c] = v;
     const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+    float s = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) s += __uint_as_float(u[j] << 16) + __uint_as_float(u[j] & 0xFFFF0000u);
-  }
 #pragma unroll
-  for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-  if (item < T * G && sub == 0) Sx[item] = s;
+    for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 15) == 0) SxT[(int64_t)(c >> 4) * ldT + r] = s;
+  }
 }
 
-// WM = wavefront rows of the workgroup: tile = (64 WM) tokens x 128 outputs, 128 WM threads,
-// each wavefront a 64 x 64 sub-tile.  WM = 2: 128-token tiles, two workgroups per compute unit;
-// WM = 4: 256-token tiles (the unpacked weight tile feeds twice as many tokens), one workgroup
-// of eight wavefronts per compute unit.
-//
-// The K loop advances in half groups of 64 columns through two LDS buffers: while the matrix
-// cores consume half-step h from one buffer, the same wavefronts unpack half-step h+1 into the
-// other and the global loads of half-step h+2 are in flight; one barrier per half-step.
-constexpr int kHalfK = 64;
-constexpr int kHalfStride = kHalfK + 8;  // bf16 per LDS row (144 bytes): conflict-free 128-bit row reads
+// mantissa factor m of a group scale (see the header): exponent field forced to 126 or 127
+__device__ inline float scale_mantissa(float s0) {
+  return __uint_as_float((__float_as_uint(s0) & 0x00FFFFFFu) ^ 0x3F800000u);
+}
+// biased bf16 exponent E (even) of (256 + V) * 2^t
+__device__ inline uint32_t scale_exponent(float s0) { return ((__float_as_uint(s0) >> 23) + 9u) & ~1u; }
 
-template <int WM>
-__global__ __launch_bounds__(WM * 128, WM == 2 ? 2 : 1) void prefill_kernel(
-    const uint16_t* __restrict__ X, int64_t T, int64_t K, const uint32_t* __restrict__ codes, size_t slice_words,
-    const float2* __restrict__ meta, int64_t N, int KB, const int32_t* __restrict__ perm,
-    const int32_t* __restrict__ offsets, const float* __restrict__ Sx, float* __restrict__ Y) {
-  constexpr int BM = 64 * WM;
-  constexpr int THREADS = 128 * WM;
-  constexpr int A_ITERS = BM * 8 / THREADS;  // 128-bit loads of a half-step of the A tile per thread (= 4)
-  constexpr int B_ITERS = 512 / THREADS;     // (code tile, lane) dwords of a half-step of the B tile per thread
-  // ---- which (precision bucket, BM-row tile) is this workgroup's ----
-  int ty = blockIdx.y, p = -1, row0 = 0, rows = 0;
-  {
-    int lo = offsets[0];
-#pragma unroll
-    for (int q = 0; q < MBQ_N_PRECISIONS; ++q) {
-      const int hi = offsets[q + 1];
-      const int tiles = (hi - lo + BM - 1) / BM;
-      if (p < 0) {
-        if (ty < tiles) {
-          p = q;
-          row0 = lo + ty * BM;
-          rows = min(BM, hi - row0);
-        } else {
-          ty -= tiles;
-        }
-      }
-      lo = hi;
-    }
-  }
-  if (p < 0) return;
-  const int G = (int)(K / kGroup);
-  const int H = 2 * G;  // half-steps
+// LDS synchronisation that leaves global loads in flight (a full fence would wait for them).
+__device__ __forceinline__ void lds_writes_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+template <int N>
+__device__ __forceinline__ void vmem_outstanding_at_most() {  // s_waitcnt vmcnt(N), N <= 63
+  static_assert(N >= 0 && N <= 63, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (wave-uniform base).
+__device__ __forceinline__ void global_to_lds_16(const void* gptr, char* lds_base) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
+                                   (void __attribute__((address_space(3)))*)lds_base, 16, 0, 0);
+}
+
+// Loads whose completion the kernel tracks itself: the compiler sees an ordinary register result, so
+// it inserts no vmcnt wait of its own (its waits are all-or-nothing across the loop back edge and
+// would drain the activation loads that are meant to stay in flight for three steps).  Every use of
+// such a register comes after vmem_outstanding_at_most<N>() followed by settled(...) on it.
+__device__ __forceinline__ uint32_t load_dword_untracked(const uint32_t* p) {
+  uint32_t r;
+  asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  return r;
+}
+__device__ __forceinline__ void settled(uint32_t& a) { asm volatile("" : "+v"(a)); }
+
+// One tile.  P = precision index of the tile's tokens, FULL = all 256 rows are tokens.
+//
+// Schedule ("ping-pong"): the K loop advances in steps of 32 columns.  Every step has a memory
+// phase X (unpack the weights of step h+1 into LDS, issue global loads several steps ahead,
+// rescale the accumulator at a group boundary, prefetch the first operand fragments of step h)
+// and a compute phase Y (16 MFMAs), each closed by a workgroup barrier.  Wavefronts 4..7 run one
+// phase behind wavefronts 0..3 (one extra barrier up front, one at the end for 0..3), and
+// wavefronts w and w+4 share a SIMD, so a SIMD always has one wavefront feeding the matrix core
+// while the other does vector and memory work.
+// LDS: the unpacked weights (B, 256 x 32 bf16, 80-byte rows) go through a ring of three slots, so
+// the writes of step h+1 never meet the late readers of step h-2.  The activations (A) are loaded
+// by the memory pipeline directly into LDS (no registers, no vector work), three steps ahead,
+// into a ring of five unpadded 16 KiB slots whose 16-byte chunks are XOR-swizzled by the row so
+// that fragment reads are bank-conflict free; each wavefront loads 32 rows that its own half of
+// the workgroup consumes, waits for them itself (vmcnt) and publishes them with the barrier at the
+// end of a compute phase.
+template <int P, bool FULL>
+__device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, int64_t K,
+                                             const uint32_t* __restrict__ codes, size_t slice_words,
+                                             const float2* __restrict__ meta, int64_t N, int NT, int KB,
+                                             const int32_t* __restrict__ perm, const float* __restrict__ SxT,
+                                             int64_t ldT, float* __restrict__ Y, int row0, int rows, int ntile_n,
+                                             char* smem) {
+  constexpr float kOff = (P == 3) ? 0.f : 256.f;
+  constexpr float kHalf = 0.5f * (float)(1 << (2 * (3 - P)));
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-  const bool wave_has_rows = 64 * wm < rows;       // a wavefront whose 64 rows are all padding skips the MFMAs
-  const int ntile0 = blockIdx.x * (kBN / kTileN);  // first 16-row code tile of this workgroup
-  const int NT = (int)((N + kTileN - 1) / kTileN);
+  const int wm = wave >> 2, wn = wave & 3;
+  const int G = (int)(K / kGroup);
+  const int H = 4 * G;                                     // steps of 32 columns
+  const int units = FULL ? 8 : (rows + 31) >> 5;           // 32-row units that hold tokens
+  const int na = FULL ? 4 : (units - wm + 1) >> 1;         // this wavefront's units: 2a + wm, a < na
 
-  __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM][kHalfStride];
-  __shared__ __attribute__((aligned(16))) uint16_t sB[2][kBN][kHalfStride];
-  __shared__ __attribute__((aligned(16))) float sSx[2][BM];
-
-  // ---- global -> register staging of one half-step ----
-  // A: thread loads rows (tid/8) + (THREADS/8) i, columns 8 (tid%8) .. +7 of the 64-column half
-  const int a_col = 8 * (tid & 7);
-  uint32_t a_src[A_ITERS];  // row offsets in units of 8 bf16 (16 bytes); ~0u marks a padding row
-  const uint32_t k8 = (uint32_t)(K >> 3);
+  // ---- A: this wavefront loads unit 2 wn + wm (32 rows) of every step: two 1 KiB instructions ----
+  // lane -> row 16 j + (lane >> 2) of the unit, LDS chunk position lane & 3, which holds the global
+  // chunk (lane & 3) ^ ((row >> 2) & 3)
+  const int a_unit = 2 * wn + wm;
+  const int a_row = lane >> 2;                                      // + 16 j
+  const int a_chunk = (lane & 3) ^ ((a_row >> 2) & 3);              // same for j = 0, 1 (16 j adds 4 to row >> 2)
+  const uint16_t* a_src = Xs + (int64_t)(row0 + 32 * a_unit + a_row) * K + 8 * a_chunk;
+  const int64_t a_src_j = 16 * K;                                   // 16 rows further
+  char* const a_ring = smem + kBRingBytes;
+  const uint32_t a_dst = (uint32_t)(32 * a_unit * kARowBytes);      // + slot, + 1 KiB j
+  auto load_a = [&](int h, uint32_t slot) {                         // h is clamped: loads are always issued
+    const int hc = h < H ? h : H - 1;
 #pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) {
-    const int r = (tid >> 3) + (THREADS / 8) * i;
-    a_src[i] = (r < rows) ? ((uint32_t)perm[row0 + r] * k8 + (uint32_t)(tid & 7)) : ~0u;
+    for (int j = 0; j < 2; ++j)
+      global_to_lds_16(a_src + a_src_j * j + (int64_t)hc * kBK, a_ring + slot + a_dst + 1024 * j);
+  };
+  // ---- B staging: items j = 0, 1: code tile (wave + 8 j) of the 16 tiles of this workgroup ----
+  const int ntile0 = ntile_n * (kBN / kTileN);
+  uint32_t b_reg[2][2][P + 1];   // [set][item][slice]: the dword that holds steps 2 u and 2 u + 1, set = u & 1
+  uint32_t b_s0[2], b_s0_next[2];  // group scale (fp32 bits) of the item's row
+  size_t b_word[2];
+  size_t b_meta[2];
+  const uint32_t b_lds = (uint32_t)((16 * wave + (lane & 15)) * kBRowBytes + (lane >> 4) * 16);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    // row tiles past the matrix (N not a multiple of 256) read tile 0: their columns are never stored
+    const int nt = (ntile0 + wave + 8 * j < NT) ? ntile0 + wave + 8 * j : 0;
+    b_word[j] = ((size_t)nt * KB * 64 + lane) * 4;
+    b_meta[j] = (size_t)nt * (2 * KB) * kTileN + (lane & 15);
   }
-  const uint4* X4 = reinterpret_cast<const uint4*>(X);
-  uint4 a_reg[A_ITERS];
-  uint32_t b_reg[B_ITERS][4];
-  float sx_reg = 0.f;
-  auto load_half = [&](int h) {
-    const int g = h >> 1, dd = h & 1;
+  const int U = 2 * G;  // step pairs
+  auto load_b = [&](int u, int set) {  // the dword of step pair u (clamped: always issued)
+    const int uc = u < U ? u : U - 1;
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i)
-      a_reg[i] = (a_src[i] != ~0u) ? X4[(size_t)a_src[i] + (size_t)h * (kHalfK / 8)] : uint4{0u, 0u, 0u, 0u};
+    for (int j = 0; j < 2; ++j) {
+      const size_t v = b_word[j] + (size_t)(uc >> 2) * kTileWords + (uc & 3);
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) {
-      const int nt = ntile0 + wave + 2 * WM * i;
-      const size_t v = (((size_t)nt * KB + (g >> 1)) * 64 + lane) * 4 + 2 * (g & 1) + dd;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) b_reg[i][e] = (nt < NT && e <= p) ? codes[e * slice_words + v] : 0u;
+      for (int e = 0; e <= P; ++e) b_reg[set][j][e] = load_dword_untracked(codes + e * slice_words + v);
     }
-    if (dd == 0 && tid < BM) sx_reg = (tid < rows) ? Sx[(int64_t)(row0 + tid) * G + g] : 0.f;
   };
-  // registers -> LDS buffer h & 1 (A as is, B merged and converted to exact bf16 integers)
-  auto store_half = [&](int h) {
-    const int buf = h & 1;
+  auto load_b_scale = [&](int g, uint32_t (&dst)[2]) {
+    const int gc = g < G ? g : G - 1;
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i)
-      *reinterpret_cast<uint4*>(&sA[buf][(tid >> 3) + (THREADS / 8) * i][a_col]) = a_reg[i];
+    for (int j = 0; j < 2; ++j)
+      dst[j] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + b_meta[j] + (size_t)gc * kTileN));
+  };
+  // registers -> B ring slot at byte offset `slot`, unpacked to exact bf16.
+  // step = which half of the staged dword (steps alternate 0, 1).
+  auto store_b = [&](uint32_t slot, int set, int step, const uint32_t (&s0)[2]) {
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) {
-      const int nl = 16 * (wave + 2 * WM * i) + (lane & 15);
-      const int kq = lane >> 4;
-      uint32_t mg[4];
-      merge_dword(b_reg[i], p, mg);
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t E = scale_exponent(__uint_as_float(s0[j]));
+      // merged fields of the four weights with bit residue 2 r, r = step and step + 2
+      uint32_t t[2];
 #pragma unroll
-      for (int step = 0; step < 2; ++step) {
-        uint4 v;
-        v.x = bf16_pair_from_bytes<0>(mg[step]);
-        v.y = bf16_pair_from_bytes<0>(mg[step + 2]);
-        v.z = bf16_pair_from_bytes<1>(mg[step]);
-        v.w = bf16_pair_from_bytes<1>(mg[step + 2]);
-        *reinterpret_cast<uint4*>(&sB[buf][nl][32 * step + 8 * kq]) = v;
+      for (int q = 0; q < 2; ++q) {
+        const int r = step + 2 * q;
+        uint32_t bits = b_reg[set][j][0] & rotl_c(0xC0C0C0C0u, 2 * r - 4);
+        if constexpr (P >= 1) bits |= b_reg[set][j][1] & rotl_c(0x30303030u, 2 * r - 4);
+        if constexpr (P >= 2) bits |= b_reg[set][j][2] & rotl_c(0x0C0C0C0Cu, 2 * r - 4);
+        if constexpr (P >= 3) bits |= b_reg[set][j][3] & rotl_c(0x03030303u, 2 * r - 4);
+        // byte-aligned: byte b = V of slot 2 (b & 1) + (b >> 1) ...; P <= 2: one bit further, V / 2
+        t[q] = rotr32(bits, (2 * r - 4 + (P == 3 ? 0 : 1)) & 31);
       }
+      const uint32_t lo = t[0], hi = t[1];
+      u32x4 v;
+      if (P == 3) {
+        const float sc = __uint_as_float((E - 8u) << 23);  // 2^t
+        auto pair = [&](uint32_t w, int b0) {
+          const float f0 = (float)((w >> (8 * b0)) & 0xFFu) * sc;
+          const float f1 = (float)((w >> (8 * (b0 + 2))) & 0xFFu) * sc;
+          return __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x07060302u);
+        };
+        v.x = pair(lo, 0);
+        v.y = pair(hi, 0);
+        v.z = pair(lo, 1);
+        v.w = pair(hi, 1);
+      } else {
+        const uint32_t eh = (E >> 1) * 0x01010101u;  // high byte of every bf16: exponent bits 7..1
+        v.x = __builtin_amdgcn_perm(eh, lo, 0x04020400u);
+        v.y = __builtin_amdgcn_perm(eh, hi, 0x04020400u);
+        v.z = __builtin_amdgcn_perm(eh, lo, 0x04030401u);
+        v.w = __builtin_amdgcn_perm(eh, hi, 0x04030401u);
+      }
+      *reinterpret_cast<u32x4*>(smem + slot + b_lds + j * 128 * kBRowBytes) = v;
     }
-    if ((h & 1) == 0 && tid < BM) sSx[(h >> 1) & 1][tid] = sx_reg;
   };
 
-  floatx16 acc[2][2], part[2][2];
+  // ---- consumer side: this lane's two output columns and their group scales ----
+  int64_t ncol[2];
+  size_t c_meta[2];
+  bool c_ok[2];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int b = 0; b < 2; ++b) {
+    ncol[b] = (int64_t)ntile_n * kBN + 64 * wn + 32 * b + (lane & 31);
+    c_ok[b] = ncol[b] < (int64_t)NT * kTileN;
+    const int64_t n = c_ok[b] ? ncol[b] : 0;  // columns past the matrix use column 0's scales; never stored
+    c_meta[b] = (size_t)(n >> 4) * (2 * KB) * kTileN + (size_t)(n & 15);
+  }
+  float m_cur[2];
+  uint32_t m_next[2];  // raw scale bits of the next group; mantissa taken at use
+  auto load_m = [&](int g, uint32_t (&dst)[2]) {
+    const int gc = g < G ? g : G - 1;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+      dst[b] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + c_meta[b] + (size_t)gc * kTileN));
+  };
+  // fragment addresses: A row 32 (2a + wm) + (lane & 31), chunk 2 kk + (lane >> 5), swizzled
+  const int f_row = lane & 31;
+  const uint32_t fa_lds0 = (uint32_t)((32 * wm + f_row) * kARowBytes + (((lane >> 5)) ^ ((f_row >> 2) & 3)) * 16);
+  const uint32_t fa_lds1 = (uint32_t)((32 * wm + f_row) * kARowBytes + ((2 + (lane >> 5)) ^ ((f_row >> 2) & 3)) * 16);
+  const uint32_t fb_lds = (uint32_t)((64 * wn + f_row) * kBRowBytes + (lane >> 5) * 16);
+
+  floatx16 acc[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-  const float half_step = 0.5f * (float)(1 << (2 * (3 - p)));
 
-  // one half-step: stage h+1, fetch h+2, multiply h; the first half of a group starts fresh
-  // partial accumulators (zero C operand), the second half ends with the group epilogue
-  auto half = [&](int h, auto first_tag, auto rows_tag) {
-    constexpr bool kFirst = decltype(first_tag)::value;
-    constexpr bool kHasRows = decltype(rows_tag)::value;
-    if (h + 1 < H) store_half(h + 1);
-    if (h + 2 < H) load_half(h + 2);
-    if (kHasRows) {
-      const int buf = h & 1;
+  u32x4 af0[4], bf0[2];
+  auto read_frags = [&](uint32_t a_slot, uint32_t b_slot, int kk, u32x4 (&af)[4], u32x4 (&bf)[2]) {
 #pragma unroll
-      for (int kk = 0; kk < kHalfK / 16; ++kk) {
-        uint4 af[2], bf[2];
+    for (int a = 0; a < 4; ++a)
+      if (FULL || a < na)
+        af[a] = *reinterpret_cast<const u32x4*>(a_ring + a_slot + (kk ? fa_lds1 : fa_lds0) + a * 64 * kARowBytes);
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
-          af[a] = *reinterpret_cast<const uint4*>(&sA[buf][64 * wm + 32 * a + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
+    for (int b = 0; b < 2; ++b)
+      bf[b] = *reinterpret_cast<const u32x4*>(smem + b_slot + fb_lds + b * 32 * kBRowBytes + kk * 32);
+  };
+  auto mfma_frags = [&](const u32x4 (&af)[4], const u32x4 (&bf)[2]) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-          bf[b] = *reinterpret_cast<const uint4*>(&sB[buf][64 * wn + 32 * b + (lane & 31)][16 * kk + 8 * (lane >> 5)]);
+    for (int a = 0; a < 4; ++a)
+      if (FULL || a < na) {
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-          for (int b = 0; b < 2; ++b) {
-            if (kFirst && kk == 0) {
-              floatx16 z;
-#pragma unroll
-              for (int i = 0; i < 16; ++i) z[i] = 0.f;
-              part[a][b] = mfma32(af[a], bf[b], z);
-            } else {
-              part[a][b] = mfma32(af[a], bf[b], part[a][b]);
-            }
-          }
+        for (int b = 0; b < 2; ++b) acc[a][b] = mfma_bf16(af[a], bf[b], acc[a][b]);
       }
-      if (!kFirst) {
-        // group finished: scale and zero point in fp32
-        const int g = h >> 1;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const int64_t n = (int64_t)blockIdx.x * kBN + 64 * wn + 32 * b + (lane & 31);
-          float s3 = 0.f, c = 0.f;
-          if (n < (int64_t)NT * kTileN) {
-            const float2 mt = meta[((size_t)(n >> 4) * (2 * KB) + g) * kTileN + (n & 15)];
-            s3 = mt.x * (1.f / 64.f);
-            c = half_step - 64.f * mt.y;
-          }
-#pragma unroll
-          for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int r = 64 * wm + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-              acc[a][b][i] += s3 * (part[a][b][i] + c * sSx[g & 1][r]);
-            }
-        }
-      }
-    }
-    __syncthreads();
   };
 
-  load_half(0);
-  store_half(0);
-  load_half(1);
-  __syncthreads();
-  // the row test is hoisted out of the K loop: a wavefront of padding rows only stages data
-  if (wave_has_rows) {
-    for (int g = 0; g < G; ++g) {
-      half(2 * g, std::true_type{}, std::true_type{});
-      half(2 * g + 1, std::false_type{}, std::true_type{});
+  // ---- prologue: A steps 0..2 on their way, B step pairs 0 and 1 in registers, B step 0 in slot 0 ----
+  load_a(0, 0u);
+  load_a(1, kASlotBytes);
+  load_a(2, 2 * kASlotBytes);
+  load_b(0, 0);
+  load_b(1, 1);
+  load_b_scale(0, b_s0);
+  load_m(0, m_next);
+  vmem_outstanding_at_most<0>();
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+#pragma unroll
+    for (int e = 0; e <= P; ++e) settled(b_reg[0][j][e]), settled(b_reg[1][j][e]);
+    settled(b_s0[j]);
+    settled(m_next[j]);
+    m_cur[j] = scale_mantissa(__uint_as_float(m_next[j]));
+    b_s0_next[j] = b_s0[j];
+  }
+  store_b(0u, 0, 0, b_s0);
+  lds_writes_done();
+  wg_barrier();
+  if (wm == 1) wg_barrier();  // wavefronts 4..7 run one phase behind
+  // ring positions: B slots (3), A slots (5); a_cur holds step h, a_new receives step h + 3
+  uint32_t b_cur = 0u, b_nxt = kBSlotBytes, b_thr = 2 * kBSlotBytes;
+  uint32_t a_cur = 0u, a_new = 3 * kASlotBytes;
+  // VMEM instructions a wavefront issues in the memory phase of step 4g + i (A loads first)
+  constexpr int kAll[4] = {2 + 2 * (P + 1) + 4, 2, 2 + 2 * (P + 1), 2};
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int h = 4 * g + i;
+      // ================= memory phase X =================
+      __builtin_amdgcn_sched_barrier(0);
+      load_a(h + 3, a_new);
+      __builtin_amdgcn_sched_barrier(0);  // the A loads stay first in the phase (vmcnt bookkeeping below)
+      // first use of registers loaded three steps ago: everything issued since may stay in flight
+      if (i == 3) {  // set 0 and the scales of group g + 1, loaded in the phase of step 4g
+        vmem_outstanding_at_most<kAll[1] + kAll[2] + 2>();
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+          for (int e = 0; e <= P; ++e) settled(b_reg[0][j][e]);
+          settled(b_s0_next[j]);
+          settled(m_next[j]);
+        }
+      }
+      if (i == 1) {  // set 1, loaded in the phase of step 4g - 2
+        vmem_outstanding_at_most<kAll[3] + kAll[0] + 2>();
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e <= P; ++e) settled(b_reg[1][j][e]);
+      }
+      // weights of step h + 1: pair (h + 1) >> 1 lives in set ((i + 1) >> 1) & 1, half (i + 1) & 1
+      if (i == 3)
+        store_b(b_nxt, 0, 0, b_s0_next);
+      else
+        store_b(b_nxt, ((i + 1) >> 1) & 1, (i + 1) & 1, b_s0);
+      if (i == 3) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b_s0[j] = b_s0_next[j];
+      }
+      float ratio[2] = {1.f, 1.f};
+      if (i == 0 && g > 0) {
+        // group boundary: the accumulator moves to the units of this group's scale mantissa
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          ratio[b] = m_cur[b] * __builtin_amdgcn_rcpf(scale_mantissa(__uint_as_float(m_next[b])));
+          m_cur[b] = m_cur[b] / ratio[b];  // the factor actually in force (keeps the chain consistent)
+        }
+      }
+      if (i == 0) {
+        load_b(2 * g + 2, 0);  // set 0 is free: its pair (2g) was just stored for the last time
+        load_b_scale(g + 1, b_s0_next);
+        load_m(g + 1, m_next);
+      }
+      if (i == 2) load_b(2 * g + 3, 1);
+      if (i == 0 && g > 0) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int a = 0; a < 4; ++a)
+            if (FULL || a < na) {
+#pragma unroll
+              for (int q = 0; q < 16; ++q) acc[a][b][q] *= ratio[b];
+            }
+      }
+      lds_writes_done();
+      read_frags(a_cur, b_cur, 0, af0, bf0);
+      __builtin_amdgcn_sched_barrier(0);
+      wg_barrier();
+      // ================= compute phase Y =================
+      {
+        u32x4 af1[4], bf1[2];
+        read_frags(a_cur, b_cur, 1, af1, bf1);
+        mfma_frags(af0, bf0);
+        mfma_frags(af1, bf1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // the A loads of step h + 1 (issued two steps ago, first in their phase) must have landed
+      // before the barrier publishes them: everything issued after them may stay in flight
+      if (i == 0) vmem_outstanding_at_most<(kAll[2] - 2) + kAll[3] + kAll[0]>();
+      if (i == 1) vmem_outstanding_at_most<(kAll[3] - 2) + kAll[0] + kAll[1]>();
+      if (i == 2) vmem_outstanding_at_most<(kAll[0] - 2) + kAll[1] + kAll[2]>();
+      if (i == 3) vmem_outstanding_at_most<(kAll[1] - 2) + kAll[2] + kAll[3]>();
+      wg_barrier();
+      const uint32_t t3 = b_cur;
+      b_cur = b_nxt;
+      b_nxt = b_thr;
+      b_thr = t3;
+      a_cur = (a_cur == 4 * kASlotBytes) ? 0u : a_cur + kASlotBytes;
+      a_new = (a_new == 4 * kASlotBytes) ? 0u : a_new + kASlotBytes;
     }
-  } else {
-    for (int g = 0; g < G; ++g) {
-      half(2 * g, std::true_type{}, std::false_type{});
-      half(2 * g + 1, std::false_type{}, std::false_type{});
+  }
+  if (wm == 0) wg_barrier();  // balance the extra barrier of wavefronts 4..7
+  vmem_outstanding_at_most<0>();  // clamped loads past the last step: nothing may still write LDS at exit
+
+  // ---- true units, then the zero-point / offset term as a rank-G fp32 MFMA update ----
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const float f = m_cur[b] * (1.f / 64.f);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+      if (FULL || a < na) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][i] *= f;
+      }
+  }
+  {
+    constexpr float kC = (kHalf - kOff) * (1.f / 64.f);
+    const float* sx_ptr = SxT + row0 + 32 * wm + (lane & 31);
+    for (int g2 = 0; g2 < G; g2 += 2) {
+      const int g = g2 + (lane >> 5);
+      const bool valid = g < G;
+      float bv[2], av[4];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const float2 mt = (valid && c_ok[b]) ? meta[c_meta[b] + (size_t)g * kTileN] : float2{0.f, 0.f};
+        bv[b] = mt.x * (kC - mt.y);
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        if (FULL || a < na) av[a] = valid ? sx_ptr[(int64_t)g * ldT + 64 * a] : 0.f;
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        if (FULL || a < na) {
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+        }
     }
   }
 
   // ---- write the tile in original token order ----
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < 4; ++a)
+    if (FULL || a < na) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = 64 * wm + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-      if (r < rows) {
-        const int64_t tok = perm[row0 + r];
+      for (int i = 0; i < 16; ++i) {
+        const int r = 32 * (2 * a + wm) + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+        if (FULL || r < rows) {
+          const int64_t tok = perm[row0 + r];
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const int64_t n = (int64_t)blockIdx.x * kBN + 64 * wn + 32 * b + (lane & 31);
-          if (n < N) Y[tok * N + n] = acc[a][b][i];
+          for (int b = 0; b < 2; ++b)
+            if (ncol[b] < N) Y[tok * N + ncol[b]] = acc[a][b][i];
         }
       }
     }
 }
 
-size_t prefill_workspace_bytes(int64_t T, const Shape& sh) { return (size_t)T * sh.G * sizeof(float); }
+__global__ __launch_bounds__(512, 1) void prefill_kernel(const uint16_t* __restrict__ Xs, int64_t K,
+                                                         const uint32_t* __restrict__ codes, size_t slice_words,
+                                                         const float2* __restrict__ meta, int64_t N, int NT, int KB,
+                                                         const int32_t* __restrict__ perm,
+                                                         const int32_t* __restrict__ offsets,
+                                                         const float* __restrict__ SxT, int64_t ldT,
+                                                         float* __restrict__ Y, int n_tiles_n) {
+  __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
+  // ---- which tile: full tiles of every bucket first, then the ragged last tile of each bucket ----
+  const int mt = blockIdx.x / n_tiles_n, ntile_n = blockIdx.x % n_tiles_n;
+  int off[MBQ_N_PRECISIONS + 1];
+#pragma unroll
+  for (int q = 0; q <= MBQ_N_PRECISIONS; ++q) off[q] = offsets[q];
+  int p = -1, row0 = 0, rows = 0, idx = mt;
+#pragma unroll
+  for (int q = 0; q < MBQ_N_PRECISIONS; ++q) {
+    const int full = (off[q + 1] - off[q]) / kBM;
+    if (p < 0) {
+      if (idx < full) {
+        p = q;
+        row0 = off[q] + idx * kBM;
+        rows = kBM;
+      } else {
+        idx -= full;
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < MBQ_N_PRECISIONS; ++q) {
+    const int cnt = off[q + 1] - off[q];
+    const int rem = cnt % kBM;
+    if (p < 0 && rem > 0) {
+      if (idx == 0) {
+        p = q;
+        row0 = off[q] + cnt - rem;
+        rows = rem;
+      } else {
+        --idx;
+      }
+    }
+  }
+  if (p < 0) return;
+#define MBQ_TILE(PP, FF)                                                                                       \
+  prefill_tile<PP, FF>(Xs, K, codes, slice_words, meta, N, NT, KB, perm, SxT, ldT, Y, row0, rows, ntile_n, smem)
+  if (rows == kBM) {
+    switch (p) {
+      case 0: MBQ_TILE(0, true); break;
+      case 1: MBQ_TILE(1, true); break;
+      case 2: MBQ_TILE(2, true); break;
+      default: MBQ_TILE(3, true); break;
+    }
+  } else {
+    switch (p) {
+      case 0: MBQ_TILE(0, false); break;
+      case 1: MBQ_TILE(1, false); break;
+      case 2: MBQ_TILE(2, false); break;
+      default: MBQ_TILE(3, false); break;
+    }
+  }
+#undef MBQ_TILE
+}
+
+static inline int64_t prefill_ld(int64_t T) { return (T + 32 + 63) / 64 * 64; }
+
+size_t prefill_workspace_bytes(int64_t T, const Shape& sh) {
+  const size_t xs = (size_t)(T + kPadRows) * sh.K * sizeof(uint16_t);
+  const size_t sx = (size_t)sh.G * prefill_ld(T) * sizeof(float);
+  return xs + sx + 256;
+}
 
 mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                  const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
                                  hipStream_t stream) {
   const uint32_t* codes = reinterpret_cast<const uint32_t*>(blob);
   const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
-  float* Sx = reinterpret_cast<float*>(ws);
-  const int64_t items = T * sh.G * 16;
-  hipLaunchKernelGGL(prefill_sx_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, X, T, sh.K,
-                     perm, Sx);
-  mbq_status st = hip_status(hipGetLastError(), "prefill_sx_kernel launch");
+  uint16_t* Xs = reinterpret_cast<uint16_t*>(ws);
+  const size_t xs_bytes = ((size_t)(T + kPadRows) * sh.K * sizeof(uint16_t) + 255) / 256 * 256;
+  float* SxT = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + xs_bytes);
+  const int64_t ldT = prefill_ld(T);
+  hipLaunchKernelGGL(prefill_prep_kernel, dim3((unsigned)T), dim3(256), 0, stream, X, T, sh.K, perm, Xs, SxT, ldT);
+  mbq_status st = hip_status(hipGetLastError(), "prefill_prep_kernel launch");
   if (st != MBQ_OK) return st;
-  // 256-token tiles halve the unpack work per token once buckets are large enough to fill them
-  int wm = knob(5);
-  if (wm != 2 && wm != 4) wm = (T >= 1024) ? 4 : 2;
-  const int bm = 64 * wm;
-  dim3 grid((unsigned)((sh.N + kBN - 1) / kBN), (unsigned)(T / bm + MBQ_N_PRECISIONS));
-  if (wm == 4)
-    hipLaunchKernelGGL(prefill_kernel<4>, grid, dim3(512), 0, stream, X, T, sh.K, codes, sh.slice_words, meta,
-                       sh.N, sh.KB, perm, offsets, Sx, Y);
-  else
-    hipLaunchKernelGGL(prefill_kernel<2>, grid, dim3(256), 0, stream, X, T, sh.K, codes, sh.slice_words, meta,
-                       sh.N, sh.KB, perm, offsets, Sx, Y);
+  const int n_tiles_n = (int)((sh.N + kBN - 1) / kBN);
+  const int64_t m_tiles_max = T / kBM + MBQ_N_PRECISIONS;
+  hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)(m_tiles_max * n_tiles_n)), dim3(512), 0, stream, Xs, sh.K,
+                     codes, sh.slice_words, meta, sh.N, sh.NT, sh.KB, perm, offsets, SxT, ldT, Y, n_tiles_n);
   return hip_status(hipGetLastError(), "prefill_kernel launch");
 }
 
