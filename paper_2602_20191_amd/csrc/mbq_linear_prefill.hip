@@ -108,6 +108,19 @@ __device__ __forceinline__ uint32_t load_dword_untracked(const uint32_t* p) {
   return r;
 }
 __device__ __forceinline__ void settled(uint32_t& a) { asm volatile("" : "+v"(a)); }
+__device__ __forceinline__ void settled(u32x4& a) { asm volatile("" : "+v"(a)); }
+// 16 bytes per lane from LDS byte address `addr` + OFF, likewise untracked (lgkmcnt kept by hand)
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read_untracked(uint32_t addr) {
+  u32x4 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+  return r;
+}
+template <int N>
+__device__ __forceinline__ void lds_outstanding_at_most() {  // s_waitcnt lgkmcnt(N)
+  static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // One tile.  P = precision index of the tile's tokens, FULL = all 256 rows are tokens.
 //
@@ -160,7 +173,10 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   };
   // ---- B staging: items j = 0, 1: code tile (wave + 8 j) of the 16 tiles of this workgroup ----
   const int ntile0 = ntile_n * (kBN / kTileN);
-  uint32_t b_reg[2][2][P + 1];   // [set][item][slice]: the dword that holds steps 2 u and 2 u + 1, set = u & 1
+  // [set][item][slice]: the dword that holds steps 2 u and 2 u + 1.  Set 0: the group's first pair, set 1: its
+  // second pair, set 2: the next group's second pair while it is in flight (moved to set 1 once it has landed,
+  // so no register with a load in flight lives across the loop's back edge)
+  uint32_t b_reg[3][2][P + 1];
   uint32_t b_s0[2], b_s0_next[2];  // group scale (fp32 bits) of the item's row
   size_t b_word[2];
   size_t b_meta[2];
@@ -264,14 +280,31 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
   u32x4 af0[4], bf0[2];
-  auto read_frags = [&](uint32_t a_slot, uint32_t b_slot, int kk, u32x4 (&af)[4], u32x4 (&bf)[2]) {
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  // kk = which 16 columns of the step.  Full tiles issue 4 + 2 untracked reads, none waited for (the
+  // straight-line code between them and their MFMAs gives the compiler no reason to copy the
+  // registers while the reads are in flight); ragged tiles have branches there, so they use ordinary
+  // loads and the compiler's own waits.
+  auto read_frags = [&](uint32_t a_slot, uint32_t b_slot, auto kk_tag, u32x4 (&af)[4], u32x4 (&bf)[2]) {
+    constexpr int kk = decltype(kk_tag)::value;
+    if constexpr (FULL) {
+      const uint32_t a_addr = smem_lds + kBRingBytes + a_slot + (kk ? fa_lds1 : fa_lds0);
+      const uint32_t b_addr = smem_lds + b_slot + fb_lds;
+      af[0] = lds_read_untracked<0 * 64 * kARowBytes>(a_addr);
+      af[1] = lds_read_untracked<1 * 64 * kARowBytes>(a_addr);
+      af[2] = lds_read_untracked<2 * 64 * kARowBytes>(a_addr);
+      af[3] = lds_read_untracked<3 * 64 * kARowBytes>(a_addr);
+      bf[0] = lds_read_untracked<kk * 32>(b_addr);
+      bf[1] = lds_read_untracked<32 * kBRowBytes + kk * 32>(b_addr);
+    } else {
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-      if (FULL || a < na)
-        af[a] = *reinterpret_cast<const u32x4*>(a_ring + a_slot + (kk ? fa_lds1 : fa_lds0) + a * 64 * kARowBytes);
+      for (int a = 0; a < 4; ++a)
+        if (a < na)
+          af[a] = *reinterpret_cast<const u32x4*>(a_ring + a_slot + (kk ? fa_lds1 : fa_lds0) + a * 64 * kARowBytes);
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-      bf[b] = *reinterpret_cast<const u32x4*>(smem + b_slot + fb_lds + b * 32 * kBRowBytes + kk * 32);
+      for (int b = 0; b < 2; ++b)
+        bf[b] = *reinterpret_cast<const u32x4*>(smem + b_slot + fb_lds + b * 32 * kBRowBytes + kk * 32);
+    }
   };
   auto mfma_frags = [&](const u32x4 (&af)[4], const u32x4 (&bf)[2]) {
 #pragma unroll
@@ -294,7 +327,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
 #pragma unroll
-    for (int e = 0; e <= P; ++e) settled(b_reg[0][j][e]), settled(b_reg[1][j][e]);
+    for (int e = 0; e <= P; ++e) settled(b_reg[0][j][e]), settled(b_reg[1][j][e]), b_reg[2][j][e] = 0u;
     settled(b_s0[j]);
     settled(m_next[j]);
     m_cur[j] = scale_mantissa(__uint_as_float(m_next[j]));
@@ -308,7 +341,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   uint32_t b_cur = 0u, b_nxt = kBSlotBytes, b_thr = 2 * kBSlotBytes;
   uint32_t a_cur = 0u, a_new = 3 * kASlotBytes;
   // VMEM instructions a wavefront issues in the memory phase of step 4g + i (A loads first)
-  constexpr int kAll[4] = {2 + 2 * (P + 1) + 4, 2, 2 + 2 * (P + 1), 2};
+  constexpr int kAll[4] = {2 + 4 * (P + 1) + 4, 2, 2, 2};
   for (int g = 0; g < G; ++g) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -317,23 +350,21 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
       __builtin_amdgcn_sched_barrier(0);
       load_a(h + 3, a_new);
       __builtin_amdgcn_sched_barrier(0);  // the A loads stay first in the phase (vmcnt bookkeeping below)
-      // first use of registers loaded three steps ago: everything issued since may stay in flight
-      if (i == 3) {  // set 0 and the scales of group g + 1, loaded in the phase of step 4g
+      if (i == 3) {
+        // first use of what the phase of step 4g loaded (the next group's packed weights and scales):
+        // everything issued since may stay in flight
         vmem_outstanding_at_most<kAll[1] + kAll[2] + 2>();
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
 #pragma unroll
-          for (int e = 0; e <= P; ++e) settled(b_reg[0][j][e]);
+          for (int e = 0; e <= P; ++e) {
+            settled(b_reg[0][j][e]);
+            settled(b_reg[2][j][e]);
+            b_reg[1][j][e] = b_reg[2][j][e];
+          }
           settled(b_s0_next[j]);
           settled(m_next[j]);
         }
-      }
-      if (i == 1) {  // set 1, loaded in the phase of step 4g - 2
-        vmem_outstanding_at_most<kAll[3] + kAll[0] + 2>();
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int e = 0; e <= P; ++e) settled(b_reg[1][j][e]);
       }
       // weights of step h + 1: pair (h + 1) >> 1 lives in set ((i + 1) >> 1) & 1, half (i + 1) & 1
       if (i == 3)
@@ -355,10 +386,10 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
       }
       if (i == 0) {
         load_b(2 * g + 2, 0);  // set 0 is free: its pair (2g) was just stored for the last time
+        load_b(2 * g + 3, 2);
         load_b_scale(g + 1, b_s0_next);
         load_m(g + 1, m_next);
       }
-      if (i == 2) load_b(2 * g + 3, 1);
       if (i == 0 && g > 0) {
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -370,15 +401,36 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
             }
       }
       lds_writes_done();
-      read_frags(a_cur, b_cur, 0, af0, bf0);
+      read_frags(a_cur, b_cur, std::integral_constant<int, 0>{}, af0, bf0);
       __builtin_amdgcn_sched_barrier(0);
       wg_barrier();
+      __builtin_amdgcn_sched_barrier(0);
       // ================= compute phase Y =================
       {
         u32x4 af1[4], bf1[2];
-        read_frags(a_cur, b_cur, 1, af1, bf1);
-        mfma_frags(af0, bf0);
-        mfma_frags(af1, bf1);
+        __builtin_amdgcn_s_setprio(1);
+        read_frags(a_cur, b_cur, std::integral_constant<int, 1>{}, af1, bf1);
+        if constexpr (FULL) {
+          // LDS reads return in order: the first half's fragments are there once at most the second
+          // half's six reads are outstanding
+          lds_outstanding_at_most<6>();
+#pragma unroll
+          for (int a = 0; a < 4; ++a) settled(af0[a]);
+          settled(bf0[0]);
+          settled(bf0[1]);
+          mfma_frags(af0, bf0);
+          __builtin_amdgcn_sched_barrier(0);  // the first eight MFMAs are issued before the second wait
+          lds_outstanding_at_most<0>();
+#pragma unroll
+          for (int a = 0; a < 4; ++a) settled(af1[a]);
+          settled(bf1[0]);
+          settled(bf1[1]);
+          mfma_frags(af1, bf1);
+        } else {
+          mfma_frags(af0, bf0);
+          mfma_frags(af1, bf1);
+        }
+        __builtin_amdgcn_s_setprio(0);
       }
       __builtin_amdgcn_sched_barrier(0);
       // the A loads of step h + 1 (issued two steps ago, first in their phase) must have landed
