@@ -28,6 +28,15 @@
 
 #include "mbq_common.h"
 
+// 1: the packed-weight and scale loads of the K loop are issued behind the compiler's back and waited for
+// by hand (see load_dword_untracked); 0: ordinary loads, for comparison
+#ifndef MBQ_UNTRACKED
+#define MBQ_UNTRACKED 1
+#endif
+#ifndef MBQ_ABL
+#define MBQ_ABL 0  // development only: bit mask that removes parts of the full-tile loop for timing
+#endif
+
 namespace mbq {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -40,7 +49,8 @@ constexpr int kBSlotBytes = kBN * kBRowBytes;      // 20 KiB per weight slot, ri
 constexpr int kBRingBytes = 3 * kBSlotBytes;
 constexpr int kARowBytes = 2 * kBK;                // activation rows are unpadded (64 bytes), chunks swizzled
 constexpr int kASlotBytes = kBM * kARowBytes;      // 16 KiB per activation slot, ring of five
-constexpr int kSmemBytes = kBRingBytes + 5 * kASlotBytes;
+constexpr int kJunkOff = kBRingBytes + 5 * kASlotBytes;  // 256 bytes that absorb cache-warming loads
+constexpr int kSmemBytes = kJunkOff + 256;
 constexpr int kPadRows = 256;       // spare sorted rows after the last token (tile loads stay in bounds)
 
 __device__ inline floatx16 mfma_bf16(const u32x4& a, const u32x4& b, floatx16 c) {
@@ -90,7 +100,14 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 template <int N>
 __device__ __forceinline__ void vmem_outstanding_at_most() {  // s_waitcnt vmcnt(N), N <= 63
   static_assert(N >= 0 && N <= 63, "vmcnt range");
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((MBQ_ABL & 1024) ? 0 : N) : "memory");
+}
+// the same wait, needed only where registers are loaded behind the compiler's back
+template <int N>
+__device__ __forceinline__ void untracked_loads_outstanding_at_most() {
+#if MBQ_UNTRACKED
+  vmem_outstanding_at_most<N>();
+#endif
 }
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (wave-uniform base).
 __device__ __forceinline__ void global_to_lds_16(const void* gptr, char* lds_base) {
@@ -98,47 +115,66 @@ __device__ __forceinline__ void global_to_lds_16(const void* gptr, char* lds_bas
                                    (void __attribute__((address_space(3)))*)lds_base, 16, 0, 0);
 }
 
+// 4 bytes per lane into a junk LDS line: a load issued only to bring its cache line into L2 (the packed
+// weights and scales are read once, so their first touch pays the full HBM latency; touching them two
+// groups ahead leaves the real loads an L2 hit).  No register is written, so nothing can be clobbered.
+__device__ __forceinline__ void warm_line(const void* gptr, char* junk) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
+                                   (void __attribute__((address_space(3)))*)junk, 4, 0, 0);
+}
+
 // Loads whose completion the kernel tracks itself: the compiler sees an ordinary register result, so
 // it inserts no vmcnt wait of its own (its waits are all-or-nothing across the loop back edge and
 // would drain the activation loads that are meant to stay in flight for three steps).  Every use of
 // such a register comes after vmem_outstanding_at_most<N>() followed by settled(...) on it.
 __device__ __forceinline__ uint32_t load_dword_untracked(const uint32_t* p) {
+#if MBQ_UNTRACKED
   uint32_t r;
   asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
   return r;
+#else
+  return *p;
+#endif
 }
-__device__ __forceinline__ void settled(uint32_t& a) { asm volatile("" : "+v"(a)); }
-__device__ __forceinline__ void settled(u32x4& a) { asm volatile("" : "+v"(a)); }
-// 16 bytes per lane from LDS byte address `addr` + OFF, likewise untracked (lgkmcnt kept by hand)
-template <int OFF>
-__device__ __forceinline__ u32x4 lds_read_untracked(uint32_t addr) {
-  u32x4 r;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2_t load_dwordx2_untracked(const uint32_t* p) {
+#if MBQ_UNTRACKED
+  u32x2_t r;
+  asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(r) : "v"(p) : "memory");
   return r;
+#else
+  return *reinterpret_cast<const u32x2_t*>(p);
+#endif
 }
-template <int N>
-__device__ __forceinline__ void lds_outstanding_at_most() {  // s_waitcnt lgkmcnt(N)
-  static_assert(N >= 0 && N <= 15, "lgkmcnt range");
-  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+__device__ __forceinline__ void settled(u32x2_t& a) {
+#if MBQ_UNTRACKED
+  asm volatile("" : "+v"(a));
+#endif
 }
-
+__device__ __forceinline__ void settled(uint32_t& a) {
+#if MBQ_UNTRACKED
+  asm volatile("" : "+v"(a));
+#endif
+}
+// LDS fragment reads are ordinary loads; touching a fragment makes the compiler place its lgkmcnt wait here
+__device__ __forceinline__ void touch(u32x4& a) { asm volatile("" : "+v"(a)); }
 // One tile.  P = precision index of the tile's tokens, FULL = all 256 rows are tokens.
 //
-// Schedule ("ping-pong"): the K loop advances in steps of 32 columns.  Every step has a memory
-// phase X (unpack the weights of step h+1 into LDS, issue global loads several steps ahead,
-// rescale the accumulator at a group boundary, prefetch the first operand fragments of step h)
-// and a compute phase Y (16 MFMAs), each closed by a workgroup barrier.  Wavefronts 4..7 run one
-// phase behind wavefronts 0..3 (one extra barrier up front, one at the end for 0..3), and
-// wavefronts w and w+4 share a SIMD, so a SIMD always has one wavefront feeding the matrix core
-// while the other does vector and memory work.
-// LDS: the unpacked weights (B, 256 x 32 bf16, 80-byte rows) go through a ring of three slots, so
-// the writes of step h+1 never meet the late readers of step h-2.  The activations (A) are loaded
-// by the memory pipeline directly into LDS (no registers, no vector work), three steps ahead,
-// into a ring of five unpadded 16 KiB slots whose 16-byte chunks are XOR-swizzled by the row so
-// that fragment reads are bank-conflict free; each wavefront loads 32 rows that its own half of
-// the workgroup consumes, waits for them itself (vmcnt) and publishes them with the barrier at the
-// end of a compute phase.
-template <int P, bool FULL>
+// Schedule: the K loop advances in steps of 32 columns, one workgroup barrier per step.  A step has
+// a memory part X (unpack the weights of step h+2 into LDS, issue global loads several steps ahead,
+// rescale the accumulator at a group boundary) and a compute part Y (16 MFMAs on step h).
+// Wavefronts 0..3 (ORDER 0) run X then Y, wavefronts 4..7 (ORDER 1) run Y then X; wavefronts w and
+// w+4 share a SIMD, so while one of them feeds the matrix core the other does its vector and memory
+// work, and the hand-over inside a step needs no barrier.  Everything a step reads was complete at
+// the barrier that opened it: weights are written two steps ahead into a ring of three slots
+// (B, 256 x 32 bf16, 80-byte rows), so the writes of step h+2 never meet readers of step h-1.
+// The activations (A) are loaded by the memory pipeline directly into LDS (no registers, no vector
+// work), four steps ahead (two to three steps of flight), into a ring of five unpadded 16 KiB slots whose 16-byte chunks are
+// XOR-swizzled by the row so that fragment reads are bank-conflict free; each wavefront loads 32
+// rows that its own half of the workgroup consumes, waits for them itself (vmcnt) and publishes
+// them with the barrier at the end of the step.  The first half's operand fragments of a step are
+// read while the memory part runs (ORDER 1: those of the next step, before the barrier).
+template <int P, bool FULL, int ORDER>
 __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, int64_t K,
                                              const uint32_t* __restrict__ codes, size_t slice_words,
                                              const float2* __restrict__ meta, int64_t N, int NT, int KB,
@@ -161,7 +197,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   const int a_unit = 2 * wn + wm;
   const int a_row = lane >> 2;                                      // + 16 j
   const int a_chunk = (lane & 3) ^ ((a_row >> 2) & 3);              // same for j = 0, 1 (16 j adds 4 to row >> 2)
-  const uint16_t* a_src = Xs + (int64_t)(row0 + 32 * a_unit + a_row) * K + 8 * a_chunk;
+  const uint16_t* a_src = Xs + (int64_t)(((MBQ_ABL & 128) ? 0 : row0) + 32 * a_unit + a_row) * K + 8 * a_chunk;
   const int64_t a_src_j = 16 * K;                                   // 16 rows further
   char* const a_ring = smem + kBRingBytes;
   const uint32_t a_dst = (uint32_t)(32 * a_unit * kARowBytes);      // + slot, + 1 KiB j
@@ -173,10 +209,12 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   };
   // ---- B staging: items j = 0, 1: code tile (wave + 8 j) of the 16 tiles of this workgroup ----
   const int ntile0 = ntile_n * (kBN / kTileN);
-  // [set][item][slice]: the dword that holds steps 2 u and 2 u + 1.  Set 0: the group's first pair, set 1: its
-  // second pair, set 2: the next group's second pair while it is in flight (moved to set 1 once it has landed,
-  // so no register with a load in flight lives across the loop's back edge)
-  uint32_t b_reg[3][2][P + 1];
+  // packed weights of one group (four steps) per item and slice: two dwords, each holding two steps.
+  // b_cur is the group being unpacked; b_nxt receives the following group (one 8-byte load per item
+  // and slice, issued in the first step of a group, first used two steps later) and is moved into
+  // b_cur once it has landed, so no register with a load in flight lives across the loop's back edge.
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 b_cur_reg[2][P + 1], b_nxt_reg[2][P + 1];
   uint32_t b_s0[2], b_s0_next[2];  // group scale (fp32 bits) of the item's row
   size_t b_word[2];
   size_t b_meta[2];
@@ -188,14 +226,13 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
     b_word[j] = ((size_t)nt * KB * 64 + lane) * 4;
     b_meta[j] = (size_t)nt * (2 * KB) * kTileN + (lane & 15);
   }
-  const int U = 2 * G;  // step pairs
-  auto load_b = [&](int u, int set) {  // the dword of step pair u (clamped: always issued)
-    const int uc = u < U ? u : U - 1;
+  auto load_b = [&](int g, u32x2 (&dst)[2][P + 1]) {  // the two dwords of group g (clamped: always issued)
+    const int gc = g < G ? g : G - 1;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const size_t v = b_word[j] + (size_t)(uc >> 2) * kTileWords + (uc & 3);
+      const size_t v = b_word[j] + (size_t)(gc >> 1) * kTileWords + 2 * (gc & 1);
 #pragma unroll
-      for (int e = 0; e <= P; ++e) b_reg[set][j][e] = load_dword_untracked(codes + e * slice_words + v);
+      for (int e = 0; e <= P; ++e) dst[j][e] = load_dwordx2_untracked(codes + e * slice_words + v);
     }
   };
   auto load_b_scale = [&](int g, uint32_t (&dst)[2]) {
@@ -204,45 +241,62 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
     for (int j = 0; j < 2; ++j)
       dst[j] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + b_meta[j] + (size_t)gc * kTileN));
   };
-  // registers -> B ring slot at byte offset `slot`, unpacked to exact bf16.
-  // step = which half of the staged dword (steps alternate 0, 1).
-  auto store_b = [&](uint32_t slot, int set, int step, const uint32_t (&s0)[2]) {
+  // warms the lines that hold group g's packed weights and scales: 2 (P + 1) + 4 loads
+  auto warm_group = [&](int g) {
+    const int gc = g < G ? g : G - 1;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const size_t v = b_word[j] + (size_t)(gc >> 1) * kTileWords + 2 * (gc & 1);
+#pragma unroll
+      for (int e = 0; e <= P; ++e) warm_line(codes + e * slice_words + v, smem + kJunkOff);
+      warm_line(meta + b_meta[j] + (size_t)gc * kTileN, smem + kJunkOff);
+    }
+  };
+  // registers -> B ring slot, unpacked to exact bf16, in pieces that the full-tile loop spreads between
+  // its MFMAs.  b_x[j] is the per-row operand constant of the group being staged: the replicated
+  // high exponent byte (P <= 2) or the bits of 2^t (P = 3).
+  uint32_t b_x[2];
+  auto set_b_const = [&](const uint32_t (&s0)[2]) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const uint32_t E = scale_exponent(__uint_as_float(s0[j]));
-      // merged fields of the four weights with bit residue 2 r, r = step and step + 2
-      uint32_t t[2];
+      b_x[j] = (P == 3) ? ((E - 8u) << 23) : ((E >> 1) * 0x01010101u);
+    }
+  };
+  // merged fields of the four weights with bit residue 2 r (r = step or step + 2), byte aligned:
+  // byte b = V of slot 2 (b & 1) + (b >> 1) ...; P <= 2: one bit further, V / 2
+  auto merge_bits = [&](int pair, int j, int r) -> uint32_t {  // pair = which dword of the group
+    uint32_t bits = b_cur_reg[j][0][pair] & rotl_c(0xC0C0C0C0u, 2 * r - 4);
+    if constexpr (P >= 1) bits |= b_cur_reg[j][1][pair] & rotl_c(0x30303030u, 2 * r - 4);
+    if constexpr (P >= 2) bits |= b_cur_reg[j][2][pair] & rotl_c(0x0C0C0C0Cu, 2 * r - 4);
+    if constexpr (P >= 3) bits |= b_cur_reg[j][3][pair] & rotl_c(0x03030303u, 2 * r - 4);
+    return rotr32(bits, (2 * r - 4 + (P == 3 ? 0 : 1)) & 31);
+  };
+  // two bf16 pairs of one merged word: bytes (0, 2) and (1, 3)
+  auto expand_pair = [&](uint32_t w, int j, int b0) -> uint32_t {
+    if constexpr (P == 3) {
+      const float sc = __uint_as_float(b_x[j]);
+      const float f0 = (float)((w >> (8 * b0)) & 0xFFu) * sc;
+      const float f1 = (float)((w >> (8 * (b0 + 2))) & 0xFFu) * sc;
+      return __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x07060302u);
+    } else {
+      return __builtin_amdgcn_perm(b_x[j], w, b0 ? 0x04030401u : 0x04020400u);
+    }
+  };
+  auto write_b = [&](uint32_t slot, int j, const u32x4& v) {
+    *reinterpret_cast<u32x4*>(smem + slot + b_lds + j * 128 * kBRowBytes) = v;
+  };
+  // step = which half of the staged dword (steps alternate 0, 1)
+  auto store_b = [&](uint32_t slot, int pair, int step) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int r = step + 2 * q;
-        uint32_t bits = b_reg[set][j][0] & rotl_c(0xC0C0C0C0u, 2 * r - 4);
-        if constexpr (P >= 1) bits |= b_reg[set][j][1] & rotl_c(0x30303030u, 2 * r - 4);
-        if constexpr (P >= 2) bits |= b_reg[set][j][2] & rotl_c(0x0C0C0C0Cu, 2 * r - 4);
-        if constexpr (P >= 3) bits |= b_reg[set][j][3] & rotl_c(0x03030303u, 2 * r - 4);
-        // byte-aligned: byte b = V of slot 2 (b & 1) + (b >> 1) ...; P <= 2: one bit further, V / 2
-        t[q] = rotr32(bits, (2 * r - 4 + (P == 3 ? 0 : 1)) & 31);
-      }
-      const uint32_t lo = t[0], hi = t[1];
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t lo = merge_bits(pair, j, step), hi = merge_bits(pair, j, step + 2);
       u32x4 v;
-      if (P == 3) {
-        const float sc = __uint_as_float((E - 8u) << 23);  // 2^t
-        auto pair = [&](uint32_t w, int b0) {
-          const float f0 = (float)((w >> (8 * b0)) & 0xFFu) * sc;
-          const float f1 = (float)((w >> (8 * (b0 + 2))) & 0xFFu) * sc;
-          return __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x07060302u);
-        };
-        v.x = pair(lo, 0);
-        v.y = pair(hi, 0);
-        v.z = pair(lo, 1);
-        v.w = pair(hi, 1);
-      } else {
-        const uint32_t eh = (E >> 1) * 0x01010101u;  // high byte of every bf16: exponent bits 7..1
-        v.x = __builtin_amdgcn_perm(eh, lo, 0x04020400u);
-        v.y = __builtin_amdgcn_perm(eh, hi, 0x04020400u);
-        v.z = __builtin_amdgcn_perm(eh, lo, 0x04030401u);
-        v.w = __builtin_amdgcn_perm(eh, hi, 0x04030401u);
-      }
-      *reinterpret_cast<u32x4*>(smem + slot + b_lds + j * 128 * kBRowBytes) = v;
+      v.x = expand_pair(lo, j, 0);
+      v.y = expand_pair(hi, j, 0);
+      v.z = expand_pair(lo, j, 1);
+      v.w = expand_pair(hi, j, 1);
+      write_b(slot, j, v);
     }
   };
 
@@ -280,31 +334,16 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
   u32x4 af0[4], bf0[2];
-  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-  // kk = which 16 columns of the step.  Full tiles issue 4 + 2 untracked reads, none waited for (the
-  // straight-line code between them and their MFMAs gives the compiler no reason to copy the
-  // registers while the reads are in flight); ragged tiles have branches there, so they use ordinary
-  // loads and the compiler's own waits.
+  // kk = which 16 columns of the step: 4 (or na) + 2 reads of 16 bytes per lane
   auto read_frags = [&](uint32_t a_slot, uint32_t b_slot, auto kk_tag, u32x4 (&af)[4], u32x4 (&bf)[2]) {
     constexpr int kk = decltype(kk_tag)::value;
-    if constexpr (FULL) {
-      const uint32_t a_addr = smem_lds + kBRingBytes + a_slot + (kk ? fa_lds1 : fa_lds0);
-      const uint32_t b_addr = smem_lds + b_slot + fb_lds;
-      af[0] = lds_read_untracked<0 * 64 * kARowBytes>(a_addr);
-      af[1] = lds_read_untracked<1 * 64 * kARowBytes>(a_addr);
-      af[2] = lds_read_untracked<2 * 64 * kARowBytes>(a_addr);
-      af[3] = lds_read_untracked<3 * 64 * kARowBytes>(a_addr);
-      bf[0] = lds_read_untracked<kk * 32>(b_addr);
-      bf[1] = lds_read_untracked<32 * kBRowBytes + kk * 32>(b_addr);
-    } else {
 #pragma unroll
-      for (int a = 0; a < 4; ++a)
-        if (a < na)
-          af[a] = *reinterpret_cast<const u32x4*>(a_ring + a_slot + (kk ? fa_lds1 : fa_lds0) + a * 64 * kARowBytes);
+    for (int a = 0; a < 4; ++a)
+      if (FULL || a < na)
+        af[a] = *reinterpret_cast<const u32x4*>(a_ring + a_slot + (kk ? fa_lds1 : fa_lds0) + a * 64 * kARowBytes);
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-        bf[b] = *reinterpret_cast<const u32x4*>(smem + b_slot + fb_lds + b * 32 * kBRowBytes + kk * 32);
-    }
+    for (int b = 0; b < 2; ++b)
+      bf[b] = *reinterpret_cast<const u32x4*>(smem + b_slot + fb_lds + b * 32 * kBRowBytes + kk * 32);
   };
   auto mfma_frags = [&](const u32x4 (&af)[4], const u32x4 (&bf)[2]) {
 #pragma unroll
@@ -315,140 +354,244 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
       }
   };
 
-  // ---- prologue: A steps 0..2 on their way, B step pairs 0 and 1 in registers, B step 0 in slot 0 ----
+  // ---- prologue: A steps 0..3 on their way, group 0's packed weights in registers, steps 0 and 1 unpacked ----
   load_a(0, 0u);
   load_a(1, kASlotBytes);
   load_a(2, 2 * kASlotBytes);
-  load_b(0, 0);
-  load_b(1, 1);
+  load_a(3, 3 * kASlotBytes);
+  load_b(0, b_cur_reg);
   load_b_scale(0, b_s0);
   load_m(0, m_next);
   vmem_outstanding_at_most<0>();
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
 #pragma unroll
-    for (int e = 0; e <= P; ++e) settled(b_reg[0][j][e]), settled(b_reg[1][j][e]), b_reg[2][j][e] = 0u;
+    for (int e = 0; e <= P; ++e) settled(b_cur_reg[j][e]), b_nxt_reg[j][e] = b_cur_reg[j][e];
     settled(b_s0[j]);
     settled(m_next[j]);
     m_cur[j] = scale_mantissa(__uint_as_float(m_next[j]));
     b_s0_next[j] = b_s0[j];
   }
-  store_b(0u, 0, 0, b_s0);
+  set_b_const(b_s0);
+  store_b(0u, 0, 0);
+  store_b(kBSlotBytes, 0, 1);
   lds_writes_done();
   wg_barrier();
-  if (wm == 1) wg_barrier();  // wavefronts 4..7 run one phase behind
-  // ring positions: B slots (3), A slots (5); a_cur holds step h, a_new receives step h + 3
-  uint32_t b_cur = 0u, b_nxt = kBSlotBytes, b_thr = 2 * kBSlotBytes;
-  uint32_t a_cur = 0u, a_new = 3 * kASlotBytes;
-  // VMEM instructions a wavefront issues in the memory phase of step 4g + i (A loads first)
-  constexpr int kAll[4] = {2 + 4 * (P + 1) + 4, 2, 2, 2};
-  for (int g = 0; g < G; ++g) {
+  // the fragments are needed from here on (full tiles: the compiler waits for their reads at this point)
+  auto settle_frags = [&](u32x4 (&af)[4], u32x4 (&bf)[2]) {
+    if constexpr (FULL) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) touch(af[a]);
+      touch(bf[0]);
+      touch(bf[1]);
+    }
+  };
+  if (FULL || ORDER == 1) {
+    read_frags(0u, 0u, std::integral_constant<int, 0>{}, af0, bf0);
+    settle_frags(af0, bf0);
+  }
+  // ring positions: B slot of step h and of step h + 2; A slot of step h and of step h + 4 (= h - 1)
+  uint32_t b_cur = 0u, b_new = 2 * kBSlotBytes;
+  uint32_t a_cur = 0u, a_new = 4 * kASlotBytes;
+  auto b_after = [](uint32_t x) { return x == 2 * kBSlotBytes ? 0u : x + kBSlotBytes; };
+  auto a_after = [](uint32_t x) { return x == 4 * kASlotBytes ? 0u : x + kASlotBytes; };
+  // VMEM instructions a wavefront issues in step 4q + i (the two A loads first)
+  constexpr int kAll[4] = {2 + 2 * (P + 1) + 4, 2, 2, 2};
+  if constexpr (FULL) {
+    // ---- full tiles: every wavefront runs the same hand-ordered step; the vector, LDS and memory
+    // work of a step is spread between its 16 MFMAs (one scheduling fence per MFMA), so the matrix
+    // core issues back to back while the unpack runs in its shadow.  On entry to a step af0/bf0 hold
+    // the first half's fragments; the second half's are read under the first eight MFMAs and the
+    // next step's first half under the last eight.
+#define MBQ_FENCE() __builtin_amdgcn_sched_barrier(0)
+    for (int q = 0; q < G; ++q) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int h = 4 * q + i;
+        const int set = i < 2 ? 1 : 0, half = i & 1;   // which dword of b_cur and which half of it: step h + 2
+        MBQ_FENCE();
+        if (!(MBQ_ABL & 1)) load_a(h + 4, a_new);
+        MBQ_FENCE();  // the A loads stay first in the step (vmcnt bookkeeping)
+        float ratio[2] = {1.f, 1.f};
+        if (i == 0) {
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            const float r = m_cur[b] * __builtin_amdgcn_rcpf(scale_mantissa(__uint_as_float(m_next[b])));
+            ratio[b] = (q > 0) ? r : 1.f;
+            m_cur[b] = m_cur[b] / ratio[b];
+          }
+          if (!(MBQ_ABL & 256)) {
+          load_b(q + 1, b_nxt_reg);
+          load_b_scale(q + 1, b_s0_next);
+          load_m(q + 1, m_next);
+          }
+        }
+        if (i == 2) {
+          untracked_loads_outstanding_at_most<(MBQ_ABL & 512) ? 0 : kAll[1] + 2>();
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int e = 0; e <= P; ++e) settled(b_nxt_reg[j][e]), b_cur_reg[j][e] = b_nxt_reg[j][e];
+            settled(b_s0_next[j]);
+            settled(m_next[j]);
+            b_s0[j] = b_s0_next[j];
+          }
+          set_b_const(b_s0);
+        }
+        MBQ_FENCE();
+        u32x4 af1[4], bf1[2];
+        if (!(MBQ_ABL & 16)) read_frags(a_cur, b_cur, std::integral_constant<int, 1>{}, af1, bf1);
+        MBQ_FENCE();
+        uint32_t lo[2], hi[2];
+        u32x4 v[2];
+        // ---- first half: MFMA (a, b), then a piece of the unpack of item j = a / 2 ----
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            if (i == 0 && !(MBQ_ABL & 8)) {
+#pragma unroll
+              for (int e = 0; e < 16; ++e) acc[a][b][e] *= ratio[b];
+            }
+            if (!(MBQ_ABL & 32)) acc[a][b] = mfma_bf16(af0[a], bf0[b], acc[a][b]);
+            const int j = a >> 1, piece = (MBQ_ABL & 2) ? 9 : 2 * (a & 1) + b;
+            if (piece == 0) lo[j] = merge_bits(set, j, half);
+            if (piece == 1) hi[j] = merge_bits(set, j, half + 2);
+            if (piece == 2) {
+              v[j].x = expand_pair(lo[j], j, 0);
+              v[j].y = expand_pair(hi[j], j, 0);
+              v[j].z = expand_pair(lo[j], j, 1);
+              v[j].w = expand_pair(hi[j], j, 1);
+            }
+            if (piece == 3) write_b(b_new, j, v[j]);
+            MBQ_FENCE();
+          }
+        }
+        // the second half's fragments: only the two weight writes were issued after their reads
+        settle_frags(af1, bf1);
+        MBQ_FENCE();
+        if (!(MBQ_ABL & 16)) read_frags(a_after(a_cur), b_after(b_cur), std::integral_constant<int, 0>{}, af0, bf0);  // step h + 1
+        MBQ_FENCE();
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            if (!(MBQ_ABL & 32)) acc[a][b] = mfma_bf16(af1[a], bf1[b], acc[a][b]);
+            MBQ_FENCE();
+          }
+        }
+        lds_writes_done();  // the weight writes and the fragment reads of the next step
+        settle_frags(af0, bf0);
+        // the A loads of step h + 2 (issued two steps ago, first in their step) must have landed before
+        // the barrier publishes them
+        if (i == 0) vmem_outstanding_at_most<(kAll[2] - 2) + kAll[3] + kAll[0]>();
+        if (i == 1) vmem_outstanding_at_most<(kAll[3] - 2) + kAll[0] + kAll[1]>();
+        if (i == 2) vmem_outstanding_at_most<(kAll[0] - 2) + kAll[1] + kAll[2]>();
+        if (i == 3) vmem_outstanding_at_most<(kAll[1] - 2) + kAll[2] + kAll[3]>();
+        wg_barrier();
+        MBQ_FENCE();
+        b_cur = b_after(b_cur);
+        b_new = b_after(b_new);
+        a_cur = a_after(a_cur);
+        a_new = a_after(a_new);
+      }
+    }
+#undef MBQ_FENCE
+  } else
+  for (int q = 0; q < G; ++q) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int h = 4 * g + i;
-      // ================= memory phase X =================
-      __builtin_amdgcn_sched_barrier(0);
-      load_a(h + 3, a_new);
-      __builtin_amdgcn_sched_barrier(0);  // the A loads stay first in the phase (vmcnt bookkeeping below)
-      if (i == 3) {
-        // first use of what the phase of step 4g loaded (the next group's packed weights and scales):
-        // everything issued since may stay in flight
-        vmem_outstanding_at_most<kAll[1] + kAll[2] + 2>();
+      const int h = 4 * q + i;
+      // ---- memory part X of step h: weights of step h + 2 into LDS, loads, accumulator rescale ----
+      auto memory_part = [&]() {
+        load_a(h + 4, a_new);
+        __builtin_amdgcn_sched_barrier(0);  // the A loads stay first in the step (vmcnt bookkeeping)
+        if (i == 2) {
+          // first use of the next group's packed weights and scales (issued two steps ago): only step
+          // 4q+1's and this step's A loads may stay in flight
+          vmem_outstanding_at_most<kAll[1] + 2>();
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+          for (int j = 0; j < 2; ++j) {
 #pragma unroll
-          for (int e = 0; e <= P; ++e) {
-            settled(b_reg[0][j][e]);
-            settled(b_reg[2][j][e]);
-            b_reg[1][j][e] = b_reg[2][j][e];
+            for (int e = 0; e <= P; ++e) settled(b_nxt_reg[j][e]), b_cur_reg[j][e] = b_nxt_reg[j][e];
+            settled(b_s0_next[j]);
+            settled(m_next[j]);
+            b_s0[j] = b_s0_next[j];
           }
-          settled(b_s0_next[j]);
-          settled(m_next[j]);
+          set_b_const(b_s0);
         }
-      }
-      // weights of step h + 1: pair (h + 1) >> 1 lives in set ((i + 1) >> 1) & 1, half (i + 1) & 1
-      if (i == 3)
-        store_b(b_nxt, 0, 0, b_s0_next);
-      else
-        store_b(b_nxt, ((i + 1) >> 1) & 1, (i + 1) & 1, b_s0);
-      if (i == 3) {
+        // step h + 2 = 4q + i + 2: second dword of group q for i = 0, 1; first dword of group q + 1
+        // (just moved into b_cur_reg) for i = 2, 3; half i & 1
+        store_b(b_new, i < 2 ? 1 : 0, i & 1);
+        // the accumulator moves to the next group's scale mantissa between the last MFMA of a group
+        // and the first of the next: X comes before Y of the same step for ORDER 0, after it for ORDER 1
+        const bool boundary = (ORDER == 0) ? (i == 0) : (i == 3);
+        const bool rescale = boundary && ((ORDER == 0) ? (q > 0) : (q + 1 < G));
+        float ratio[2] = {1.f, 1.f};
+        if (boundary) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b_s0[j] = b_s0_next[j];
-      }
-      float ratio[2] = {1.f, 1.f};
-      if (i == 0 && g > 0) {
-        // group boundary: the accumulator moves to the units of this group's scale mantissa
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          ratio[b] = m_cur[b] * __builtin_amdgcn_rcpf(scale_mantissa(__uint_as_float(m_next[b])));
-          m_cur[b] = m_cur[b] / ratio[b];  // the factor actually in force (keeps the chain consistent)
+          for (int b = 0; b < 2; ++b) {
+            const float r = m_cur[b] * __builtin_amdgcn_rcpf(scale_mantissa(__uint_as_float(m_next[b])));
+            ratio[b] = rescale ? r : 1.f;      // a select, not a branch: fragment reads may be in flight here
+            m_cur[b] = m_cur[b] / ratio[b];    // the factor actually in force (keeps the chain consistent)
+          }
         }
-      }
-      if (i == 0) {
-        load_b(2 * g + 2, 0);  // set 0 is free: its pair (2g) was just stored for the last time
-        load_b(2 * g + 3, 2);
-        load_b_scale(g + 1, b_s0_next);
-        load_m(g + 1, m_next);
-      }
-      if (i == 0 && g > 0) {
+        if (i == 0) {
+          load_b(q + 1, b_nxt_reg);
+          load_b_scale(q + 1, b_s0_next);
+          load_m(q + 1, m_next);
+        }
+        if (boundary) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+          for (int b = 0; b < 2; ++b)
 #pragma unroll
-          for (int a = 0; a < 4; ++a)
-            if (FULL || a < na) {
+            for (int a = 0; a < 4; ++a)
+              if (FULL || a < na) {
 #pragma unroll
-              for (int q = 0; q < 16; ++q) acc[a][b][q] *= ratio[b];
-            }
-      }
-      lds_writes_done();
-      read_frags(a_cur, b_cur, std::integral_constant<int, 0>{}, af0, bf0);
-      __builtin_amdgcn_sched_barrier(0);
-      wg_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      // ================= compute phase Y =================
-      {
+                for (int e = 0; e < 16; ++e) acc[a][b][e] *= ratio[b];
+              }
+        }
+        lds_writes_done();  // also the end of any fragment read issued before this part
+      };
+      // ---- compute part Y of step h: 16 MFMAs; af0/bf0 hold the first half's fragments ----
+      auto compute_part = [&]() {
         u32x4 af1[4], bf1[2];
-        __builtin_amdgcn_s_setprio(1);
         read_frags(a_cur, b_cur, std::integral_constant<int, 1>{}, af1, bf1);
-        if constexpr (FULL) {
-          // LDS reads return in order: the first half's fragments are there once at most the second
-          // half's six reads are outstanding
-          lds_outstanding_at_most<6>();
-#pragma unroll
-          for (int a = 0; a < 4; ++a) settled(af0[a]);
-          settled(bf0[0]);
-          settled(bf0[1]);
-          mfma_frags(af0, bf0);
-          __builtin_amdgcn_sched_barrier(0);  // the first eight MFMAs are issued before the second wait
-          lds_outstanding_at_most<0>();
-#pragma unroll
-          for (int a = 0; a < 4; ++a) settled(af1[a]);
-          settled(bf1[0]);
-          settled(bf1[1]);
-          mfma_frags(af1, bf1);
-        } else {
-          mfma_frags(af0, bf0);
-          mfma_frags(af1, bf1);
-        }
-        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(af0, bf0);
+        __builtin_amdgcn_sched_barrier(0);  // the first eight MFMAs are issued before the wait
+        settle_frags(af1, bf1);
+        mfma_frags(af1, bf1);
+      };
+      __builtin_amdgcn_sched_barrier(0);
+      if (ORDER == 0) {
+        read_frags(a_cur, b_cur, std::integral_constant<int, 0>{}, af0, bf0);
+        memory_part();
+        settle_frags(af0, bf0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_part();
+      } else {
+        compute_part();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(a_after(a_cur), b_after(b_cur), std::integral_constant<int, 0>{}, af0, bf0);  // step h + 1
+        memory_part();
+        settle_frags(af0, bf0);
       }
       __builtin_amdgcn_sched_barrier(0);
-      // the A loads of step h + 1 (issued two steps ago, first in their phase) must have landed
-      // before the barrier publishes them: everything issued after them may stay in flight
+      // the A loads of step h + 2 (issued two steps ago, first in their step) must have landed before
+      // the barrier publishes them
       if (i == 0) vmem_outstanding_at_most<(kAll[2] - 2) + kAll[3] + kAll[0]>();
       if (i == 1) vmem_outstanding_at_most<(kAll[3] - 2) + kAll[0] + kAll[1]>();
       if (i == 2) vmem_outstanding_at_most<(kAll[0] - 2) + kAll[1] + kAll[2]>();
       if (i == 3) vmem_outstanding_at_most<(kAll[1] - 2) + kAll[2] + kAll[3]>();
       wg_barrier();
-      const uint32_t t3 = b_cur;
-      b_cur = b_nxt;
-      b_nxt = b_thr;
-      b_thr = t3;
-      a_cur = (a_cur == 4 * kASlotBytes) ? 0u : a_cur + kASlotBytes;
-      a_new = (a_new == 4 * kASlotBytes) ? 0u : a_new + kASlotBytes;
+      __builtin_amdgcn_sched_barrier(0);
+      b_cur = b_after(b_cur);
+      b_new = b_after(b_new);
+      a_cur = a_after(a_cur);
+      a_new = a_after(a_new);
     }
   }
-  if (wm == 0) wg_barrier();  // balance the extra barrier of wavefronts 4..7
   vmem_outstanding_at_most<0>();  // clamped loads past the last step: nothing may still write LDS at exit
 
   // ---- true units, then the zero-point / offset term as a rank-G fp32 MFMA update ----
@@ -465,7 +608,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   {
     constexpr float kC = (kHalf - kOff) * (1.f / 64.f);
     const float* sx_ptr = SxT + row0 + 32 * wm + (lane & 31);
-    for (int g2 = 0; g2 < G; g2 += 2) {
+    for (int g2 = 0; g2 < ((MBQ_ABL & 64) ? 0 : G); g2 += 2) {
       const int g = g2 + (lane >> 5);
       const bool valid = g < G;
       float bv[2], av[4];
@@ -546,8 +689,17 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const uint16_t* __restr
     }
   }
   if (p < 0) return;
+  // wavefronts 0..3 run each step memory part first, wavefronts 4..7 compute part first (wave-uniform branch)
+  const bool first_half = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8) == 0;
 #define MBQ_TILE(PP, FF)                                                                                       \
-  prefill_tile<PP, FF>(Xs, K, codes, slice_words, meta, N, NT, KB, perm, SxT, ldT, Y, row0, rows, ntile_n, smem)
+  do {                                                                                                         \
+    if (FF || first_half)                                                                                      \
+      prefill_tile<PP, FF, 0>(Xs, K, codes, slice_words, meta, N, NT, KB, perm, SxT, ldT, Y, row0, rows,        \
+                              ntile_n, smem);                                                                  \
+    else                                                                                                       \
+      prefill_tile<PP, FF, 1>(Xs, K, codes, slice_words, meta, N, NT, KB, perm, SxT, ldT, Y, row0, rows,        \
+                              ntile_n, smem);                                                                  \
+  } while (0)
   if (rows == kBM) {
     switch (p) {
       case 0: MBQ_TILE(0, true); break;
