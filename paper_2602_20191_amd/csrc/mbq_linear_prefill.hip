@@ -19,11 +19,10 @@
 //   done at the end with fp32 MFMAs (32x32x2), so it costs no vector work in the K loop.
 //
 // Workgroup: 512 threads = 2 (tokens) x 4 (outputs) wavefronts, tile 256 sorted tokens x 256
-// outputs, K step 64 (half a group) through two LDS buffers; wavefront tile 128 x 64 as
-// 4 x 2 MFMAs of 32x32x16.  While the matrix cores consume step h, the same wavefronts unpack
-// step h+1 into the other buffer and the global loads of step h+2 are in flight.
-// A small pre-kernel gathers the activations into sorted order (so the main kernel streams
-// contiguous rows) and writes the group sums transposed ([group][sorted row]).
+// outputs, wavefront tile 128 x 64 as 4 x 2 MFMAs of 32x32x16, K step 32 (a quarter group) with
+// one workgroup barrier per step; the schedule is described at prefill_tile.  A small pre-kernel
+// gathers the activations into sorted order (so the main kernel streams contiguous rows straight
+// into LDS) and writes the group sums transposed ([group][sorted row]).
 #include <type_traits>
 
 #include "mbq_common.h"
@@ -32,9 +31,6 @@
 // by hand (see load_dword_untracked); 0: ordinary loads, for comparison
 #ifndef MBQ_UNTRACKED
 #define MBQ_UNTRACKED 1
-#endif
-#ifndef MBQ_ABL
-#define MBQ_ABL 0  // development only: bit mask that removes parts of the full-tile loop for timing
 #endif
 
 namespace mbq {
@@ -49,8 +45,7 @@ constexpr int kBSlotBytes = kBN * kBRowBytes;      // 20 KiB per weight slot, ri
 constexpr int kBRingBytes = 3 * kBSlotBytes;
 constexpr int kARowBytes = 2 * kBK;                // activation rows are unpadded (64 bytes), chunks swizzled
 constexpr int kASlotBytes = kBM * kARowBytes;      // 16 KiB per activation slot, ring of five
-constexpr int kJunkOff = kBRingBytes + 5 * kASlotBytes;  // 256 bytes that absorb cache-warming loads
-constexpr int kSmemBytes = kJunkOff + 256;
+constexpr int kSmemBytes = kBRingBytes + 5 * kASlotBytes;
 constexpr int kPadRows = 256;       // spare sorted rows after the last token (tile loads stay in bounds)
 
 __device__ inline floatx16 mfma_bf16(const u32x4& a, const u32x4& b, floatx16 c) {
@@ -100,7 +95,7 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 template <int N>
 __device__ __forceinline__ void vmem_outstanding_at_most() {  // s_waitcnt vmcnt(N), N <= 63
   static_assert(N >= 0 && N <= 63, "vmcnt range");
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((MBQ_ABL & 1024) ? 0 : N) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 // the same wait, needed only where registers are loaded behind the compiler's back
 template <int N>
@@ -113,14 +108,6 @@ __device__ __forceinline__ void untracked_loads_outstanding_at_most() {
 __device__ __forceinline__ void global_to_lds_16(const void* gptr, char* lds_base) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
                                    (void __attribute__((address_space(3)))*)lds_base, 16, 0, 0);
-}
-
-// 4 bytes per lane into a junk LDS line: a load issued only to bring its cache line into L2 (the packed
-// weights and scales are read once, so their first touch pays the full HBM latency; touching them two
-// groups ahead leaves the real loads an L2 hit).  No register is written, so nothing can be clobbered.
-__device__ __forceinline__ void warm_line(const void* gptr, char* junk) {
-  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
-                                   (void __attribute__((address_space(3)))*)junk, 4, 0, 0);
 }
 
 // Loads whose completion the kernel tracks itself: the compiler sees an ordinary register result, so
@@ -197,7 +184,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   const int a_unit = 2 * wn + wm;
   const int a_row = lane >> 2;                                      // + 16 j
   const int a_chunk = (lane & 3) ^ ((a_row >> 2) & 3);              // same for j = 0, 1 (16 j adds 4 to row >> 2)
-  const uint16_t* a_src = Xs + (int64_t)(((MBQ_ABL & 128) ? 0 : row0) + 32 * a_unit + a_row) * K + 8 * a_chunk;
+  const uint16_t* a_src = Xs + (int64_t)(row0 + 32 * a_unit + a_row) * K + 8 * a_chunk;
   const int64_t a_src_j = 16 * K;                                   // 16 rows further
   char* const a_ring = smem + kBRingBytes;
   const uint32_t a_dst = (uint32_t)(32 * a_unit * kARowBytes);      // + slot, + 1 KiB j
@@ -240,17 +227,6 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
 #pragma unroll
     for (int j = 0; j < 2; ++j)
       dst[j] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + b_meta[j] + (size_t)gc * kTileN));
-  };
-  // warms the lines that hold group g's packed weights and scales: 2 (P + 1) + 4 loads
-  auto warm_group = [&](int g) {
-    const int gc = g < G ? g : G - 1;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const size_t v = b_word[j] + (size_t)(gc >> 1) * kTileWords + 2 * (gc & 1);
-#pragma unroll
-      for (int e = 0; e <= P; ++e) warm_line(codes + e * slice_words + v, smem + kJunkOff);
-      warm_line(meta + b_meta[j] + (size_t)gc * kTileN, smem + kJunkOff);
-    }
   };
   // registers -> B ring slot, unpacked to exact bf16, in pieces that the full-tile loop spreads between
   // its MFMAs.  b_x[j] is the per-row operand constant of the group being staged: the replicated
@@ -410,7 +386,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
         const int h = 4 * q + i;
         const int set = i < 2 ? 1 : 0, half = i & 1;   // which dword of b_cur and which half of it: step h + 2
         MBQ_FENCE();
-        if (!(MBQ_ABL & 1)) load_a(h + 4, a_new);
+        load_a(h + 4, a_new);
         MBQ_FENCE();  // the A loads stay first in the step (vmcnt bookkeeping)
         float ratio[2] = {1.f, 1.f};
         if (i == 0) {
@@ -420,14 +396,12 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
             ratio[b] = (q > 0) ? r : 1.f;
             m_cur[b] = m_cur[b] / ratio[b];
           }
-          if (!(MBQ_ABL & 256)) {
           load_b(q + 1, b_nxt_reg);
           load_b_scale(q + 1, b_s0_next);
           load_m(q + 1, m_next);
-          }
         }
         if (i == 2) {
-          untracked_loads_outstanding_at_most<(MBQ_ABL & 512) ? 0 : kAll[1] + 2>();
+          untracked_loads_outstanding_at_most<kAll[1] + 2>();
 #pragma unroll
           for (int j = 0; j < 2; ++j) {
 #pragma unroll
@@ -440,7 +414,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
         }
         MBQ_FENCE();
         u32x4 af1[4], bf1[2];
-        if (!(MBQ_ABL & 16)) read_frags(a_cur, b_cur, std::integral_constant<int, 1>{}, af1, bf1);
+        read_frags(a_cur, b_cur, std::integral_constant<int, 1>{}, af1, bf1);
         MBQ_FENCE();
         uint32_t lo[2], hi[2];
         u32x4 v[2];
@@ -449,12 +423,12 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
         for (int a = 0; a < 4; ++a) {
 #pragma unroll
           for (int b = 0; b < 2; ++b) {
-            if (i == 0 && !(MBQ_ABL & 8)) {
+            if (i == 0) {
 #pragma unroll
               for (int e = 0; e < 16; ++e) acc[a][b][e] *= ratio[b];
             }
-            if (!(MBQ_ABL & 32)) acc[a][b] = mfma_bf16(af0[a], bf0[b], acc[a][b]);
-            const int j = a >> 1, piece = (MBQ_ABL & 2) ? 9 : 2 * (a & 1) + b;
+            acc[a][b] = mfma_bf16(af0[a], bf0[b], acc[a][b]);
+            const int j = a >> 1, piece = 2 * (a & 1) + b;
             if (piece == 0) lo[j] = merge_bits(set, j, half);
             if (piece == 1) hi[j] = merge_bits(set, j, half + 2);
             if (piece == 2) {
@@ -470,13 +444,13 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
         // the second half's fragments: only the two weight writes were issued after their reads
         settle_frags(af1, bf1);
         MBQ_FENCE();
-        if (!(MBQ_ABL & 16)) read_frags(a_after(a_cur), b_after(b_cur), std::integral_constant<int, 0>{}, af0, bf0);  // step h + 1
+        read_frags(a_after(a_cur), b_after(b_cur), std::integral_constant<int, 0>{}, af0, bf0);  // step h + 1
         MBQ_FENCE();
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
 #pragma unroll
           for (int b = 0; b < 2; ++b) {
-            if (!(MBQ_ABL & 32)) acc[a][b] = mfma_bf16(af1[a], bf1[b], acc[a][b]);
+            acc[a][b] = mfma_bf16(af1[a], bf1[b], acc[a][b]);
             MBQ_FENCE();
           }
         }
@@ -608,7 +582,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   {
     constexpr float kC = (kHalf - kOff) * (1.f / 64.f);
     const float* sx_ptr = SxT + row0 + 32 * wm + (lane & 31);
-    for (int g2 = 0; g2 < ((MBQ_ABL & 64) ? 0 : G); g2 += 2) {
+    for (int g2 = 0; g2 < G; g2 += 2) {
       const int g = g2 + (lane >> 5);
       const bool valid = g < G;
       float bv[2], av[4];

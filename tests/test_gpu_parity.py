@@ -166,6 +166,25 @@ def test_linear_single_precision_is_a_dense_gemm(mbq, algo, p):
     assert_output_close(Y, dense.numpy(), f"{algo} uniform p={p}")
 
 
+@pytest.mark.parametrize("N,K,T,mix", [
+    (300, 128, 70, None),            # one group (no rescale), N not a multiple of 16 or 256, one ragged tile per bucket
+    (520, 1152, 513, None),          # odd group count (tail pairs end on a single group), three column tiles
+    (272, 512, 300, (0.9, 0.1, 0.0, 0.0)),   # one full 256-row tile plus ragged rest in bucket 0, an empty bucket
+    (256, 768, 600, (0.0, 0.0, 0.5, 0.5)),   # full tiles at precisions 2 and 3 (8-bit operand path)
+])
+def test_prefill_tile_shapes(mbq, N, K, T, mix):
+    """Full and ragged 256-row tiles, group-boundary rescale, the fp32 zero-point tail, column padding."""
+    print(f"[case] prefill tiles N={N} K={K} T={T} mix={mix}", flush=True)
+    W = make_weight(N, K, [17, N, K], 4.0)
+    xb = tokens(T, K, [N, K, T, 1])
+    rng = np.random.default_rng([N, T, 3])
+    prec = (rng.integers(0, 4, size=T) if mix is None else rng.choice(4, size=T, p=mix)).astype(np.int32)
+    codes, s0, z0 = O.encode(W)
+    Yref = O.linear(xb, codes, s0, z0, prec)
+    Y = run_linear(mbq, W, xb, prec, ALGOS["prefill"])
+    assert_output_close(Y, Yref, f"prefill N={N} K={K} T={T}")
+
+
 @pytest.mark.parametrize("K", [768, 2048, 4096, 5120, 11008])
 @pytest.mark.parametrize("pmax", [0, 1, 2, 3])
 @pytest.mark.parametrize("T", [7, 16, 40])
