@@ -582,25 +582,50 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   {
     constexpr float kC = (kHalf - kOff) * (1.f / 64.f);
     const float* sx_ptr = SxT + row0 + 32 * wm + (lane & 31);
-    for (int g2 = 0; g2 < G; g2 += 2) {
+    // operands of one MFMA step (groups g2 and g2 + 1, one per half wavefront); loaded two steps
+    // ahead of their use through two register sets
+    struct TailOps {
+      float2 mt[2];
+      float av[4];
+    };
+    auto fetch = [&](int g2, TailOps& o) {
       const int g = g2 + (lane >> 5);
       const bool valid = g < G;
-      float bv[2], av[4];
+      const int gc = valid ? g : G - 1;
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        const float2 mt = (valid && c_ok[b]) ? meta[c_meta[b] + (size_t)g * kTileN] : float2{0.f, 0.f};
-        bv[b] = mt.x * (kC - mt.y);
+        const float2 mt = meta[c_meta[b] + (size_t)gc * kTileN];
+        o.mt[b] = (valid && c_ok[b]) ? mt : float2{0.f, 0.f};
       }
 #pragma unroll
       for (int a = 0; a < 4; ++a)
-        if (FULL || a < na) av[a] = valid ? sx_ptr[(int64_t)g * ldT + 64 * a] : 0.f;
+        if (FULL || a < na) {
+          const float v = sx_ptr[(int64_t)gc * ldT + 64 * a];
+          o.av[a] = valid ? v : 0.f;
+        }
+    };
+    auto apply = [&](const TailOps& o) {
+      float bv[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) bv[b] = o.mt[b].x * (kC - o.mt[b].y);
 #pragma unroll
       for (int a = 0; a < 4; ++a)
         if (FULL || a < na) {
 #pragma unroll
           for (int b = 0; b < 2; ++b)
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.av[a], bv[b], acc[a][b], 0, 0, 0);
         }
+    };
+    TailOps t0, t1;
+    fetch(0, t0);
+    if (2 < G) fetch(2, t1);
+    for (int g2 = 0; g2 < G; g2 += 4) {
+      apply(t0);
+      if (g2 + 4 < G) fetch(g2 + 4, t0);
+      if (g2 + 2 < G) {
+        apply(t1);
+        if (g2 + 6 < G) fetch(g2 + 6, t1);
+      }
     }
   }
 
