@@ -283,8 +283,8 @@ def main() -> int:
 
 def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
     """Side figures, each timed with HIP events over eager back-to-back launches:
-    the same block at the other decode batches of the config, and one prefill linear
-    (BASELINE configs[2], gate projection, 2048 tokens) as TFLOP/s."""
+    the same block at the other decode batches of the config, and the three prefill linears of
+    BASELINE configs[2] (2048 tokens) as TFLOP/s."""
     from workloads import CONFIGS, make_case
 
     extra = {}
@@ -336,33 +336,44 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
             byts += algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax) + 16 * l["spec"].K
         extra[f"decode_batch_{T}"] = {"ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
                                       "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9}
-    # one prefill linear
+    # the prefill linears of BASELINE configs[2] (gate, up, down; 2048 tokens), each as the whole mbq_linear call
+    # (gather/group-sum pre-kernel + tile kernel) timed with HIP events over back-to-back launches
     pcfg = CONFIGS[2]
     T = pcfg.token_counts[0]
-    case = make_case(pcfg, 0, T)
-    spec = pcfg.linears[0]
-    Wd = torch.from_numpy(case["W"]).to(dev)
-    blob = mbq.mbq_encode(Wd)
-    del Wd
-    X = torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev)
-    Wr, br = torch.from_numpy(case["Wr"]).to(dev), torch.from_numpy(case["br"]).to(dev)
-    prec, perm, offsets = mbq.mbq_route(X, Wr, br)
-    Y = torch.empty((T, spec.N), dtype=torch.float32, device=dev)
-    ws = mbq.linear_workspace(T, spec.N, spec.K, dev)
-    for _ in range(2):
-        mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
-    a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n = 10
-    a.record()
-    for _ in range(n):
-        mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
-    b2.record()
-    torch.cuda.synchronize()
-    ms = a.elapsed_time(b2) / n
-    tf = 2.0 * T * spec.N * spec.K / (ms * 1e-3) / 1e12
-    extra["prefill_gate_2048tok"] = {"workload": "BASELINE configs[2] gate 11008x4096, 2048 tokens, {50,30,15,5}% mix + 2% outlier tokens",
-                                     "ms": ms, "tflops": tf, "mfma_bf16_peak_tflops": 2500.0, "frac": tf / 2500.0,
-                                     "mix": np.bincount(prec.cpu().numpy(), minlength=4).tolist()}
+    per_linear, flops_sum, ms_sum = {}, 0.0, 0.0
+    for li, spec in enumerate(pcfg.linears):
+        case = make_case(pcfg, li, T)
+        Wd = torch.from_numpy(case["W"]).to(dev)
+        blob = mbq.mbq_encode(Wd)
+        del Wd
+        X = torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev)
+        Wr, br = torch.from_numpy(case["Wr"]).to(dev), torch.from_numpy(case["br"]).to(dev)
+        prec, perm, offsets = mbq.mbq_route(X, Wr, br)
+        Y = torch.empty((T, spec.N), dtype=torch.float32, device=dev)
+        ws = mbq.linear_workspace(T, spec.N, spec.K, dev)
+        for _ in range(3):
+            mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
+        a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 20
+        a.record()
+        for _ in range(n):
+            mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
+        b2.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b2) / n
+        flops = 2.0 * T * spec.N * spec.K
+        per_linear[spec.name] = {"N": spec.N, "K": spec.K, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+                                 "mix": np.bincount(prec.cpu().numpy(), minlength=4).tolist()}
+        flops_sum += flops
+        ms_sum += ms
+        del blob, X, Y, ws
+    tf = flops_sum / (ms_sum * 1e-3) / 1e12
+    extra["prefill_mlp_2048tok"] = {
+        "workload": "BASELINE configs[2]: gate/up 11008x4096 and down 4096x11008, 2048 tokens, {50,30,15,5}% mix + 2% "
+                    "outlier tokens at 8 bits; useful flops 2 T N K over the whole mbq_linear call",
+        "ms_total": ms_sum, "tflops": tf, "per_linear": per_linear,
+        "roofline": {"bound": "mfma", "kernel": "mbq::prefill_kernel (+ mbq::prefill_prep_kernel)", "achieved": tf,
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
     return extra
 
 
