@@ -60,12 +60,15 @@ __host__ __device__ constexpr uint32_t rotl_c(uint32_t m, int r) {
   return ((r & 31) == 0) ? m : ((m << (r & 31)) | (m >> (32 - (r & 31))));
 }
 
-// ---- pre-kernel: Xs[r][:] = X[perm[r]][:], SxT[g][r] = sum_{k in g} X[perm[r]][k] ----------
+// ---- pre-kernel: Xs[r][:] = X[perm[r]][:], SxT[g][r] = sum_{k in g} X[perm[r]][k];
+// with a K split also Y[r][:] = 0 (the tile kernel then adds its partial sums) ----------
 __global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
                                                            const int32_t* __restrict__ perm,
                                                            uint16_t* __restrict__ Xs, float* __restrict__ SxT,
-                                                           int64_t ldT) {
+                                                           int64_t ldT, float* __restrict__ Yzero, int64_t N) {
   const int64_t r = blockIdx.x;
+  if (Yzero)
+    for (int64_t n = threadIdx.x; n < N; n += 256) Yzero[r * N + n] = 0.f;
   const uint4* src = reinterpret_cast<const uint4*>(X + (int64_t)perm[r] * K);
   uint4* dst = reinterpret_cast<uint4*>(Xs + r * K);
   const int chunks = (int)(K >> 3);  // a multiple of 16: groups of 16 lanes are whole
@@ -167,13 +170,13 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
                                              const float2* __restrict__ meta, int64_t N, int NT, int KB,
                                              const int32_t* __restrict__ perm, const float* __restrict__ SxT,
                                              int64_t ldT, float* __restrict__ Y, int row0, int rows, int ntile_n,
-                                             char* smem) {
+                                             char* smem, int g0, int Gs, bool accumulate) {
   constexpr float kOff = (P == 3) ? 0.f : 256.f;
   constexpr float kHalf = 0.5f * (float)(1 << (2 * (3 - P)));
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
-  const int G = (int)(K / kGroup);
+  const int G = Gs;                                        // this workgroup's groups: g0 .. g0 + Gs - 1
   const int H = 4 * G;                                     // steps of 32 columns
   const int units = FULL ? 8 : (rows + 31) >> 5;           // 32-row units that hold tokens
   const int na = FULL ? 4 : (units - wm + 1) >> 1;         // this wavefront's units: 2a + wm, a < na
@@ -184,7 +187,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   const int a_unit = 2 * wn + wm;
   const int a_row = lane >> 2;                                      // + 16 j
   const int a_chunk = (lane & 3) ^ ((a_row >> 2) & 3);              // same for j = 0, 1 (16 j adds 4 to row >> 2)
-  const uint16_t* a_src = Xs + (int64_t)(row0 + 32 * a_unit + a_row) * K + 8 * a_chunk;
+  const uint16_t* a_src = Xs + (int64_t)(row0 + 32 * a_unit + a_row) * K + (int64_t)g0 * kGroup + 8 * a_chunk;
   const int64_t a_src_j = 16 * K;                                   // 16 rows further
   char* const a_ring = smem + kBRingBytes;
   const uint32_t a_dst = (uint32_t)(32 * a_unit * kARowBytes);      // + slot, + 1 KiB j
@@ -217,7 +220,8 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
     const int gc = g < G ? g : G - 1;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const size_t v = b_word[j] + (size_t)(gc >> 1) * kTileWords + 2 * (gc & 1);
+      const int ga = g0 + gc;
+      const size_t v = b_word[j] + (size_t)(ga >> 1) * kTileWords + 2 * (ga & 1);
 #pragma unroll
       for (int e = 0; e <= P; ++e) dst[j][e] = load_dwordx2_untracked(codes + e * slice_words + v);
     }
@@ -226,7 +230,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
     const int gc = g < G ? g : G - 1;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
-      dst[j] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + b_meta[j] + (size_t)gc * kTileN));
+      dst[j] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + b_meta[j] + (size_t)(g0 + gc) * kTileN));
   };
   // registers -> B ring slot, unpacked to exact bf16, in pieces that the full-tile loop spreads between
   // its MFMAs.  b_x[j] is the per-row operand constant of the group being staged: the replicated
@@ -293,7 +297,7 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
     const int gc = g < G ? g : G - 1;
 #pragma unroll
     for (int b = 0; b < 2; ++b)
-      dst[b] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + c_meta[b] + (size_t)gc * kTileN));
+      dst[b] = load_dword_untracked(reinterpret_cast<const uint32_t*>(meta + c_meta[b] + (size_t)(g0 + gc) * kTileN));
   };
   // fragment addresses: A row 32 (2a + wm) + (lane & 31), chunk 2 kk + (lane >> 5), swizzled
   const int f_row = lane & 31;
@@ -594,13 +598,13 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
       const int gc = valid ? g : G - 1;
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        const float2 mt = meta[c_meta[b] + (size_t)gc * kTileN];
+        const float2 mt = meta[c_meta[b] + (size_t)(g0 + gc) * kTileN];
         o.mt[b] = (valid && c_ok[b]) ? mt : float2{0.f, 0.f};
       }
 #pragma unroll
       for (int a = 0; a < 4; ++a)
         if (FULL || a < na) {
-          const float v = sx_ptr[(int64_t)gc * ldT + 64 * a];
+          const float v = sx_ptr[(int64_t)(g0 + gc) * ldT + 64 * a];
           o.av[a] = valid ? v : 0.f;
         }
     };
@@ -640,7 +644,12 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
           const int64_t tok = perm[row0 + r];
 #pragma unroll
           for (int b = 0; b < 2; ++b)
-            if (ncol[b] < N) Y[tok * N + ncol[b]] = acc[a][b][i];
+            if (ncol[b] < N) {
+              if (accumulate)
+                unsafeAtomicAdd(&Y[tok * N + ncol[b]], acc[a][b][i]);  // K split: Y was zeroed by the pre-kernel
+              else
+                Y[tok * N + ncol[b]] = acc[a][b][i];
+            }
         }
       }
     }
@@ -652,10 +661,15 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const uint16_t* __restr
                                                          const int32_t* __restrict__ perm,
                                                          const int32_t* __restrict__ offsets,
                                                          const float* __restrict__ SxT, int64_t ldT,
-                                                         float* __restrict__ Y, int n_tiles_n) {
+                                                         float* __restrict__ Y, int n_tiles_n, int splits) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
   // ---- which tile: full tiles of every bucket first, then the ragged last tile of each bucket ----
-  const int mt = blockIdx.x / n_tiles_n, ntile_n = blockIdx.x % n_tiles_n;
+  // (tile row, tile column, K split): workgroups of one tile row are neighbours (they share activations)
+  const int per_mt = n_tiles_n * splits;
+  const int mt = blockIdx.x / per_mt, ntile_n = (blockIdx.x % per_mt) / splits, split = blockIdx.x % splits;
+  const int Gtot = (int)(K / kGroup);
+  const int g0 = (int)((int64_t)split * Gtot / splits);
+  const int Gs = (int)((int64_t)(split + 1) * Gtot / splits) - g0;
   int off[MBQ_N_PRECISIONS + 1];
 #pragma unroll
   for (int q = 0; q <= MBQ_N_PRECISIONS; ++q) off[q] = offsets[q];
@@ -694,10 +708,10 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const uint16_t* __restr
   do {                                                                                                         \
     if (FF || first_half)                                                                                      \
       prefill_tile<PP, FF, 0>(Xs, K, codes, slice_words, meta, N, NT, KB, perm, SxT, ldT, Y, row0, rows,        \
-                              ntile_n, smem);                                                                  \
+                              ntile_n, smem, g0, Gs, splits > 1);                                              \
     else                                                                                                       \
       prefill_tile<PP, FF, 1>(Xs, K, codes, slice_words, meta, N, NT, KB, perm, SxT, ldT, Y, row0, rows,        \
-                              ntile_n, smem);                                                                  \
+                              ntile_n, smem, g0, Gs, splits > 1);                                              \
   } while (0)
   if (rows == kBM) {
     switch (p) {
@@ -734,13 +748,27 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
   const size_t xs_bytes = ((size_t)(T + kPadRows) * sh.K * sizeof(uint16_t) + 255) / 256 * 256;
   float* SxT = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + xs_bytes);
   const int64_t ldT = prefill_ld(T);
-  hipLaunchKernelGGL(prefill_prep_kernel, dim3((unsigned)T), dim3(256), 0, stream, X, T, sh.K, perm, Xs, SxT, ldT);
-  mbq_status st = hip_status(hipGetLastError(), "prefill_prep_kernel launch");
-  if (st != MBQ_OK) return st;
   const int n_tiles_n = (int)((sh.N + kBN - 1) / kBN);
   const int64_t m_tiles_max = T / kBM + MBQ_N_PRECISIONS;
-  hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)(m_tiles_max * n_tiles_n)), dim3(512), 0, stream, Xs, sh.K,
-                     codes, sh.slice_words, meta, sh.N, sh.NT, sh.KB, perm, offsets, SxT, ldT, Y, n_tiles_n);
+  // K split: a launch with few tiles leaves compute units idle in its last round; when the K work per
+  // output is large (K >= 8192) the tiles are cut along K into 2 or 4 workgroups that add their
+  // partial sums into a zeroed Y.  knob 5 forces the split (1, 2 or 4).
+  constexpr int kComputeUnits = 256;
+  int splits = 1;
+  if (knob(5) == 1 || knob(5) == 2 || knob(5) == 4) {
+    splits = knob(5);
+  } else if (sh.K >= 8192) {
+    const int64_t est_tiles = (T / kBM + 2) * n_tiles_n;
+    while (splits < 4 && est_tiles * splits < 3 * kComputeUnits) splits *= 2;
+  }
+  while (splits > 1 && sh.G / splits < 4) splits /= 2;
+  hipLaunchKernelGGL(prefill_prep_kernel, dim3((unsigned)T), dim3(256), 0, stream, X, T, sh.K, perm, Xs, SxT, ldT,
+                     splits > 1 ? Y : nullptr, sh.N);
+  mbq_status st = hip_status(hipGetLastError(), "prefill_prep_kernel launch");
+  if (st != MBQ_OK) return st;
+  hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)(m_tiles_max * n_tiles_n * splits)), dim3(512), 0, stream, Xs,
+                     sh.K, codes, sh.slice_words, meta, sh.N, sh.NT, sh.KB, perm, offsets, SxT, ldT, Y, n_tiles_n,
+                     splits);
   return hip_status(hipGetLastError(), "prefill_kernel launch");
 }
 

@@ -185,6 +185,24 @@ def test_prefill_tile_shapes(mbq, N, K, T, mix):
     assert_output_close(Y, Yref, f"prefill N={N} K={K} T={T}")
 
 
+@pytest.mark.parametrize("splits", [2, 4])
+def test_prefill_k_split(mbq, splits):
+    """The K range of a tile cut into workgroups that add their partial sums into a zeroed Y."""
+    N, K, T = 272, 2304, 300     # 18 groups: uneven split ranges
+    print(f"[case] prefill K split {splits}", flush=True)
+    W = make_weight(N, K, [19, splits], 4.0)
+    xb = tokens(T, K, [N, K, T, 2])
+    prec = np.random.default_rng([splits, 5]).integers(0, 4, size=T).astype(np.int32)
+    codes, s0, z0 = O.encode(W)
+    Yref = O.linear(xb, codes, s0, z0, prec)
+    mbq.set_knob(5, splits)
+    try:
+        Y = run_linear(mbq, W, xb, prec, ALGOS["prefill"])
+    finally:
+        mbq.set_knob(5, 0)
+    assert_output_close(Y, Yref, f"prefill K split {splits}")
+
+
 @pytest.mark.parametrize("K", [768, 2048, 4096, 5120, 11008])
 @pytest.mark.parametrize("pmax", [0, 1, 2, 3])
 @pytest.mark.parametrize("T", [7, 16, 40])
