@@ -21,7 +21,13 @@ Readings of the paper taken here (the paper is silent or inconsistent on them):
     z0 = -min / s0 is a continuous (non-integer) zero point; both stored fp32;
   * degenerate groups (max == min) get a range floor, see ``group_params``;
   * the router is a single linear map to 4 logits, argmax picks the precision,
-    first maximum wins ties.
+    first maximum wins ties;
+  * the paper's own router (``route_mlp``): a 2-layer MLP whose hidden width and
+    activation the paper does not give - taken as ReLU between two affine maps; one
+    score per slice, slice e active iff score - delta > 0 (Sec. 4.2, runtime
+    threshold), the base slice always active (shared-expert slice), and - because
+    the precision of a token is a prefix of slices - precision = number of leading
+    active residual slices (an active slice after an inactive one is ignored).
 """
 from __future__ import annotations
 
@@ -38,6 +44,7 @@ __all__ = [
     "bf16_bits_to_f64", "group_params", "encode", "encode_digits", "slice_matrix",
     "dequant", "merged_code", "dequant_merged", "pack_canonical", "unpack_canonical",
     "blob_bytes", "pack_blob", "route", "bucket", "linear", "avg_bits",
+    "route_mlp", "threshold_quantile",
 ]
 
 
@@ -232,6 +239,46 @@ def route(x_bits: np.ndarray, Wr: np.ndarray, br: np.ndarray):
     else:
         gap = np.zeros(0)
     return S, prec, gap
+
+
+def route_mlp(x_bits: np.ndarray, W1: np.ndarray, b1: np.ndarray, W2: np.ndarray, b2: np.ndarray,
+              delta: float):
+    """The paper's router (Sec. 4.2 Eq. 4 and the runtime threshold of Sec. 4.2, last paragraph):
+    S = relu(X W1^T + b1) W2^T + b2 in fp64, one score per slice (S is T x E);
+    G[i, e] = 1[(S[i, e] - delta) > 0]; slice 0 is always active (shared-expert slice) and the
+    precision of token i is the number of leading active residual slices e = 1, 2, ...
+    Returns (S fp64 [T, E], prec int32 [T], margin fp64 [T]) where margin is the smallest
+    |S - delta| among the comparisons that decided the token's precision."""
+    X = bf16_bits_to_f64(x_bits)
+    Hd = X @ W1.astype(np.float64).T + b1.astype(np.float64)[None, :]
+    Hd = np.maximum(Hd, 0.0)
+    S = Hd @ W2.astype(np.float64).T + b2.astype(np.float64)[None, :]
+    T, E = S.shape
+    prec = np.zeros(T, dtype=np.int32)
+    margin = np.full(T, np.inf)
+    for i in range(T):
+        p = 0
+        for e in range(1, E):
+            d = S[i, e] - delta
+            margin[i] = min(margin[i], abs(d))
+            if d > 0:
+                p = e
+            else:
+                break
+        prec[i] = p
+    return S, prec, margin
+
+
+def threshold_quantile(S: np.ndarray, rho: float) -> float:
+    """Layer-wise threshold calibration (App. C.2): the threshold that leaves a fraction rho of
+    the residual-slice scores of a calibration batch active.  With M = T (E - 1) residual scores
+    and k = floor(rho M + 1/2) (clipped to 0..M), the threshold is the (k+1)-th largest of them,
+    so that exactly the k largest satisfy score - delta > 0 (ties aside); -inf if k = M."""
+    R = np.sort(np.asarray(S, dtype=np.float64)[:, 1:].reshape(-1))[::-1]
+    M = R.size
+    k = int(np.floor(rho * M + 0.5))
+    k = max(0, min(M, k))
+    return float(R[k]) if k < M else float("-inf")
 
 
 def bucket(prec: np.ndarray, n_prec: int = N_SLICES):

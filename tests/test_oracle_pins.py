@@ -378,3 +378,84 @@ def test_pins_detect_planted_mistakes(monkeypatch, mistake):
             if abs(M.dequant(codes, s0, z0, p)[0, idx] - want_rec[p]) > 1e-9:
                 bad = True
     assert bad
+
+
+# ------------------------------------------------------------- the paper's router (2-layer MLP + threshold)
+def _mlp_case(T=9, K=128, H=6, seed=3):
+    from workloads import make_mlp_router, make_tokens
+    xb, _ = make_tokens(T, K, [seed, T], outlier_channel_frac=0.0)
+    W1, b1, W2, b2 = make_mlp_router(K, H, [seed])
+    return xb, W1, b1, W2, b2
+
+
+def test_route_mlp_scores_against_fsum_loops():
+    """Scores of the 2-layer router (Sec. 4.2 Eq. 4) against exactly rounded Python sums, ReLU written out."""
+    xb, W1, b1, W2, b2 = _mlp_case()
+    S, prec, margin = O.route_mlp(xb, W1, b1, W2, b2, delta=0.0)
+    X = O.bf16_bits_to_f64(xb)
+    for i in range(X.shape[0]):
+        hidden = []
+        for j in range(W1.shape[0]):
+            a = math.fsum([float(X[i, k]) * float(W1[j, k]) for k in range(X.shape[1])] + [float(b1[j])])
+            hidden.append(a if a > 0.0 else 0.0)
+        for e in range(W2.shape[0]):
+            want = math.fsum([hidden[j] * float(W2[e, j]) for j in range(len(hidden))] + [float(b2[e])])
+            assert abs(S[i, e] - want) <= 1e-12 * max(1.0, abs(want))
+
+
+def test_route_mlp_prefix_closure_all_patterns():
+    """Every on/off pattern of the three residual slices (threshold gate of Sec. 4.2): the precision is the number
+    of LEADING active residual slices; the base slice's own score never matters (shared-expert slice)."""
+    K, H = 128, 3
+    # a router whose scores are chosen directly: hidden unit j = relu(x_j) with x_j = 1, score_e = sum_j W2[e, j]
+    xb = f32_to_bf16_bits(np.zeros((8, K), dtype=np.float32) + np.eye(8, K, dtype=np.float32)[:, :K] * 0)
+    X = np.zeros((8, K), dtype=np.float32)
+    X[:, 0] = 1.0
+    xb = f32_to_bf16_bits(X)
+    W1 = np.zeros((H, K), dtype=np.float32)
+    W1[0, 0] = 1.0                                  # hidden = [1, 0, 0] for every token
+    b1 = np.zeros(H, dtype=np.float32)
+    expected = {(0, 0, 0): 0, (1, 0, 0): 1, (1, 1, 0): 2, (1, 1, 1): 3,
+                (0, 1, 0): 0, (0, 1, 1): 0, (1, 0, 1): 1, (0, 0, 1): 0}
+    for base_score in (-5.0, 5.0):                   # slice 0's score is ignored
+        for pattern, want in expected.items():
+            W2 = np.zeros((4, H), dtype=np.float32)
+            b2 = np.array([base_score] + [1.0 if on else -1.0 for on in pattern], dtype=np.float32)
+            S, prec, margin = O.route_mlp(xb, W1, b1, W2, b2, delta=0.25)
+            assert (prec == want).all(), (pattern, prec)
+            assert np.allclose(S[:, 1:], np.array(b2[1:], dtype=np.float64)[None, :])
+    # the comparison is strict: a score equal to the threshold is inactive
+    b2 = np.array([0.0, 0.25, 9.0, 9.0], dtype=np.float32)
+    S, prec, margin = O.route_mlp(xb, W1, b1, np.zeros((4, H), dtype=np.float32), b2, delta=0.25)
+    assert (prec == 0).all() and (margin == 0.0).all()
+
+
+def test_route_mlp_threshold_is_monotone_and_switches_precision():
+    """Raising delta never raises a token's precision (Sec. 4.2: a larger threshold activates fewer slices), and the
+    two ends of the sweep are all-2-bit and (for scores that allow it) up to 8-bit."""
+    xb, W1, b1, W2, b2 = _mlp_case(T=64, K=256, H=8, seed=5)
+    prev = None
+    avg = []
+    for delta in [-1e3] + list(np.linspace(-6.0, 6.0, 25)) + [1e3]:
+        S, prec, margin = O.route_mlp(xb, W1, b1, W2, b2, delta=float(delta))
+        if prev is not None:
+            assert (prec <= prev).all()
+        prev = prec
+        avg.append(O.avg_bits(prec))
+    assert avg[0] == 8.0 and avg[-1] == 2.0 and all(a >= b for a, b in zip(avg, avg[1:]))
+
+
+def test_threshold_quantile_against_sorted_brute_force():
+    """Layer-wise threshold calibration (App. C.2): exactly round(rho M) residual scores exceed the threshold."""
+    rng = np.random.default_rng(11)
+    S = rng.standard_normal((257, 4))
+    M = 257 * 3
+    for rho in (0.0, 1.0 / 6.0, 1.0 / 3.0, 0.5, 0.9, 1.0):
+        d = O.threshold_quantile(S, rho)
+        k = int(math.floor(rho * M + 0.5))
+        assert int((S[:, 1:] - d > 0).sum()) == k
+        if k < M:   # the threshold is itself one of the scores: the largest one that stays inactive
+            resid = sorted(S[:, 1:].reshape(-1).tolist(), reverse=True)
+            assert d == resid[k]
+    # target bits -> ratio (App. C.2): rho = (target - 2) / 6; the realised average follows for independent slices only
+    # when routing is a prefix, so only the activation count is pinned here

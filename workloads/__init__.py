@@ -12,6 +12,7 @@ from .generate import (  # noqa: F401
     WorkloadConfig,
     f32_to_bf16_bits,
     make_case,
+    make_mlp_router,
     make_router,
     make_tokens,
     make_weight,

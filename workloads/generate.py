@@ -229,6 +229,19 @@ def make_router(K: int, seed: Sequence[int], mix: Optional[Sequence[float]] = No
     return wr, br.astype(np.float32)
 
 
+def make_mlp_router(K: int, hidden: int, seed: Sequence[int], n_slices: int = N_PRECISIONS
+                    ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """Parameters of a 2-layer router: ``W1`` (hidden x K), ``b1`` (hidden), ``W2`` (n_slices x hidden),
+    ``b2`` (n_slices), all fp32.  Rows of W1 ~ N(0, 1/K) so hidden pre-activations are O(1) on N(0,1) tokens;
+    W2 ~ N(0, 4/hidden); b2 falls with the slice index so that later slices are active less often."""
+    rng = np.random.default_rng(list(seed) + [40])
+    w1 = (rng.standard_normal((hidden, K)) / np.sqrt(K)).astype(np.float32)
+    b1 = (0.1 * rng.standard_normal(hidden)).astype(np.float32)
+    w2 = (2.0 * rng.standard_normal((n_slices, hidden)) / np.sqrt(hidden)).astype(np.float32)
+    b2 = (0.5 - 0.5 * np.arange(n_slices)).astype(np.float32)
+    return w1, b1, w2, b2
+
+
 # --------------------------------------------------------------------------- case
 def make_case(cfg: WorkloadConfig, linear_index: int, T: int,
               weight_rows: Optional[np.ndarray] = None, with_weight: bool = True) -> dict:
