@@ -139,6 +139,40 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
                            int32_t* const* offsets_host, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * mbq_route_mlp - the paper's own router (Sec. 4.2 Eq. 4: a 2-layer MLP gives one score per slice) with
+ * the run-time threshold of Sec. 4.2 (efficient runtime precision switching, G = 1[(S - delta) > 0]):
+ *   S[i][e] = sum_j relu(sum_k X[i][k] W1[j][k] + b1[j]) * W2[e][j] + b2[e]      accumulated in fp64
+ *   slice e >= 1 of token i is active iff (S[i][e] - delta) > 0;  slice 0 is always active (the
+ *   shared-expert slice), its score is computed but never used
+ *   prec[i] = number of leading active residual slices e = 1, 2, 3 (a precision names a prefix of
+ *             slices, so an active slice behind an inactive one is ignored)
+ *   perm/offsets = as in mbq_route.
+ * The paper gives neither the hidden width nor the activation of the MLP; ReLU is the reading taken.
+ * delta is the layer's threshold plus any global shift: raising it lowers precisions, the packed blob is
+ * untouched.
+ *   X : bf16 [T][K]   W1 : fp32 [H][K]   b1 : fp32 [H]   W2 : fp32 [E][H]   b2 : fp32 [E]
+ *   1 <= H <= 512, E = 4;  prec, perm, offsets as in mbq_route;  scores : fp64 [T][E] (out, may be NULL)
+ *   ws as in mbq_route (zero before first use, left zero).  T = 0 is legal.
+ */
+mbq_status mbq_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
+                         const float* W2, const float* b2, int E, double delta, int32_t* prec,
+                         int32_t* perm, int32_t* offsets, double* scores, void* ws, size_t ws_bytes,
+                         void* stream);
+
+/*
+ * mbq_threshold_quantile - layer-wise threshold calibration (App. C.2): from the scores of a
+ * calibration batch, the threshold that leaves a fraction rho of the T (E - 1) residual-slice scores
+ * active.  With k = floor(rho T (E-1) + 1/2) clipped to 0 .. T (E-1), *delta_out is the (k+1)-th
+ * largest residual score, so exactly the k largest satisfy score - delta > 0 (ties aside); -inf if
+ * k = T (E-1).  For the default slices a target of b average bits is rho = (b - 2) / 6.  An offline
+ * step (one workgroup).
+ *   scores : fp64 [T][E] as written by mbq_route_mlp, T >= 1, E = 4;  0 <= rho <= 1
+ *   delta_out : one double (device, out)
+ */
+mbq_status mbq_threshold_quantile(const double* scores, int64_t T, int E, double rho, double* delta_out,
+                                  void* stream);
+
+/*
  * mbq_linear - routed output (Sec. 4.2 Eq. 6 with the prefix mask of slices 0..p_i):
  *   Y[i][n] = sum_k X[i][k] * What^(prec[i])[n][k],  fp32 accumulate, fp32 output,
  * reading for each token only the slices its precision needs.

@@ -24,6 +24,7 @@ EXPORTS = (
     "mbq_version", "mbq_last_error", "mbq_blob_bytes", "mbq_route_workspace_bytes",
     "mbq_linear_workspace_bytes", "mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route",
     "mbq_route_group", "mbq_linear", "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob",
+    "mbq_route_mlp", "mbq_threshold_quantile",
 )
 
 _lib = None
@@ -55,6 +56,9 @@ def load() -> ctypes.CDLL:
     lib.mbq_dequant.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p]
     lib.mbq_route.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
     lib.mbq_route_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_sz, c_p]
+    lib.mbq_route_mlp.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_int, c_p, c_p, c_int, ctypes.c_double, c_p, c_p, c_p,
+                                  c_p, c_p, c_sz, c_p]
+    lib.mbq_threshold_quantile.argtypes = [c_p, c_i64, c_int, ctypes.c_double, c_p, c_p]
     lib.mbq_linear.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_routed_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_p,
@@ -153,6 +157,44 @@ def mbq_route(X: torch.Tensor, Wr: torch.Tensor, br: torch.Tensor, want_logits: 
     _check(load().mbq_route(_ptr(X), T, K, _ptr(Wr), _ptr(br), P, _ptr(prec), _ptr(perm), _ptr(offsets),
                             _ptr(logits), _ptr(ws), ws.numel(), _stream()), "mbq_route")
     return (prec, perm, offsets, logits) if want_logits else (prec, perm, offsets)
+
+
+def mbq_route_mlp(X: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, W2: torch.Tensor, b2: torch.Tensor,
+                  delta: float, want_scores: bool = False,
+                  out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+                  ws: Optional[torch.Tensor] = None):
+    """The 2-layer router with a run-time threshold: X bf16 [T, K], W1 fp32 [H, K], b1 [H], W2 fp32 [4, H],
+    b2 [4] -> (prec, perm, offsets[, scores fp64 [T, 4]])."""
+    assert X.dtype == torch.bfloat16 and all(t.dtype == torch.float32 for t in (W1, b1, W2, b2))
+    T, K = X.shape
+    H, E = W1.shape[0], W2.shape[0]
+    assert W1.shape == (H, K) and b1.shape == (H,) and W2.shape == (E, H) and b2.shape == (E,)
+    dev = X.device
+    if out is None:
+        prec = torch.empty(T, dtype=torch.int32, device=dev)
+        perm = torch.empty(T, dtype=torch.int32, device=dev)
+        offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    else:
+        prec, perm, offsets = out
+    scores = torch.empty((T, E), dtype=torch.float64, device=dev) if want_scores else None
+    if ws is None:
+        ws = route_workspace(T, K, dev)
+    _check(load().mbq_route_mlp(_ptr(X), T, K, _ptr(W1), _ptr(b1), H, _ptr(W2), _ptr(b2), E, float(delta),
+                                _ptr(prec), _ptr(perm), _ptr(offsets), _ptr(scores), _ptr(ws), ws.numel(),
+                                _stream()), "mbq_route_mlp")
+    return (prec, perm, offsets, scores) if want_scores else (prec, perm, offsets)
+
+
+def mbq_threshold_quantile(scores: torch.Tensor, rho: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores fp64 [T, 4] (device) -> one-element fp64 device tensor: the threshold that leaves a fraction rho of
+    the residual-slice scores active."""
+    assert scores.dtype == torch.float64 and scores.dim() == 2 and scores.is_contiguous()
+    T, E = scores.shape
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=scores.device)
+    _check(load().mbq_threshold_quantile(_ptr(scores), T, E, float(rho), _ptr(out), _stream()),
+           "mbq_threshold_quantile")
+    return out
 
 
 def _ptr_array(tensors: Sequence[torch.Tensor]):

@@ -206,6 +206,49 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
                             (hipStream_t)stream, nullptr, 0);
 }
 
+mbq_status mbq_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
+                         const float* W2, const float* b2, int E, double delta, int32_t* prec, int32_t* perm,
+                         int32_t* offsets, double* scores, void* ws, size_t ws_bytes, void* stream) {
+  if (E != MBQ_N_PRECISIONS || H < 1 || H > route_mlp_max_hidden()) {
+    set_error("mbq_route_mlp: E=%d (must be %d) or hidden width %d outside 1..%d", E, MBQ_N_PRECISIONS, H,
+              route_mlp_max_hidden());
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (T < 0 || K <= 0 || K % kGroup != 0 || T > (int64_t)1 << 24 || K > (int64_t)1 << 24) {
+    set_error("mbq_route_mlp: bad sizes T=%lld K=%lld", (long long)T, (long long)K);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (!offsets || (T > 0 && (!X || !W1 || !b1 || !W2 || !b2 || !prec || !perm)) || !aligned(X, 16) ||
+      !aligned(W1, 16) || delta != delta) {
+    set_error("mbq_route_mlp: null or misaligned pointer (X and W1 need 16-byte alignment) or delta is NaN");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws || !aligned(ws, 8)) {
+    set_error("mbq_route_mlp: workspace too small or misaligned (%zu < %zu)", ws_bytes,
+              mbq_route_workspace_bytes(T, K));
+    return MBQ_ERR_WORKSPACE;
+  }
+  return launch_route_mlp(X, T, K, W1, b1, H, W2, b2, delta, prec, perm, offsets, scores, ws, (hipStream_t)stream);
+}
+
+mbq_status mbq_threshold_quantile(const double* scores, int64_t T, int E, double rho, double* delta_out,
+                                  void* stream) {
+  if (E != MBQ_N_PRECISIONS || T < 1 || T > (int64_t)1 << 28) {
+    set_error("mbq_threshold_quantile: E=%d (must be %d) or T=%lld outside 1..2^28", E, MBQ_N_PRECISIONS,
+              (long long)T);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (!scores || !delta_out || !(rho >= 0.0 && rho <= 1.0)) {
+    set_error("mbq_threshold_quantile: null pointer or rho outside [0, 1]");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  const int64_t M = T * (E - 1);
+  long long k = (long long)__builtin_floor(rho * (double)M + 0.5);
+  if (k < 0) k = 0;
+  if (k > M) k = M;
+  return launch_threshold_quantile(scores, T, k, delta_out, (hipStream_t)stream);
+}
+
 mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
                                    const float* const* Wr_host, const float* const* br_host, int P,
                                    const void* const* blob_host, const int64_t* N_host, int32_t* const* prec_host,

@@ -66,6 +66,12 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
                               void* prep, int prep_blocks);
 bool route_can_carry_prep(int64_t T);
+mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
+                            const float* W2, const float* b2, double delta, int32_t* prec, int32_t* perm,
+                            int32_t* offsets, double* scores, void* ws, hipStream_t stream);
+int route_mlp_max_hidden();
+mbq_status launch_threshold_quantile(const double* scores, int64_t T, long long k, double* delta_out,
+                                     hipStream_t stream);
 mbq_status launch_linear_simple(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                 const int32_t* prec, float* Y, hipStream_t stream);
 mbq_status launch_linear_decode(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,

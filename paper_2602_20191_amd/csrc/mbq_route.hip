@@ -333,4 +333,183 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
                             nullptr, 0);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The paper's own router (Sec. 4.2 Eq. 4): a 2-layer MLP scores every slice, S = relu(X W1^T + b1)
+// W2^T + b2 (the activation is not given in the paper; ReLU is the reading taken), and the
+// run-time threshold of Sec. 4.2 turns scores into slice gates, G = 1[(S - delta) > 0].  The base
+// slice is always active (shared-expert slice); a token's precision is the number of leading
+// active residual slices, so that it names a prefix of slices like every other path here.
+//
+// One workgroup of 256 threads handles TPW consecutive tokens.  Hidden units are produced eight
+// at a time: the K axis is split over the threads in chunks of 8 columns (bf16 x fp32 products
+// are exact in fp64, accumulation in fp64), partial sums meet through wavefront shuffles and LDS,
+// bias and ReLU are applied and the hidden vector stays in LDS.  Then one thread per (token,
+// slice) forms the score in a fixed order, one thread per token decides, and the workgroup that
+// finishes last buckets all tokens (same ticket scheme as route_kernel).
+constexpr int kMlpHiddenChunk = 8;
+constexpr int kMlpMaxHidden = 512;
+
+template <int TPW>
+__global__ __launch_bounds__(256) void route_mlp_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
+                                                        const float* __restrict__ W1, const float* __restrict__ b1,
+                                                        int H, const float* __restrict__ W2,
+                                                        const float* __restrict__ b2, double delta, int32_t* prec,
+                                                        int32_t* __restrict__ perm, int32_t* __restrict__ offsets,
+                                                        double* __restrict__ scores,
+                                                        unsigned int* __restrict__ ticket) {
+  constexpr int HC = kMlpHiddenChunk;
+  const int64_t tok0 = (int64_t)blockIdx.x * TPW;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ double s_hidden[TPW][kMlpMaxHidden];
+  __shared__ double s_red[4][TPW][HC];
+  __shared__ double s_score[TPW][kP];
+  __shared__ unsigned int s_ticket;
+
+  for (int h0 = 0; h0 < H; h0 += HC) {
+    double acc[TPW][HC];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t)
+#pragma unroll
+      for (int j = 0; j < HC; ++j) acc[t][j] = 0.0;
+    for (int64_t k = (int64_t)tid * 8; k < K; k += 256 * 8) {
+      float x[TPW][8];
+#pragma unroll
+      for (int t = 0; t < TPW; ++t) {
+        const int64_t tok = (tok0 + t < T) ? tok0 + t : T - 1;  // a valid row either way
+        const uint4 xv = *reinterpret_cast<const uint4*>(X + tok * K + k);
+        x[t][0] = bf16_lo(xv.x); x[t][1] = bf16_hi(xv.x); x[t][2] = bf16_lo(xv.y); x[t][3] = bf16_hi(xv.y);
+        x[t][4] = bf16_lo(xv.z); x[t][5] = bf16_hi(xv.z); x[t][6] = bf16_lo(xv.w); x[t][7] = bf16_hi(xv.w);
+      }
+#pragma unroll
+      for (int j = 0; j < HC; ++j) {
+        const int h = (h0 + j < H) ? h0 + j : H - 1;  // a valid row either way; surplus units are dropped below
+        const float4* src = reinterpret_cast<const float4*>(W1 + (int64_t)h * K + k);
+        const float4 a = src[0], b = src[1];
+        const float w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int t = 0; t < TPW; ++t)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[t][j] = fma((double)x[t][c], (double)w[c], acc[t][j]);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < TPW; ++t)
+#pragma unroll
+      for (int j = 0; j < HC; ++j) {
+        double v = acc[t][j];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+        if (lane == 0) s_red[wave][t][j] = v;
+      }
+    __syncthreads();
+    if (tid < TPW * HC) {
+      const int t = tid / HC, j = tid % HC;
+      if (h0 + j < H) {
+        const double pre = ((s_red[0][t][j] + s_red[1][t][j]) + (s_red[2][t][j] + s_red[3][t][j])) + (double)b1[h0 + j];
+        s_hidden[t][h0 + j] = pre > 0.0 ? pre : 0.0;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid < TPW * kP) {
+    const int t = tid / kP, e = tid % kP;
+    double s = 0.0;
+    for (int j = 0; j < H; ++j) s = fma(s_hidden[t][j], (double)W2[(int64_t)e * H + j], s);
+    s += (double)b2[e];
+    s_score[t][e] = s;
+    if (scores && tok0 + t < T) scores[(tok0 + t) * kP + e] = s;
+  }
+  __syncthreads();
+  if (tid < TPW && tok0 + tid < T) {
+    int p = 0;
+#pragma unroll
+    for (int e = 1; e < kP; ++e) {
+      if (p == e - 1 && (s_score[tid][e] - delta) > 0.0) p = e;  // strict: a score on the threshold is inactive
+    }
+    prec[tok0 + tid] = p;
+    __threadfence();  // publish this workgroup's choices before taking a ticket
+  }
+  __syncthreads();
+  if (tid == 0) s_ticket = atomicAdd(ticket, 1u);
+  __syncthreads();
+  if (s_ticket != gridDim.x - 1) return;
+  __threadfence();
+  bucket_by_workgroup<4>(prec, T, perm, offsets);
+  if (tid == 0) *ticket = 0u;
+}
+
+mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
+                            const float* W2, const float* b2, double delta, int32_t* prec, int32_t* perm,
+                            int32_t* offsets, double* scores, void* ws, hipStream_t stream) {
+  unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
+  if (T == 0) {
+    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(64), 0, stream, prec, T, perm, offsets);
+    return hip_status(hipGetLastError(), "bucket_kernel launch");
+  }
+  if (T <= 512)
+    hipLaunchKernelGGL(route_mlp_kernel<1>, dim3((unsigned)T), dim3(256), 0, stream, X, T, K, W1, b1, H, W2, b2,
+                       delta, prec, perm, offsets, scores, ticket);
+  else
+    hipLaunchKernelGGL(route_mlp_kernel<4>, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, stream, X, T, K, W1, b1, H,
+                       W2, b2, delta, prec, perm, offsets, scores, ticket);
+  return hip_status(hipGetLastError(), "route_mlp_kernel launch");
+}
+int route_mlp_max_hidden() { return kMlpMaxHidden; }
+
+// Layer-wise threshold calibration (App. C.2): the (k+1)-th largest of the T (E-1) residual-slice
+// scores, found by a most-significant-bit-first radix selection on the order-preserving integer
+// image of the doubles; one workgroup, 64 passes over the scores (an offline step).
+__device__ inline unsigned long long ordered_key(double v) {
+  const unsigned long long u = (unsigned long long)__double_as_longlong(v);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+__global__ __launch_bounds__(1024) void threshold_quantile_kernel(const double* __restrict__ scores, int64_t T,
+                                                                   long long k, double* __restrict__ delta_out) {
+  const int64_t M = T * (kP - 1);
+  __shared__ unsigned long long s_cnt[16];
+  __shared__ unsigned long long s_total;
+  if (k >= M) {  // every residual score stays active
+    if (threadIdx.x == 0) *delta_out = -__builtin_huge_val();
+    return;
+  }
+  unsigned long long prefix = 0ull, mask = 0ull;
+  long long want = k;  // rank (0 = largest) among the scores that match the prefix so far
+  for (int bit = 63; bit >= 0; --bit) {
+    const unsigned long long cand = prefix | (1ull << bit), cmask = mask | (1ull << bit);
+    unsigned long long c = 0;
+    for (int64_t i = threadIdx.x; i < M; i += 1024) {
+      const double v = scores[(i / (kP - 1)) * kP + 1 + (i % (kP - 1))];
+      c += ((ordered_key(v) & cmask) == cand) ? 1ull : 0ull;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) c += __shfl_down(c, off, 64);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      unsigned long long tot = 0;
+      for (int w = 0; w < 16; ++w) tot += s_cnt[w];
+      s_total = tot;
+    }
+    __syncthreads();
+    const unsigned long long ones = s_total;  // scores that match the prefix and have this bit set (the larger ones)
+    if ((unsigned long long)want < ones) {
+      prefix = cand;
+    } else {
+      want -= (long long)ones;
+    }
+    mask = cmask;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const unsigned long long u = (prefix >> 63) ? (prefix & 0x7FFFFFFFFFFFFFFFull) : ~prefix;
+    *delta_out = __longlong_as_double((long long)u);
+  }
+}
+
+mbq_status launch_threshold_quantile(const double* scores, int64_t T, long long k, double* delta_out,
+                                     hipStream_t stream) {
+  hipLaunchKernelGGL(threshold_quantile_kernel, dim3(1), dim3(1024), 0, stream, scores, T, k, delta_out);
+  return hip_status(hipGetLastError(), "threshold_quantile_kernel launch");
+}
+
 }  // namespace mbq

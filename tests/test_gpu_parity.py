@@ -65,6 +65,75 @@ def test_route_and_bucket_are_bit_exact(mbq, T, K):
     assert offsets[4] == T
 
 
+# ------------------------------------------------------------- the paper's router (2-layer MLP + threshold)
+@pytest.mark.parametrize("T,K,H", [(0, 256, 8), (1, 128, 1), (16, 4096, 64), (37, 384, 13), (513, 512, 32),
+                                   (2048, 1024, 64), (300, 256, 512)])
+def test_route_mlp_matches_oracle(mbq, T, K, H):
+    """Scores to fp64 rounding, precisions bit-exact away from the threshold, permutation exact; a sweep of the
+    threshold over one set of parameters switches precisions without touching anything else."""
+    from workloads import make_mlp_router
+    print(f"[case] route_mlp T={T} K={K} H={H}", flush=True)
+    xb = tokens(T, K, [T, K, H])
+    W1, b1, W2, b2 = make_mlp_router(K, H, [T, K, H])
+    X = dev_bf16(xb).reshape(T, K)
+    d = [dev(a) for a in (W1, b1, W2, b2)]
+    avgs = []
+    for delta in (-1e3, -0.75, 0.0, 0.4, 1e3):
+        S, prec_ref, margin = O.route_mlp(xb, W1, b1, W2, b2, delta)
+        prec, perm, offsets, scores = mbq.mbq_route_mlp(X, *d, delta, want_scores=True)
+        torch.cuda.synchronize()
+        prec, perm, offsets = prec.cpu().numpy(), perm.cpu().numpy(), offsets.cpu().numpy()
+        if T:
+            np.testing.assert_allclose(scores.cpu().numpy(), S, rtol=0, atol=1e-10)
+        compare_routing(prec, prec_ref, margin, f"route_mlp T={T} K={K} H={H} delta={delta}")
+        check_bucket(prec, perm, offsets)
+        assert offsets[4] == T
+        avgs.append(O.avg_bits(prec))
+    if T:
+        assert avgs[0] == 8.0 and avgs[-1] == 2.0 and all(a >= b for a, b in zip(avgs, avgs[1:]))
+
+
+def test_threshold_quantile_is_exact(mbq):
+    """The calibration quantile is an order statistic: fed the oracle's scores it must return the same double."""
+    rng = np.random.default_rng(23)
+    S = rng.standard_normal((1000, 4)) * 3.0
+    S[5, 1] = S[9, 2]                      # a tie among the residual scores
+    Sd = dev(S)
+    for rho in (0.0, 1.0 / 6.0, 1.0 / 3.0, 0.5, 0.77, 1.0):
+        want = O.threshold_quantile(S, rho)
+        got = float(mbq.mbq_threshold_quantile(Sd, rho).cpu().numpy()[0])
+        assert got == want, (rho, got, want)
+    with pytest.raises(mbq.MbqError):
+        mbq.mbq_threshold_quantile(Sd, 1.5)
+
+
+def test_route_mlp_target_bits_and_linear(mbq):
+    """Layer-wise calibration end to end (App. C.2): scores of a calibration batch -> threshold for a target of
+    4 average bits -> routing of a fresh batch -> routed linear against the oracle with the same routing."""
+    from workloads import make_mlp_router
+    N, K, H, T = 272, 512, 16, 200
+    W = make_weight(N, K, [29], 4.0)
+    W1, b1, W2, b2 = make_mlp_router(K, H, [29])
+    d = [dev(a) for a in (W1, b1, W2, b2)]
+    cal = tokens(4096, K, [29, 1])
+    *_, cal_scores = mbq.mbq_route_mlp(dev_bf16(cal).reshape(-1, K), *d, 0.0, want_scores=True)
+    rho = (4.0 - 2.0) / 6.0
+    delta = float(mbq.mbq_threshold_quantile(cal_scores, rho).cpu().numpy()[0])
+    S_cal, _, _ = O.route_mlp(cal, W1, b1, W2, b2, 0.0)
+    active = float(np.mean(S_cal[:, 1:] - delta > 0))
+    assert abs(active - rho) < 2e-3                       # the requested fraction of residual slices is active
+    xb = tokens(T, K, [29, 2])
+    X = dev_bf16(xb).reshape(T, K)
+    prec, perm, offsets = mbq.mbq_route_mlp(X, *d, delta)
+    S, prec_ref, margin = O.route_mlp(xb, W1, b1, W2, b2, delta)
+    compare_routing(prec.cpu().numpy(), prec_ref, margin, "route_mlp calibrated")
+    blob = mbq.mbq_encode(dev(W))
+    codes, s0, z0 = O.encode(W)
+    for algo in (1, 3):
+        Y = mbq.mbq_linear(X, blob, N, K, prec, perm, offsets, algo=algo)
+        assert_output_close(Y.cpu().numpy(), O.linear(xb, codes, s0, z0, prec.cpu().numpy()), f"mlp-routed linear algo={algo}")
+
+
 @pytest.mark.parametrize("T,K,n", [(1, 4096, 3), (16, 4096, 3), (28, 1280, 4), (16, 11008, 1), (40, 512, 2),
                                    (0, 256, 2)])
 def test_route_group_equals_separate_calls(mbq, T, K, n):
