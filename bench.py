@@ -374,6 +374,30 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         "ms_total": ms_sum, "tflops": tf, "per_linear": per_linear,
         "roofline": {"bound": "mfma", "kernel": "mbq::prefill_kernel (+ mbq::prefill_prep_kernel)", "achieved": tf,
                      "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
+    # the paper's 2-layer router (hidden width 64) at the decode batch and at 2048 tokens, K = 4096
+    from workloads import make_mlp_router, make_tokens
+    Kr, Hr = 4096, 64
+    W1, b1, W2, b2 = (torch.from_numpy(a).to(dev) for a in make_mlp_router(Kr, Hr, [7]))
+    mlp = {}
+    for Tr in (16, 2048):
+        xb, _ = make_tokens(Tr, Kr, [7, Tr], outlier_channel_frac=0.01)
+        Xr = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).to(dev).reshape(Tr, Kr)
+        outr = (torch.empty(Tr, dtype=torch.int32, device=dev), torch.empty(Tr, dtype=torch.int32, device=dev),
+                torch.empty(5, dtype=torch.int32, device=dev))
+        wsr = mbq.route_mlp_workspace(Tr, Kr, Hr, dev)
+        for _ in range(3):
+            mbq.mbq_route_mlp(Xr, W1, b1, W2, b2, 0.0, out=outr, ws=wsr)
+        a, b2e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 50
+        a.record()
+        for _ in range(n):
+            mbq.mbq_route_mlp(Xr, W1, b1, W2, b2, 0.0, out=outr, ws=wsr)
+        b2e.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b2e) / n * 1e3
+        mlp[f"tokens_{Tr}"] = {"us": us, "fp64_gflops": 2.0 * Tr * Kr * Hr / (us * 1e-6) / 1e9,
+                               "mix": np.bincount(outr[0].cpu().numpy(), minlength=4).tolist()}
+    extra["route_mlp_hidden64_K4096"] = mlp
     return extra
 
 

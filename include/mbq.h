@@ -152,8 +152,11 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
  * untouched.
  *   X : bf16 [T][K]   W1 : fp32 [H][K]   b1 : fp32 [H]   W2 : fp32 [E][H]   b2 : fp32 [E]
  *   1 <= H <= 512, E = 4;  prec, perm, offsets as in mbq_route;  scores : fp64 [T][E] (out, may be NULL)
- *   ws as in mbq_route (zero before first use, left zero).  T = 0 is legal.
+ *   ws : at least mbq_route_mlp_workspace_bytes(T, K, H) bytes, 256-byte aligned; its first 256 bytes
+ *        hold a ticket counter (ZERO before first use, left zero), the rest the hidden layer.
+ * T = 0 is legal.
  */
+size_t mbq_route_mlp_workspace_bytes(int64_t T, int64_t K, int H);
 mbq_status mbq_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
                          const float* W2, const float* b2, int E, double delta, int32_t* prec,
                          int32_t* perm, int32_t* offsets, double* scores, void* ws, size_t ws_bytes,

@@ -24,7 +24,7 @@ EXPORTS = (
     "mbq_version", "mbq_last_error", "mbq_blob_bytes", "mbq_route_workspace_bytes",
     "mbq_linear_workspace_bytes", "mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route",
     "mbq_route_group", "mbq_linear", "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob",
-    "mbq_route_mlp", "mbq_threshold_quantile",
+    "mbq_route_mlp", "mbq_route_mlp_workspace_bytes", "mbq_threshold_quantile",
 )
 
 _lib = None
@@ -58,6 +58,8 @@ def load() -> ctypes.CDLL:
     lib.mbq_route_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_sz, c_p]
     lib.mbq_route_mlp.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_int, c_p, c_p, c_int, ctypes.c_double, c_p, c_p, c_p,
                                   c_p, c_p, c_sz, c_p]
+    lib.mbq_route_mlp_workspace_bytes.restype = c_sz
+    lib.mbq_route_mlp_workspace_bytes.argtypes = [c_i64, c_i64, c_int]
     lib.mbq_threshold_quantile.argtypes = [c_p, c_i64, c_int, ctypes.c_double, c_p, c_p]
     lib.mbq_linear.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
@@ -159,6 +161,12 @@ def mbq_route(X: torch.Tensor, Wr: torch.Tensor, br: torch.Tensor, want_logits: 
     return (prec, perm, offsets, logits) if want_logits else (prec, perm, offsets)
 
 
+def route_mlp_workspace(T: int, K: int, H: int, device) -> torch.Tensor:
+    """Zeroed workspace of mbq_route_mlp (ticket counter + hidden layer)."""
+    n = load().mbq_route_mlp_workspace_bytes(T, K, H)
+    return torch.zeros(max(int(n), 256), dtype=torch.uint8, device=device)
+
+
 def mbq_route_mlp(X: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, W2: torch.Tensor, b2: torch.Tensor,
                   delta: float, want_scores: bool = False,
                   out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
@@ -178,7 +186,7 @@ def mbq_route_mlp(X: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, W2: torch
         prec, perm, offsets = out
     scores = torch.empty((T, E), dtype=torch.float64, device=dev) if want_scores else None
     if ws is None:
-        ws = route_workspace(T, K, dev)
+        ws = route_mlp_workspace(T, K, H, dev)
     _check(load().mbq_route_mlp(_ptr(X), T, K, _ptr(W1), _ptr(b1), H, _ptr(W2), _ptr(b2), E, float(delta),
                                 _ptr(prec), _ptr(perm), _ptr(offsets), _ptr(scores), _ptr(ws), ws.numel(),
                                 _stream()), "mbq_route_mlp")

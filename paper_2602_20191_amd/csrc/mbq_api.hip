@@ -206,6 +206,12 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
                             (hipStream_t)stream, nullptr, 0);
 }
 
+size_t mbq_route_mlp_workspace_bytes(int64_t T, int64_t K, int H) {
+  (void)K;
+  if (T < 0 || H < 1 || H > route_mlp_max_hidden()) return 0;
+  return route_mlp_workspace_bytes(T, H);
+}
+
 mbq_status mbq_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
                          const float* W2, const float* b2, int E, double delta, int32_t* prec, int32_t* perm,
                          int32_t* offsets, double* scores, void* ws, size_t ws_bytes, void* stream) {
@@ -223,9 +229,9 @@ mbq_status mbq_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W
     set_error("mbq_route_mlp: null or misaligned pointer (X and W1 need 16-byte alignment) or delta is NaN");
     return MBQ_ERR_INVALID_ARG;
   }
-  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws || !aligned(ws, 8)) {
+  if (ws_bytes < mbq_route_mlp_workspace_bytes(T, K, H) || !ws || !aligned(ws, 256)) {
     set_error("mbq_route_mlp: workspace too small or misaligned (%zu < %zu)", ws_bytes,
-              mbq_route_workspace_bytes(T, K));
+              mbq_route_mlp_workspace_bytes(T, K, H));
     return MBQ_ERR_WORKSPACE;
   }
   return launch_route_mlp(X, T, K, W1, b1, H, W2, b2, delta, prec, perm, offsets, scores, ws, (hipStream_t)stream);

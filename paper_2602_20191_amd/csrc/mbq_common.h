@@ -70,6 +70,7 @@ mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float
                             const float* W2, const float* b2, double delta, int32_t* prec, int32_t* perm,
                             int32_t* offsets, double* scores, void* ws, hipStream_t stream);
 int route_mlp_max_hidden();
+size_t route_mlp_workspace_bytes(int64_t T, int H);
 mbq_status launch_threshold_quantile(const double* scores, int64_t T, long long k, double* delta_out,
                                      hipStream_t stream);
 mbq_status launch_linear_simple(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,

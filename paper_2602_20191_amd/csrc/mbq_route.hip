@@ -340,93 +340,146 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
 // slice is always active (shared-expert slice); a token's precision is the number of leading
 // active residual slices, so that it names a prefix of slices like every other path here.
 //
-// One workgroup of 256 threads handles TPW consecutive tokens.  Hidden units are produced eight
-// at a time: the K axis is split over the threads in chunks of 8 columns (bf16 x fp32 products
-// are exact in fp64, accumulation in fp64), partial sums meet through wavefront shuffles and LDS,
-// bias and ReLU are applied and the hidden vector stays in LDS.  Then one thread per (token,
-// slice) forms the score in a fixed order, one thread per token decides, and the workgroup that
-// finishes last buckets all tokens (same ticket scheme as route_kernel).
+// Two launches.  Hidden layer: a workgroup of 256 threads produces eight hidden units of TPW consecutive
+// tokens (grid = token groups x hidden chunks, so small batches still fill the chip): the K axis is
+// split over the threads in chunks of 8 columns (bf16 x fp32 products are exact in fp64, accumulation
+// in fp64), partial sums meet through wavefront shuffles and LDS, bias and ReLU are applied and the
+// hidden vector goes to the workspace.  Scores: one thread per (token, slice) forms the score in a
+// fixed order, one thread per token decides, and the workgroup that finishes last buckets all tokens
+// (same ticket scheme as route_kernel).
 constexpr int kMlpHiddenChunk = 8;
 constexpr int kMlpMaxHidden = 512;
 
 template <int TPW>
-__global__ __launch_bounds__(256) void route_mlp_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
-                                                        const float* __restrict__ W1, const float* __restrict__ b1,
-                                                        int H, const float* __restrict__ W2,
-                                                        const float* __restrict__ b2, double delta, int32_t* prec,
-                                                        int32_t* __restrict__ perm, int32_t* __restrict__ offsets,
-                                                        double* __restrict__ scores,
-                                                        unsigned int* __restrict__ ticket) {
+__global__ __launch_bounds__(256) void route_mlp_hidden_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
+                                                               const float* __restrict__ W1,
+                                                               const float* __restrict__ b1, int H,
+                                                               double* __restrict__ hidden) {
   constexpr int HC = kMlpHiddenChunk;
   const int64_t tok0 = (int64_t)blockIdx.x * TPW;
+  const int h0 = (int)blockIdx.y * HC;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  __shared__ double s_hidden[TPW][kMlpMaxHidden];
   __shared__ double s_red[4][TPW][HC];
-  __shared__ double s_score[TPW][kP];
-  __shared__ unsigned int s_ticket;
-
-  for (int h0 = 0; h0 < H; h0 += HC) {
-    double acc[TPW][HC];
+  double acc[TPW][HC];
 #pragma unroll
-    for (int t = 0; t < TPW; ++t)
+  for (int t = 0; t < TPW; ++t)
 #pragma unroll
-      for (int j = 0; j < HC; ++j) acc[t][j] = 0.0;
-    for (int64_t k = (int64_t)tid * 8; k < K; k += 256 * 8) {
-      float x[TPW][8];
+    for (int j = 0; j < HC; ++j) acc[t][j] = 0.0;
+  for (int64_t k = (int64_t)tid * 8; k < K; k += 256 * 8) {
+    double w[HC][8];
 #pragma unroll
-      for (int t = 0; t < TPW; ++t) {
-        const int64_t tok = (tok0 + t < T) ? tok0 + t : T - 1;  // a valid row either way
-        const uint4 xv = *reinterpret_cast<const uint4*>(X + tok * K + k);
-        x[t][0] = bf16_lo(xv.x); x[t][1] = bf16_hi(xv.x); x[t][2] = bf16_lo(xv.y); x[t][3] = bf16_hi(xv.y);
-        x[t][4] = bf16_lo(xv.z); x[t][5] = bf16_hi(xv.z); x[t][6] = bf16_lo(xv.w); x[t][7] = bf16_hi(xv.w);
-      }
-#pragma unroll
-      for (int j = 0; j < HC; ++j) {
-        const int h = (h0 + j < H) ? h0 + j : H - 1;  // a valid row either way; surplus units are dropped below
-        const float4* src = reinterpret_cast<const float4*>(W1 + (int64_t)h * K + k);
-        const float4 a = src[0], b = src[1];
-        const float w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-        for (int t = 0; t < TPW; ++t)
-#pragma unroll
-          for (int c = 0; c < 8; ++c) acc[t][j] = fma((double)x[t][c], (double)w[c], acc[t][j]);
-      }
+    for (int j = 0; j < HC; ++j) {
+      const int h = (h0 + j < H) ? h0 + j : H - 1;  // a valid row either way; surplus units are dropped below
+      const float4* src = reinterpret_cast<const float4*>(W1 + (int64_t)h * K + k);
+      const float4 a = src[0], b = src[1];
+      w[j][0] = a.x; w[j][1] = a.y; w[j][2] = a.z; w[j][3] = a.w;
+      w[j][4] = b.x; w[j][5] = b.y; w[j][6] = b.z; w[j][7] = b.w;
     }
 #pragma unroll
-    for (int t = 0; t < TPW; ++t)
+    for (int t = 0; t < TPW; ++t) {
+      const int64_t tok = (tok0 + t < T) ? tok0 + t : T - 1;  // a valid row either way
+      const uint4 xv = *reinterpret_cast<const uint4*>(X + tok * K + k);
+      const double x[8] = {bf16_lo(xv.x), bf16_hi(xv.x), bf16_lo(xv.y), bf16_hi(xv.y),
+                           bf16_lo(xv.z), bf16_hi(xv.z), bf16_lo(xv.w), bf16_hi(xv.w)};
 #pragma unroll
-      for (int j = 0; j < HC; ++j) {
-        double v = acc[t][j];
+      for (int j = 0; j < HC; ++j)
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
-        if (lane == 0) s_red[wave][t][j] = v;
-      }
-    __syncthreads();
-    if (tid < TPW * HC) {
-      const int t = tid / HC, j = tid % HC;
-      if (h0 + j < H) {
-        const double pre = ((s_red[0][t][j] + s_red[1][t][j]) + (s_red[2][t][j] + s_red[3][t][j])) + (double)b1[h0 + j];
-        s_hidden[t][h0 + j] = pre > 0.0 ? pre : 0.0;
-      }
+        for (int c = 0; c < 8; ++c) acc[t][j] = fma(x[c], w[j][c], acc[t][j]);
     }
-    __syncthreads();
   }
-  if (tid < TPW * kP) {
-    const int t = tid / kP, e = tid % kP;
+#pragma unroll
+  for (int t = 0; t < TPW; ++t)
+#pragma unroll
+    for (int j = 0; j < HC; ++j) {
+      double v = acc[t][j];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+      if (lane == 0) s_red[wave][t][j] = v;
+    }
+  __syncthreads();
+  if (tid < TPW * HC) {
+    const int t = tid / HC, j = tid % HC;
+    if (h0 + j < H && tok0 + t < T) {
+      const double pre = ((s_red[0][t][j] + s_red[1][t][j]) + (s_red[2][t][j] + s_red[3][t][j])) + (double)b1[h0 + j];
+      hidden[(tok0 + t) * H + h0 + j] = pre > 0.0 ? pre : 0.0;
+    }
+  }
+}
+
+// Hidden layer of larger batches on the fp64 matrix cores.  A workgroup of four wavefronts owns a tile
+// of 16 tokens x 16 hidden units; the K axis is dealt to the wavefronts in blocks of 32 columns.  One
+// v_mfma_f64_16x16x4 takes A[token i][k] from lane i + 16 k and B[k][unit j] from lane j + 16 k, so a
+// lane reads 8 consecutive columns of its token row and of its unit's weight row (16-byte loads) and
+// feeds them to 8 MFMAs, column c of every lane quarter forming the K = 4 of MFMA c.  The result lane
+// l, register r is D[token 4 r + l / 16][unit l % 16]; the four partial tiles meet in LDS.
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void route_mlp_hidden_mfma_kernel(const uint16_t* __restrict__ X, int64_t T,
+                                                                    int64_t K, const float* __restrict__ W1,
+                                                                    const float* __restrict__ b1, int H,
+                                                                    double* __restrict__ hidden) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t tok0 = (int64_t)blockIdx.x * 16;
+  const int h0 = (int)blockIdx.y * 16;
+  const int64_t tok = (tok0 + (lane & 15) < T) ? tok0 + (lane & 15) : T - 1;  // valid rows either way;
+  const int h = (h0 + (lane & 15) < H) ? h0 + (lane & 15) : H - 1;            // surplus results are dropped
+  const uint16_t* xrow = X + tok * K;
+  const float* wrow = W1 + (int64_t)h * K;
+  f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+  for (int64_t k = (int64_t)wave * 32 + (lane >> 4) * 8; k < K; k += 4 * 32) {
+    const uint4 xv = *reinterpret_cast<const uint4*>(xrow + k);
+    const float4 wa = *reinterpret_cast<const float4*>(wrow + k);
+    const float4 wb = *reinterpret_cast<const float4*>(wrow + k + 4);
+    const double x[8] = {bf16_lo(xv.x), bf16_hi(xv.x), bf16_lo(xv.y), bf16_hi(xv.y),
+                         bf16_lo(xv.z), bf16_hi(xv.z), bf16_lo(xv.w), bf16_hi(xv.w)};
+    const double w[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x[c], w[c], acc, 0, 0, 0);
+  }
+  __shared__ double s_part[4][64][4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) s_part[wave][lane][r] = acc[r];
+  __syncthreads();
+  {
+    const int l = tid >> 2, r = tid & 3;  // one result of the 16 x 16 tile per thread
+    const int64_t t = tok0 + 4 * r + (l >> 4);
+    const int hu = h0 + (l & 15);
+    if (t < T && hu < H) {
+      const double pre = ((s_part[0][l][r] + s_part[1][l][r]) + (s_part[2][l][r] + s_part[3][l][r])) + (double)b1[hu];
+      hidden[t * H + hu] = pre > 0.0 ? pre : 0.0;
+    }
+  }
+}
+
+// 64 tokens per workgroup: thread (token, slice) forms the score, then one thread per token decides.
+__global__ __launch_bounds__(256) void route_mlp_score_kernel(const double* __restrict__ hidden, int64_t T, int H,
+                                                              const float* __restrict__ W2,
+                                                              const float* __restrict__ b2, double delta,
+                                                              int32_t* prec, int32_t* __restrict__ perm,
+                                                              int32_t* __restrict__ offsets,
+                                                              double* __restrict__ scores,
+                                                              unsigned int* __restrict__ ticket) {
+  const int tid = threadIdx.x;
+  const int64_t tok = (int64_t)blockIdx.x * 64 + (tid >> 2);
+  const int e = tid & 3;
+  __shared__ double s_score[64][kP];
+  __shared__ unsigned int s_ticket;
+  if (tok < T) {
+    const double* hrow = hidden + tok * H;
     double s = 0.0;
-    for (int j = 0; j < H; ++j) s = fma(s_hidden[t][j], (double)W2[(int64_t)e * H + j], s);
+    for (int j = 0; j < H; ++j) s = fma(hrow[j], (double)W2[(int64_t)e * H + j], s);
     s += (double)b2[e];
-    s_score[t][e] = s;
-    if (scores && tok0 + t < T) scores[(tok0 + t) * kP + e] = s;
+    s_score[tid >> 2][e] = s;
+    if (scores) scores[tok * kP + e] = s;
   }
   __syncthreads();
-  if (tid < TPW && tok0 + tid < T) {
+  if (tid < 64 && (int64_t)blockIdx.x * 64 + tid < T) {
     int p = 0;
 #pragma unroll
-    for (int e = 1; e < kP; ++e) {
-      if (p == e - 1 && (s_score[tid][e] - delta) > 0.0) p = e;  // strict: a score on the threshold is inactive
+    for (int q = 1; q < kP; ++q) {
+      if (p == q - 1 && (s_score[tid][q] - delta) > 0.0) p = q;  // strict: a score on the threshold is inactive
     }
-    prec[tok0 + tid] = p;
+    prec[(int64_t)blockIdx.x * 64 + tid] = p;
     __threadfence();  // publish this workgroup's choices before taking a ticket
   }
   __syncthreads();
@@ -438,21 +491,30 @@ __global__ __launch_bounds__(256) void route_mlp_kernel(const uint16_t* __restri
   if (tid == 0) *ticket = 0u;
 }
 
+// ws: the ticket counter in the first 256 bytes, then the hidden layer, fp64 [T][H]
+size_t route_mlp_workspace_bytes(int64_t T, int H) { return 256 + (size_t)T * (size_t)H * sizeof(double); }
+
 mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
                             const float* W2, const float* b2, double delta, int32_t* prec, int32_t* perm,
                             int32_t* offsets, double* scores, void* ws, hipStream_t stream) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
+  double* hidden = reinterpret_cast<double*>(reinterpret_cast<char*>(ws) + 256);
   if (T == 0) {
     hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(64), 0, stream, prec, T, perm, offsets);
     return hip_status(hipGetLastError(), "bucket_kernel launch");
   }
-  if (T <= 512)
-    hipLaunchKernelGGL(route_mlp_kernel<1>, dim3((unsigned)T), dim3(256), 0, stream, X, T, K, W1, b1, H, W2, b2,
-                       delta, prec, perm, offsets, scores, ticket);
+  const unsigned chunks = (unsigned)((H + kMlpHiddenChunk - 1) / kMlpHiddenChunk);
+  if (T <= 256)
+    hipLaunchKernelGGL(route_mlp_hidden_kernel<1>, dim3((unsigned)T, chunks), dim3(256), 0, stream, X, T, K, W1, b1,
+                       H, hidden);
   else
-    hipLaunchKernelGGL(route_mlp_kernel<4>, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, stream, X, T, K, W1, b1, H,
-                       W2, b2, delta, prec, perm, offsets, scores, ticket);
-  return hip_status(hipGetLastError(), "route_mlp_kernel launch");
+    hipLaunchKernelGGL(route_mlp_hidden_mfma_kernel, dim3((unsigned)((T + 15) / 16), (unsigned)((H + 15) / 16)),
+                       dim3(256), 0, stream, X, T, K, W1, b1, H, hidden);
+  mbq_status st = hip_status(hipGetLastError(), "route_mlp_hidden_kernel launch");
+  if (st != MBQ_OK) return st;
+  hipLaunchKernelGGL(route_mlp_score_kernel, dim3((unsigned)((T + 63) / 64)), dim3(256), 0, stream, hidden, T, H, W2,
+                     b2, delta, prec, perm, offsets, scores, ticket);
+  return hip_status(hipGetLastError(), "route_mlp_score_kernel launch");
 }
 int route_mlp_max_hidden() { return kMlpMaxHidden; }
 

@@ -67,7 +67,7 @@ def test_route_and_bucket_are_bit_exact(mbq, T, K):
 
 # ------------------------------------------------------------- the paper's router (2-layer MLP + threshold)
 @pytest.mark.parametrize("T,K,H", [(0, 256, 8), (1, 128, 1), (16, 4096, 64), (37, 384, 13), (513, 512, 32),
-                                   (2048, 1024, 64), (300, 256, 512)])
+                                   (2048, 1024, 64), (300, 256, 512), (290, 384, 21)])
 def test_route_mlp_matches_oracle(mbq, T, K, H):
     """Scores to fp64 rounding, precisions bit-exact away from the threshold, permutation exact; a sweep of the
     threshold over one set of parameters switches precisions without touching anything else."""
