@@ -1,4 +1,4 @@
-// Preparation of the activations for the FP4-operand decode kernel: bf16 -> three BF8 (E5M2)
+// Preparation of the activations for the FP4-operand decode kernel: bf16 -> two FP8 (E4M3)
 // pieces in MFMA A-operand order, group sums and per-block scale exponents.  Shared by the
 // stand-alone preparation kernel and by the router launch that carries it along.
 #pragma once
@@ -8,8 +8,14 @@
 namespace mbq {
 namespace f4 {
 
-constexpr int kPieces = 3;
-// Prepared activations of one 256-column block: [2 groups][3 pieces][64 lanes] x 32 bytes, then
+constexpr int kPieces = 2;
+// The second piece holds the remainder of the first multiplied by 2^kPieceShift (its MFMAs get a block
+// scale that much smaller): a bf16 value v = 2^a (1.f) with a >= -6 in the scaled block is then
+// exactly piece0 + piece1 / 16 (four significant bits each), i.e. the split is exact over 13 binades
+// below the block's largest element and off by at most 2^-21 of that element further down.
+constexpr int kPieceShift = 4;
+// Prepared activations of one 256-column block: [2 groups][2 pieces][2 halves][64 lanes] x 16 bytes
+// (a lane's 32 operand bytes are split so that each 16-byte load of a wavefront is contiguous), then
 // per group the 16 token sums (fp32), then the 16 scale exponents (int32).
 constexpr size_t kPrepVecPerBlock = 2 * kPieces * 64 * 2;  // uint4 units
 constexpr size_t kPrepBytesPerBlock = kPrepVecPerBlock * 16 + 2 * 16 * 4 + 16 * 4;
@@ -56,9 +62,9 @@ __device__ inline void prep_block_rows(const uint16_t* __restrict__ X, int token
       }
   mx = max(mx, (uint32_t)__shfl_xor((int)mx, 16, 64));
   mx = max(mx, (uint32_t)__shfl_xor((int)mx, 32, 64));
-  // scale the largest element into [2^14, 2^15): below the BF8 maximum 57344
-  int scale_byte = (int)(mx >> 23) - 14;  // = 127 + k, x = 2^k * scaled
-  scale_byte = min(max(scale_byte, 1), 254);
+  // scale the largest element into [2^7, 2^8): below the FP8 (E4M3) maximum 448
+  int scale_byte = (int)(mx >> 23) - 7;  // = 127 + k, x = 2^k * scaled
+  scale_byte = min(max(scale_byte, 1 + kPieceShift), 254);
   const int down = 127 - scale_byte;      // exponent of the factor applied to x
   if (qa == 0) scl[m] = scale_byte;
 
@@ -84,13 +90,13 @@ __device__ inline void prep_block_rows(const uint16_t* __restrict__ X, int token
         for (int piece = 0; piece < kPieces; ++piece)
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            int packed = __builtin_amdgcn_cvt_pk_bf8_f32(v[h][0], v[h][1], 0, false);
-            packed = __builtin_amdgcn_cvt_pk_bf8_f32(v[h][2], v[h][3], packed, true);
+            int packed = __builtin_amdgcn_cvt_pk_fp8_f32(v[h][0], v[h][1], 0, false);
+            packed = __builtin_amdgcn_cvt_pk_fp8_f32(v[h][2], v[h][3], packed, true);
             piece_regs[piece][4 * c + 2 * step + h] = packed;
-            v[h][0] -= __builtin_amdgcn_cvt_f32_bf8(packed, 0);
-            v[h][1] -= __builtin_amdgcn_cvt_f32_bf8(packed, 1);
-            v[h][2] -= __builtin_amdgcn_cvt_f32_bf8(packed, 2);
-            v[h][3] -= __builtin_amdgcn_cvt_f32_bf8(packed, 3);
+            v[h][0] = (v[h][0] - __builtin_amdgcn_cvt_f32_fp8(packed, 0)) * (float)(1 << kPieceShift);
+            v[h][1] = (v[h][1] - __builtin_amdgcn_cvt_f32_fp8(packed, 1)) * (float)(1 << kPieceShift);
+            v[h][2] = (v[h][2] - __builtin_amdgcn_cvt_f32_fp8(packed, 2)) * (float)(1 << kPieceShift);
+            v[h][3] = (v[h][3] - __builtin_amdgcn_cvt_f32_fp8(packed, 3)) * (float)(1 << kPieceShift);
           }
       }
     sum += __shfl_xor(sum, 16, 64);
@@ -98,10 +104,10 @@ __device__ inline void prep_block_rows(const uint16_t* __restrict__ X, int token
     if (qa == 0) sums[16 * g + m] = sum;
 #pragma unroll
     for (int piece = 0; piece < kPieces; ++piece) {
-      uint4* dst = out + ((size_t)(g * kPieces + piece) * 64 + lane) * 2;
+      uint4* dst = out + (size_t)(g * kPieces + piece) * 128 + lane;
       const int* r = piece_regs[piece];
       dst[0] = uint4{(uint32_t)r[0], (uint32_t)r[1], (uint32_t)r[2], (uint32_t)r[3]};
-      dst[1] = uint4{(uint32_t)r[4], (uint32_t)r[5], (uint32_t)r[6], (uint32_t)r[7]};
+      dst[64] = uint4{(uint32_t)r[4], (uint32_t)r[5], (uint32_t)r[6], (uint32_t)r[7]};
     }
   }
 }

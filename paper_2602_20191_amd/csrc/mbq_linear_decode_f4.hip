@@ -9,26 +9,27 @@
 //
 // Arithmetic.  A 2-bit code c zero-extended to four bits IS the FP4 (E2M1) number c/2, so a
 // packed dword turns into MFMA operands with a rotate and a mask per eight codes.  The bf16
-// activations are split once, by a small preparation kernel, into three BF8 (E5M2) pieces
-// x = x1 + x2 + x3 (each the round-to-nearest of what is left; 3 + 3 + 2 significant bits, so
-// the split is exact over 24 binades below the largest element of the token's 256-column block,
-// which a per-block power-of-two scale moves to the top of the BF8 range).  Every product
-// piece x code is exact and v_mfma_scale_f32_16x16x128_f8f6f4 accumulates in fp32.  Its
-// per-lane block scales do the rest of the bookkeeping at no cost:
+// activations are split once, by a small preparation kernel, into two FP8 (E4M3) pieces
+// x = x1 + x2 / 16 (x1 the round-to-nearest of x, x2 that of 16 (x - x1); four significant bits
+// each), after a power-of-two scale per (token, 256-column block) that puts the block's largest
+// element just below 2^8: the split is exact for every element within 13 binades of that largest
+// element and off by at most 2^-21 of it below.  Every product piece x code is exact and
+// v_mfma_scale_f32_16x16x128_f8f6f4 accumulates in fp32.  Its per-lane block scales do the rest of
+// the bookkeeping at no cost:
 //   - the B scale of slice e is 2^(1-2e): the operand c/2 counts as c / 4^e;
-//   - the A scale byte of token i and slice e undoes the block scale when e <= p_i and is
-//     2^-127 otherwise, so one accumulator chain over the slices yields sum_{e<=p_i} for
-//     every token at once (the leak of a masked slice is below 2^-100 of the output).
+//   - the A scale byte of token i and slice e undoes the block scale (times 2^-4 for the second
+//     piece) when e <= p_i and is 2^-127 otherwise, so one accumulator chain over the slices yields
+//     sum_{e<=p_i} for every token at once (the leak of a masked slice is below 2^-100 of the output).
 // With D that chain and Sx the group sum of x,
 //   y += s0 * (D + (0.5 - 1.5 q_p - z0) Sx),   q_p = sum_{1 <= e <= p} 4^-e.
 //
 // Work split: the 16-row code tiles of all matrices form one list; a workgroup of 8 wavefronts
-// owns tiles blockIdx.x, blockIdx.x + gridDim.x, ...  Wavefront w owns the 256-column blocks
-// w and w + 8 of every tile, keeps their activation pieces in registers for the whole kernel
-// and streams only packed weights, always fetching the next tile before consuming the current
-// one.  The load count per tile is fixed (a slice that the tile does not need is replaced by a
-// load of one fixed KiB that stays in the vector cache), so the hardware wait counters let the
-// next tile's loads stay in flight.
+// owns tiles blockIdx.x, blockIdx.x + gridDim.x, ...  A wavefront owns two 256-column blocks of
+// every tile (K <= 4096) and keeps their activation pieces in registers for the whole kernel, so
+// only packed weights stream; they travel through a per-wavefront ring in LDS that the memory
+// system fills directly (see decode_f4_ring_kernel).  The load count per block is fixed (a slice
+// that the tile does not need is replaced by a load of one fixed KiB that stays in the vector
+// cache), so the wavefront can count its own outstanding loads.
 #include "mbq_common.h"
 #include "mbq_f4_prep.h"
 
@@ -73,7 +74,7 @@ __device__ inline void nibbles(uint32_t w, uint32_t mask, int& step0, int& step1
 }
 
 template <int E>
-__device__ inline floatx4 slice_group(const intx8* A, uint32_t w_lo, uint32_t w_hi, uint32_t mask, int sa, int sb,
+__device__ inline floatx4 slice_group(const intx8* A, uint32_t w_lo, uint32_t w_hi, uint32_t mask, int sa, int sa2, int sb,
                                        floatx4 D) {
   intx8 B = {0, 0, 0, 0, 0, 0, 0, 0};
   int b0, b1, b2, b3;
@@ -82,7 +83,8 @@ __device__ inline floatx4 slice_group(const intx8* A, uint32_t w_lo, uint32_t w_
   B[0] = b0; B[1] = b1; B[2] = b2; B[3] = b3;
 #pragma unroll
   for (int piece = 0; piece < kPieces; ++piece)
-    D = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A[piece], B, D, 1 /* A: BF8 */, 4 /* B: FP4 */, E, sa, E, sb);
+    D = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A[piece], B, D, 0 /* A: FP8 E4M3 */, 4 /* B: FP4 */, E,
+                                                         piece == 0 ? sa : sa2, E, sb);
   return D;
 }
 
@@ -93,52 +95,111 @@ struct Item {  // one 16 x 256 block: four slices and the {s0, z0} of its two gr
 
 }  // namespace f4
 
-template <int kWaves, int CPW>
-__global__ __launch_bounds__(kWaves * 64) void decode_f4_kernel(const char* __restrict__ prep, int T, int KB,
-                                                                     const f4::Group g) {
+// ---- the same kernel with the packed weights in flight in LDS instead of registers -------------
+// A load that is in flight to a register pins that register, and the register file (activation
+// pieces + one tile being consumed + one arriving) allows one tile ahead: 64 KiB per compute unit,
+// too little to cover the memory latency at 8 TB/s.  Here each wavefront owns a ring of kRingDepth
+// slots in LDS and asks the memory system to write the 16 x 256 blocks ("items": four slices of
+// 1 KiB + the 256 bytes of {s0, z0}) straight into them (global_load_lds), kRingDepth items ahead;
+// an item is copied to registers just before it is consumed, and its slot is handed to the item
+// kRingDepth further on.  Slots are private to a wavefront, so no barrier guards them; the wavefront
+// counts its own outstanding loads (they complete in issue order; a younger store or load in the
+// count only makes a wait stricter).
+namespace f4 {
+constexpr int kRingDepth = 4;
+constexpr int kLoadsPerItem = 5;                // 4 slices (16 bytes per lane) + 1 meta (4 bytes per lane)
+constexpr int kSlotBytes = 4 * 1024 + 256;
+
+__device__ __forceinline__ void to_lds_16(const void* gptr, char* lds_base) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
+                                   (void __attribute__((address_space(3)))*)lds_base, 16, 0, 0);
+}
+__device__ __forceinline__ void to_lds_4(const void* gptr, char* lds_base) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
+                                   (void __attribute__((address_space(3)))*)lds_base, 4, 0, 0);
+}
+// wait until at most `items_behind` later items are still on their way
+__device__ __forceinline__ void ring_wait(int items_behind) {
+  if (items_behind >= 3) asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
+  else if (items_behind == 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+  else if (items_behind == 1) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+// One item from its slot to registers.  Written as one asm block (reads + their wait) for two
+// reasons: the compiler orders every LDS read it knows about after ALL outstanding loads into LDS,
+// which would drain the ring; and no register is visible to it while its read is in flight.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void read_slot(uint32_t lane_addr, uint32_t row_addr, u32x4 (&w)[4], f32x2 (&mt)[2]) {
+  asm volatile(
+      "ds_read_b128 %0, %6\n\t"
+      "ds_read_b128 %1, %6 offset:1024\n\t"
+      "ds_read_b128 %2, %6 offset:2048\n\t"
+      "ds_read_b128 %3, %6 offset:3072\n\t"
+      "ds_read_b64 %4, %7 offset:4096\n\t"
+      "ds_read_b64 %5, %7 offset:4224\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3]), "=&v"(mt[0]), "=&v"(mt[1])
+      : "v"(lane_addr), "v"(row_addr)
+      : "memory");
+}
+// the eight wavefronts' partial sums of one output (1 KiB apart), same reasons
+__device__ __forceinline__ float read_partials_sum(uint32_t addr) {
+  float v[8];
+  asm volatile(
+      "ds_read_b32 %0, %8\n\t"
+      "ds_read_b32 %1, %8 offset:1024\n\t"
+      "ds_read_b32 %2, %8 offset:2048\n\t"
+      "ds_read_b32 %3, %8 offset:3072\n\t"
+      "ds_read_b32 %4, %8 offset:4096\n\t"
+      "ds_read_b32 %5, %8 offset:5120\n\t"
+      "ds_read_b32 %6, %8 offset:6144\n\t"
+      "ds_read_b32 %7, %8 offset:7168\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+      : "v"(addr)
+      : "memory");
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sum += v[i];
+  return sum;
+}
+// workgroup barrier that orders LDS traffic only (the loads into the ring stay in flight across it)
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// wait until at most `kLater` younger loads are outstanding; the four registers, written by loads
+// that the compiler does not know about, may be looked at only after this
+template <int kLater>
+__device__ __forceinline__ void loads_arrived(int& a, int& b, int& c, int& d) {
+  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(kLater) : "memory");
+}
+static_assert(kPieces == 2, "slice_group picks the scale of a piece by piece == 0");
+static_assert(kRingDepth == 4 && kLoadsPerItem == 5, "ring_wait's constants are (kRingDepth - 1 .. 0) * kLoadsPerItem");
+}  // namespace f4
+
+template <int CPW>
+__global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restrict__ prep, int T, int KB,
+                                                             const f4::Group g) {
   using namespace f4;
+  constexpr int kWaves = 8;
+  constexpr int kXaLoads = 2 * kPieces * 2 + 2 + 1;  // loads of one block's prepared activations
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int m = lane & 15;   // token row of A / weight row of B / output column
-  const int kq = lane >> 4;  // k sub-block; output rows 4 kq .. 4 kq + 3
-  const int my_tiles = (g.tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int m = lane & 15;
+  const int kq = lane >> 4;
+  const int bid = (int)blockIdx.x;
+  const int my_tiles = (g.tiles - bid + (int)gridDim.x - 1) / (int)gridDim.x;
   if (my_tiles <= 0) return;
+  const int total = my_tiles * CPW;  // items of this wavefront: (tile index q / CPW, chunk q % CPW)
+  // This wavefront's 256-column blocks are blk0 and blk0 + 8.  The assignment rotates with the
+  // workgroup so that the compute units of one XCD, which all start by fetching the prepared
+  // activations of their blocks, do not all ask the L2 for the same lines at the same moment.
+  const int blk0 = (wave + bid) & (kWaves - 1);
 
-  __shared__ float red[2][kWaves][64][4];  // per-wavefront partial tiles, double buffered
-
-  // ---- precisions of every matrix (the first loads issued: what depends on them waits least) ----
-  int pl[MBQ_MAX_GROUP];
-#pragma unroll
-  for (int j = 0; j < MBQ_MAX_GROUP; ++j) pl[j] = (j < g.n && lane < T) ? g.p[j].prec[lane] : -1;
-
-  // ---- prepared activations of this wavefront's blocks ----
-  // block c is wave + 8 c; a block past the end contributes zeros (its token scales are set to
-  // 2^-127 and its sums to zero) and its weight loads are pointed at block 0 of the tile.
-  intx8 xa[CPW][2][kPieces];
-  floatx4 sx[CPW][2];  // group sums of the tokens 4 kq .. 4 kq + 3
-  int tok_scale[CPW];
-  int kb_of[CPW];
-#pragma unroll
-  for (int c = 0; c < CPW; ++c) {
-    const int kb = wave + kWaves * c;
-    const bool there = kb < KB;
-    kb_of[c] = there ? kb : 0;
-    const char* base = prep + (size_t)kb_of[c] * kPrepBytesPerBlock;
-    const uint4* src = reinterpret_cast<const uint4*>(base);
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-#pragma unroll
-      for (int piece = 0; piece < kPieces; ++piece) {
-        const uint4 lo = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2];
-        const uint4 hi = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2 + 1];
-        xa[c][h][piece] = intx8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-      }
-      const floatx4 s = *reinterpret_cast<const floatx4*>(base + kPrepVecPerBlock * 16 + (16 * h + 4 * kq) * 4);
-      sx[c][h] = there ? s : floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-    const int sc = reinterpret_cast<const int*>(base + kPrepVecPerBlock * 16 + 2 * 16 * 4)[m];
-    tok_scale[c] = there ? sc : 0;
-  }
+  __shared__ __attribute__((aligned(1024))) char ring[kWaves * kRingDepth * kSlotBytes];
+  __shared__ float red[2][kWaves][64][4];
+  char* const my_ring = ring + wave * (kRingDepth * kSlotBytes);
+  const uint32_t red_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)&red[0][0][0][0];
+  const uint32_t my_ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)my_ring;
 
   const uint4* dummy = reinterpret_cast<const uint4*>(prep);  // 1 KiB that stays in the vector cache
   auto proj_of = [&](int t) {
@@ -148,52 +209,127 @@ __global__ __launch_bounds__(kWaves * 64) void decode_f4_kernel(const char* __re
       if (i < g.n && t >= g.p[i].tile_begin) j = i;
     return j;
   };
-  auto load_base = [&](int t, Item (&I)[CPW]) {
+  // request item q (q < total) with slices 0..pm
+  auto request = [&](int q, int pm) {
+    const int t = bid + (q / CPW) * (int)gridDim.x;
+    int kb = blk0 + kWaves * (q % CPW);
+    if (kb >= KB) kb = 0;  // a block past the end: its activations are zeros, any weights will do
     const Proj& P = g.p[proj_of(t)];
     const int nt = t - P.tile_begin;
+    char* slot = my_ring + (q % kRingDepth) * kSlotBytes;
+    const size_t tile = ((size_t)nt * KB + kb) * 64 + lane;
 #pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-      I[c].w[0] = P.codes[((size_t)nt * KB + kb_of[c]) * 64 + lane];
-      I[c].mt[0] = P.meta[((size_t)nt * (2 * KB) + 2 * kb_of[c]) * kTileN + m];
-      I[c].mt[1] = P.meta[((size_t)nt * (2 * KB) + 2 * kb_of[c] + 1) * kTileN + m];
+    for (int e = 0; e < 4; ++e) {
+      const uint4* src = (e <= pm) ? P.codes + ((size_t)e * P.slice_vec + tile) : dummy + lane;
+      to_lds_16(src, slot + e * 1024);
     }
+    to_lds_4(reinterpret_cast<const char*>(P.meta + ((size_t)nt * (2 * KB) + 2 * kb) * kTileN) + 4 * lane, slot + 4096);
   };
-  auto load_rest = [&](int t, int pm, Item (&I)[CPW]) {
-    const Proj& P = g.p[proj_of(t)];
-    const int nt = t - P.tile_begin;
-#pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-      const size_t tile = ((size_t)nt * KB + kb_of[c]) * 64 + lane;
-#pragma unroll
-      for (int e = 1; e < 4; ++e) {
-        const uint4* src = (e <= pm) ? P.codes + ((size_t)e * P.slice_vec + tile) : dummy + lane;
-        I[c].w[e] = *src;
-      }
-    }
-  };
-  Item cur[CPW], nxt[CPW];
-  load_base((int)blockIdx.x, cur);
 
-  // ---- routing facts: highest precision present per matrix ----
-  int pmax[MBQ_MAX_GROUP];
+  // Every load of the prologue is hidden from the compiler (it orders each wait of its own after ALL
+  // loads into LDS, which would serialise the prologue); the registers they write are looked at only
+  // after the hand-counted waits below, and only straight-line code lies between a load and its wait.
+  //   precisions of every matrix: no branch on g.n (an unused slot of g repeats matrix 0 and its result
+  //   is never looked at); lanes past T are set to -1 in find_pmax
+  int pl[MBQ_MAX_GROUP];
+  auto load_precisions = [&]() {
 #pragma unroll
-  for (int j = 0; j < MBQ_MAX_GROUP; ++j)
-    pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
+    for (int j = 0; j < MBQ_MAX_GROUP; ++j)
+      asm volatile("global_load_dword %0, %1, off" : "=v"(pl[j]) : "v"(g.p[j].prec + (lane < T ? lane : 0)) : "memory");
+  };
+  //   prepared activations of this wavefront's blocks (kept in registers throughout); a block past the
+  //   end reads block 0 and is zeroed after the wait
+  u32x4 xa_raw[CPW][2][kPieces][2];
+  floatx4 sx[CPW][2];
+  int tok_scale[CPW];
+  auto load_activations = [&](int c) {
+    const int kb = blk0 + kWaves * c;
+    const char* base = prep + (size_t)(kb < KB ? kb : 0) * kPrepBytesPerBlock;
+    const char* lane_vec = base + (size_t)lane * 16;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int piece = 0; piece < kPieces; ++piece) {
+        const char* src = lane_vec + (size_t)(h * kPieces + piece) * 2048;
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(xa_raw[c][h][piece][0]) : "v"(src) : "memory");
+        asm volatile("global_load_dwordx4 %0, %1, off offset:1024" : "=v"(xa_raw[c][h][piece][1]) : "v"(src) : "memory");
+      }
+      asm volatile("global_load_dwordx4 %0, %1, off"
+                   : "=v"(sx[c][h]) : "v"(base + kPrepVecPerBlock * 16 + (16 * h + 4 * kq) * 4) : "memory");
+    }
+    asm volatile("global_load_dword %0, %1, off"
+                 : "=v"(tok_scale[c]) : "v"(base + kPrepVecPerBlock * 16 + 2 * 16 * 4 + 4 * m) : "memory");
+  };
+
+  // Routing facts: highest precision present per matrix.
+  int pmax[MBQ_MAX_GROUP];
+  auto find_pmax = [&]() {
+#pragma unroll
+    for (int j = 0; j < MBQ_MAX_GROUP; ++j) pl[j] = lane < T ? pl[j] : -1;
+#pragma unroll
+    for (int j = 0; j < MBQ_MAX_GROUP; ++j)
+      pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
+  };
   auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
-  load_rest((int)blockIdx.x, pmax_of(proj_of((int)blockIdx.x)), cur);
+  auto request_routed = [&](int q) { request(q, pmax_of(proj_of(bid + (q / CPW) * (int)gridDim.x))); };
+
+  // With eight or more tokens some token almost always wants every slice: the first tile then asks for
+  // all four at once instead of waiting for the precisions to arrive (one memory latency less before
+  // the first MFMA; a slice fetched in vain costs bandwidth only).
+  int first_routed;  // first item that has not been requested yet
+  if (T >= 8) {
+    load_precisions();
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      request(c, 3);
+      load_activations(c);
+    }
+    loads_arrived<CPW * (kLoadsPerItem + kXaLoads)>(pl[0], pl[1], pl[2], pl[3]);
+    find_pmax();
+    first_routed = CPW;
+  } else {
+    load_precisions();
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) load_activations(c);
+    loads_arrived<CPW * kXaLoads>(pl[0], pl[1], pl[2], pl[3]);
+    find_pmax();
+    first_routed = 0;
+  }
+  // Only the first tile is requested before the loop: the memory pipeline of the compute unit serves
+  // requests in order, and what the first MFMAs need (this tile and the activations) should not queue
+  // behind prefetches.  The loop then keeps the ring full.
+  for (int q = first_routed; q < CPW; ++q) request_routed(q);
+  int next_request = CPW;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the activations (and the first tile) have arrived
+  intx8 xa[CPW][2][kPieces];
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int piece = 0; piece < kPieces; ++piece) {
+        asm volatile("" : "+v"(xa_raw[c][h][piece][0]), "+v"(xa_raw[c][h][piece][1]));
+        const u32x4 lo = xa_raw[c][h][piece][0], hi = xa_raw[c][h][piece][1];
+        xa[c][h][piece] = intx8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+      }
+      asm volatile("" : "+v"(sx[c][h]));
+    }
+    asm volatile("" : "+v"(tok_scale[c]));
+    if (blk0 + kWaves * c >= KB) {
+      tok_scale[c] = 0;
+      sx[c][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+      sx[c][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+  }
 
   uint32_t nib_mask = 0x33333333u;
   asm volatile("" : "+s"(nib_mask));  // keep the mask in a register: one v_and_b32 per operand dword
   const int sb = 0x7A7C7E80;          // B scale bytes 2^(1-2e), e = 0..3
   const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-  // one step: fetch tile ti+1 into `nx`, consume tile ti from `cu`, reduce and store
-  auto step = [&](int ti, Item (&cu)[CPW], Item (&nx)[CPW]) {
-    const int t = (int)blockIdx.x + ti * (int)gridDim.x;
-    const int tn = (int)blockIdx.x + min(ti + 1, my_tiles - 1) * (int)gridDim.x;
-    load_base(tn, nx);
-    load_rest(tn, pmax_of(proj_of(tn)), nx);
-
+#pragma unroll 1
+  for (int ti = 0; ti < my_tiles; ++ti) {
+    const int t = bid + ti * (int)gridDim.x;
     const int j = proj_of(t);
     const int pm = pmax_of(j);
     const int plv = j == 0 ? pl[0] : j == 1 ? pl[1] : j == 2 ? pl[2] : pl[3];
@@ -210,22 +346,35 @@ __global__ __launch_bounds__(kWaves * 64) void decode_f4_kernel(const char* __re
     floatx4 acc = zero4;
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
-      const Item& I = cu[c];
+      const int q = ti * CPW + c;
+      const uint32_t slot = my_ring_addr + (uint32_t)((q % kRingDepth) * kSlotBytes);
+      ring_wait(min(next_request, total) - 1 - q);  // items q + 1 .. next_request - 1 may still be on their way
+      u32x4 wv[4];
+      f32x2 mv[2];
+      read_slot(slot + lane * 16, slot + m * 8, wv, mv);
+      // the slot has been read: items up to q + kRingDepth fit in the ring
+      for (; next_request <= q + kRingDepth && next_request < total; ++next_request) request_routed(next_request);
+      Item I;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) I.w[e] = uint4{wv[e].x, wv[e].y, wv[e].z, wv[e].w};
+      I.mt[0] = float2{mv[0].x, mv[0].y};
+      I.mt[1] = float2{mv[1].x, mv[1].y};
+
       const int sa = (int)(((uint32_t)tok_scale[c] * 0x01010101u) & gate);
-      // the two groups of the block run as two independent accumulator chains
-      floatx4 D0 = slice_group<0>(xa[c][0], I.w[0].x, I.w[0].y, nib_mask, sa, sb, zero4);
-      floatx4 D1 = slice_group<0>(xa[c][1], I.w[0].z, I.w[0].w, nib_mask, sa, sb, zero4);
+      const int sa2 = (int)(((uint32_t)max(tok_scale[c] - kPieceShift, 0) * 0x01010101u) & gate);  // second piece is stored 2^kPieceShift times larger
+      floatx4 D0 = slice_group<0>(xa[c][0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
+      floatx4 D1 = slice_group<0>(xa[c][1], I.w[0].z, I.w[0].w, nib_mask, sa, sa2, sb, zero4);
       if (pm >= 1) {
-        D0 = slice_group<1>(xa[c][0], I.w[1].x, I.w[1].y, nib_mask, sa, sb, D0);
-        D1 = slice_group<1>(xa[c][1], I.w[1].z, I.w[1].w, nib_mask, sa, sb, D1);
+        D0 = slice_group<1>(xa[c][0], I.w[1].x, I.w[1].y, nib_mask, sa, sa2, sb, D0);
+        D1 = slice_group<1>(xa[c][1], I.w[1].z, I.w[1].w, nib_mask, sa, sa2, sb, D1);
       }
       if (pm >= 2) {
-        D0 = slice_group<2>(xa[c][0], I.w[2].x, I.w[2].y, nib_mask, sa, sb, D0);
-        D1 = slice_group<2>(xa[c][1], I.w[2].z, I.w[2].w, nib_mask, sa, sb, D1);
+        D0 = slice_group<2>(xa[c][0], I.w[2].x, I.w[2].y, nib_mask, sa, sa2, sb, D0);
+        D1 = slice_group<2>(xa[c][1], I.w[2].z, I.w[2].w, nib_mask, sa, sa2, sb, D1);
       }
       if (pm >= 3) {
-        D0 = slice_group<3>(xa[c][0], I.w[3].x, I.w[3].y, nib_mask, sa, sb, D0);
-        D1 = slice_group<3>(xa[c][1], I.w[3].z, I.w[3].w, nib_mask, sa, sb, D1);
+        D0 = slice_group<3>(xa[c][0], I.w[3].x, I.w[3].y, nib_mask, sa, sa2, sb, D0);
+        D1 = slice_group<3>(xa[c][1], I.w[3].z, I.w[3].w, nib_mask, sa, sa2, sb, D1);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -236,22 +385,15 @@ __global__ __launch_bounds__(kWaves * 64) void decode_f4_kernel(const char* __re
     // sum the wavefronts' partial tiles; rows leave in token order
     const int buf = ti & 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) red[buf][wave][lane][i] = acc[i];
-    __syncthreads();
+    for (int i = 0; i < 4; ++i) red[buf][blk0][lane][i] = acc[i];  // filed by block, so the sum below does not depend on the rotation
+    lds_barrier();
     if (threadIdx.x < 256) {
       const Proj& P = g.p[j];
       const int r = threadIdx.x >> 4, cc = threadIdx.x & 15;
       const int64_t col = (int64_t)(t - P.tile_begin) * kTileN + cc;
-      float sum = 0.f;
-#pragma unroll
-      for (int wv = 0; wv < kWaves; ++wv) sum += red[buf][wv][16 * (r >> 2) + cc][r & 3];
+      const float sum = read_partials_sum(red_addr + (uint32_t)(buf * (kWaves * 1024) + (16 * (r >> 2) + cc) * 16 + (r & 3) * 4));
       if (r < T && col < P.N) P.Y[(int64_t)r * P.N + col] = sum;
     }
-  };
-#pragma unroll 1
-  for (int ti = 0; ti < my_tiles; ti += 2) {
-    step(ti, cur, nxt);
-    if (ti + 1 < my_tiles) step(ti + 1, nxt, cur);
   }
 }
 
@@ -304,8 +446,8 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
       for (int piece = 0; piece < kPieces; ++piece) {
-        const uint4 lo = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2];
-        const uint4 hi = src[((size_t)(h * kPieces + piece) * 64 + lane) * 2 + 1];
+        const uint4 lo = src[(size_t)(h * kPieces + piece) * 128 + lane];
+        const uint4 hi = src[(size_t)(h * kPieces + piece) * 128 + 64 + lane];
         I.xa[h][piece] = intx8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
       }
       I.sx[h] = *reinterpret_cast<const floatx4*>(base + kPrepVecPerBlock * 16 + (16 * h + 4 * kq) * 4);
@@ -374,19 +516,20 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
     }
     const Item& I = cu.w;
     const int sa = (int)(((uint32_t)cu.scale * 0x01010101u) & gate);
-    floatx4 D0 = slice_group<0>(cu.xa[0], I.w[0].x, I.w[0].y, nib_mask, sa, sb, zero4);
-    floatx4 D1 = slice_group<0>(cu.xa[1], I.w[0].z, I.w[0].w, nib_mask, sa, sb, zero4);
+    const int sa2 = (int)(((uint32_t)max(cu.scale - kPieceShift, 0) * 0x01010101u) & gate);
+    floatx4 D0 = slice_group<0>(cu.xa[0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
+    floatx4 D1 = slice_group<0>(cu.xa[1], I.w[0].z, I.w[0].w, nib_mask, sa, sa2, sb, zero4);
     if (pm >= 1) {
-      D0 = slice_group<1>(cu.xa[0], I.w[1].x, I.w[1].y, nib_mask, sa, sb, D0);
-      D1 = slice_group<1>(cu.xa[1], I.w[1].z, I.w[1].w, nib_mask, sa, sb, D1);
+      D0 = slice_group<1>(cu.xa[0], I.w[1].x, I.w[1].y, nib_mask, sa, sa2, sb, D0);
+      D1 = slice_group<1>(cu.xa[1], I.w[1].z, I.w[1].w, nib_mask, sa, sa2, sb, D1);
     }
     if (pm >= 2) {
-      D0 = slice_group<2>(cu.xa[0], I.w[2].x, I.w[2].y, nib_mask, sa, sb, D0);
-      D1 = slice_group<2>(cu.xa[1], I.w[2].z, I.w[2].w, nib_mask, sa, sb, D1);
+      D0 = slice_group<2>(cu.xa[0], I.w[2].x, I.w[2].y, nib_mask, sa, sa2, sb, D0);
+      D1 = slice_group<2>(cu.xa[1], I.w[2].z, I.w[2].w, nib_mask, sa, sa2, sb, D1);
     }
     if (pm >= 3) {
-      D0 = slice_group<3>(cu.xa[0], I.w[3].x, I.w[3].y, nib_mask, sa, sb, D0);
-      D1 = slice_group<3>(cu.xa[1], I.w[3].z, I.w[3].w, nib_mask, sa, sb, D1);
+      D0 = slice_group<3>(cu.xa[0], I.w[3].x, I.w[3].y, nib_mask, sa, sa2, sb, D0);
+      D1 = slice_group<3>(cu.xa[1], I.w[3].z, I.w[3].w, nib_mask, sa, sa2, sb, D1);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -480,9 +623,9 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
   if (s0.KB > 16)
     hipLaunchKernelGGL(decode_f4_stream_kernel, dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
   else if (s0.KB <= 8)
-    hipLaunchKernelGGL((decode_f4_kernel<8, 1>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
+    hipLaunchKernelGGL((decode_f4_ring_kernel<1>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
   else
-    hipLaunchKernelGGL((decode_f4_kernel<8, 2>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
+    hipLaunchKernelGGL((decode_f4_ring_kernel<2>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
   return hip_status(hipGetLastError(), "decode_f4_kernel launch");
 }
 
