@@ -65,7 +65,9 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
       // precision-sorted tokens: the register-stationary chunked kernel when K <= 4096 or a
       // workgroup has many row tiles; short, wide matrices keep every column block in flight.
       if (knob(3) == 0 && decode_f4_supports(T, sh)) {
-        mbq_status st = launch_decode_f4_prep(X, T, sh.K, sh.KB, ws, s);
+        ZeroList zl;
+        decode_f4_zero_list(T, 1, &sh, &Y, &zl);
+        mbq_status st = launch_decode_f4_prep(X, T, sh.K, sh.KB, ws, zl, s);
         if (st != MBQ_OK) return st;
         return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s);
       }
@@ -203,7 +205,7 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
     return MBQ_ERR_WORKSPACE;
   }
   return launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr, ws,
-                            (hipStream_t)stream, nullptr, 0);
+                            (hipStream_t)stream, nullptr, 0, nullptr);
 }
 
 size_t mbq_route_mlp_workspace_bytes(int64_t T, int64_t K, int H) {
@@ -274,8 +276,10 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
            offsets_host[i] && ws_linear_bytes >= mbq_linear_workspace_bytes(T, N_host[i], K);
     }
     if (ok && knob(3) == 0 && decode_f4_supports(T, sh[0]) && route_can_carry_prep(T)) {
+      ZeroList zl;
+      decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
       mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
-                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB);
+                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl);
       if (st != MBQ_OK) return st;
       return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream);
     }
@@ -371,7 +375,9 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
   hipStream_t s = (hipStream_t)stream;
   if (algo == MBQ_ALGO_DECODE && knob(3) == 0 && decode_f4_supports(T, sh[0])) {
     // knob 6 = 1 (measurement only): the workspace already holds the prepared activations
-    mbq_status st = knob(6) == 1 ? MBQ_OK : launch_decode_f4_prep(X, T, K, sh[0].KB, ws, s);
+    ZeroList zl;
+    decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
+    mbq_status st = knob(6) == 1 ? MBQ_OK : launch_decode_f4_prep(X, T, K, sh[0].KB, ws, zl, s);
     if (st != MBQ_OK) return st;
     return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s);
   }

@@ -53,6 +53,13 @@ __host__ __device__ inline size_t meta_index(int KB, int64_t n, int g) {
   return ((size_t)(n >> 4) * (2 * KB) + g) * kTileN + (size_t)(n & 15);
 }
 
+// Output arrays that the activation-preparation launch clears for a linear kernel that adds into
+// them (all null: nothing to clear).
+struct ZeroList {
+  float* p[MBQ_MAX_GROUP];
+  long long n[MBQ_MAX_GROUP];  // floats
+};
+
 // ---- kernels' host launchers (each enqueues on `stream`, returns a status) ------
 mbq_status launch_encode(const float* W, const Shape& sh, void* blob, hipStream_t stream);
 mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* codes, float* scale, float* zero,
@@ -64,7 +71,7 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
-                              void* prep, int prep_blocks);
+                              void* prep, int prep_blocks, const ZeroList* zl);
 bool route_can_carry_prep(int64_t T);
 mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
                             const float* W2, const float* b2, double delta, int32_t* prec, int32_t* perm,
@@ -84,8 +91,21 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
 bool decode_f4_supports(int64_t T, const Shape& sh);
+int decode_f4_k_parts(const Shape& sh);
+void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);
+// share `part` of `parts` of the clearing, done by `nthreads` threads of which this is `tid`
+__device__ inline void zero_share(const ZeroList& zl, int part, int parts, int tid, int nthreads) {
+#pragma unroll
+  for (int j = 0; j < MBQ_MAX_GROUP; ++j) {
+    float* p = zl.p[j];
+    if (p == nullptr) continue;
+    const long long n = zl.n[j];
+    for (long long i = (long long)part * nthreads + tid; i < n; i += (long long)parts * nthreads) p[i] = 0.f;
+  }
+}
 size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh);
-mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, hipStream_t stream);
+mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, const ZeroList& zl,
+                                 hipStream_t stream);
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
                                    const int32_t* const* prec, float* const* Y, const void* ws,
                                    hipStream_t stream);

@@ -176,7 +176,7 @@ static_assert(kPieces == 2, "slice_group picks the scale of a piece by piece == 
 static_assert(kRingDepth == 4 && kLoadsPerItem == 5, "ring_wait's constants are (kRingDepth - 1 .. 0) * kLoadsPerItem");
 }  // namespace f4
 
-template <int CPW>
+template <int CPW, int S>
 __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restrict__ prep, int T, int KB,
                                                              const f4::Group g) {
   using namespace f4;
@@ -186,14 +186,22 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 15;
   const int kq = lane >> 4;
-  const int bid = (int)blockIdx.x;
-  const int my_tiles = (g.tiles - bid + (int)gridDim.x - 1) / (int)gridDim.x;
+  // S = 2: the K axis is cut in two parts of 8 CPW blocks; workgroups 2 r and 2 r + 1 take the two parts
+  // of the same tiles and add their results into a Y that the preparation launch has zeroed (two
+  // addends: the sum does not depend on who comes first).  Each compute unit then fetches half of the
+  // prepared activations, which it would otherwise pull through the same port as the weights.
+  static_assert(S == 1 || S == 2, "one or two parts");
+  const int part = (int)blockIdx.x % S;
+  const int bid = (int)blockIdx.x / S;        // position in the tile list
+  const int stride = (int)gridDim.x / S;      // the launcher makes gridDim.x a multiple of S
+  const int my_tiles = (g.tiles - bid + stride - 1) / stride;
   if (my_tiles <= 0) return;
   const int total = my_tiles * CPW;  // items of this wavefront: (tile index q / CPW, chunk q % CPW)
   // This wavefront's 256-column blocks are blk0 and blk0 + 8.  The assignment rotates with the
   // workgroup so that the compute units of one XCD, which all start by fetching the prepared
   // activations of their blocks, do not all ask the L2 for the same lines at the same moment.
-  const int blk0 = (wave + bid) & (kWaves - 1);
+  const int rot = (wave + bid) & (kWaves - 1);
+  const int blk0 = part * (kWaves * CPW) + rot;
 
   __shared__ __attribute__((aligned(1024))) char ring[kWaves * kRingDepth * kSlotBytes];
   __shared__ float red[2][kWaves][64][4];
@@ -211,7 +219,7 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
   };
   // request item q (q < total) with slices 0..pm
   auto request = [&](int q, int pm) {
-    const int t = bid + (q / CPW) * (int)gridDim.x;
+    const int t = bid + (q / CPW) * stride;
     int kb = blk0 + kWaves * (q % CPW);
     if (kb >= KB) kb = 0;  // a block past the end: its activations are zeros, any weights will do
     const Proj& P = g.p[proj_of(t)];
@@ -271,7 +279,7 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
       pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
   };
   auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
-  auto request_routed = [&](int q) { request(q, pmax_of(proj_of(bid + (q / CPW) * (int)gridDim.x))); };
+  auto request_routed = [&](int q) { request(q, pmax_of(proj_of(bid + (q / CPW) * stride))); };
 
   // With eight or more tokens some token almost always wants every slice: the first tile then asks for
   // all four at once instead of waiting for the precisions to arrive (one memory latency less before
@@ -329,7 +337,7 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
 
 #pragma unroll 1
   for (int ti = 0; ti < my_tiles; ++ti) {
-    const int t = bid + ti * (int)gridDim.x;
+    const int t = bid + ti * stride;
     const int j = proj_of(t);
     const int pm = pmax_of(j);
     const int plv = j == 0 ? pl[0] : j == 1 ? pl[1] : j == 2 ? pl[2] : pl[3];
@@ -385,14 +393,17 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
     // sum the wavefronts' partial tiles; rows leave in token order
     const int buf = ti & 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) red[buf][blk0][lane][i] = acc[i];  // filed by block, so the sum below does not depend on the rotation
+    for (int i = 0; i < 4; ++i) red[buf][rot][lane][i] = acc[i];  // filed by block, so the sum below does not depend on the rotation
     lds_barrier();
     if (threadIdx.x < 256) {
       const Proj& P = g.p[j];
       const int r = threadIdx.x >> 4, cc = threadIdx.x & 15;
       const int64_t col = (int64_t)(t - P.tile_begin) * kTileN + cc;
       const float sum = read_partials_sum(red_addr + (uint32_t)(buf * (kWaves * 1024) + (16 * (r >> 2) + cc) * 16 + (r & 3) * 4));
-      if (r < T && col < P.N) P.Y[(int64_t)r * P.N + col] = sum;
+      if (r < T && col < P.N) {
+        if constexpr (S == 1) P.Y[(int64_t)r * P.N + col] = sum;
+        else unsafeAtomicAdd(&P.Y[(int64_t)r * P.N + col], sum);
+      }
     }
   }
 }
@@ -580,17 +591,39 @@ static int f4_compute_units() {
 }
 
 bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16; }
+// Blocks per part that fit in registers, in units of 16: three blocks per wavefront.
+static int f4_max_parts_blocks() { return 3; }
+// Parts of the K axis the linear kernel works in (2: Y must be zero when it starts; see
+// decode_f4_zero_list).  Up to 8 blocks one workgroup holds everything in a single block per wavefront.
+int decode_f4_k_parts(const Shape& sh) {
+  if (sh.KB <= 8 || sh.KB > 16 * f4_max_parts_blocks()) return 1;
+  return (knob(7) == 1 && sh.KB <= 8 * f4_max_parts_blocks()) ? 1 : 2;  // knob 7 = 1: one part where it fits (comparison runs)
+}
+void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl) {
+  for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
+    zl->p[i] = nullptr;
+    zl->n[i] = 0;
+  }
+  if (decode_f4_k_parts(shapes[0]) != 2) return;
+  for (int i = 0; i < n; ++i) {
+    zl->p[i] = Y[i];
+    zl->n[i] = (long long)T * shapes[i].N;
+  }
+}
 size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh) {
   return decode_f4_supports(T, sh) ? (size_t)sh.KB * f4::kPrepBytesPerBlock : 0;
 }
 
-__global__ __launch_bounds__(64) void decode_f4_prep_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
-                                                            char* __restrict__ prep) {
-  f4::prep_block(X, T, K, prep, (int)blockIdx.x, (int)threadIdx.x);
+__global__ __launch_bounds__(256) void decode_f4_prep_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
+                                                             char* __restrict__ prep, const ZeroList zl) {
+  if (threadIdx.x < 64) f4::prep_block(X, T, K, prep, (int)blockIdx.x, (int)threadIdx.x);
+  else zero_share(zl, (int)blockIdx.x, (int)gridDim.x, (int)threadIdx.x - 64, 192);
 }
 
-mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, hipStream_t stream) {
-  hipLaunchKernelGGL(decode_f4_prep_kernel, dim3(KB), dim3(64), 0, stream, X, (int)T, K, reinterpret_cast<char*>(ws));
+mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, const ZeroList& zl,
+                                 hipStream_t stream) {
+  hipLaunchKernelGGL(decode_f4_prep_kernel, dim3(KB), dim3(256), 0, stream, X, (int)T, K, reinterpret_cast<char*>(ws),
+                     zl);
   return hip_status(hipGetLastError(), "decode_f4_prep_kernel launch");
 }
 
@@ -616,16 +649,25 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
   g.n = n;
   g.tiles = tiles;
   const Shape& s0 = shapes[0];
-  int per_cu = knob(2) > 0 ? knob(2) : 1;
-  int grid = f4_compute_units() * per_cu;
-  if (grid > tiles) grid = tiles;
+  int grid = f4_compute_units();
   const char* prep = reinterpret_cast<const char*>(ws);
-  if (s0.KB > 16)
+  if (s0.KB > 16 * f4_max_parts_blocks()) {
+    if (grid > tiles) grid = tiles;
     hipLaunchKernelGGL(decode_f4_stream_kernel, dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
-  else if (s0.KB <= 8)
-    hipLaunchKernelGGL((decode_f4_ring_kernel<1>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
-  else
-    hipLaunchKernelGGL((decode_f4_ring_kernel<2>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
+  } else {
+    const int S = decode_f4_k_parts(shapes[0]);
+    grid = grid / S * S;
+    if (grid > tiles * S) grid = tiles * S;
+    const int cpw = (s0.KB + 8 * S - 1) / (8 * S);
+#define MBQ_RING(C, P) hipLaunchKernelGGL((decode_f4_ring_kernel<C, P>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g)
+    if (S == 1 && cpw == 1) MBQ_RING(1, 1);
+    else if (S == 1 && cpw == 2) MBQ_RING(2, 1);
+    else if (S == 1) MBQ_RING(3, 1);
+    else if (cpw == 1) MBQ_RING(1, 2);
+    else if (cpw == 2) MBQ_RING(2, 2);
+    else MBQ_RING(3, 2);
+#undef MBQ_RING
+  }
   return hip_status(hipGetLastError(), "decode_f4_kernel launch");
 }
 

@@ -182,10 +182,15 @@ struct RouteGroup {
 // wavefront (prep == nullptr: no such plane).
 __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
                                                           RouteGroup group, int n_routers,
-                                                          unsigned long long* words, char* prep, int prep_blocks) {
+                                                          unsigned long long* words, char* prep, int prep_blocks,
+                                                          const ZeroList zl) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if ((int)blockIdx.y == n_routers) {
-    if ((int)blockIdx.x < prep_blocks && wave == 0) f4::prep_block(X, T, K, prep, (int)blockIdx.x, lane);
+    if (wave == 0) {
+      if ((int)blockIdx.x < prep_blocks) f4::prep_block(X, T, K, prep, (int)blockIdx.x, lane);
+    } else {
+      zero_share(zl, (int)blockIdx.x, (int)gridDim.x, tid - 64, 448);  // outputs a split-K linear kernel adds into
+    }
     return;
   }
   if ((int)blockIdx.x >= T) return;
@@ -303,7 +308,7 @@ bool route_can_carry_prep(int64_t T) { return T >= 1 && T <= kSmallRouteTokens &
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
-                              void* prep, int prep_blocks) {
+                              void* prep, int prep_blocks, const ZeroList* zl) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
   if (route_can_carry_prep(T)) {
     RouteGroup g;
@@ -314,7 +319,8 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
     unsigned long long* words = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(ws) + 64);
     const unsigned gx = (prep && prep_blocks > (int)T) ? (unsigned)prep_blocks : (unsigned)T;
     hipLaunchKernelGGL(route_small_kernel, dim3(gx, (unsigned)n + (prep ? 1u : 0u)), dim3(512), 0, stream, X, (int)T,
-                       K, g, n, words, reinterpret_cast<char*>(prep), prep ? prep_blocks : 0);
+                       K, g, n, words, reinterpret_cast<char*>(prep), prep ? prep_blocks : 0,
+                       (prep && zl) ? *zl : ZeroList{});
     return hip_status(hipGetLastError(), "route_small_kernel launch");
   }
   for (int i = 0; i < n; ++i) {
@@ -330,7 +336,7 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
                         hipStream_t stream) {
   double* const lg[1] = {logits};
   return launch_route_group(X, T, K, 1, &Wr, &br, &prec, &perm, &offsets, logits ? lg : nullptr, ws, stream,
-                            nullptr, 0);
+                            nullptr, 0, nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------
