@@ -210,28 +210,50 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
   const uint32_t my_ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)my_ring;
 
   const uint4* dummy = reinterpret_cast<const uint4*>(prep);  // 1 KiB that stays in the vector cache
+  // The per-matrix facts live in scalar registers for the whole kernel (pinned: left to itself the
+  // compiler re-reads them from the argument block in every tile, a chain of scalar-load round trips
+  // that costs more than the tile's MFMAs).
+  const uint4* m_codes[MBQ_MAX_GROUP];
+  const float2* m_meta[MBQ_MAX_GROUP];
+  float* m_Y[MBQ_MAX_GROUP];
+  size_t m_slice_vec[MBQ_MAX_GROUP];
+  int m_N[MBQ_MAX_GROUP], m_begin[MBQ_MAX_GROUP];
+#pragma unroll
+  for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
+    m_codes[i] = g.p[i].codes;
+    m_meta[i] = g.p[i].meta;
+    m_Y[i] = g.p[i].Y;
+    m_slice_vec[i] = g.p[i].slice_vec;
+    m_N[i] = (int)g.p[i].N;
+    m_begin[i] = i < g.n ? g.p[i].tile_begin : 0x7fffffff;  // unused slots are never reached
+    asm volatile("" : "+s"(m_codes[i]), "+s"(m_meta[i]), "+s"(m_Y[i]), "+s"(m_slice_vec[i]), "+s"(m_N[i]), "+s"(m_begin[i]));
+  }
   auto proj_of = [&](int t) {
     int j = 0;
 #pragma unroll
     for (int i = 1; i < MBQ_MAX_GROUP; ++i)
-      if (i < g.n && t >= g.p[i].tile_begin) j = i;
+      if (t >= m_begin[i]) j = i;
     return j;
   };
+#define MBQ_PICK(arr, j) ((j) == 0 ? arr[0] : (j) == 1 ? arr[1] : (j) == 2 ? arr[2] : arr[3])
   // request item q (q < total) with slices 0..pm
   auto request = [&](int q, int pm) {
     const int t = bid + (q / CPW) * stride;
     int kb = blk0 + kWaves * (q % CPW);
     if (kb >= KB) kb = 0;  // a block past the end: its activations are zeros, any weights will do
-    const Proj& P = g.p[proj_of(t)];
-    const int nt = t - P.tile_begin;
+    const int j = proj_of(t);
+    const uint4* codes = MBQ_PICK(m_codes, j);
+    const size_t slice_vec = MBQ_PICK(m_slice_vec, j);
+    const int nt = t - MBQ_PICK(m_begin, j);
     char* slot = my_ring + (q % kRingDepth) * kSlotBytes;
     const size_t tile = ((size_t)nt * KB + kb) * 64 + lane;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const uint4* src = (e <= pm) ? P.codes + ((size_t)e * P.slice_vec + tile) : dummy + lane;
+      const uint4* src = (e <= pm) ? codes + ((size_t)e * slice_vec + tile) : dummy + lane;
       to_lds_16(src, slot + e * 1024);
     }
-    to_lds_4(reinterpret_cast<const char*>(P.meta + ((size_t)nt * (2 * KB) + 2 * kb) * kTileN) + 4 * lane, slot + 4096);
+    to_lds_4(reinterpret_cast<const char*>(MBQ_PICK(m_meta, j) + ((size_t)nt * (2 * KB) + 2 * kb) * kTileN) + 4 * lane,
+             slot + 4096);
   };
 
   // Every load of the prologue is hidden from the compiler (it orders each wait of its own after ALL
@@ -330,6 +352,21 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
     }
   }
 
+  // per matrix: the A scale gate of this lane's token (row m of the A operand: slice e counts iff
+  // e <= its precision) and 0.5 - 1.5 q_p of the output rows 4 kq + i
+  uint32_t m_gate[MBQ_MAX_GROUP];
+  floatx4 m_kp[MBQ_MAX_GROUP];
+#pragma unroll
+  for (int jj = 0; jj < MBQ_MAX_GROUP; ++jj) {
+    const int pa = __shfl(pl[jj], m, 64);
+    m_gate[jj] = (pa >= 3) ? 0xFFFFFFFFu : (pa == 2) ? 0x00FFFFFFu : (pa == 1) ? 0x0000FFFFu : (pa == 0) ? 0x000000FFu : 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int p = __shfl(pl[jj], 4 * kq + i, 64);
+      m_kp[jj][i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
+    }
+  }
+
   uint32_t nib_mask = 0x33333333u;
   asm volatile("" : "+s"(nib_mask));  // keep the mask in a register: one v_and_b32 per operand dword
   const int sb = 0x7A7C7E80;          // B scale bytes 2^(1-2e), e = 0..3
@@ -340,17 +377,10 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
     const int t = bid + ti * stride;
     const int j = proj_of(t);
     const int pm = pmax_of(j);
-    const int plv = j == 0 ? pl[0] : j == 1 ? pl[1] : j == 2 ? pl[2] : pl[3];
-    // A scale bytes of this lane's token (row m of the A operand): slice e counts iff e <= its precision
-    const int pa = __shfl(plv, m, 64);
-    const uint32_t gate = (pa >= 3) ? 0xFFFFFFFFu : (pa == 2) ? 0x00FFFFFFu : (pa == 1) ? 0x0000FFFFu
-                          : (pa == 0) ? 0x000000FFu : 0u;
-    float kp[4];  // 0.5 - 1.5 q_p of the output rows 4 kq + i
+    const uint32_t gate = MBQ_PICK(m_gate, j);
+    float kp[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int p = __shfl(plv, 4 * kq + i, 64);
-      kp[i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
-    }
+    for (int i = 0; i < 4; ++i) kp[i] = MBQ_PICK(m_kp, j)[i];
     floatx4 acc = zero4;
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
@@ -360,8 +390,12 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
       u32x4 wv[4];
       f32x2 mv[2];
       read_slot(slot + lane * 16, slot + m * 8, wv, mv);
-      // the slot has been read: items up to q + kRingDepth fit in the ring
-      for (; next_request <= q + kRingDepth && next_request < total; ++next_request) request_routed(next_request);
+      // The slot has been read: items up to q + kRingDepth fit in the ring.  At most two requests per
+      // item: the ring fills over the first steps instead of holding the first MFMAs back behind a burst
+      // of loads (a wavefront issues in order).
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+        if (next_request <= q + kRingDepth && next_request < total) request_routed(next_request++);
       Item I;
 #pragma unroll
       for (int e = 0; e < 4; ++e) I.w[e] = uint4{wv[e].x, wv[e].y, wv[e].z, wv[e].w};
@@ -396,17 +430,19 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
     for (int i = 0; i < 4; ++i) red[buf][rot][lane][i] = acc[i];  // filed by block, so the sum below does not depend on the rotation
     lds_barrier();
     if (threadIdx.x < 256) {
-      const Proj& P = g.p[j];
+      float* Yj = MBQ_PICK(m_Y, j);
+      const int Nj = MBQ_PICK(m_N, j);
       const int r = threadIdx.x >> 4, cc = threadIdx.x & 15;
-      const int64_t col = (int64_t)(t - P.tile_begin) * kTileN + cc;
+      const int col = (t - MBQ_PICK(m_begin, j)) * kTileN + cc;
       const float sum = read_partials_sum(red_addr + (uint32_t)(buf * (kWaves * 1024) + (16 * (r >> 2) + cc) * 16 + (r & 3) * 4));
-      if (r < T && col < P.N) {
-        if constexpr (S == 1) P.Y[(int64_t)r * P.N + col] = sum;
-        else unsafeAtomicAdd(&P.Y[(int64_t)r * P.N + col], sum);
+      if (r < T && col < Nj) {
+        if constexpr (S == 1) Yj[(int64_t)r * Nj + col] = sum;
+        else unsafeAtomicAdd(&Yj[(int64_t)r * Nj + col], sum);
       }
     }
   }
 }
+#undef MBQ_PICK
 
 
 // K > 4096: the activation pieces no longer fit in registers next to two weight buffers, so
