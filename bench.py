@@ -267,8 +267,8 @@ def main() -> int:
         "hbm_gbps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "event_ms_per_step": ev_ms_per_step,
         "roofline": {
-            "bound": "hbm", "kernel": "the linear kernel of each stage: mbq::decode_f4_kernel (q+k+v, o, gate+up), "
-                                      "mbq::decode_kernel (down)",
+            "bound": "hbm", "kernel": "the linear kernel of each stage: mbq::decode_f4_ring_kernel (q+k+v, o, gate+up), "
+                                      "mbq::decode_f4_stream_kernel (down)",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
             "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(T),
             "avg_launch_us": avg_launch_us, "avg_launch_bytes": avg_launch_bytes,

@@ -303,32 +303,16 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
   auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
   auto request_routed = [&](int q) { request(q, pmax_of(proj_of(bid + (q / CPW) * stride))); };
 
-  // With eight or more tokens some token almost always wants every slice: the first tile then asks for
-  // all four at once instead of waiting for the precisions to arrive (one memory latency less before
-  // the first MFMA; a slice fetched in vain costs bandwidth only).
-  int first_routed;  // first item that has not been requested yet
-  if (T >= 8) {
-    load_precisions();
+  // Order of the prologue: precisions, then the activations, then (once the precisions are here) the
+  // first tile.  Only the first tile is requested before the loop: the memory pipeline of the compute
+  // unit serves requests in order, and what the first MFMAs need should not queue behind prefetches.
+  // The loop then fills the ring.
+  load_precisions();
 #pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-      request(c, 3);
-      load_activations(c);
-    }
-    loads_arrived<CPW * (kLoadsPerItem + kXaLoads)>(pl[0], pl[1], pl[2], pl[3]);
-    find_pmax();
-    first_routed = CPW;
-  } else {
-    load_precisions();
-#pragma unroll
-    for (int c = 0; c < CPW; ++c) load_activations(c);
-    loads_arrived<CPW * kXaLoads>(pl[0], pl[1], pl[2], pl[3]);
-    find_pmax();
-    first_routed = 0;
-  }
-  // Only the first tile is requested before the loop: the memory pipeline of the compute unit serves
-  // requests in order, and what the first MFMAs need (this tile and the activations) should not queue
-  // behind prefetches.  The loop then keeps the ring full.
-  for (int q = first_routed; q < CPW; ++q) request_routed(q);
+  for (int c = 0; c < CPW; ++c) load_activations(c);
+  loads_arrived<CPW * kXaLoads>(pl[0], pl[1], pl[2], pl[3]);
+  find_pmax();
+  for (int q = 0; q < CPW; ++q) request_routed(q);
   int next_request = CPW;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the activations (and the first tile) have arrived
   intx8 xa[CPW][2][kPieces];
@@ -627,8 +611,9 @@ static int f4_compute_units() {
 }
 
 bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16; }
-// Blocks per part that fit in registers, in units of 16: three blocks per wavefront.
-static int f4_max_parts_blocks() { return 3; }
+// Blocks per part, in units of 8: up to two blocks per wavefront (K <= 8192 in two parts); beyond
+// that the streaming kernel, which keeps nothing resident, is the faster one.
+static int f4_max_parts_blocks() { return 2; }
 // Parts of the K axis the linear kernel works in (2: Y must be zero when it starts; see
 // decode_f4_zero_list).  Up to 8 blocks one workgroup holds everything in a single block per wavefront.
 int decode_f4_k_parts(const Shape& sh) {
@@ -697,11 +682,9 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
     const int cpw = (s0.KB + 8 * S - 1) / (8 * S);
 #define MBQ_RING(C, P) hipLaunchKernelGGL((decode_f4_ring_kernel<C, P>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g)
     if (S == 1 && cpw == 1) MBQ_RING(1, 1);
-    else if (S == 1 && cpw == 2) MBQ_RING(2, 1);
-    else if (S == 1) MBQ_RING(3, 1);
+    else if (S == 1) MBQ_RING(2, 1);
     else if (cpw == 1) MBQ_RING(1, 2);
-    else if (cpw == 2) MBQ_RING(2, 2);
-    else MBQ_RING(3, 2);
+    else MBQ_RING(2, 2);
 #undef MBQ_RING
   }
   return hip_status(hipGetLastError(), "decode_f4_kernel launch");
