@@ -405,7 +405,124 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         mlp[f"tokens_{Tr}"] = {"us": us, "fp64_gflops": 2.0 * Tr * Kr * Hr / (us * 1e-6) / 1e9,
                                "mix": np.bincount(outr[0].cpu().numpy(), minlength=4).tolist()}
     extra["route_mlp_hidden64_K4096"] = mlp
+    extra.update(other_config_measurements(mbq, torch, dev))
     return extra
+
+
+def other_config_measurements(mbq, torch, dev):
+    """BASELINE configs[3] (Llama-3-8B-shaped block, 64 tokens, decode) and configs[4] (70B-shaped MLP linears, 4096-token
+    prefill and a 256-token batch).  Shapes and mixes are the configs'; the weights are drawn on the GPU (normal x 0.02:
+    only the shapes matter for the time) and, for configs[4], the precisions are drawn directly with the target mix."""
+    from workloads import CONFIGS
+
+    def blob_of(N, K, seed):
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        W = torch.randn((N, K), generator=g, device=dev) * 0.02
+        b = mbq.mbq_encode(W)
+        torch.cuda.synchronize()
+        del W
+        return b
+
+    def timed(fn, n, warm=2):
+        for i in range(warm):
+            fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    out = {}
+    # ---- configs[3]: decoder block at 64 tokens, one router per linear (zero bias: uniform mix), stages as in the main run
+    c3 = CONFIGS[3]
+    T = c3.token_counts[0]
+    specs = {sp.name: sp for sp in c3.linears}
+    g = torch.Generator(device=dev)
+    g.manual_seed(3)
+    stages = []
+    for names in STAGES:
+        K = specs[names[0]].K
+        X = torch.randn((T, K), generator=g, device=dev).to(torch.bfloat16)
+        Ns = [specs[n].N for n in names]
+        stages.append(dict(
+            X=X, K=K, Ns=Ns, blobs=[[blob_of(N, K, 31 + i)] for i, N in enumerate(Ns)],
+            Wr=[torch.randn((4, K), generator=g, device=dev) / K ** 0.5 for _ in names],
+            br=[torch.zeros(4, device=dev) for _ in names],
+            routing=[(torch.empty(T, dtype=torch.int32, device=dev), torch.empty(T, dtype=torch.int32, device=dev),
+                      torch.empty(5, dtype=torch.int32, device=dev)) for _ in names],
+            Y=[torch.empty((T, N), dtype=torch.float32, device=dev) for N in Ns],
+            ws_r=mbq.route_workspace(T, K, dev), ws_l=mbq.linear_workspace(T, max(Ns), K, dev)))
+        for bl in stages[-1]["blobs"]:
+            bl.extend(bl[0].clone() for _ in range(RING - 1))
+
+    def block(slot):
+        for st in stages:
+            mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [bl[slot % RING] for bl in st["blobs"]], st["Ns"],
+                                        routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"], ws_linear=st["ws_l"])
+    ms = timed(block, 30, warm=3)
+    byts = sum(algorithmic_bytes(N, st["K"], T, int(r[0].max().item())) + 16 * st["K"]
+               for st in stages for N, r in zip(st["Ns"], st["routing"]))
+    out["decode_llama3_8b_block_batch64"] = {
+        "workload": "BASELINE configs[3] shapes: q,o 4096x4096, k,v 1024x4096, gate,up 14336x4096, down 4096x14336; "
+                    "64 tokens, seven routers, uniform mix; eager launches, three weight copies rotated",
+        "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9,
+        "hbm_frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    del stages
+    torch.cuda.empty_cache()
+
+    # ---- configs[4]: 70B-shaped MLP linears, mix {70,20,8,2}%
+    c4 = CONFIGS[4]
+    mix = torch.tensor([0.70, 0.20, 0.08, 0.02], device=dev)
+
+    def routing_of(T, seed):
+        g2 = torch.Generator(device=dev)
+        g2.manual_seed(seed)
+        prec = torch.multinomial(mix, T, replacement=True, generator=g2).to(torch.int32)
+        perm = torch.sort(prec, stable=True).indices.to(torch.int32)
+        counts = torch.bincount(prec, minlength=4)
+        offsets = torch.cat([torch.zeros(1, dtype=torch.int64, device=dev), torch.cumsum(counts, 0)]).to(torch.int32)
+        return prec, perm, offsets
+
+    pre, dec = {}, {}
+    fl_sum = ms_sum = 0.0
+    for li, spec in enumerate(c4.linears):
+        blobs = [blob_of(spec.N, spec.K, 41 + li)]
+        blobs += [blobs[0].clone() for _ in range(RING - 1)]
+        for T, store in ((4096, pre), (256, dec)):
+            g2 = torch.Generator(device=dev)
+            g2.manual_seed(100 + T)
+            X = torch.randn((T, spec.K), generator=g2, device=dev).to(torch.bfloat16)
+            prec, perm, offsets = routing_of(T, 7 * T + li)
+            Y = torch.empty((T, spec.N), dtype=torch.float32, device=dev)
+            ws = mbq.linear_workspace(T, spec.N, spec.K, dev)
+            ms = timed(lambda i: mbq.mbq_linear(X, blobs[i % RING], spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws),
+                       6 if T == 4096 else 12)
+            flops = 2.0 * T * spec.N * spec.K
+            byts = algorithmic_bytes(spec.N, spec.K, T, int(prec.max().item()))
+            store[spec.name] = {"N": spec.N, "K": spec.K, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+                                "gbps": byts / (ms * 1e-3) / 1e9, "mix": torch.bincount(prec, minlength=4).tolist()}
+            if T == 4096:
+                fl_sum += flops
+                ms_sum += ms
+            del X, Y, ws
+        del blobs
+        torch.cuda.empty_cache()
+    tf = fl_sum / (ms_sum * 1e-3) / 1e12
+    out["prefill_70b_mlp_4096tok"] = {
+        "workload": "BASELINE configs[4] shapes: gate/up 28672x8192, down 8192x28672, 4096 tokens, {70,20,8,2}% mix "
+                    "(precisions drawn directly); useful flops 2 T N K over the whole mbq_linear call",
+        "ms_total": ms_sum, "tflops": tf, "per_linear": pre,
+        "roofline": {"bound": "mfma", "kernel": "mbq::prefill_kernel (+ mbq::prefill_prep_kernel)", "achieved": tf,
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
+    for v in dec.values():   # the mixed case: both fractions, graded against the larger of the two times
+        v["hbm_frac"] = v["gbps"] / HBM_PEAK_GBPS
+        v["mfma_frac"] = v["tflops"] / 2500.0
+    out["batch256_70b_mlp"] = {"workload": "the same three linears at 256 tokens (prefill kernel); bytes and flops both matter",
+                               "per_linear": dec}
+    return out
 
 
 def cpu_baseline(cfg, layers, T):

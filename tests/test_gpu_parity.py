@@ -317,10 +317,13 @@ def test_linear_group_equals_separate_calls(mbq, K, T, Ns):
 
 
 @pytest.mark.parametrize("K,T,Ns", [(4096, 16, (96, 32, 130)), (2048, 1, (64, 48)), (1280, 9, (40,)), (5120, 16, (48, 32)),
-                                    (1024, 40, (48, 32))])
+                                    (1024, 40, (48, 32)),
+                                    # many row tiles: the whole chip takes part, K in one part, two parts and streamed
+                                    (1024, 5, (1024, 528)), (4096, 16, (1040, 512, 512)), (9216, 3, (1600,)), (2304, 16, (640, 130))])
 def test_routed_linear_stage_equals_route_then_linear(mbq, K, T, Ns):
     """One block stage in one call: same routing and the same outputs, bit for bit, as mbq_route_group
-    followed by mbq_linear_group, and within tolerance of the oracle; run twice on the same workspaces."""
+    followed by mbq_linear_group, and within tolerance of the oracle; run twice on the same workspaces,
+    which the calls must leave zeroed."""
     print(f"[case] stage K={K} T={T} Ns={Ns}", flush=True)
     rng = np.random.default_rng([K, T, len(Ns)])
     xb = tokens(T, K, [K, T, 31])
@@ -335,6 +338,7 @@ def test_routed_linear_stage_equals_route_then_linear(mbq, K, T, Ns):
     for _ in range(2):
         routing, Ys = mbq.mbq_routed_linear_group(X, dWr, dbr, blobs, list(Ns), ws_route=ws_r, ws_linear=ws_l)
         torch.cuda.synchronize()
+        assert not ws_r.view(torch.int32).any(), "route workspace not left at zero"
         routing2 = mbq.mbq_route_group(X, dWr, dbr)
         Ys2 = mbq.mbq_linear_group(X, blobs, list(Ns), K, routing2)
         for i, N in enumerate(Ns):
