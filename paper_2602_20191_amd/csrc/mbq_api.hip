@@ -69,7 +69,7 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
         decode_f4_zero_list(T, 1, &sh, &Y, &zl);
         mbq_status st = launch_decode_f4_prep(X, T, sh.K, sh.KB, ws, zl, s);
         if (st != MBQ_OK) return st;
-        return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s);
+        return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s, nullptr, nullptr);
       }
       if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 1024))
         return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
@@ -205,7 +205,7 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
     return MBQ_ERR_WORKSPACE;
   }
   return launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr, ws,
-                            (hipStream_t)stream, nullptr, 0, nullptr);
+                            (hipStream_t)stream, nullptr, 0, nullptr, false);
 }
 
 size_t mbq_route_mlp_workspace_bytes(int64_t T, int64_t K, int H) {
@@ -279,9 +279,10 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
       ZeroList zl;
       decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
       mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
-                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl);
+                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl, true);
       if (st != MBQ_OK) return st;
-      return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream);
+      return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream,
+                                     perm_host, offsets_host);
     }
   }
   // otherwise exactly the two calls (they check the arguments)
@@ -379,7 +380,7 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
     mbq_status st = knob(6) == 1 ? MBQ_OK : launch_decode_f4_prep(X, T, K, sh[0].KB, ws, zl, s);
     if (st != MBQ_OK) return st;
-    return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s);
+    return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s, nullptr, nullptr);
   }
   for (int i = 0; i < n_proj; ++i) {
     mbq_status st =

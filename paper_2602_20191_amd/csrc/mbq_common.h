@@ -71,7 +71,7 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
-                              void* prep, int prep_blocks, const ZeroList* zl);
+                              void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket);
 bool route_can_carry_prep(int64_t T);
 mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
                             const float* W2, const float* b2, double delta, int32_t* prec, int32_t* perm,
@@ -106,9 +106,10 @@ __device__ inline void zero_share(const ZeroList& zl, int part, int parts, int t
 size_t decode_f4_workspace_bytes(int64_t T, const Shape& sh);
 mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB, void* ws, const ZeroList& zl,
                                  hipStream_t stream);
+// perm/offsets (arrays of n, or null): the launch also sorts the tokens of every matrix by precision
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
-                                   const int32_t* const* prec, float* const* Y, const void* ws,
-                                   hipStream_t stream);
+                                   const int32_t* const* prec, float* const* Y, const void* ws, hipStream_t stream,
+                                   int32_t* const* perm, int32_t* const* offsets);
 size_t decode_workspace_bytes(int64_t T, const Shape& sh);
 size_t prefill_workspace_bytes(int64_t T, const Shape& sh);
 

@@ -45,6 +45,8 @@ struct Proj {
   const uint4* codes;
   const float2* meta;
   const int32_t* prec;
+  int32_t* perm;     // with offsets: where the launch leaves the tokens sorted by precision (null: nowhere)
+  int32_t* offsets;
   float* Y;
   size_t slice_vec;  // uint4 per slice
   int64_t N;
@@ -86,6 +88,22 @@ __device__ inline floatx4 slice_group(const intx8* A, uint32_t w_lo, uint32_t w_
     D = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A[piece], B, D, 0 /* A: FP8 E4M3 */, 4 /* B: FP4 */, E,
                                                          piece == 0 ? sa : sa2, E, sb);
   return D;
+}
+
+// Stable counting sort of the T <= 64 tokens of one matrix by precision (Sec. 4.3, token permutation),
+// by one wavefront: p = precision of token `lane`, -1 past the last token.
+__device__ inline void bucket_by_wave(int p, int lane, int32_t* __restrict__ perm, int32_t* __restrict__ offsets) {
+  const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int start = 0, my_pos = 0;
+#pragma unroll
+  for (int q = 0; q < MBQ_N_PRECISIONS; ++q) {
+    const uint64_t b = __ballot(p == q);
+    if (p == q) my_pos = start + __popcll(b & below);
+    if (lane == q) offsets[q] = start;
+    start += __popcll(b);
+  }
+  if (lane == MBQ_N_PRECISIONS) offsets[MBQ_N_PRECISIONS] = start;
+  if (p >= 0) perm[my_pos] = lane;
 }
 
 struct Item {  // one 16 x 256 block: four slices and the {s0, z0} of its two groups
@@ -351,6 +369,12 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
     }
   }
 
+  if (blockIdx.x == 0 && wave == 0) {  // one wavefront of the launch sorts the tokens, where the caller wants them sorted
+#pragma unroll
+    for (int j = 0; j < MBQ_MAX_GROUP; ++j)
+      if (j < g.n && g.p[j].perm != nullptr) bucket_by_wave(pl[j], lane, g.p[j].perm, g.p[j].offsets);
+  }
+
   uint32_t nib_mask = 0x33333333u;
   asm volatile("" : "+s"(nib_mask));  // keep the mask in a register: one v_and_b32 per operand dword
   const int sb = 0x7A7C7E80;          // B scale bytes 2^(1-2e), e = 0..3
@@ -509,6 +533,11 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
     pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
   auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
   load_rest((int)blockIdx.x, wave, pmax_of(proj_of((int)blockIdx.x)), A);
+  if (blockIdx.x == 0 && wave == 0) {
+#pragma unroll
+    for (int j = 0; j < MBQ_MAX_GROUP; ++j)
+      if (j < g.n && g.p[j].perm != nullptr) bucket_by_wave(pl[j], lane, g.p[j].perm, g.p[j].offsets);
+  }
 
   uint32_t nib_mask = 0x33333333u;
   asm volatile("" : "+s"(nib_mask));
@@ -650,8 +679,8 @@ mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB
 
 // All matrices share K (the caller has checked); T <= 16; ws holds the prepared activations.
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
-                                   const int32_t* const* prec, float* const* Y, const void* ws,
-                                   hipStream_t stream) {
+                                   const int32_t* const* prec, float* const* Y, const void* ws, hipStream_t stream,
+                                   int32_t* const* perm, int32_t* const* offsets) {
   f4::Group g;
   int tiles = 0;
   for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
@@ -660,6 +689,8 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
     g.p[i].codes = reinterpret_cast<const uint4*>(blobs[j]);
     g.p[i].meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blobs[j]) + sh.meta_offset);
     g.p[i].prec = prec[j];
+    g.p[i].perm = (perm && offsets && i < n) ? perm[i] : nullptr;
+    g.p[i].offsets = (perm && offsets && i < n) ? offsets[i] : nullptr;
     g.p[i].Y = Y[j];
     g.p[i].slice_vec = sh.slice_words / 4;
     g.p[i].N = sh.N;

@@ -179,11 +179,13 @@ struct RouteGroup {
 //
 // The launch can carry the activation preparation of the FP4-operand decode kernel along: plane
 // blockIdx.y == n_routers of the grid prepares 256-column block blockIdx.x with its first
-// wavefront (prep == nullptr: no such plane).
+// wavefront (prep == nullptr: no such plane).  defer_bucket: only the precisions are written; the linear
+// kernel that follows sorts the tokens (it reads every precision anyway), which takes the atomic
+// round trip and the sort out of this launch.
 __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
                                                           RouteGroup group, int n_routers,
                                                           unsigned long long* words, char* prep, int prep_blocks,
-                                                          const ZeroList zl) {
+                                                          const ZeroList zl, int defer_bucket) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if ((int)blockIdx.y == n_routers) {
     if (wave == 0) {
@@ -252,6 +254,10 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
       arg = q;
     }
   }
+  if (defer_bucket) {  // the consumer of the precisions sorts the tokens itself: no meeting, the workgroup is done
+    if (lane == 0) out.prec[tok] = arg;
+    return;
+  }
   unsigned long long all = 0ull;
   if (lane == 0) {
     out.prec[tok] = arg;
@@ -308,7 +314,7 @@ bool route_can_carry_prep(int64_t T) { return T >= 1 && T <= kSmallRouteTokens &
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
-                              void* prep, int prep_blocks, const ZeroList* zl) {
+                              void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
   if (route_can_carry_prep(T)) {
     RouteGroup g;
@@ -320,7 +326,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
     const unsigned gx = (prep && prep_blocks > (int)T) ? (unsigned)prep_blocks : (unsigned)T;
     hipLaunchKernelGGL(route_small_kernel, dim3(gx, (unsigned)n + (prep ? 1u : 0u)), dim3(512), 0, stream, X, (int)T,
                        K, g, n, words, reinterpret_cast<char*>(prep), prep ? prep_blocks : 0,
-                       (prep && zl) ? *zl : ZeroList{});
+                       (prep && zl) ? *zl : ZeroList{}, (prep && defer_bucket) ? 1 : 0);
     return hip_status(hipGetLastError(), "route_small_kernel launch");
   }
   for (int i = 0; i < n; ++i) {
@@ -336,7 +342,7 @@ mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr
                         hipStream_t stream) {
   double* const lg[1] = {logits};
   return launch_route_group(X, T, K, 1, &Wr, &br, &prec, &perm, &offsets, logits ? lg : nullptr, ws, stream,
-                            nullptr, 0, nullptr);
+                            nullptr, 0, nullptr, false);
 }
 
 // ---------------------------------------------------------------------------------------------
