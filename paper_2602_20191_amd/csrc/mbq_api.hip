@@ -62,8 +62,9 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
     case MBQ_ALGO_DECODE:
       // One token tile (T <= 16): the FP4-operand kernels (activation preparation, then the
       // linear kernel).  17..64 tokens run the bf16-operand kernels, one pass per 16
-      // precision-sorted tokens: the register-stationary chunked kernel when K <= 4096 or a
-      // workgroup has many row tiles; short, wide matrices keep every column block in flight.
+      // precision-sorted tokens: the register-stationary chunked kernel, except for matrices with few
+      // row tiles, where keeping every column block in flight (K split + reduction) fills the chip
+      // better (measured on weights that are not in the last-level cache).
       if (knob(3) == 0 && decode_f4_supports(T, sh)) {
         ZeroList zl;
         decode_f4_zero_list(T, 1, &sh, &Y, &zl);
@@ -71,7 +72,7 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
         if (st != MBQ_OK) return st;
         return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s, nullptr, nullptr);
       }
-      if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 1024))
+      if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 128 || (T > 32 && sh.NT >= 32)))
         return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
       return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
     default:

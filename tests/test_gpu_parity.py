@@ -290,6 +290,26 @@ def test_decode_every_highest_precision(mbq, K, pmax, T):
     assert_output_close(Y, Yref, f"decode pmax={pmax} K={K} T={T}")
 
 
+@pytest.mark.parametrize("T,K,N", [(17, 4096, 130), (31, 2304, 48), (32, 4096, 64), (33, 1024, 272), (48, 4096, 40),
+                                   (49, 2048, 130), (64, 4096, 2064), (64, 256, 16)])
+def test_decode_several_token_tiles(mbq, T, K, N):
+    """17..64 tokens: one pass over the weights per 16 precision-sorted tokens, each reading the slices of
+    ITS highest precision; mixes chosen so that the passes differ."""
+    print(f"[case] decode token tiles T={T} K={K} N={N}", flush=True)
+    W = make_weight(N, K, [37, N, K], 4.0)
+    xb = tokens(T, K, [T, K, 41])
+    rng = np.random.default_rng([T, K, N])
+    prec = rng.integers(0, 4, size=T).astype(np.int32)
+    prec[:32] = np.minimum(prec[:32], 2)      # first window: at most 6 bits
+    prec[5] = 2
+    if T > 40:
+        prec[40] = 3
+    codes, s0, z0 = O.encode(W)
+    Yref = O.linear(xb, codes, s0, z0, prec)
+    Y = run_linear(mbq, W, xb, prec, ALGOS["decode"])
+    assert_output_close(Y, Yref, f"decode token tiles T={T} K={K} N={N}")
+
+
 @pytest.mark.parametrize("K,T,Ns", [(4096, 16, (96, 32, 130)), (4096, 1, (64, 64)), (2048, 7, (80, 48, 16, 33)),
                                     (768, 16, (40,)), (3072, 5, (48, 96)), (5120, 16, (48, 32)), (1024, 40, (48, 32))])
 def test_linear_group_equals_separate_calls(mbq, K, T, Ns):
