@@ -89,6 +89,19 @@ size_t mbq_linear_workspace_bytes(int64_t T, int64_t N, int64_t K);
 mbq_status mbq_encode(const float* W, int64_t N, int64_t K, void* blob, void* stream);
 
 /*
+ * mbq_encode_with_params - the same recursion with the base-slice scale and zero point given by the
+ * caller instead of fitted: the paper calibrates (s0, z0) with a learned clipping range (Sec. 4.1,
+ * App. B "first slice (s0, z0) is calibrated"), which is outside this library.  A weight outside the
+ * range the parameters span saturates: the clamp of App. B's quantiser gives it code 0 (or 3) in
+ * every slice.
+ *   scale, zero : fp32 [N][K/128] row-major (read); every scale must be finite and > 0, every zero
+ *                 point finite (not checked: other values give meaningless codes, never a fault)
+ *   W, blob     : as in mbq_encode; the blob stores scale and zero as given
+ */
+mbq_status mbq_encode_with_params(const float* W, int64_t N, int64_t K, const float* scale, const float* zero,
+                                  void* blob, void* stream);
+
+/*
  * mbq_unpack - blob -> canonical arrays, for inspection and tests.
  *   codes : uint8 [4][N][K], one code (0..3) per byte          (may be NULL)
  *   scale : fp32 [N][K/128]  base-slice scale s0               (may be NULL)

@@ -22,7 +22,7 @@ GROUP = 128
 
 EXPORTS = (
     "mbq_version", "mbq_last_error", "mbq_blob_bytes", "mbq_route_workspace_bytes",
-    "mbq_linear_workspace_bytes", "mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route",
+    "mbq_linear_workspace_bytes", "mbq_encode", "mbq_encode_with_params", "mbq_unpack", "mbq_dequant", "mbq_route",
     "mbq_route_group", "mbq_linear", "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob",
     "mbq_route_mlp", "mbq_route_mlp_workspace_bytes", "mbq_threshold_quantile",
 )
@@ -52,6 +52,7 @@ def load() -> ctypes.CDLL:
     lib.mbq_linear_workspace_bytes.restype = c_sz
     lib.mbq_linear_workspace_bytes.argtypes = [c_i64, c_i64, c_i64]
     lib.mbq_encode.argtypes = [c_p, c_i64, c_i64, c_p, c_p]
+    lib.mbq_encode_with_params.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_p, c_p]
     lib.mbq_unpack.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_p, c_p]
     lib.mbq_dequant.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p]
     lib.mbq_route.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
@@ -66,7 +67,7 @@ def load() -> ctypes.CDLL:
     lib.mbq_routed_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_p,
                                             c_p, c_sz, c_p, c_sz, c_int, c_p]
     lib.mbq_set_knob.argtypes = [c_int, c_int]
-    for name in ("mbq_encode", "mbq_unpack", "mbq_dequant", "mbq_route", "mbq_route_group", "mbq_linear",
+    for name in ("mbq_encode", "mbq_encode_with_params", "mbq_unpack", "mbq_dequant", "mbq_route", "mbq_route_group", "mbq_linear",
                  "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob"):
         getattr(lib, name).restype = c_int
     _lib = lib
@@ -112,6 +113,20 @@ def mbq_encode(W: torch.Tensor, blob: Optional[torch.Tensor] = None) -> torch.Te
     if blob is None:
         blob = torch.empty(blob_bytes(N, K), dtype=torch.uint8, device=W.device)
     _check(load().mbq_encode(_ptr(W), N, K, _ptr(blob), _stream()), "mbq_encode")
+    return blob
+
+
+def mbq_encode_with_params(W: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor,
+                           blob: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """As mbq_encode, with the base-slice scale and zero point (fp32 [N, K/128]) given instead of fitted."""
+    assert W.dtype == torch.float32 and W.dim() == 2
+    N, K = W.shape
+    assert scale.dtype == zero.dtype == torch.float32 and tuple(scale.shape) == tuple(zero.shape) == (N, K // 128)
+    assert scale.is_contiguous() and zero.is_contiguous() and W.is_contiguous()
+    if blob is None:
+        blob = torch.empty(blob_bytes(N, K), dtype=torch.uint8, device=W.device)
+    _check(load().mbq_encode_with_params(_ptr(W), N, K, _ptr(scale), _ptr(zero), _ptr(blob), _stream()),
+           "mbq_encode_with_params")
     return blob
 
 

@@ -128,7 +128,18 @@ mbq_status mbq_encode(const float* W, int64_t N, int64_t K, void* blob, void* st
     set_error("mbq_encode: W must be 16-byte and blob 256-byte aligned and non-null");
     return MBQ_ERR_INVALID_ARG;
   }
-  return launch_encode(W, sh, blob, (hipStream_t)stream);
+  return launch_encode(W, sh, blob, nullptr, nullptr, (hipStream_t)stream);
+}
+
+mbq_status mbq_encode_with_params(const float* W, int64_t N, int64_t K, const float* scale, const float* zero,
+                                  void* blob, void* stream) {
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!W || !blob || !scale || !zero || !aligned(blob, 256) || !aligned(W, 16)) {
+    set_error("mbq_encode_with_params: W must be 16-byte and blob 256-byte aligned; W, scale, zero, blob non-null");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_encode(W, sh, blob, scale, zero, (hipStream_t)stream);
 }
 
 mbq_status mbq_unpack(const void* blob, int64_t N, int64_t K, uint8_t* codes, float* scale, float* zero,

@@ -61,7 +61,8 @@ struct ZeroList {
 };
 
 // ---- kernels' host launchers (each enqueues on `stream`, returns a status) ------
-mbq_status launch_encode(const float* W, const Shape& sh, void* blob, hipStream_t stream);
+mbq_status launch_encode(const float* W, const Shape& sh, void* blob, const float* ext_scale, const float* ext_zero,
+                         hipStream_t stream);
 mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* codes, float* scale, float* zero,
                          hipStream_t stream);
 mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream);

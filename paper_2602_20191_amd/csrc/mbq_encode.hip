@@ -13,7 +13,9 @@ namespace mbq {
 // columns 64*d + 32*step + 8*kq + s for step in {0,1}, s in 0..7 (kq = lane/16).
 __global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ W, int64_t N, int64_t K,
                                                      int NT, int KB, uint32_t* __restrict__ codes,
-                                                     size_t slice_words, float2* __restrict__ meta) {
+                                                     size_t slice_words, float2* __restrict__ meta,
+                                                     const float* __restrict__ ext_scale,
+                                                     const float* __restrict__ ext_zero) {
 #pragma clang fp contract(off)
   const int nt = blockIdx.x;
   const int kb = blockIdx.y;
@@ -63,8 +65,14 @@ __global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ W
   const float mag = fmaxf(fabsf(lo), fabsf(hi));
   const float floor_rng = fmaxf(mag * 0x1p-16f, 0x1p-100f);
   rng = fmaxf(rng, floor_rng);
-  const float s0 = rng * 0.25f;
-  const float z0 = (float)((double)(-lo) / (double)s0);  // equals the IEEE fp32 quotient
+  float s0 = rng * 0.25f;
+  float z0 = (float)((double)(-lo) / (double)s0);  // equals the IEEE fp32 quotient
+  // calibrated parameters from outside (e.g. a learned clipping range, Sec. 4.1 / App. B): weights beyond
+  // the range they span saturate in the clamp of every slice
+  if (ext_scale != nullptr && real) {
+    s0 = ext_scale[n * (K / kGroup) + g];
+    z0 = ext_zero[n * (K / kGroup) + g];
+  }
 
   uint32_t word[kSlices] = {0u, 0u, 0u, 0u};
   if (real) {
@@ -132,12 +140,13 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
   What[idx] = (float)(((double)m.x / pw) * (((double)I - pw * (double)m.y) + 0.5));
 }
 
-mbq_status launch_encode(const float* W, const Shape& sh, void* blob, hipStream_t stream) {
+mbq_status launch_encode(const float* W, const Shape& sh, void* blob, const float* ext_scale, const float* ext_zero,
+                         hipStream_t stream) {
   uint32_t* codes = reinterpret_cast<uint32_t*>(blob);
   float2* meta = reinterpret_cast<float2*>(reinterpret_cast<char*>(blob) + sh.meta_offset);
   dim3 grid(sh.NT, sh.KB);
   hipLaunchKernelGGL(encode_kernel, grid, dim3(256), 0, stream, W, sh.N, sh.K, sh.NT, sh.KB, codes,
-                     sh.slice_words, meta);
+                     sh.slice_words, meta, ext_scale, ext_zero);
   return hip_status(hipGetLastError(), "encode_kernel launch");
 }
 

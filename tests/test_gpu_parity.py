@@ -44,6 +44,32 @@ def test_encode_blob_is_bit_exact(mbq, N, K):
         np.testing.assert_allclose(What, ref, rtol=2e-7, atol=1e-12)
 
 
+@pytest.mark.parametrize("N,K,keep", [(3, 128, 0.7), (130, 1280, 0.6), (272, 4096, 0.9)])
+def test_encode_with_external_parameters(mbq, N, K, keep):
+    """Calibrated (clipped) base-slice parameters handed in: blob bit-exact with the oracle's, weights outside the range
+    saturated, and the routed linear over such a blob within tolerance of the oracle's."""
+    print(f"[case] encode with params N={N} K={K} keep={keep}", flush=True)
+    W = make_weight(N, K, [53, N, K], 4.0)
+    Wg = W.reshape(N, K // 128, 128)
+    lo = (Wg.min(axis=2) * np.float32(keep)).astype(np.float32)
+    hi = (Wg.max(axis=2) * np.float32(keep)).astype(np.float32)
+    s0 = ((hi - lo) / np.float32(4.0)).astype(np.float32)
+    z0 = ((-lo) / s0).astype(np.float32)
+    codes, _, _ = O.encode(W, s0, z0)
+    blob = mbq.mbq_encode_with_params(dev(W), dev(s0), dev(z0))
+    torch.cuda.synchronize()
+    assert np.array_equal(blob.cpu().numpy(), O.pack_blob(codes, s0, z0))
+    c, s, z = mbq.mbq_unpack(blob, N, K)
+    assert np.array_equal(c.cpu().numpy(), codes)
+    assert np.array_equal(s.cpu().numpy(), s0) and np.array_equal(z.cpu().numpy(), z0)
+    T = 16
+    xb = tokens(T, K, [N, K, 59])
+    prec = np.random.default_rng([N, K]).integers(0, 4, size=T).astype(np.int32)
+    perm, offsets = O.bucket(prec)
+    Y = mbq.mbq_linear(dev_bf16(xb).reshape(T, K), blob, N, K, dev(prec), dev(perm), dev(offsets))
+    assert_output_close(Y.cpu().numpy(), O.linear(xb, codes, s0, z0, prec), f"linear over clipped blob N={N} K={K}")
+
+
 # ------------------------------------------------------------------------------ route
 @pytest.mark.parametrize("T,K", [(0, 256), (1, 128), (5, 384), (16, 4096), (16, 11008), (28, 8192), (29, 8320),
                                  (32, 2048), (64, 4096), (65, 1024), (1023, 256), (1024, 256), (1025, 256),

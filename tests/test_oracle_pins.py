@@ -459,3 +459,54 @@ def test_threshold_quantile_against_sorted_brute_force():
             assert d == resid[k]
     # target bits -> ratio (App. C.2): rho = (target - 2) / 6; the realised average follows for independent slices only
     # when routing is a prefix, so only the activation count is pinned here
+
+
+# ------------------------------------------------ encode with calibrated (external) base-slice parameters
+def clipped_params(W, keep):
+    """(s0, z0) of a range shrunk to `keep` of the group's min and max: what a learned clipping would hand over."""
+    N, K = W.shape
+    Wg = W.reshape(N, K // 128, 128)
+    lo = (Wg.min(axis=2) * np.float32(keep)).astype(np.float32)
+    hi = (Wg.max(axis=2) * np.float32(keep)).astype(np.float32)
+    s0 = ((hi - lo) / np.float32(4.0)).astype(np.float32)
+    z0 = ((-lo) / s0).astype(np.float32)
+    return s0, z0
+
+
+@pytest.mark.parametrize("keep", [0.6, 0.9])
+def test_external_parameters_saturate_outside_and_bound_inside(keep):
+    """Paper App. B: the quantiser clamps, so with a clipped range (Sec. 4.1: (s0, z0) are calibrated, not fitted)
+    a weight outside the range gets code 0 (or 3) in EVERY slice and reconstructs to the centre of the lowest
+    (highest) bin of the precision, lo + s_p/2 (hi - s_p/2); a weight inside keeps the half-step bound; and the
+    sliced code still equals the single-shot floor quantiser with (s0/4^p, 4^p z0)."""
+    W = student_matrix(seed=23)
+    s0, z0 = clipped_params(W, keep)
+    codes, s0_out, z0_out = O.encode(W, s0, z0)
+    assert np.array_equal(s0_out, s0) and np.array_equal(z0_out, z0)        # stored as given
+    S = np.repeat(s0.astype(np.float64), 128, axis=1)
+    Z = np.repeat(z0.astype(np.float64), 128, axis=1)
+    lo = -Z * S
+    hi = lo + 4.0 * S
+    Wd = W.astype(np.float64)
+    below, above = Wd < lo - 1e-9 * S, Wd >= hi + 1e-9 * S
+    inside = (Wd > lo + 1e-9 * S) & (Wd < hi - 1e-9 * S)
+    assert below.sum() > 50 and above.sum() > 50 and inside.sum() > 1000      # the clip really cuts both tails
+    for e in range(4):
+        assert np.all(codes[e][below] == 0) and np.all(codes[e][above] == 3)
+    for p in range(4):
+        sp = S / 4 ** p
+        What = O.dequant(codes, s0, z0, p)
+        np.testing.assert_allclose(What[below], (lo + sp / 2)[below], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(What[above], (hi - sp / 2)[above], rtol=0, atol=1e-12)
+        assert np.all(np.abs(Wd - What)[inside] <= (sp / 2 + 1e-12)[inside])
+        q, deq = uniform_floor_quantiser(Wd, sp, Z * 4 ** p, 2 * (p + 1))
+        frac = (Wd / sp + Z * 4 ** p) % 1.0
+        edge = np.minimum(frac, 1 - frac) < 1e-9
+        assert np.all((q == O.merged_code(codes, p)) | edge)
+
+
+def test_external_parameters_equal_to_the_fit_change_nothing():
+    W = student_matrix(seed=29)
+    codes, s0, z0 = O.encode(W)
+    codes2, _, _ = O.encode(W, s0, z0)
+    assert np.array_equal(codes, codes2)
