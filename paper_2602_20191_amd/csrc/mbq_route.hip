@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   if (tid == 0) *ticket = 0u;  // leave the counter ready for the next call
 }
 
-// Small batches (T <= kSmallRouteTokens), one or several routers over the same activations
+// Small batches (T <= 64; the packed meeting word below up to kSmallRouteTokens), one or several routers over the same activations
 // (the projections of a decoder block that share their input, Sec. 4.3, fused router launch).
 // blockIdx.x = token, blockIdx.y = router.  512 threads split the K axis in chunks of 8 columns,
 // two chunks in flight per thread.  Workgroups meet through ONE 64-bit atomic add per token: the
@@ -258,6 +258,33 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
     if (lane == 0) out.prec[tok] = arg;
     return;
   }
+  if (T > kSmallRouteTokens) {
+    // Too many tokens for the packed word: the word only counts arrivals; precisions travel through memory
+    // (store, fence, count; the last to arrive fences and reads them back) and one wavefront sorts them.
+    unsigned long long arrived = 0ull;
+    if (lane == 0) {
+      out.prec[tok] = arg;
+      __threadfence();
+      arrived = atomicAdd(words + blockIdx.y, 1ull) + 1ull;
+    }
+    arrived = __shfl(arrived, 0, 64);
+    if ((int)arrived != T) return;
+    __threadfence();
+    const int p = (lane < T) ? __hip_atomic_load(out.prec + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int start = 0, my_pos = 0;
+#pragma unroll
+    for (int q = 0; q < kP; ++q) {
+      const uint64_t b = __ballot(p == q);
+      if (p == q) my_pos = start + __popcll(b & below);
+      if (lane == q) out.offsets[q] = start;
+      start += __popcll(b);
+    }
+    if (lane == kP) out.offsets[kP] = start;
+    if (p >= 0) out.perm[my_pos] = lane;
+    if (lane == 0) words[blockIdx.y] = 0ull;
+    return;
+  }
   unsigned long long all = 0ull;
   if (lane == 0) {
     out.prec[tok] = arg;
@@ -308,6 +335,8 @@ static mbq_status launch_route_one(const uint16_t* X, int64_t T, int64_t K, cons
 // Workspace: the ticket counter of the general kernels at byte 0, the per-router words of the
 // small-batch kernel from byte 64.
 bool route_can_carry_prep(int64_t T) { return T >= 1 && T <= kSmallRouteTokens && knob(4) != 1; }
+// one launch for all routers of a call: up to one wavefront of tokens
+static bool route_small_supports(int64_t T) { return T >= 1 && T <= 64 && knob(4) != 1; }
 
 // prep != nullptr (only when route_can_carry_prep(T)): the launch also prepares the activations
 // of the FP4-operand decode kernel, prep_blocks 256-column blocks, into prep.
@@ -316,7 +345,8 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
                               void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
-  if (route_can_carry_prep(T)) {
+  if (route_small_supports(T)) {
+    if (!route_can_carry_prep(T)) prep = nullptr;
     RouteGroup g;
     for (int i = 0; i < kRouteGroupMax; ++i) {
       const int j = i < n ? i : 0;
