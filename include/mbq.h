@@ -246,7 +246,8 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
  *   knob 5: K split of the prefill kernel (1, 2 or 4 workgroups per tile, partial sums added into Y), 0 = automatic
  *   knob 3: decode kernel choice: 0 automatic, 1 multi-tile kernel, 2 single-matrix stationary kernel
  *   knob 4: 1 = route small batches with the general kernel too
- *   knob 7: 1 = the one-token-tile decode kernel works on the whole K axis per workgroup where it fits (no two-part split)
+ *   knob 7: 1 = the one-token-tile decode kernel works on the whole K axis per workgroup where it fits (no two-part split);
+ *           3 = the 17..64-token kernel takes one token tile per workgroup
  *   knob 6: 1 = mbq_linear_group skips the activation preparation launch (the workspace must hold
  *           the result of an earlier call on the same X): for timing the linear kernel alone
  */

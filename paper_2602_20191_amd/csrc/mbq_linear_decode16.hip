@@ -31,7 +31,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace d16 {
 
-constexpr int kMaxTilesMulti = 32;  // tiles per workgroup whose partial sums fit the LDS budget
+constexpr int kMaxTilesMulti = 32;  // tiles per workgroup whose partial sums fit the LDS budget (per token tile: 32 / TT)
 constexpr int kStageStride = 272;   // bytes between token rows of the activation staging area (256 + 16: no bank conflicts)
 constexpr int kAreaBytes = 16 * kStageStride;  // >= 4 * 64 * 16 bytes of per-block constants
 
@@ -93,17 +93,17 @@ __device__ inline void unpack_dword(uint32_t w, const UnpackConsts& uc, uint4& B
   Ba.w = (t3 & ma) | ba; Bb.w = (t3 & mb) | bb;
 }
 
-// D += X_group * slice-E operands of the two dwords (w_lo, w_hi) of one group.
+// the four B operands of one group (two dwords) of slice E, and the four MFMAs that consume them
 template <int E>
-__device__ inline floatx4 slice_group(const uint4 A[4], const UnpackConsts& uc, uint32_t w_lo, uint32_t w_hi,
-                                       floatx4 D) {
-  uint4 Ba, Bb;
-  unpack_dword<E>(w_lo, uc, Ba, Bb);
-  D = mfma(A[0], Ba, D);
-  D = mfma(A[1], Bb, D);
-  unpack_dword<E>(w_hi, uc, Ba, Bb);
-  D = mfma(A[2], Ba, D);
-  D = mfma(A[3], Bb, D);
+__device__ inline void unpack_group(const UnpackConsts& uc, uint32_t w_lo, uint32_t w_hi, uint4 (&B)[4]) {
+  unpack_dword<E>(w_lo, uc, B[0], B[1]);
+  unpack_dword<E>(w_hi, uc, B[2], B[3]);
+}
+__device__ inline floatx4 mfma_group(const uint4 A[4], const uint4 (&B)[4], floatx4 D) {
+  D = mfma(A[0], B[0], D);
+  D = mfma(A[1], B[1], D);
+  D = mfma(A[2], B[2], D);
+  D = mfma(A[3], B[3], D);
   return D;
 }
 
@@ -115,7 +115,9 @@ struct Item {
 }  // namespace d16
 
 // MULTI: the K axis needs more than one chunk (KB > WAVES); partial tiles go through LDS.
-template <int WAVES, bool MULTI>
+// TT: token tiles of 16 per workgroup (1 or 2): the weights of a block are unpacked once and meet the
+// activation fragments of every tile, so 17..64 tokens take one pass over the weights per 32 tokens.
+template <int WAVES, bool MULTI, int TT>
 __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
     const uint16_t* __restrict__ X, int T, int64_t K, const uint4* __restrict__ codes, size_t slice_vec,
     const float2* __restrict__ meta, int64_t N, int NT, int KB, const int32_t* __restrict__ prec,
@@ -123,8 +125,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   using namespace d16;
   // blockIdx.y = token tile: rows 16 y .. 16 y + 15 of the token order (of the precision-sorted
   // order `perm` when there are several tiles, so that a tile reads only the slices it needs)
-  const int row0 = 16 * (int)blockIdx.y;
-  T = min(16, T - row0);
+  const int row0 = 16 * TT * (int)blockIdx.y;
+  T = min(16 * TT, T - row0);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps tile addresses scalar
   const int m = lane & 15;   // token row of A / weight row of B / output column
@@ -132,51 +134,61 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   const int chunks = MULTI ? (KB + WAVES - 1) / WAVES : 1;
   const int my_tiles = (NT - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
 
-  __shared__ float red[2][WAVES][64][4];                   // per-wavefront partial tiles, double buffered
+  __shared__ float red[2][TT][WAVES][64][4];               // per-wavefront partial tiles, double buffered
   // Private to each wavefront: first the staging rows of its activation block (16 tokens x 128
-  // columns, row stride kStageStride bytes), afterwards C1[2], SS[2] of that block.
-  __shared__ __attribute__((aligned(16))) char area[WAVES][kAreaBytes];
-  __shared__ float part[MULTI ? kMaxTilesMulti : 1][256];  // sums over chunks
+  // columns, row stride kStageStride bytes; one token tile after the other), afterwards C1[2], SS[2]
+  // of that block for every token tile.
+  __shared__ __attribute__((aligned(16))) char area[WAVES][TT * kAreaBytes];
+  __shared__ float part[MULTI ? kMaxTilesMulti / TT : 1][TT][256];  // sums over chunks
   char* const stage = area[wave];
-  floatx4* const cst = reinterpret_cast<floatx4*>(area[wave]);  // [4][64]
+  auto cst_of = [&](int tt) { return reinterpret_cast<floatx4*>(area[wave] + tt * kAreaBytes); };  // [4][64]
 
   // ---- loads that depend on nothing: precisions first, then activations, slice 0 ----
-  const int my_token = (lane < T) ? (perm ? perm[row0 + lane] : row0 + lane) : -1;
-  const int pl = (lane < T) ? prec[my_token] : -1;
+  int my_token[TT], pl[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+    const int r = 16 * tt + lane;  // lanes 0..15 of each tile hold its tokens
+    my_token[tt] = (lane < 16 && r < T) ? (perm ? perm[row0 + r] : row0 + r) : -1;
+    pl[tt] = (my_token[tt] >= 0) ? prec[my_token[tt]] : -1;
+  }
   // Activations: a load instruction covers four token rows, a quarter wavefront reading 256
   // contiguous bytes of each (whole cache lines); the MFMA A layout (token = lane % 16) is then
   // produced by a round trip through the wavefront's LDS rows, one half block at a time (LDS
   // operations of one wavefront execute in order; every access to the area uses one vector type).
-  uint4 xa[8];
+  uint4 xa[TT][8];
   auto load_x = [&](int kb) {
     const int64_t k0 = (int64_t)kb * kTileK + 8 * m;  // K is a multiple of 128: a half block is all there or absent
     const uint16_t* col = X + k0;
     const int second = (k0 + 128 < K) ? 128 : 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int tok = __shfl(my_token, 4 * i + kq, 64);
-      const uint16_t* src = col + (int64_t)max(tok, 0) * K;  // always a valid address
-      xa[i] = *reinterpret_cast<const uint4*>(src);
-      xa[4 + i] = *reinterpret_cast<const uint4*>(src + second);
-    }
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int tok = __shfl(my_token[tt], 4 * i + kq, 64);
+        const uint16_t* src = col + (int64_t)max(tok, 0) * K;  // always a valid address
+        xa[tt][i] = *reinterpret_cast<const uint4*>(src);
+        xa[tt][4 + i] = *reinterpret_cast<const uint4*>(src + second);
+      }
   };
   // Rows past the last token and an absent second half block become zeros on the way through.
   auto transpose_x = [&](int kb) {
     const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
     const bool second = (int64_t)kb * kTileK + 128 < K;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool there = (4 * i + kq < T) && (h == 0 || second);
-        *reinterpret_cast<floatx4*>(stage + (4 * i + kq) * kStageStride + 16 * m) =
-            there ? __builtin_bit_cast(floatx4, xa[4 * h + i]) : zero;
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool there = (16 * tt + 4 * i + kq < T) && (h == 0 || second);
+          *reinterpret_cast<floatx4*>(stage + (4 * i + kq) * kStageStride + 16 * m) =
+              there ? __builtin_bit_cast(floatx4, xa[tt][4 * h + i]) : zero;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          xa[tt][4 * h + j] = __builtin_bit_cast(
+              uint4, *reinterpret_cast<const floatx4*>(stage + m * kStageStride + 64 * j + 16 * kq));
       }
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        xa[4 * h + j] = __builtin_bit_cast(
-            uint4, *reinterpret_cast<const floatx4*>(stage + m * kStageStride + 64 * j + 16 * kq));
-    }
   };
   auto load_base = [&](int nt, int kb, Item& I) {
     const size_t tile = ((size_t)nt * KB + kb) * 64 + lane;
@@ -191,12 +203,18 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   }
 
   // ---- routing facts (the only dependent step): highest precision present, per-row constants ----
-  const int pmax =
-      (__ballot(pl == 3) != 0ull) ? 3 : (__ballot(pl == 2) != 0ull) ? 2 : (__ballot(pl == 1) != 0ull) ? 1 : 0;
-  int prow[4];
+  int plmax = pl[0];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) prow[i] = __shfl(pl, 4 * kq + i, 64);
-  const int y_token = __shfl(my_token, (int)(threadIdx.x >> 4) & 15, 64);  // output row of the reducing thread
+  for (int tt = 1; tt < TT; ++tt) plmax = max(plmax, pl[tt]);
+  const int pmax = (__ballot(plmax == 3) != 0ull) ? 3 : (__ballot(plmax == 2) != 0ull) ? 2
+                   : (__ballot(plmax == 1) != 0ull) ? 1 : 0;
+  int prow[TT][4], y_token[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) prow[tt][i] = __shfl(pl[tt], 4 * kq + i, 64);
+    y_token[tt] = __shfl(my_token[tt], (int)(threadIdx.x >> 4) & 15, 64);  // output row of the reducing thread
+  }
 
   const UnpackConsts uc = make_unpack_consts();
   const uint4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
@@ -226,91 +244,94 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
         transpose_x(kb);
         // group sums of this block's activations, in accumulator layout, and the offset term
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          floatx4 Sa = mfma(xa[4 * h + 0], ones, zero4);
-          Sa = mfma(xa[4 * h + 2], ones, Sa);
-          floatx4 Sb = mfma(xa[4 * h + 1], ones, zero4);
-          Sb = mfma(xa[4 * h + 3], ones, Sb);
-          floatx4 c1, ss;
+        for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int p = prow[i];
-            // offsets accumulated up to slice p: sums of the operand biases of slices 0..p
-            const float coefA = (p >= 3) ? 74.f : (p == 2) ? 72.f : (p == 1) ? 64.f : 32.f;
-            const float coefB = (p >= 3) ? 18.5f : (p == 2) ? 18.f : (p == 1) ? 16.f : 8.f;
-            // residual zero points: sum_{1 <= e <= p} 4^-e (2 - 0.5), and the base slice's -0.5
-            const float q = (p >= 3) ? 0.328125f : (p == 2) ? 0.3125f : (p == 1) ? 0.25f : 0.f;
-            ss[i] = Sa[i] + Sb[i];
-            c1[i] = coefA * Sa[i] + coefB * Sb[i] + (1.5f * q - 0.5f) * ss[i];
+          for (int h = 0; h < 2; ++h) {
+            floatx4 Sa = mfma(xa[tt][4 * h + 0], ones, zero4);
+            Sa = mfma(xa[tt][4 * h + 2], ones, Sa);
+            floatx4 Sb = mfma(xa[tt][4 * h + 1], ones, zero4);
+            Sb = mfma(xa[tt][4 * h + 3], ones, Sb);
+            floatx4 c1, ss;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int p = prow[tt][i];
+              // offsets accumulated up to slice p: sums of the operand biases of slices 0..p
+              const float coefA = (p >= 3) ? 74.f : (p == 2) ? 72.f : (p == 1) ? 64.f : 32.f;
+              const float coefB = (p >= 3) ? 18.5f : (p == 2) ? 18.f : (p == 1) ? 16.f : 8.f;
+              // residual zero points: sum_{1 <= e <= p} 4^-e (2 - 0.5), and the base slice's -0.5
+              const float q = (p >= 3) ? 0.328125f : (p == 2) ? 0.3125f : (p == 1) ? 0.25f : 0.f;
+              ss[i] = Sa[i] + Sb[i];
+              c1[i] = coefA * Sa[i] + coefB * Sb[i] + (1.5f * q - 0.5f) * ss[i];
+            }
+            cst_of(tt)[h * 64 + lane] = c1;
+            cst_of(tt)[(2 + h) * 64 + lane] = ss;
           }
-          cst[h * 64 + lane] = c1;
-          cst[(2 + h) * 64 + lane] = ss;
-        }
       }
       // one step: fetch tile ti+1 into `n`, consume tile ti from `c`, reduce and store
       auto step = [&](int ti, Item& c, Item& n) {
         const int nt = (int)blockIdx.x + ti * (int)gridDim.x;
-        floatx4 acc = zero4;
+        floatx4 acc[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc[tt] = zero4;
         if (active) {
           const int tn = (int)blockIdx.x + min(ti + 1, my_tiles - 1) * (int)gridDim.x;
           load_base(tn, kb, n);
           load_rest(tn, kb, n);
-          // the two groups of the block run as two independent accumulator chains
-          floatx4 D[2], v[2];
-          D[0] = slice_group<0>(&xa[0], uc, c.w[0].x, c.w[0].y, zero4);
-          D[1] = slice_group<0>(&xa[4], uc, c.w[0].z, c.w[0].w, zero4);
-          v[0] = D[0];
-          v[1] = D[1];
-          if constexpr (PM >= 1) {
-            D[0] = slice_group<1>(&xa[0], uc, c.w[1].x, c.w[1].y, D[0]);
-            D[1] = slice_group<1>(&xa[4], uc, c.w[1].z, c.w[1].w, D[1]);
+          // the two groups of the block run as two independent accumulator chains per token tile; the
+          // operands built from a packed dword serve every token tile
+          floatx4 D[TT][2], v[TT][2];
+          auto slice = [&](auto e_tag) {
+            constexpr int E = decltype(e_tag)::value;
+            uint4 B0[4], B1[4];
+            unpack_group<E>(uc, c.w[E].x, c.w[E].y, B0);
+            unpack_group<E>(uc, c.w[E].z, c.w[E].w, B1);
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int tt = 0; tt < TT; ++tt) {
+              D[tt][0] = mfma_group(&xa[tt][0], B0, E == 0 ? zero4 : D[tt][0]);
+              D[tt][1] = mfma_group(&xa[tt][4], B1, E == 0 ? zero4 : D[tt][1]);
 #pragma unroll
-              for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 1) ? D[h][i] : v[h][i];
-          }
-          if constexpr (PM >= 2) {
-            D[0] = slice_group<2>(&xa[0], uc, c.w[2].x, c.w[2].y, D[0]);
-            D[1] = slice_group<2>(&xa[4], uc, c.w[2].z, c.w[2].w, D[1]);
+              for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+                for (int i = 0; i < 4; ++i) v[tt][h][i] = (E == 0 || prow[tt][i] >= E) ? D[tt][h][i] : v[tt][h][i];
+            }
+          };
+          slice(std::integral_constant<int, 0>{});
+          if constexpr (PM >= 1) slice(std::integral_constant<int, 1>{});
+          if constexpr (PM >= 2) slice(std::integral_constant<int, 2>{});
+          if constexpr (PM >= 3) slice(std::integral_constant<int, 3>{});
 #pragma unroll
-              for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 2) ? D[h][i] : v[h][i];
-          }
-          if constexpr (PM >= 3) {
-            D[0] = slice_group<3>(&xa[0], uc, c.w[3].x, c.w[3].y, D[0]);
-            D[1] = slice_group<3>(&xa[4], uc, c.w[3].z, c.w[3].w, D[1]);
+          for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < 2; ++h) {
+              const float s0 = c.mt[h].x, s0z0 = c.mt[h].x * c.mt[h].y;
+              const floatx4 c1 = cst_of(tt)[h * 64 + lane];
+              const floatx4 ss = cst_of(tt)[(2 + h) * 64 + lane];
 #pragma unroll
-              for (int i = 0; i < 4; ++i) v[h][i] = (prow[i] >= 3) ? D[h][i] : v[h][i];
-          }
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            const float s0 = c.mt[h].x, s0z0 = c.mt[h].x * c.mt[h].y;
-            const floatx4 c1 = cst[h * 64 + lane];
-            const floatx4 ss = cst[(2 + h) * 64 + lane];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] += s0 * (v[h][i] - c1[i]) - s0z0 * ss[i];
-          }
+              for (int i = 0; i < 4; ++i) acc[tt][i] += s0 * (v[tt][h][i] - c1[i]) - s0z0 * ss[i];
+            }
         }
         // sum the wavefronts' partial tiles; rows leave in original token order
         const int buf = step_count & 1;
         ++step_count;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) red[buf][wave][lane][i] = acc[i];
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) red[buf][tt][wave][lane][i] = acc[tt][i];
         __syncthreads();
         if (threadIdx.x < 256) {
           const int r = threadIdx.x >> 4, cc = threadIdx.x & 15;
           const int64_t col = (int64_t)nt * kTileN + cc;
-          float sum = 0.f;
 #pragma unroll
-          for (int wv = 0; wv < WAVES; ++wv) sum += red[buf][wv][16 * (r >> 2) + cc][r & 3];
-          if (MULTI) {
-            if (chunk > 0) sum += part[ti][threadIdx.x];
-            if (chunk + 1 < chunks) part[ti][threadIdx.x] = sum;
+          for (int tt = 0; tt < TT; ++tt) {
+            float sum = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < WAVES; ++wv) sum += red[buf][tt][wv][16 * (r >> 2) + cc][r & 3];
+            if (MULTI) {
+              if (chunk > 0) sum += part[ti][tt][threadIdx.x];
+              if (chunk + 1 < chunks) part[ti][tt][threadIdx.x] = sum;
+            }
+            if (chunk + 1 == chunks && 16 * tt + r < T && col < N) Y[(int64_t)y_token[tt] * N + col] = sum;
           }
-          if (chunk + 1 == chunks && r < T && col < N) Y[(int64_t)y_token * N + col] = sum;
         }
       };
 #pragma unroll 1
@@ -328,11 +349,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   }
 }
 
-template <int WAVES, bool MULTI>
+template <int WAVES, bool MULTI, int TT>
 static void launch_decode16(int grid, hipStream_t stream, const uint16_t* X, int T, const Shape& sh,
                             const uint4* codes, const float2* meta, const int32_t* prec, const int32_t* perm,
                             float* Y) {
-  hipLaunchKernelGGL((decode16_kernel<WAVES, MULTI>), dim3(grid, (T + 15) / 16), dim3(WAVES * 64), 0, stream, X, T,
+  hipLaunchKernelGGL((decode16_kernel<WAVES, MULTI, TT>), dim3(grid, (T + 16 * TT - 1) / (16 * TT)), dim3(WAVES * 64), 0, stream, X, T,
                      sh.K, codes, sh.slice_words / 4, meta, sh.N, sh.NT, sh.KB, prec, T > 16 ? perm : nullptr, Y);
 }
 
@@ -359,18 +380,22 @@ mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob
   const bool multi = sh.KB > waves;
   int per_cu = knob(2);
   if (per_cu <= 0) per_cu = (waves == 4) ? 2 : 1;  // resident workgroups per compute unit at these register counts
-  const int token_tiles = (int)((T + 15) / 16);
-  int grid = (compute_units() * per_cu + token_tiles - 1) / token_tiles;  // workgroups per token tile
+  // two token tiles per workgroup above 32 tokens (eight wavefronts: the second tile's fragments need the
+  // registers): two passes over the weights instead of three or four; measured on cold weights, 14336 x 4096 at 48
+  // tokens 39 us against 57 us, at 64 tokens 39 against 44; up to 32 tokens two one-tile passes side by side are as fast
+  const int tt = (T > 32 && waves == 8 && knob(7) != 3) ? 2 : 1;
+  const int token_passes = (int)((T + 16 * tt - 1) / (16 * tt));
+  int grid = (compute_units() * per_cu + token_passes - 1) / token_passes;  // workgroups per pass
   if (grid > sh.NT) grid = sh.NT;
   // with several K chunks the per-tile partial sums live in LDS: bound the tiles per workgroup
-  if (multi && (sh.NT + grid - 1) / grid > d16::kMaxTilesMulti)
-    grid = (sh.NT + d16::kMaxTilesMulti - 1) / d16::kMaxTilesMulti;
-#define MBQ_D16(WV)                                                                          \
-  if (waves == WV) {                                                                         \
-    if (multi) launch_decode16<WV, true>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);  \
-    else launch_decode16<WV, false>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);       \
+  const int max_tiles = d16::kMaxTilesMulti / tt;
+  if (multi && (sh.NT + grid - 1) / grid > max_tiles) grid = (sh.NT + max_tiles - 1) / max_tiles;
+#define MBQ_D16(WV, TTV)                                                                           \
+  if (waves == WV && tt == TTV) {                                                                  \
+    if (multi) launch_decode16<WV, true, TTV>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);  \
+    else launch_decode16<WV, false, TTV>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);       \
   }
-  MBQ_D16(4) MBQ_D16(8) MBQ_D16(16)
+  MBQ_D16(4, 1) MBQ_D16(8, 1) MBQ_D16(16, 1) MBQ_D16(8, 2)
 #undef MBQ_D16
   return hip_status(hipGetLastError(), "decode16_kernel launch");
 }
