@@ -37,6 +37,7 @@ namespace mbq {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBM = 256, kBN = 256, kBK = 32;
@@ -634,6 +635,42 @@ __device__ __forceinline__ void prefill_tile(const uint16_t* __restrict__ Xs, in
   }
 
   // ---- write the tile in original token order ----
+  // The accumulator layout gives a store instruction 32 consecutive columns of two rows (2 x 128 bytes); 128 such
+  // instructions per wavefront cost more address-unit time than their bytes.  When rows can take 16-byte stores the
+  // tile goes through LDS once (the rings are free now; 64 x 64 floats per wavefront and half) and leaves as
+  // 16 bytes per lane, four rows of 256 bytes per instruction: a quarter of the instructions.
+  if (!accumulate && (N & 3) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0) {
+    static_assert(kSmemBytes >= 8 * 64 * 64 * 4, "staging area of the epilogue");
+    wg_barrier();  // every wavefront has left the rings
+    float* stg = reinterpret_cast<float*>(smem) + wave * (64 * 64);
+    const int64_t col4 = (int64_t)ntile_n * kBN + 64 * wn + 4 * (lane & 15);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+      for (int aa = 0; aa < 2; ++aa) {
+        const int a = 2 * half + aa;
+        if (FULL || a < na) {
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              stg[(32 * aa + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3)) * 64 + 32 * b + (lane & 31)] = acc[a][b][i];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int rowl = 4 * q + (lane >> 4);  // row of the staged 64
+        const int a = 2 * half + (rowl >> 5);
+        const int r = 32 * (2 * a + wm) + (rowl & 31);
+        if ((FULL || (a < na && r < rows)) && col4 < N) {
+          const floatx4 v = *reinterpret_cast<const floatx4*>(stg + rowl * 64 + 4 * (lane & 15));
+          const int64_t tok = perm[row0 + r];
+          *reinterpret_cast<floatx4*>(Y + tok * N + col4) = v;
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int a = 0; a < 4; ++a)
     if (FULL || a < na) {
