@@ -11,7 +11,8 @@ routed outputs).  Weights, activations and router parameters are resident in HBM
 before the timed region; three distinct copies of the packed block (> 600 MB) are
 rotated so that no step finds its weights in the 256 MB last-level cache.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric/value/unit and timing of the step, `roofline` (dominant kernel against the HBM
+peak), `cpu_baseline` (the CPU oracle on a sample of the same workload) and `extra` (side measurements).
 """
 from __future__ import annotations
 
