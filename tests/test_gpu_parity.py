@@ -399,6 +399,78 @@ def test_routed_linear_stage_equals_route_then_linear(mbq, K, T, Ns):
             assert_output_close(Ys[i].cpu().numpy(), O.linear(xb, codes, s0, z0, prec), f"stage matrix {i}")
 
 
+@pytest.mark.parametrize("algo,T", [("decode", 12), ("decode", 40), ("prefill", 300)])
+def test_linear_special_activation_rows(mbq, algo, T):
+    """Rows that stress the activation handling: all zeros, all tiny (1e-30), one element 2^20 times the rest of
+    its block, negative zeros, a constant row; every row is held to the bar on its own as well."""
+    N, K = 130, 1280
+    print(f"[case] special rows {algo} T={T}", flush=True)
+    W = make_weight(N, K, [43, T], 4.0)
+    rng = np.random.default_rng([43, T])
+    x = rng.standard_normal((T, K)).astype(np.float32)
+    x[0] = 0.0
+    x[1] *= 1e-30
+    x[2] *= 1e-3
+    x[2, 300] = 1e3
+    x[3, ::2] = -0.0
+    x[4] = 0.75
+    xb = f32_to_bf16_bits(x)
+    prec = rng.integers(0, 4, size=T).astype(np.int32)
+    prec[:5] = [3, 2, 3, 1, 0]
+    codes, s0, z0 = O.encode(W)
+    Yref = O.linear(xb, codes, s0, z0, prec)
+    Y = run_linear(mbq, W, xb, prec, ALGOS[algo])
+    assert np.all(np.isfinite(Y))
+    assert_output_close(Y, Yref, f"special rows {algo} T={T}")
+    assert not Y[0].any(), "an all-zero token must give an all-zero output row"
+    for i in range(1, 5):
+        assert_output_close(Y[i:i + 1], Yref[i:i + 1], f"special row {i}")
+
+
+def test_stage_call_replays_from_a_hip_graph(mbq):
+    """The stage call captured once and replayed with new activations in the same buffers (eager work and
+    synchronisation between the replays): every replay equals the eager call bit for bit.  K = 4096 takes the
+    two-part decode kernel, whose outputs the router launch zeroes with a kernel (not a memset node)."""
+    K, T, Ns = 4096, 16, (272, 130)
+    print("[case] stage call under graph replay", flush=True)
+    rng = np.random.default_rng(47)
+    Wrs = [dev((rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32)) for _ in Ns]
+    brs = [dev(rng.normal(0, 0.3, size=4).astype(np.float32)) for _ in Ns]
+    blobs = [mbq.mbq_encode(dev(make_weight(N, K, [47, N], 4.0))) for N in Ns]
+    X = dev_bf16(tokens(T, K, [47, 0])).reshape(T, K)
+    ws_r = mbq.route_workspace(T, K, "cuda")
+    ws_l = mbq.linear_workspace(T, max(Ns), K, "cuda")
+    routing = [(torch.empty(T, dtype=torch.int32, device="cuda"), torch.empty(T, dtype=torch.int32, device="cuda"),
+                torch.empty(5, dtype=torch.int32, device="cuda")) for _ in Ns]
+    Ys = [torch.empty((T, N), dtype=torch.float32, device="cuda") for N in Ns]
+
+    def call():
+        mbq.mbq_routed_linear_group(X, Wrs, brs, blobs, list(Ns), routing=routing, Y=Ys, ws_route=ws_r, ws_linear=ws_l)
+
+    call()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    for rep in range(4):
+        X.copy_(dev_bf16(tokens(T, K, [47, rep + 1])).reshape(T, K))
+        call()
+        torch.cuda.synchronize()
+        want = [[t.clone() for t in r] for r in routing], [y.clone() for y in Ys]
+        for y in Ys:
+            y.fill_(float("nan"))
+        for r in routing:
+            for t in r:
+                t.fill_(-7)
+        g.replay()
+        torch.cuda.synchronize()
+        for i in range(len(Ns)):
+            for a, b in zip(want[0][i], routing[i]):
+                assert torch.equal(a, b), (rep, i)
+            assert torch.equal(want[1][i], Ys[i]), (rep, i)
+        assert not ws_r.view(torch.int32).any()
+
+
 def test_linear_zero_tokens_and_bad_arguments(mbq):
     N, K = 32, 256
     W = make_weight(N, K, [17], 4.0)
