@@ -243,7 +243,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
  *   knob 0: waves per workgroup of the decode kernel (4, 8 or 16)
  *   knob 1: K-split (workgroups along K) of the multi-tile decode kernel, 0 = automatic
  *   knob 2: workgroups per compute unit of the single-tile decode kernel, 0 = automatic
- *   knob 5: K split of the prefill kernel (1, 2 or 4 workgroups per tile, partial sums added into Y), 0 = automatic
+ *   knob 5: K split of the prefill kernel (1..8 workgroups per tile, partial sums added into Y), 0 = automatic
  *   knob 3: decode kernel choice: 0 automatic, 1 multi-tile kernel, 2 single-matrix stationary kernel
  *   knob 4: 1 = route small batches with the general kernel too
  *   knob 7: 1 = the one-token-tile decode kernel works on the whole K axis per workgroup where it fits (no two-part split);

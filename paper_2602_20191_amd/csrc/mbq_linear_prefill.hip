@@ -788,17 +788,27 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
   const int n_tiles_n = (int)((sh.N + kBN - 1) / kBN);
   const int64_t m_tiles_max = T / kBM + MBQ_N_PRECISIONS;
   // K split: a launch with few tiles leaves compute units idle in its last round; when the K work per
-  // output is large (K >= 8192) the tiles are cut along K into 2 or 4 workgroups that add their
-  // partial sums into a zeroed Y.  knob 5 forces the split (1, 2 or 4).
+  // output is large (K >= 8192) the tiles are cut along K into S workgroups that add their partial sums
+  // into a zeroed Y.  S minimises the estimated makespan ceil(tiles S / compute units) / S, each further
+  // part priced at 5 % (its prologue and its atomic adds; measured on 4096 x 11008 and 8192 x 28672).
+  // knob 5 forces the split (1..8).
   constexpr int kComputeUnits = 256;
   int splits = 1;
-  if (knob(5) == 1 || knob(5) == 2 || knob(5) == 4) {
+  if (knob(5) >= 1 && knob(5) <= 8) {
     splits = knob(5);
   } else if (sh.K >= 8192) {
     const int64_t est_tiles = (T / kBM + 2) * n_tiles_n;
-    while (splits < 4 && est_tiles * splits < 3 * kComputeUnits) splits *= 2;
+    double best = 0.0;
+    for (int s = 1; s <= 6; ++s) {
+      const int64_t rounds = (est_tiles * s + kComputeUnits - 1) / kComputeUnits;
+      const double cost = (double)rounds / s * (1.0 + 0.05 * (s - 1));
+      if (s == 1 || cost < best) {
+        best = cost;
+        splits = s;
+      }
+    }
   }
-  while (splits > 1 && sh.G / splits < 4) splits /= 2;
+  while (splits > 1 && sh.G / splits < 4) --splits;
   hipLaunchKernelGGL(prefill_prep_kernel, dim3((unsigned)T), dim3(256), 0, stream, X, T, sh.K, perm, Xs, SxT, ldT,
                      splits > 1 ? Y : nullptr, sh.N);
   mbq_status st = hip_status(hipGetLastError(), "prefill_prep_kernel launch");

@@ -280,7 +280,7 @@ def test_prefill_tile_shapes(mbq, N, K, T, mix):
     assert_output_close(Y, Yref, f"prefill N={N} K={K} T={T}")
 
 
-@pytest.mark.parametrize("splits", [2, 4])
+@pytest.mark.parametrize("splits", [2, 3, 4, 7])
 def test_prefill_k_split(mbq, splits):
     """The K range of a tile cut into workgroups that add their partial sums into a zeroed Y."""
     N, K, T = 272, 2304, 300     # 18 groups: uneven split ranges
