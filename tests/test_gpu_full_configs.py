@@ -1,5 +1,5 @@
-"""GPU parity at the full sizes of BASELINE configs 1-4, in the launch configuration the
-bench uses (automatic kernel choice).  The oracle cannot redo a whole Llama-sized layer in
+"""GPU parity at the full sizes of BASELINE configs 1-4 with the automatic kernel choice, per matrix
+(mbq_route + mbq_linear) and, for the block the bench times, per stage call (mbq_routed_linear_group).  The oracle cannot redo a whole Llama-sized layer in
 seconds, so it recomputes what it can one by one: a seeded sample of weight rows (= output
 columns), including the rows at tile edges - their codes and scales bit for bit, and the
 outputs of ALL tokens on those columns within the floating-point bar.  Routing and the
@@ -74,3 +74,39 @@ def test_config3_llama3_8b_decode64(mbq, li):
 @pytest.mark.parametrize("li", range(3))
 def test_config4_llama70b_mlp(mbq, li):
     check_linear(mbq, CONFIGS[4], li)
+
+
+@pytest.mark.parametrize("names", [("q", "k", "v"), ("o",), ("gate", "up"), ("down",)])
+def test_config1_block_stage_calls(mbq, names):
+    """The launch form the bench times: one mbq_routed_linear_group call per stage of the Llama-2-7B-shaped
+    block (projections that share their input routed and computed together), at every batch size of the
+    config.  Routing in full, outputs on the sampled columns, against the oracle."""
+    cfg = CONFIGS[1]
+    by_name = {s.name: i for i, s in enumerate(cfg.linears)}
+    lis = [by_name[n] for n in names]
+    K = cfg.linears[lis[0]].K
+    Ns = [cfg.linears[li].N for li in lis]
+    print(f"[case] config 1 stage {names}", flush=True)
+    blobs, sampled = [], []
+    for li in lis:
+        W = make_case(cfg, li, 1)["W"]
+        blobs.append(mbq.mbq_encode(dev(W)))
+        rows = sample_rows(W.shape[0], cfg.seed + li, n_random=64)
+        sampled.append((rows, O.encode(W[rows])))
+        del W
+    for T in cfg.token_counts:
+        cases = [make_case(cfg, li, T, with_weight=False) for li in lis]
+        xb = cases[0]["X"]                     # the stage's projections read the first one's activations
+        X = dev_bf16(xb)
+        routing, Ys = mbq.mbq_routed_linear_group(X, [dev(c["Wr"]) for c in cases], [dev(c["br"]) for c in cases],
+                                                  blobs, Ns)
+        torch.cuda.synchronize()
+        for i, li in enumerate(lis):
+            what = f"config 1 stage {names} {cfg.linears[li].name} T={T}"
+            S, prec_ref, gap = O.route(xb, cases[i]["Wr"], cases[i]["br"])
+            p = routing[i][0].cpu().numpy()
+            compare_routing(p, prec_ref, gap, what)
+            check_bucket(p, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
+            rows, (codes_s, s0_s, z0_s) = sampled[i]
+            Yref = O.linear(xb, codes_s, s0_s, z0_s, p)
+            assert_output_close(Ys[i][:, torch.from_numpy(rows).cuda()].cpu().numpy(), Yref, what)
