@@ -130,11 +130,18 @@ constexpr int kSlotBytes = 4 * 1024 + 256;
 
 __device__ __forceinline__ void to_lds_16(const void* gptr, char* lds_base) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
-                                   (void __attribute__((address_space(3)))*)lds_base, 16, 0, 0);
+                                   (void __attribute__((address_space(3)))*)lds_base, 16, 0, 2);
 }
 __device__ __forceinline__ void to_lds_4(const void* gptr, char* lds_base) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
-                                   (void __attribute__((address_space(3)))*)lds_base, 4, 0, 0);
+                                   (void __attribute__((address_space(3)))*)lds_base, 4, 0, 2);
+}
+// a 16-byte load of data that is read once (non-temporal hint, as on the ring loads above: the weight stream
+// then does not push the activations and router parameters of the next launch out of the caches)
+__device__ __forceinline__ uint4 load_once(const uint4* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return uint4{v.x, v.y, v.z, v.w};
 }
 // wait until at most `items_behind` later items are still on their way
 __device__ __forceinline__ void ring_wait(int items_behind) {
@@ -510,7 +517,7 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
     I.scale = reinterpret_cast<const int*>(base + kPrepVecPerBlock * 16 + 2 * 16 * 4)[m];
     const Proj& P = g.p[proj_of(t)];
     const int nt = t - P.tile_begin;
-    I.w.w[0] = P.codes[((size_t)nt * KB + kb) * 64 + lane];
+    I.w.w[0] = load_once(P.codes + ((size_t)nt * KB + kb) * 64 + lane);
     I.w.mt[0] = P.meta[((size_t)nt * (2 * KB) + 2 * kb) * kTileN + m];
     I.w.mt[1] = P.meta[((size_t)nt * (2 * KB) + 2 * kb + 1) * kTileN + m];
   };
@@ -521,7 +528,7 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
 #pragma unroll
     for (int e = 1; e < 4; ++e) {
       const uint4* src = (e <= pm) ? P.codes + ((size_t)e * P.slice_vec + tile) : dummy + lane;
-      I.w.w[e] = *src;
+      I.w.w[e] = load_once(src);
     }
   };
   StreamItem A, B;
