@@ -95,6 +95,14 @@ bool decode_f4_supports(int64_t T, const Shape& sh);
 int decode_f4_k_parts(const Shape& sh);
 void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);
 // share `part` of `parts` of the clearing, done by `nthreads` threads of which this is `tid`
+// A 16-byte load of data that a launch reads once (packed weights in the decode kernels), with the
+// non-temporal hint: the stream then does not push the activations, router parameters and outputs that
+// the neighbouring launches share out of the caches.
+__device__ __forceinline__ uint4 load_once(const uint4* p) {
+  typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
+  const u32x4_nt v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(p));
+  return uint4{v.x, v.y, v.z, v.w};
+}
 __device__ inline void zero_share(const ZeroList& zl, int part, int parts, int tid, int nthreads) {
 #pragma unroll
   for (int j = 0; j < MBQ_MAX_GROUP; ++j) {

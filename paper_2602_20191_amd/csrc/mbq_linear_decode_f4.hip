@@ -136,13 +136,6 @@ __device__ __forceinline__ void to_lds_4(const void* gptr, char* lds_base) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
                                    (void __attribute__((address_space(3)))*)lds_base, 4, 0, 2);
 }
-// a 16-byte load of data that is read once (non-temporal hint, as on the ring loads above: the weight stream
-// then does not push the activations and router parameters of the next launch out of the caches)
-__device__ __forceinline__ uint4 load_once(const uint4* p) {
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-  return uint4{v.x, v.y, v.z, v.w};
-}
 // wait until at most `items_behind` later items are still on their way
 __device__ __forceinline__ void ring_wait(int items_behind) {
   if (items_behind >= 3) asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
