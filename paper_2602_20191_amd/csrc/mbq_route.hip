@@ -153,6 +153,37 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   if (tid == 0) *ticket = 0u;  // leave the counter ready for the next call
 }
 
+// Cross-lane moves of a double through the data-parallel-primitive path of the vector ALU (no LDS
+// round trip as for a general shuffle): CTRL is a DPP control word, here a permutation inside each
+// group of four lanes (quad_perm) or a rotation inside each row of 16 lanes (row_ror).
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  const long long b = __builtin_bit_cast(long long, v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(b & 0xFFFFFFFFll), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
+  return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
+}
+constexpr int kDppQuadXor1 = 0xB1, kDppQuadXor2 = 0x4E;  // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kDppRowRor4 = 0x124, kDppRowRor8 = 0x128;
+
+// Sums four per-lane values over the wavefront.  The first two exchanges halve the number of values a
+// lane carries (lanes 1 apart split the four between them, then lanes 2 apart), so that seven moves of
+// a double do the work of twenty-four; afterwards lane l holds the total of value wave_sum4_index(l).
+__device__ __forceinline__ int wave_sum4_index(int lane) { return 2 * (lane & 1) + ((lane >> 1) & 1); }
+__device__ __forceinline__ double wave_sum4(const double (&acc)[4], int lane) {
+  const bool odd = (lane & 1) != 0, upper = (lane & 2) != 0;
+  double keep0 = odd ? acc[2] : acc[0], keep1 = odd ? acc[3] : acc[1];
+  keep0 += dpp_move<kDppQuadXor1>(odd ? acc[0] : acc[2]);
+  keep1 += dpp_move<kDppQuadXor1>(odd ? acc[1] : acc[3]);
+  double v = upper ? keep1 : keep0;
+  v += dpp_move<kDppQuadXor2>(upper ? keep0 : keep1);
+  v += dpp_move<kDppRowRor4>(v);
+  v += dpp_move<kDppRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
 // Small batches (T <= 64; the packed meeting word below up to kSmallRouteTokens), one or several routers over the same activations
 // (the projections of a decoder block that share their input, Sec. 4.3, fused router launch).
 // blockIdx.x = token, blockIdx.y = router.  512 threads split the K axis in chunks of 8 columns,
@@ -228,12 +259,9 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
     if (two) add(xb, wb);
   }
   __shared__ double red[8][kP];
-#pragma unroll
-  for (int q = 0; q < kP; ++q) {
-    double v = acc[q];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
-    if (lane == 0) red[wave][q] = v;
+  {
+    const double v = wave_sum4(acc, lane);
+    if (lane < kP) red[wave][wave_sum4_index(lane)] = v;
   }
   __syncthreads();
   if (wave != 0) return;
