@@ -7,7 +7,10 @@ router, one decode batch of bf16 tokens with 1% outlier channels, uniform precis
 A *step* is one pass of the whole hot path over all seven linears for one batch, as the four
 dependent stages of the block: {q, k, v} (one input), {o}, {gate, up} (one input), {down};
 each stage is one mbq_routed_linear_group call (route every projection's tokens, then the
-routed outputs).  Weights, activations and router parameters are resident in HBM
+routed outputs).  Steps are replayed from HIP graphs that hold up to 32 consecutive steps each (the
+decode step of a 32-layer model replays its 32 blocks at once: a replay costs about 6 us of idle
+GPU, which one step per replay would charge to every block); what is left of --steps after
+whole replays runs from one-step graphs.  Weights, activations and router parameters are resident in HBM
 before the timed region; three distinct copies of the packed block (> 600 MB) are
 rotated so that no step finds its weights in the 256 MB last-level cache.
 
@@ -50,6 +53,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--batch", type=int, default=16, help="decode batch (tokens per step): 1, 4 or 16")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--steps-per-replay", type=int, default=32,
+                    help="steps captured in one HIP graph (a decode step of a 32-layer model replays 32 blocks "
+                         "at once); the remainder of --steps runs from one-step graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the batch-1/4 and prefill side measurements")
     ap.add_argument("--probe", choices=["decode", "prefill"], default=None,
@@ -149,7 +155,11 @@ def main() -> int:
 
     # ------------------------------------------------------------- launch mechanism
     launch = "eager"
-    graphs = None
+    graphs = None          # one step per replay, one graph per weight copy
+    long_graphs = None     # `per_replay` consecutive steps per replay, one graph per starting copy
+    # whole replays of equal length cover the timed steps: K = 300 -> 10 replays of 30, K = 50 -> 2 of 25
+    n_replays = max(1, -(-args.steps // max(1, args.steps_per_replay)))
+    per_replay = max(1, args.steps // n_replays)
     step(0)
     torch.cuda.synchronize()
     if not args.no_graph:
@@ -160,26 +170,40 @@ def main() -> int:
                 with torch.cuda.graph(g):
                     step(slot)
                 graphs.append(g)
-            launch = "hipgraph"
+            if per_replay > 1:
+                long_graphs = []
+                for slot in range(RING):
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        for j in range(per_replay):
+                            step((slot + j) % RING)
+                    long_graphs.append(g)
+            launch = "hipgraph" if per_replay == 1 else f"hipgraph, {per_replay} steps per replay"
         except Exception as exc:  # capture not available: time eager launches instead
             print(f"[bench] graph capture failed ({exc}); falling back to eager launches", file=sys.stderr)
-            graphs = None
+            graphs = long_graphs = None
             torch.cuda.synchronize()
 
-    def run(i: int) -> None:
-        if graphs is not None:
-            graphs[i % RING].replay()
-        else:
-            step(i % RING)
+    def run_steps(first: int, count: int) -> None:
+        """Steps first .. first + count - 1; step i works on weight copy i % RING."""
+        i, end = first, first + count
+        while i < end:
+            if long_graphs is not None and end - i >= per_replay:
+                long_graphs[i % RING].replay()
+                i += per_replay
+            elif graphs is not None:
+                graphs[i % RING].replay()
+                i += 1
+            else:
+                step(i % RING)
+                i += 1
 
-    for i in range(args.warmup):
-        run(i)
+    run_steps(0, args.warmup)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_start = time.perf_counter()
     ev0.record()
-    for i in range(args.steps):
-        run(i)
+    run_steps(args.warmup, args.steps)
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_start) * 1e3
@@ -343,7 +367,8 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
             pmax = int(b["prec"].max().item())
             byts += algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax) + 16 * l["spec"].K
         extra[f"decode_batch_{T}"] = {"ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
-                                      "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9}
+                                      "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9,
+                                      "launch": "hipgraph, one step per replay" if graphs else "eager"}
     # the prefill linears of BASELINE configs[2] (gate, up, down; 2048 tokens), each as the whole mbq_linear call
     # (gather/group-sum pre-kernel + tile kernel) timed with HIP events over back-to-back launches
     pcfg = CONFIGS[2]
