@@ -37,7 +37,7 @@ STAGES = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))   # projections th
 # HBM bytes per linear-kernel launch at batch 16 (mean over the four stages) from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of `bench.py --probe decode`, scaled by what the same counters read for a plain 256 MiB copy
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/decode_linear_hbm_traffic_llama2_7b_batch16.txt
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 53.53e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 54.64e6}
 
 
 def algorithmic_bytes(N, K, T, pmax):
