@@ -52,6 +52,12 @@ bool make_shape(int64_t N, int64_t K, Shape* out) {
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// 17..64 tokens (and one token tile when the FP4-operand kernels are switched off): the register-stationary
+// kernel, except for matrices with few row tiles (see dispatch_linear)
+static bool takes_stationary_kernel(int64_t T, const Shape& sh) {
+  return knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 128 || (T > 32 && sh.NT >= 32));
+}
+
 // algo is DECODE (T <= 64), PREFILL or SIMPLE here
 mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const Shape& sh, const int32_t* prec,
                            const int32_t* perm, const int32_t* offsets, float* Y, void* ws, int algo,
@@ -72,8 +78,7 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
         if (st != MBQ_OK) return st;
         return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s, nullptr, nullptr);
       }
-      if (knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 128 || (T > 32 && sh.NT >= 32)))
-        return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
+      if (takes_stationary_kernel(T, sh)) return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
       return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
     default:
       return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s);
@@ -393,6 +398,12 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     mbq_status st = knob(6) == 1 ? MBQ_OK : launch_decode_f4_prep(X, T, K, sh[0].KB, ws, zl, s);
     if (st != MBQ_OK) return st;
     return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s, nullptr, nullptr);
+  }
+  if (algo == MBQ_ALGO_DECODE && n_proj > 1) {
+    // the matrices share one launch of the register-stationary kernel when each of them would take it
+    bool all = true;
+    for (int i = 0; i < n_proj; ++i) all = all && takes_stationary_kernel(T, sh[i]);
+    if (all) return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host, s);
   }
   for (int i = 0; i < n_proj; ++i) {
     mbq_status st =

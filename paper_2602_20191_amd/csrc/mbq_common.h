@@ -91,6 +91,10 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
                                  hipStream_t stream);
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
+// the same for up to MBQ_MAX_GROUP matrices over one X (one K), each with its own routing, in one launch
+mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
+                                        const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
+                                        float* const* Y, hipStream_t stream);
 bool decode_f4_supports(int64_t T, const Shape& sh);
 int decode_f4_k_parts(const Shape& sh);
 void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);

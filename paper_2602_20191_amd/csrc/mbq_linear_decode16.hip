@@ -4,8 +4,8 @@
 // shared-scale structure of App. B (s_e = s0/4^e, z_e = 2 for e >= 1); only slices
 // 0..max_i p_i are fetched (Sec. 4.3, on-demand slice access).
 //
-// Work split: a workgroup of WAVES wavefronts owns the 16-row code tiles nt = blockIdx.x,
-// blockIdx.x + gridDim.x, ...  The K axis is cut into chunks of WAVES 256-column blocks;
+// Work split: a workgroup of WAVES wavefronts owns the 16-row code tiles nt = w, w + W, ... of its matrix
+// (w = its index among the W workgroups of that matrix).  The K axis is cut into chunks of WAVES 256-column blocks;
 // inside a chunk wavefront w owns block chunk*WAVES + w, keeps its activation fragments in
 // registers (and their group sums in LDS) and streams only packed weights from HBM while it
 // walks over the workgroup's tiles, always fetching the next tile before consuming the
@@ -112,17 +112,48 @@ struct Item {
   float2 mt[2];
 };
 
+// One launch serves up to MBQ_MAX_GROUP matrices that read the same activations (each with its own
+// routing): matrix j owns workgroups wg_begin .. wg_begin + wg_count - 1 of every token pass.
+struct Proj {
+  const uint4* codes;
+  size_t slice_vec;
+  const float2* meta;
+  int64_t N;
+  int NT;
+  const int32_t* prec;
+  const int32_t* perm;
+  float* Y;
+  int wg_begin, wg_count;
+};
+struct Group {
+  Proj p[MBQ_MAX_GROUP];
+  int n;
+};
+
 }  // namespace d16
 
 // MULTI: the K axis needs more than one chunk (KB > WAVES); partial tiles go through LDS.
 // TT: token tiles of 16 per workgroup (1 or 2): the weights of a block are unpacked once and meet the
 // activation fragments of every tile, so 17..64 tokens take one pass over the weights per 32 tokens.
 template <int WAVES, bool MULTI, int TT>
-__global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
-    const uint16_t* __restrict__ X, int T, int64_t K, const uint4* __restrict__ codes, size_t slice_vec,
-    const float2* __restrict__ meta, int64_t N, int NT, int KB, const int32_t* __restrict__ prec,
-    const int32_t* __restrict__ perm, float* __restrict__ Y) {
+__global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
+                                                              int KB, const d16::Group g) {
   using namespace d16;
+  // which matrix this workgroup works on (uniform), and its place among that matrix's workgroups
+  // (selects between the argument block's entries: indexing it with a run-time value would move it to scratch)
+  Proj P = g.p[0];
+#pragma unroll
+  for (int j = 1; j < MBQ_MAX_GROUP; ++j)
+    if (j < g.n && (int)blockIdx.x >= g.p[j].wg_begin) P = g.p[j];
+  const uint4* __restrict__ codes = P.codes;
+  const size_t slice_vec = P.slice_vec;
+  const float2* __restrict__ meta = P.meta;
+  const int64_t N = P.N;
+  const int NT = P.NT;
+  const int32_t* __restrict__ prec = P.prec;
+  const int32_t* __restrict__ perm = P.perm;
+  float* __restrict__ Y = P.Y;
+  const int wg = (int)blockIdx.x - P.wg_begin, wgs = P.wg_count;
   // blockIdx.y = token tile: rows 16 y .. 16 y + 15 of the token order (of the precision-sorted
   // order `perm` when there are several tiles, so that a tile reads only the slices it needs)
   const int row0 = 16 * TT * (int)blockIdx.y;
@@ -132,7 +163,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   const int m = lane & 15;   // token row of A / weight row of B / output column
   const int kq = lane >> 4;  // k quarter of a k-step; output rows 4 kq .. 4 kq + 3
   const int chunks = MULTI ? (KB + WAVES - 1) / WAVES : 1;
-  const int my_tiles = (NT - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int my_tiles = (NT - wg + wgs - 1) / wgs;
 
   __shared__ float red[2][TT][WAVES][64][4];               // per-wavefront partial tiles, double buffered
   // Private to each wavefront: first the staging rows of its activation block (16 tokens x 128
@@ -199,7 +230,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
   Item cur, nxt;
   if (!MULTI && my_tiles > 0 && wave < KB) {
     load_x(wave);
-    load_base((int)blockIdx.x, wave, cur);
+    load_base(wg, wave, cur);
   }
 
   // ---- routing facts (the only dependent step): highest precision present, per-row constants ----
@@ -238,9 +269,9 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
       if (active) {
         if (MULTI) {
           load_x(kb);
-          load_base((int)blockIdx.x, kb, cur);
+          load_base(wg, kb, cur);
         }
-        load_rest((int)blockIdx.x, kb, cur);
+        load_rest(wg, kb, cur);
         transpose_x(kb);
         // group sums of this block's activations, in accumulator layout, and the offset term
 #pragma unroll
@@ -269,12 +300,12 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
       }
       // one step: fetch tile ti+1 into `n`, consume tile ti from `c`, reduce and store
       auto step = [&](int ti, Item& c, Item& n) {
-        const int nt = (int)blockIdx.x + ti * (int)gridDim.x;
+        const int nt = wg + ti * wgs;
         floatx4 acc[TT];
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) acc[tt] = zero4;
         if (active) {
-          const int tn = (int)blockIdx.x + min(ti + 1, my_tiles - 1) * (int)gridDim.x;
+          const int tn = wg + min(ti + 1, my_tiles - 1) * wgs;
           load_base(tn, kb, n);
           load_rest(tn, kb, n);
           // the two groups of the block run as two independent accumulator chains per token tile; the
@@ -350,11 +381,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(
 }
 
 template <int WAVES, bool MULTI, int TT>
-static void launch_decode16(int grid, hipStream_t stream, const uint16_t* X, int T, const Shape& sh,
-                            const uint4* codes, const float2* meta, const int32_t* prec, const int32_t* perm,
-                            float* Y) {
-  hipLaunchKernelGGL((decode16_kernel<WAVES, MULTI, TT>), dim3(grid, (T + 16 * TT - 1) / (16 * TT)), dim3(WAVES * 64), 0, stream, X, T,
-                     sh.K, codes, sh.slice_words / 4, meta, sh.N, sh.NT, sh.KB, prec, T > 16 ? perm : nullptr, Y);
+static void launch_decode16(int grid, hipStream_t stream, const uint16_t* X, int T, int64_t K, int KB,
+                            const d16::Group& g) {
+  hipLaunchKernelGGL((decode16_kernel<WAVES, MULTI, TT>), dim3(grid, (T + 16 * TT - 1) / (16 * TT)), dim3(WAVES * 64), 0,
+                     stream, X, T, K, KB, g);
 }
 
 static int compute_units() {
@@ -370,10 +400,10 @@ static int compute_units() {
   return cached;
 }
 
-mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
-                                  const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream) {
-  const uint4* codes = reinterpret_cast<const uint4*>(blob);
-  const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
+mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
+                                        const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
+                                        float* const* Y, hipStream_t stream) {
+  const Shape& sh = shapes[0];  // K, and with it the kernel variant, is common to the matrices of a call
   int waves = knob(0);
   // eight wavefronts leave 256 registers each: room for the staged activations and both weight buffers
   if (waves != 4 && waves != 8 && waves != 16) waves = (sh.KB <= 4) ? 4 : 8;
@@ -385,19 +415,48 @@ mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob
   // tokens 39 us against 57 us, at 64 tokens 39 against 44; up to 32 tokens two one-tile passes side by side are as fast
   const int tt = (T > 32 && waves == 8 && knob(7) != 3) ? 2 : 1;
   const int token_passes = (int)((T + 16 * tt - 1) / (16 * tt));
-  int grid = (compute_units() * per_cu + token_passes - 1) / token_passes;  // workgroups per pass
-  if (grid > sh.NT) grid = sh.NT;
+  const int budget = (compute_units() * per_cu + token_passes - 1) / token_passes;  // workgroups per pass
   // with several K chunks the per-tile partial sums live in LDS: bound the tiles per workgroup
   const int max_tiles = d16::kMaxTilesMulti / tt;
-  if (multi && (sh.NT + grid - 1) / grid > max_tiles) grid = (sh.NT + max_tiles - 1) / max_tiles;
-#define MBQ_D16(WV, TTV)                                                                           \
-  if (waves == WV && tt == TTV) {                                                                  \
-    if (multi) launch_decode16<WV, true, TTV>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);  \
-    else launch_decode16<WV, false, TTV>(grid, stream, X, (int)T, sh, codes, meta, prec, perm, Y);       \
+  int64_t all_tiles = 0;
+  for (int i = 0; i < n; ++i) all_tiles += shapes[i].NT;
+  d16::Group g;
+  int grid = 0;
+  for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
+    const int j = i < n ? i : 0;
+    const Shape& s = shapes[j];
+    // the pass's workgroups are dealt to the matrices in proportion to their row tiles
+    int share = (int)(((int64_t)budget * s.NT + all_tiles - 1) / all_tiles);
+    if (share < 1) share = 1;
+    if (share > s.NT) share = s.NT;
+    if (multi && (s.NT + share - 1) / share > max_tiles) share = (s.NT + max_tiles - 1) / max_tiles;
+    d16::Proj& p = g.p[i];
+    p.codes = reinterpret_cast<const uint4*>(blobs[j]);
+    p.slice_vec = s.slice_words / 4;
+    p.meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blobs[j]) + s.meta_offset);
+    p.N = s.N;
+    p.NT = s.NT;
+    p.prec = prec[j];
+    p.perm = T > 16 ? perm[j] : nullptr;
+    p.Y = Y[j];
+    p.wg_begin = grid;
+    p.wg_count = i < n ? share : 0;
+    if (i < n) grid += share;
+  }
+  g.n = n;
+#define MBQ_D16(WV, TTV)                                                                     \
+  if (waves == WV && tt == TTV) {                                                            \
+    if (multi) launch_decode16<WV, true, TTV>(grid, stream, X, (int)T, sh.K, sh.KB, g);      \
+    else launch_decode16<WV, false, TTV>(grid, stream, X, (int)T, sh.K, sh.KB, g);           \
   }
   MBQ_D16(4, 1) MBQ_D16(8, 1) MBQ_D16(16, 1) MBQ_D16(8, 2)
 #undef MBQ_D16
   return hip_status(hipGetLastError(), "decode16_kernel launch");
+}
+
+mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
+                                  const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream) {
+  return launch_linear_decode16_group(X, T, 1, &blob, &sh, &prec, &perm, &Y, stream);
 }
 
 }  // namespace mbq

@@ -337,10 +337,12 @@ def test_decode_several_token_tiles(mbq, T, K, N):
 
 
 @pytest.mark.parametrize("K,T,Ns", [(4096, 16, (96, 32, 130)), (4096, 1, (64, 64)), (2048, 7, (80, 48, 16, 33)),
-                                    (768, 16, (40,)), (3072, 5, (48, 96)), (5120, 16, (48, 32)), (1024, 40, (48, 32))])
+                                    (768, 16, (40,)), (3072, 5, (48, 96)), (5120, 16, (48, 32)), (1024, 40, (48, 32)),
+                                    (4096, 64, (1040, 130, 256)), (2304, 33, (272, 48, 16, 640)), (4352, 48, (2064, 16))])
 def test_linear_group_equals_separate_calls(mbq, K, T, Ns):
     """Several matrices over one X, each with its own routing: against the oracle and bit for bit
-    against mbq_linear (the last two shapes take the per-matrix kernels inside the group call)."""
+    against mbq_linear (17..64 tokens: one launch of the register-stationary kernel for all matrices when
+    each would take it, else per-matrix kernels inside the group call - the last shape)."""
     print(f"[case] linear group K={K} T={T} Ns={Ns}", flush=True)
     xb = tokens(T, K, [K, T, 9])
     X = dev_bf16(xb).reshape(T, K)
