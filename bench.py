@@ -343,16 +343,19 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         one(0)
         torch.cuda.synchronize()
         graphs = []
+        per_replay = 10                    # consecutive steps per graph replay, as in the main run
         try:
             for slot in range(RING):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g):
-                    one(slot)
+                    for j in range(per_replay):
+                        one((slot + j) % RING)
                 graphs.append(g)
         except Exception:
             graphs = []
-        n = 60
-        for i in range(6):
+            per_replay = 1
+        n = 6 if graphs else 60
+        for i in range(1 if graphs else 6):
             graphs[i % RING].replay() if graphs else one(i % RING)
         a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
@@ -360,7 +363,7 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
             graphs[i % RING].replay() if graphs else one(i % RING)
         b2.record()
         torch.cuda.synchronize()
-        ms = a.elapsed_time(b2) / n
+        ms = a.elapsed_time(b2) / (n * per_replay)
         byts = 0
         for l in layers:
             b = bufs[l["spec"].name]
@@ -368,7 +371,7 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
             byts += algorithmic_bytes(l["spec"].N, l["spec"].K, T, pmax) + 16 * l["spec"].K
         extra[f"decode_batch_{T}"] = {"ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
                                       "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9,
-                                      "launch": "hipgraph, one step per replay" if graphs else "eager"}
+                                      "launch": f"hipgraph, {per_replay} steps per replay" if graphs else "eager"}
     # the prefill linears of BASELINE configs[2] (gate, up, down; 2048 tokens), each as the whole mbq_linear call
     # (gather/group-sum pre-kernel + tile kernel) timed with HIP events over back-to-back launches
     pcfg = CONFIGS[2]
@@ -491,21 +494,26 @@ def other_config_measurements(mbq, torch, dev):
     block(0)
     torch.cuda.synchronize()
     graphs = []
-    try:                                   # replay from HIP graphs, one per weight copy, as in the main run
+    per_replay = 10                        # consecutive blocks per graph replay, as in the main run
+    try:
         for slot in range(RING):
             gr = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gr):
-                block(slot)
+                for j in range(per_replay):
+                    block(slot + j)
             graphs.append(gr)
     except Exception:
         graphs = []
         torch.cuda.synchronize()
-    ms = timed((lambda i: graphs[i % RING].replay()) if graphs else block, 30, warm=3)
+    if graphs:
+        ms = timed(lambda i: graphs[i % RING].replay(), 6, warm=1) / per_replay
+    else:
+        ms = timed(block, 30, warm=3)
     byts = sum(algorithmic_bytes(N, st["K"], T, int(r[0].max().item())) + 16 * st["K"]
                for st in stages for N, r in zip(st["Ns"], st["routing"]))
     out["decode_llama3_8b_block_batch64"] = {
         "workload": "BASELINE configs[3] shapes: q,o 4096x4096, k,v 1024x4096, gate,up 14336x4096, down 4096x14336; "
-                    "64 tokens, seven routers, uniform mix; HIP-graph replays, three weight copies rotated",
+                    "64 tokens, seven routers, uniform mix; HIP-graph replays of 10 blocks, three weight copies rotated",
         "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9,
         "hbm_frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     del stages
