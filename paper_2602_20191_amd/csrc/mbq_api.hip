@@ -301,6 +301,19 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
       return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream,
                                      perm_host, offsets_host);
     }
+    // up to 64 tokens with every matrix on the register-stationary kernel: the router launch only writes the
+    // precisions (no meeting of its workgroups), the linear launch sorts the tokens itself
+    if (ok && T <= kMaxDecodeTokens && route_defers_sort(T)) {
+      bool all = true;
+      for (int i = 0; i < n_proj; ++i) all = all && takes_stationary_kernel(T, sh[i]);
+      if (all) {
+        mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
+                                           nullptr, ws_route, (hipStream_t)stream, nullptr, 0, nullptr, true);
+        if (st != MBQ_OK) return st;
+        return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host,
+                                            (hipStream_t)stream, perm_host, offsets_host);
+      }
+    }
   }
   // otherwise exactly the two calls (they check the arguments)
   mbq_status st = mbq_route_group(X, T, K, n_proj, Wr_host, br_host, P, prec_host, perm_host, offsets_host,
@@ -403,7 +416,7 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     // the matrices share one launch of the register-stationary kernel when each of them would take it
     bool all = true;
     for (int i = 0; i < n_proj; ++i) all = all && takes_stationary_kernel(T, sh[i]);
-    if (all) return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host, s);
+    if (all) return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host, s, nullptr, nullptr);
   }
   for (int i = 0; i < n_proj; ++i) {
     mbq_status st =

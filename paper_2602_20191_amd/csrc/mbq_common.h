@@ -74,6 +74,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
                               void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket);
 bool route_can_carry_prep(int64_t T);
+bool route_defers_sort(int64_t T);
 mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
                             const float* W2, const float* b2, double delta, int32_t* prec, int32_t* perm,
                             int32_t* offsets, double* scores, void* ws, hipStream_t stream);
@@ -92,9 +93,12 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
 // the same for up to MBQ_MAX_GROUP matrices over one X (one K), each with its own routing, in one launch
+// sort_perm / sort_offsets (arrays of n, or null): the tokens are not sorted yet (perm is ignored); the launch sorts
+// them by the precisions itself and writes the order and the bucket offsets there (T <= 64)
 mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
                                         const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
-                                        float* const* Y, hipStream_t stream);
+                                        float* const* Y, hipStream_t stream, int32_t* const* sort_perm,
+                                        int32_t* const* sort_offsets);
 bool decode_f4_supports(int64_t T, const Shape& sh);
 int decode_f4_k_parts(const Shape& sh);
 void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);

@@ -121,7 +121,12 @@ struct Proj {
   int64_t N;
   int NT;
   const int32_t* prec;
-  const int32_t* perm;
+  const int32_t* perm;   // precision-sorted token order (read), or null: original order (one tile) / sorted here
+  // sort_perm != null (T <= 64): the tokens have not been sorted yet.  Every wavefront derives the order from
+  // the precisions itself (one load and a few ballots instead of two dependent loads), and the matrix's
+  // first workgroup writes perm and offsets out for the caller.
+  int32_t* sort_perm;
+  int32_t* sort_offsets;
   float* Y;
   int wg_begin, wg_count;
 };
@@ -157,6 +162,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
   // blockIdx.y = token tile: rows 16 y .. 16 y + 15 of the token order (of the precision-sorted
   // order `perm` when there are several tiles, so that a tile reads only the slices it needs)
   const int row0 = 16 * TT * (int)blockIdx.y;
+  const int T_all = T;
   T = min(16 * TT, T - row0);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps tile addresses scalar
@@ -180,7 +186,36 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
   for (int tt = 0; tt < TT; ++tt) {
     const int r = 16 * tt + lane;  // lanes 0..15 of each tile hold its tokens
     my_token[tt] = (lane < 16 && r < T) ? (perm ? perm[row0 + r] : row0 + r) : -1;
-    pl[tt] = (my_token[tt] >= 0) ? prec[my_token[tt]] : -1;
+    pl[tt] = (my_token[tt] >= 0 && P.sort_perm == nullptr) ? prec[my_token[tt]] : -1;
+  }
+  if (P.sort_perm != nullptr) {
+    // stable counting sort of all T_all <= 64 tokens by precision (Sec. 4.3, token permutation): lane = token
+    const int p_mine = lane < T_all ? min(max(prec[lane], 0), MBQ_N_PRECISIONS - 1) : -1;
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int start = 0, my_pos = 0, off_mine = 0;
+#pragma unroll
+    for (int q = 0; q < MBQ_N_PRECISIONS; ++q) {
+      const uint64_t b = __ballot(p_mine == q);
+      if (p_mine == q) my_pos = start + __popcll(b & below);
+      if (lane == q) off_mine = start;
+      start += __popcll(b);
+    }
+    if (lane == MBQ_N_PRECISIONS) off_mine = start;
+    // position -> (token, precision) through the wavefront's own LDS rows (in order within a wavefront)
+    int* const order = reinterpret_cast<int*>(stage);
+    if (p_mine >= 0) order[my_pos] = lane | (p_mine << 8);
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      const int r = 16 * tt + lane;
+      const int e = (lane < 16 && r < T) ? order[row0 + r] : -1;
+      my_token[tt] = e < 0 ? -1 : (e & 0xFF);
+      pl[tt] = e < 0 ? -1 : (e >> 8);
+    }
+    asm volatile("" ::: "memory");  // the rows are reused below through another type: keep these reads in front
+    if (wg == 0 && blockIdx.y == 0 && wave == 0) {
+      if (p_mine >= 0) P.sort_perm[my_pos] = lane;
+      if (lane <= MBQ_N_PRECISIONS) P.sort_offsets[lane] = off_mine;
+    }
   }
   // Activations: a load instruction covers four token rows, a quarter wavefront reading 256
   // contiguous bytes of each (whole cache lines); the MFMA A layout (token = lane % 16) is then
@@ -402,7 +437,8 @@ static int compute_units() {
 
 mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
                                         const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
-                                        float* const* Y, hipStream_t stream) {
+                                        float* const* Y, hipStream_t stream, int32_t* const* sort_perm,
+                                        int32_t* const* sort_offsets) {
   const Shape& sh = shapes[0];  // K, and with it the kernel variant, is common to the matrices of a call
   int waves = knob(0);
   // eight wavefronts leave 256 registers each: room for the staged activations and both weight buffers
@@ -437,7 +473,9 @@ mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, con
     p.N = s.N;
     p.NT = s.NT;
     p.prec = prec[j];
-    p.perm = T > 16 ? perm[j] : nullptr;
+    p.perm = (T > 16 && !sort_perm) ? perm[j] : nullptr;
+    p.sort_perm = sort_perm ? sort_perm[j] : nullptr;
+    p.sort_offsets = sort_perm ? sort_offsets[j] : nullptr;
     p.Y = Y[j];
     p.wg_begin = grid;
     p.wg_count = i < n ? share : 0;
@@ -456,7 +494,7 @@ mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, con
 
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream) {
-  return launch_linear_decode16_group(X, T, 1, &blob, &sh, &prec, &perm, &Y, stream);
+  return launch_linear_decode16_group(X, T, 1, &blob, &sh, &prec, &perm, &Y, stream, nullptr, nullptr);
 }
 
 }  // namespace mbq

@@ -365,6 +365,8 @@ static mbq_status launch_route_one(const uint16_t* X, int64_t T, int64_t K, cons
 bool route_can_carry_prep(int64_t T) { return T >= 1 && T <= kSmallRouteTokens && knob(4) != 1; }
 // one launch for all routers of a call: up to one wavefront of tokens
 static bool route_small_supports(int64_t T) { return T >= 1 && T <= 64 && knob(4) != 1; }
+// the one-launch kernel can leave the token sort to the consumer of the precisions (defer_bucket below)
+bool route_defers_sort(int64_t T) { return route_small_supports(T); }
 
 // prep != nullptr (only when route_can_carry_prep(T)): the launch also prepares the activations
 // of the FP4-operand decode kernel, prep_blocks 256-column blocks, into prep.
@@ -384,7 +386,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
     const unsigned gx = (prep && prep_blocks > (int)T) ? (unsigned)prep_blocks : (unsigned)T;
     hipLaunchKernelGGL(route_small_kernel, dim3(gx, (unsigned)n + (prep ? 1u : 0u)), dim3(512), 0, stream, X, (int)T,
                        K, g, n, words, reinterpret_cast<char*>(prep), prep ? prep_blocks : 0,
-                       (prep && zl) ? *zl : ZeroList{}, (prep && defer_bucket) ? 1 : 0);
+                       (prep && zl) ? *zl : ZeroList{}, defer_bucket ? 1 : 0);
     return hip_status(hipGetLastError(), "route_small_kernel launch");
   }
   for (int i = 0; i < n; ++i) {

@@ -366,6 +366,9 @@ def test_linear_group_equals_separate_calls(mbq, K, T, Ns):
 
 @pytest.mark.parametrize("K,T,Ns", [(4096, 16, (96, 32, 130)), (2048, 1, (64, 48)), (1280, 9, (40,)), (5120, 16, (48, 32)),
                                     (1024, 40, (48, 32)),
+                                    # 29..64 tokens: the linear launch sorts the tokens; last shape: one matrix takes
+                                    # another kernel, so the stage falls back to the two calls
+                                    (4096, 64, (1040, 130)), (2304, 33, (272, 48, 16)), (512, 17, (40,)), (4352, 48, (2064, 16)),
                                     # many row tiles: the whole chip takes part, K in one part, two parts and streamed
                                     (1024, 5, (1024, 528)), (4096, 16, (1040, 512, 512)), (9216, 3, (1600,)), (2304, 16, (640, 130))])
 def test_routed_linear_stage_equals_route_then_linear(mbq, K, T, Ns):
