@@ -78,7 +78,13 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
         if (st != MBQ_OK) return st;
         return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s, nullptr, nullptr);
       }
-      if (takes_stationary_kernel(T, sh)) return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
+      if (takes_stationary_kernel(T, sh)) {
+        ZeroList zl;
+        decode16_zero_list(T, 1, &sh, &Y, &zl);
+        mbq_status st = launch_zero_outputs(zl, s);  // nothing to do unless the launch splits K
+        if (st != MBQ_OK) return st;
+        return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
+      }
       return launch_linear_decode(X, T, blob, sh, perm, offsets, Y, ws, s);
     default:
       return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s);
@@ -307,8 +313,10 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
       bool all = true;
       for (int i = 0; i < n_proj; ++i) all = all && takes_stationary_kernel(T, sh[i]);
       if (all) {
+        ZeroList zl;  // outputs the linear launch adds into: cleared by a plane of the router launch
+        decode16_zero_list(T, n_proj, sh, Y_host, &zl);
         mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
-                                           nullptr, ws_route, (hipStream_t)stream, nullptr, 0, nullptr, true);
+                                           nullptr, ws_route, (hipStream_t)stream, nullptr, 0, &zl, true);
         if (st != MBQ_OK) return st;
         return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host,
                                             (hipStream_t)stream, perm_host, offsets_host);
@@ -416,7 +424,14 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     // the matrices share one launch of the register-stationary kernel when each of them would take it
     bool all = true;
     for (int i = 0; i < n_proj; ++i) all = all && takes_stationary_kernel(T, sh[i]);
-    if (all) return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host, s, nullptr, nullptr);
+    if (all) {
+      ZeroList zl;
+      decode16_zero_list(T, n_proj, sh, Y_host, &zl);
+      mbq_status st = launch_zero_outputs(zl, s);
+      if (st != MBQ_OK) return st;
+      return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host, s, nullptr,
+                                          nullptr);
+    }
   }
   for (int i = 0; i < n_proj; ++i) {
     mbq_status st =

@@ -93,6 +93,10 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
 // the same for up to MBQ_MAX_GROUP matrices over one X (one K), each with its own routing, in one launch
+// Outputs that launch_linear_decode16(_group) ADDS into for this call (K split of small outputs): the caller clears
+// them first, with launch_zero_outputs or through the router launch.
+void decode16_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);
+mbq_status launch_zero_outputs(const ZeroList& zl, hipStream_t stream);
 // sort_perm / sort_offsets (arrays of n, or null): the tokens are not sorted yet (perm is ignored); the launch sorts
 // them by the precisions itself and writes the order and the bucket offsets there (T <= 64)
 mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,

@@ -129,6 +129,9 @@ struct Proj {
   int32_t* sort_offsets;
   float* Y;
   int wg_begin, wg_count;
+  // 2: the K chunks are dealt to two workgroups per tile set (even / odd workgroup of the matrix take the first /
+  // second half of the chunks) that ADD their results into Y, which the caller has zeroed; 1: one workgroup, stores
+  int ksplit;
 };
 struct Group {
   Proj p[MBQ_MAX_GROUP];
@@ -158,7 +161,9 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
   const int32_t* __restrict__ prec = P.prec;
   const int32_t* __restrict__ perm = P.perm;
   float* __restrict__ Y = P.Y;
-  const int wg = (int)blockIdx.x - P.wg_begin, wgs = P.wg_count;
+  const int halves = MULTI ? P.ksplit : 1;
+  const int wg = ((int)blockIdx.x - P.wg_begin) / halves, wgs = P.wg_count / halves;
+  const int half = ((int)blockIdx.x - P.wg_begin) % halves;
   // blockIdx.y = token tile: rows 16 y .. 16 y + 15 of the token order (of the precision-sorted
   // order `perm` when there are several tiles, so that a tile reads only the slices it needs)
   const int row0 = 16 * TT * (int)blockIdx.y;
@@ -168,7 +173,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps tile addresses scalar
   const int m = lane & 15;   // token row of A / weight row of B / output column
   const int kq = lane >> 4;  // k quarter of a k-step; output rows 4 kq .. 4 kq + 3
-  const int chunks = MULTI ? (KB + WAVES - 1) / WAVES : 1;
+  const int chunks_all = MULTI ? (KB + WAVES - 1) / WAVES : 1;
+  // this workgroup's chunks: all of them, or the first / second half
+  const int chunk_begin = (halves == 2 && half == 1) ? (chunks_all + 1) / 2 : 0;
+  const int chunks = (halves == 2 && half == 0) ? (chunks_all + 1) / 2 : chunks_all;
   const int my_tiles = (NT - wg + wgs - 1) / wgs;
 
   __shared__ float red[2][TT][WAVES][64][4];               // per-wavefront partial tiles, double buffered
@@ -212,7 +220,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
       pl[tt] = e < 0 ? -1 : (e >> 8);
     }
     asm volatile("" ::: "memory");  // the rows are reused below through another type: keep these reads in front
-    if (wg == 0 && blockIdx.y == 0 && wave == 0) {
+    if ((int)blockIdx.x == P.wg_begin && blockIdx.y == 0 && wave == 0) {
       if (p_mine >= 0) P.sort_perm[my_pos] = lane;
       if (lane <= MBQ_N_PRECISIONS) P.sort_offsets[lane] = off_mine;
     }
@@ -298,7 +306,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
     };
     int step_count = 0;
 #pragma unroll 1
-    for (int chunk = 0; chunk < chunks; ++chunk) {
+    for (int chunk = chunk_begin; chunk < chunks; ++chunk) {
       const int kb = chunk * WAVES + wave;
       const bool active = (kb < KB) && my_tiles > 0;
       if (active) {
@@ -393,10 +401,14 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
 #pragma unroll
             for (int wv = 0; wv < WAVES; ++wv) sum += red[buf][tt][wv][16 * (r >> 2) + cc][r & 3];
             if (MULTI) {
-              if (chunk > 0) sum += part[ti][tt][threadIdx.x];
+              if (chunk > chunk_begin) sum += part[ti][tt][threadIdx.x];
               if (chunk + 1 < chunks) part[ti][tt][threadIdx.x] = sum;
             }
-            if (chunk + 1 == chunks && 16 * tt + r < T && col < N) Y[(int64_t)y_token[tt] * N + col] = sum;
+            if (chunk + 1 == chunks && 16 * tt + r < T && col < N) {
+              float* const y = &Y[(int64_t)y_token[tt] * N + col];
+              if (halves == 2) unsafeAtomicAdd(y, sum);  // two addends into a zeroed output: order-independent
+              else *y = sum;
+            }
           }
         }
       };
@@ -435,37 +447,96 @@ static int compute_units() {
   return cached;
 }
 
+namespace d16 {
+// Launch shape of a call (common K): kernel variant, workgroups per token pass and matrix, K split per matrix.
+struct Plan {
+  int waves, tt, token_passes;
+  bool multi;
+  int share[MBQ_MAX_GROUP];   // workgroups per pass (tile sets)
+  int ksplit[MBQ_MAX_GROUP];  // workgroups per tile set along K (1 or 2)
+};
+
+static Plan make_plan(int64_t T, int n, const Shape* shapes) {
+  const Shape& sh = shapes[0];  // K, and with it the kernel variant, is common to the matrices of a call
+  Plan pl;
+  pl.waves = knob(0);
+  // eight wavefronts leave 256 registers each: room for the staged activations and both weight buffers
+  if (pl.waves != 4 && pl.waves != 8 && pl.waves != 16) pl.waves = (sh.KB <= 4) ? 4 : 8;
+  pl.multi = sh.KB > pl.waves;
+  int per_cu = knob(2);
+  if (per_cu <= 0) per_cu = (pl.waves == 4) ? 2 : 1;  // resident workgroups per compute unit at these register counts
+  // two token tiles per workgroup above 32 tokens (eight wavefronts: the second tile's fragments need the
+  // registers): two passes over the weights instead of three or four; measured on cold weights, 14336 x 4096 at 48
+  // tokens 39 us against 57 us, at 64 tokens 39 against 44; up to 32 tokens two one-tile passes side by side are as fast
+  pl.tt = (T > 32 && pl.waves == 8 && knob(7) != 3) ? 2 : 1;
+  pl.token_passes = (int)((T + 16 * pl.tt - 1) / (16 * pl.tt));
+  const int budget = (compute_units() * per_cu + pl.token_passes - 1) / pl.token_passes;  // workgroups per pass
+  // with several K chunks the per-tile partial sums live in LDS: bound the tiles per workgroup
+  const int max_tiles = kMaxTilesMulti / pl.tt;
+  int64_t all_tiles = 0;
+  for (int i = 0; i < n; ++i) all_tiles += shapes[i].NT;
+  for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
+    pl.share[i] = 0;
+    pl.ksplit[i] = 1;
+    if (i >= n) continue;
+    const Shape& s = shapes[i];
+    // the pass's workgroups are dealt to the matrices in proportion to their row tiles
+    int share = (int)(((int64_t)budget * s.NT + all_tiles - 1) / all_tiles);
+    if (share < 1) share = 1;
+    if (share > s.NT) share = s.NT;
+    const int min_share = pl.multi ? (s.NT + max_tiles - 1) / max_tiles : 1;
+    if (share < min_share) share = min_share;
+    // A workgroup pays a prologue per K chunk (the chunk's activations through LDS, group sums: about 4 us);
+    // with few tiles per workgroup that dominates (4096 x 14336 at 64 tokens: seven chunks of two tiles each).
+    // Two workgroups along K with twice the tiles each halve the prologues per tile; they add into an output
+    // that the caller zeroes first, so only small outputs take the split.
+    // The choice looks at the matrix alone (not at its share of a grouped launch), so that a matrix gives the
+    // same bits in a grouped and in a single call.
+    if (pl.multi && s.NT <= 6 * budget && (int64_t)T * s.N * 4 <= (2 << 20)) {
+      pl.ksplit[i] = 2;
+      share = share / 2 > min_share ? share / 2 : min_share;
+    }
+    pl.share[i] = share;
+  }
+  return pl;
+}
+}  // namespace d16
+
+// outputs that the launch below ADDS into: the caller clears them first (zero_outputs, or the router launch)
+void decode16_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl) {
+  const d16::Plan pl = d16::make_plan(T, n, shapes);
+  for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
+    const bool add = i < n && pl.ksplit[i] == 2;
+    zl->p[i] = add ? Y[i] : nullptr;
+    zl->n[i] = add ? (long long)T * shapes[i].N : 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void zero_outputs_kernel(const ZeroList zl) {
+  zero_share(zl, (int)blockIdx.x, (int)gridDim.x, (int)threadIdx.x, 256);
+}
+
+mbq_status launch_zero_outputs(const ZeroList& zl, hipStream_t stream) {
+  bool any = false;
+  for (int i = 0; i < MBQ_MAX_GROUP; ++i) any = any || zl.p[i] != nullptr;
+  if (!any) return MBQ_OK;
+  hipLaunchKernelGGL(zero_outputs_kernel, dim3(128), dim3(256), 0, stream, zl);
+  return hip_status(hipGetLastError(), "zero_outputs_kernel launch");
+}
+
 mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
                                         const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
                                         float* const* Y, hipStream_t stream, int32_t* const* sort_perm,
                                         int32_t* const* sort_offsets) {
-  const Shape& sh = shapes[0];  // K, and with it the kernel variant, is common to the matrices of a call
-  int waves = knob(0);
-  // eight wavefronts leave 256 registers each: room for the staged activations and both weight buffers
-  if (waves != 4 && waves != 8 && waves != 16) waves = (sh.KB <= 4) ? 4 : 8;
-  const bool multi = sh.KB > waves;
-  int per_cu = knob(2);
-  if (per_cu <= 0) per_cu = (waves == 4) ? 2 : 1;  // resident workgroups per compute unit at these register counts
-  // two token tiles per workgroup above 32 tokens (eight wavefronts: the second tile's fragments need the
-  // registers): two passes over the weights instead of three or four; measured on cold weights, 14336 x 4096 at 48
-  // tokens 39 us against 57 us, at 64 tokens 39 against 44; up to 32 tokens two one-tile passes side by side are as fast
-  const int tt = (T > 32 && waves == 8 && knob(7) != 3) ? 2 : 1;
-  const int token_passes = (int)((T + 16 * tt - 1) / (16 * tt));
-  const int budget = (compute_units() * per_cu + token_passes - 1) / token_passes;  // workgroups per pass
-  // with several K chunks the per-tile partial sums live in LDS: bound the tiles per workgroup
-  const int max_tiles = d16::kMaxTilesMulti / tt;
-  int64_t all_tiles = 0;
-  for (int i = 0; i < n; ++i) all_tiles += shapes[i].NT;
+  const Shape& sh = shapes[0];
+  const d16::Plan pl = d16::make_plan(T, n, shapes);
+  const int waves = pl.waves, tt = pl.tt;
+  const bool multi = pl.multi;
   d16::Group g;
   int grid = 0;
   for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
     const int j = i < n ? i : 0;
     const Shape& s = shapes[j];
-    // the pass's workgroups are dealt to the matrices in proportion to their row tiles
-    int share = (int)(((int64_t)budget * s.NT + all_tiles - 1) / all_tiles);
-    if (share < 1) share = 1;
-    if (share > s.NT) share = s.NT;
-    if (multi && (s.NT + share - 1) / share > max_tiles) share = (s.NT + max_tiles - 1) / max_tiles;
     d16::Proj& p = g.p[i];
     p.codes = reinterpret_cast<const uint4*>(blobs[j]);
     p.slice_vec = s.slice_words / 4;
@@ -477,9 +548,10 @@ mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, con
     p.sort_perm = sort_perm ? sort_perm[j] : nullptr;
     p.sort_offsets = sort_perm ? sort_offsets[j] : nullptr;
     p.Y = Y[j];
+    p.ksplit = i < n ? pl.ksplit[i] : 1;
     p.wg_begin = grid;
-    p.wg_count = i < n ? share : 0;
-    if (i < n) grid += share;
+    p.wg_count = i < n ? pl.share[i] * pl.ksplit[i] : 0;
+    if (i < n) grid += pl.share[i] * pl.ksplit[i];
   }
   g.n = n;
 #define MBQ_D16(WV, TTV)                                                                     \

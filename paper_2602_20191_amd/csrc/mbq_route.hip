@@ -383,10 +383,14 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
       g.r[i] = RouteOut{Wr[j], br[j], prec[j], perm[j], offsets[j], logits ? logits[j] : nullptr};
     }
     unsigned long long* words = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(ws) + 64);
+    bool clears = false;  // outputs to clear also without a preparation: the extra plane then only clears
+    if (zl)
+      for (int i = 0; i < kRouteGroupMax; ++i) clears = clears || zl->p[i] != nullptr;
+    const bool plane = prep != nullptr || clears;
     const unsigned gx = (prep && prep_blocks > (int)T) ? (unsigned)prep_blocks : (unsigned)T;
-    hipLaunchKernelGGL(route_small_kernel, dim3(gx, (unsigned)n + (prep ? 1u : 0u)), dim3(512), 0, stream, X, (int)T,
+    hipLaunchKernelGGL(route_small_kernel, dim3(gx, (unsigned)n + (plane ? 1u : 0u)), dim3(512), 0, stream, X, (int)T,
                        K, g, n, words, reinterpret_cast<char*>(prep), prep ? prep_blocks : 0,
-                       (prep && zl) ? *zl : ZeroList{}, defer_bucket ? 1 : 0);
+                       (plane && zl) ? *zl : ZeroList{}, defer_bucket ? 1 : 0);
     return hip_status(hipGetLastError(), "route_small_kernel launch");
   }
   for (int i = 0; i < n; ++i) {
