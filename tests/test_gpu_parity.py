@@ -432,12 +432,14 @@ def test_linear_special_activation_rows(mbq, algo, T):
         assert_output_close(Y[i:i + 1], Yref[i:i + 1], f"special row {i}")
 
 
-def test_stage_call_replays_from_a_hip_graph(mbq):
+@pytest.mark.parametrize("T", [16, 64])
+def test_stage_call_replays_from_a_hip_graph(mbq, T):
     """The stage call captured once and replayed with new activations in the same buffers (eager work and
     synchronisation between the replays): every replay equals the eager call bit for bit.  K = 4096 takes the
-    two-part decode kernel, whose outputs the router launch zeroes with a kernel (not a memset node)."""
-    K, T, Ns = 4096, 16, (272, 130)
-    print("[case] stage call under graph replay", flush=True)
+    two-part kernels at both token counts, whose outputs the router launch zeroes with a kernel (not a memset
+    node); at 64 tokens the linear launch also sorts the tokens."""
+    K, Ns = 4096, (272, 130)
+    print(f"[case] stage call under graph replay T={T}", flush=True)
     rng = np.random.default_rng(47)
     Wrs = [dev((rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32)) for _ in Ns]
     brs = [dev(rng.normal(0, 0.3, size=4).astype(np.float32)) for _ in Ns]
