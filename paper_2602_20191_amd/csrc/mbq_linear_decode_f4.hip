@@ -412,19 +412,34 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
 
       const int sa = (int)(((uint32_t)tok_scale[c] * 0x01010101u) & gate);
       const int sa2 = (int)(((uint32_t)max(tok_scale[c] - kPieceShift, 0) * 0x01010101u) & gate);  // second piece is stored 2^kPieceShift times larger
-      floatx4 D0 = slice_group<0>(xa[c][0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
-      floatx4 D1 = slice_group<0>(xa[c][1], I.w[0].z, I.w[0].w, nib_mask, sa, sa2, sb, zero4);
-      if (pm >= 1) {
+      floatx4 D0, D1;
+      if (pm >= 3) {
+        // all four slices (the usual case at 16 tokens) as one straight run of code: the operands of a slice
+        // are then built while the MFMAs of the slice before occupy the matrix core
+        D0 = slice_group<0>(xa[c][0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
+        D1 = slice_group<0>(xa[c][1], I.w[0].z, I.w[0].w, nib_mask, sa, sa2, sb, zero4);
         D0 = slice_group<1>(xa[c][0], I.w[1].x, I.w[1].y, nib_mask, sa, sa2, sb, D0);
         D1 = slice_group<1>(xa[c][1], I.w[1].z, I.w[1].w, nib_mask, sa, sa2, sb, D1);
-      }
-      if (pm >= 2) {
         D0 = slice_group<2>(xa[c][0], I.w[2].x, I.w[2].y, nib_mask, sa, sa2, sb, D0);
         D1 = slice_group<2>(xa[c][1], I.w[2].z, I.w[2].w, nib_mask, sa, sa2, sb, D1);
-      }
-      if (pm >= 3) {
         D0 = slice_group<3>(xa[c][0], I.w[3].x, I.w[3].y, nib_mask, sa, sa2, sb, D0);
         D1 = slice_group<3>(xa[c][1], I.w[3].z, I.w[3].w, nib_mask, sa, sa2, sb, D1);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {  // scheduling hint: one MFMA, then three vector instructions, sixteen times
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
+      } else {
+        D0 = slice_group<0>(xa[c][0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
+        D1 = slice_group<0>(xa[c][1], I.w[0].z, I.w[0].w, nib_mask, sa, sa2, sb, zero4);
+        if (pm >= 1) {
+          D0 = slice_group<1>(xa[c][0], I.w[1].x, I.w[1].y, nib_mask, sa, sa2, sb, D0);
+          D1 = slice_group<1>(xa[c][1], I.w[1].z, I.w[1].w, nib_mask, sa, sa2, sb, D1);
+        }
+        if (pm >= 2) {
+          D0 = slice_group<2>(xa[c][0], I.w[2].x, I.w[2].y, nib_mask, sa, sa2, sb, D0);
+          D1 = slice_group<2>(xa[c][1], I.w[2].z, I.w[2].w, nib_mask, sa, sa2, sb, D1);
+        }
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
