@@ -478,6 +478,34 @@ def test_stage_call_replays_from_a_hip_graph(mbq, T):
         assert not ws_r.view(torch.int32).any()
 
 
+def test_stage_calls_on_drawn_shapes(mbq):
+    """Stage calls on seeded random shapes (1..4 matrices, 1..64 tokens, K up to 6144, ragged N): routing,
+    permutation and outputs against the oracle.  Covers the launch arithmetic of the grouped kernels (shares of
+    workgroups per matrix, K parts, token passes) beyond the hand-picked shapes above."""
+    rng = np.random.default_rng(2027)
+    for case in range(14):
+        n = int(rng.integers(1, 5))
+        T = int(rng.choice([1, 7, 16, 17, 29, 33, 48, 63, 64]))
+        K = 128 * int(rng.integers(1, 49))
+        Ns = [int(rng.integers(1, 700)) for _ in range(n)]
+        print(f"[case] drawn stage {case}: T={T} K={K} Ns={Ns}", flush=True)
+        xb = tokens(T, K, [2027, case])
+        X = dev_bf16(xb).reshape(T, K)
+        Wrs = [(rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32) for _ in Ns]
+        brs = [rng.normal(0, 0.3, size=4).astype(np.float32) for _ in Ns]
+        Ws = [make_weight(N, K, [53, case, i], 4.0) for i, N in enumerate(Ns)]
+        blobs = [mbq.mbq_encode(dev(W)) for W in Ws]
+        routing, Ys = mbq.mbq_routed_linear_group(X, [dev(w) for w in Wrs], [dev(b) for b in brs], blobs, Ns)
+        torch.cuda.synchronize()
+        for i, N in enumerate(Ns):
+            S, prec_ref, gap = O.route(xb, Wrs[i], brs[i])
+            prec = routing[i][0].cpu().numpy()
+            compare_routing(prec, prec_ref, gap, f"drawn stage {case} router {i}")
+            check_bucket(prec, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
+            codes, s0, z0 = O.encode(Ws[i])
+            assert_output_close(Ys[i].cpu().numpy(), O.linear(xb, codes, s0, z0, prec), f"drawn stage {case} matrix {i}")
+
+
 def test_linear_zero_tokens_and_bad_arguments(mbq):
     N, K = 32, 256
     W = make_weight(N, K, [17], 4.0)
