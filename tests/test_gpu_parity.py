@@ -506,6 +506,23 @@ def test_stage_calls_on_drawn_shapes(mbq):
             assert_output_close(Ys[i].cpu().numpy(), O.linear(xb, codes, s0, z0, prec), f"drawn stage {case} matrix {i}")
 
 
+def test_prefill_on_drawn_shapes(mbq):
+    """mbq_linear above 64 tokens on seeded random shapes, automatic launch choice (including the K split that
+    launches with few tiles take from K = 8192 on): outputs against the oracle."""
+    rng = np.random.default_rng(2029)
+    shapes = [(int(rng.integers(65, 700)), int(rng.integers(1, 600)), 128 * int(rng.integers(1, 40))) for _ in range(6)]
+    shapes += [(130, 272, 8192), (600, 520, 9216), (257, 40, 12288)]
+    for case, (T, N, K) in enumerate(shapes):
+        print(f"[case] drawn prefill {case}: T={T} N={N} K={K}", flush=True)
+        W = make_weight(N, K, [59, case], 4.0)
+        xb = tokens(T, K, [2029, case])
+        prec = rng.choice(4, size=T, p=[0.4, 0.3, 0.2, 0.1]).astype(np.int32)
+        codes, s0, z0 = O.encode(W)
+        Yref = O.linear(xb, codes, s0, z0, prec)
+        Y = run_linear(mbq, W, xb, prec, 0)
+        assert_output_close(Y, Yref, f"drawn prefill {case}")
+
+
 def test_linear_zero_tokens_and_bad_arguments(mbq):
     N, K = 32, 256
     W = make_weight(N, K, [17], 4.0)
