@@ -376,7 +376,7 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
     # (gather/group-sum pre-kernel + tile kernel) timed with HIP events over back-to-back launches
     pcfg = CONFIGS[2]
     T = pcfg.token_counts[0]
-    per_linear, flops_sum, ms_sum = {}, 0.0, 0.0
+    per_linear, flops_sum, ms_sum, route_sum = {}, 0.0, 0.0, 0.0
     for li, spec in enumerate(pcfg.linears):
         case = make_case(pcfg, li, T)
         Wd = torch.from_numpy(case["W"]).to(dev)
@@ -397,17 +397,30 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         b2.record()
         torch.cuda.synchronize()
         ms = a.elapsed_time(b2) / n
+        # the router launch of the same call sequence, alone
+        ws_r = mbq.route_workspace(T, spec.K, dev)
+        for _ in range(3):
+            mbq.mbq_route(X, Wr, br, out=(prec, perm, offsets), ws=ws_r)
+        a.record()
+        for _ in range(n):
+            mbq.mbq_route(X, Wr, br, out=(prec, perm, offsets), ws=ws_r)
+        b2.record()
+        torch.cuda.synchronize()
+        route_ms = a.elapsed_time(b2) / n
         flops = 2.0 * T * spec.N * spec.K
         per_linear[spec.name] = {"N": spec.N, "K": spec.K, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+                                 "route_ms": route_ms, "route_share_of_call": route_ms / (route_ms + ms),
                                  "mix": np.bincount(prec.cpu().numpy(), minlength=4).tolist()}
         flops_sum += flops
         ms_sum += ms
+        route_sum += route_ms
         del blob, X, Y, ws
     tf = flops_sum / (ms_sum * 1e-3) / 1e12
     extra["prefill_mlp_2048tok"] = {
         "workload": "BASELINE configs[2]: gate/up 11008x4096 and down 4096x11008, 2048 tokens, {50,30,15,5}% mix + 2% "
                     "outlier tokens at 8 bits; useful flops 2 T N K over the whole mbq_linear call",
-        "ms_total": ms_sum, "tflops": tf, "per_linear": per_linear,
+        "ms_total": ms_sum, "tflops": tf, "route_ms_total": route_sum,
+        "tflops_route_and_linear": flops_sum / ((ms_sum + route_sum) * 1e-3) / 1e12, "per_linear": per_linear,
         "roofline": {"bound": "mfma", "kernel": "mbq::prefill_kernel (+ mbq::prefill_prep_kernel)", "achieved": tf,
                      "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
     # the paper's 2-layer router (hidden width 64) at the decode batch and at 2048 tokens, K = 4096
