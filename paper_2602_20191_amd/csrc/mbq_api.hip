@@ -58,13 +58,36 @@ static bool takes_stationary_kernel(int64_t T, const Shape& sh) {
   return knob(3) != 1 && (knob(3) == 2 || sh.KB <= 16 || sh.NT >= 128 || (T > 32 && sh.NT >= 32));
 }
 
-// algo is DECODE (T <= 64), PREFILL or SIMPLE here
+// Above the decode limit the register-stationary kernel still beats the prefill kernel for a while: it walks the
+// weights once per 32 sorted tokens, the prefill kernel unpacks them once per bucket into 256-row tiles that are
+// mostly empty at these token counts (measured on 4096 x 4096, 14336 x 4096, 4096 x 14336: 17 / 42 / 48 us at 64
+// tokens against 98 / 102 / 121 us at 65 with the prefill kernel; at 128 tokens 28 / 71 / 83 us against 110 / 111 /
+// 132; at 192 tokens 48 / 114 / 153 against 110 / 111 / 139).  AUTO takes it up to 128 tokens, and up to 192 for
+// matrices of at most 8192 code blocks of 16 x 256.
+constexpr int kMaxStationaryTokens = 128, kMaxStationaryTokensSmall = 192;
+constexpr int64_t kSmallMatrixBlocks = 8192;
+constexpr int kAlgoStationary = 100;  // internal: what AUTO resolves to in that range
+static int resolve_auto(int64_t T, const Shape& sh) {
+  if (T <= kMaxDecodeTokens) return MBQ_ALGO_DECODE;
+  const int limit = (int64_t)sh.NT * sh.KB <= kSmallMatrixBlocks ? kMaxStationaryTokensSmall : kMaxStationaryTokens;
+  if (T <= limit && knob(3) == 0 && takes_stationary_kernel(T, sh)) return kAlgoStationary;
+  return MBQ_ALGO_PREFILL;
+}
+
+// algo is DECODE (T <= 64), PREFILL, SIMPLE or kAlgoStationary here
 mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const Shape& sh, const int32_t* prec,
                            const int32_t* perm, const int32_t* offsets, float* Y, void* ws, int algo,
                            hipStream_t s) {
   switch (algo) {
     case MBQ_ALGO_SIMPLE:
       return launch_linear_simple(X, T, blob, sh, prec, Y, s);
+    case kAlgoStationary: {
+      ZeroList zl;
+      decode16_zero_list(T, 1, &sh, &Y, &zl);
+      mbq_status st = launch_zero_outputs(zl, s);
+      if (st != MBQ_OK) return st;
+      return launch_linear_decode16(X, T, blob, sh, prec, perm, Y, s);
+    }
     case MBQ_ALGO_DECODE:
       // One token tile (T <= 16): the FP4-operand kernels (activation preparation, then the
       // linear kernel).  17..64 tokens run the bf16-operand kernels, one pass per 16
@@ -354,7 +377,7 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
               mbq_linear_workspace_bytes(T, N, K));
     return MBQ_ERR_WORKSPACE;
   }
-  if (algo == MBQ_ALGO_AUTO) algo = (T <= kMaxDecodeTokens) ? MBQ_ALGO_DECODE : MBQ_ALGO_PREFILL;
+  if (algo == MBQ_ALGO_AUTO) algo = resolve_auto(T, sh);
   if (algo == MBQ_ALGO_DECODE && T > kMaxDecodeTokens) {
     set_error("mbq_linear: the decode kernel handles at most %d tokens (T=%lld)", kMaxDecodeTokens,
               (long long)T);
@@ -405,7 +428,13 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     set_error("mbq_linear_group: workspace too small or misaligned (%zu < %zu)", ws_bytes, need);
     return MBQ_ERR_WORKSPACE;
   }
-  if (algo == MBQ_ALGO_AUTO) algo = (T <= kMaxDecodeTokens) ? MBQ_ALGO_DECODE : MBQ_ALGO_PREFILL;
+  int algo_of[MBQ_MAX_GROUP];  // per matrix: AUTO may pick different kernels above the decode limit
+  bool all_stationary = true;
+  for (int i = 0; i < n_proj; ++i) {
+    algo_of[i] = algo == MBQ_ALGO_AUTO ? resolve_auto(T, sh[i]) : algo;
+    all_stationary = all_stationary && algo_of[i] == kAlgoStationary;
+  }
+  if (algo == MBQ_ALGO_AUTO) algo = all_stationary ? kAlgoStationary : (T <= kMaxDecodeTokens ? MBQ_ALGO_DECODE : MBQ_ALGO_PREFILL);
   if (algo == MBQ_ALGO_DECODE && T > kMaxDecodeTokens) {
     set_error("mbq_linear_group: the decode kernel handles at most %d tokens (T=%lld)", kMaxDecodeTokens,
               (long long)T);
@@ -420,7 +449,7 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     if (st != MBQ_OK) return st;
     return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s, nullptr, nullptr);
   }
-  if (algo == MBQ_ALGO_DECODE && n_proj > 1) {
+  if ((algo == MBQ_ALGO_DECODE || algo == kAlgoStationary) && n_proj > 1) {
     // the matrices share one launch of the register-stationary kernel when each of them would take it
     bool all = true;
     for (int i = 0; i < n_proj; ++i) all = all && takes_stationary_kernel(T, sh[i]);
@@ -435,7 +464,7 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
   }
   for (int i = 0; i < n_proj; ++i) {
     mbq_status st =
-        dispatch_linear(X, T, blob_host[i], sh[i], prec_host[i], perm_host[i], offsets_host[i], Y_host[i], ws, algo, s);
+        dispatch_linear(X, T, blob_host[i], sh[i], prec_host[i], perm_host[i], offsets_host[i], Y_host[i], ws, algo_of[i], s);
     if (st != MBQ_OK) return st;
   }
   return MBQ_OK;

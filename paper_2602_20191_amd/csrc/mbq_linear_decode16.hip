@@ -166,9 +166,12 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
   const int half = ((int)blockIdx.x - P.wg_begin) % halves;
   // blockIdx.y = token tile: rows 16 y .. 16 y + 15 of the token order (of the precision-sorted
   // order `perm` when there are several tiles, so that a tile reads only the slices it needs)
-  const int row0 = 16 * TT * (int)blockIdx.y;
+  // the tokens are dealt evenly to the passes (65 tokens: 22 + 22 + 21, not 32 + 32 + 1: a pass costs its slices
+  // whatever its token count)
+  const int per_pass = (T + (int)gridDim.y - 1) / (int)gridDim.y;  // <= 16 TT
+  const int row0 = per_pass * (int)blockIdx.y;
   const int T_all = T;
-  T = min(16 * TT, T - row0);
+  T = min(per_pass, T - row0);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps tile addresses scalar
   const int m = lane & 15;   // token row of A / weight row of B / output column

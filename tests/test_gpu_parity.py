@@ -523,6 +523,33 @@ def test_prefill_on_drawn_shapes(mbq):
         assert_output_close(Y, Yref, f"drawn prefill {case}")
 
 
+@pytest.mark.parametrize("T,K,Ns", [(65, 4096, (130,)), (96, 2304, (48,)), (128, 4096, (272,)), (100, 1024, (40,)),
+                                    (128, 4352, (2064,)), (96, 4096, (272, 130, 16)), (127, 512, (48, 300)),
+                                    (80, 4352, (2064, 16)), (192, 4096, (130, 272)), (161, 2304, (48,))])
+def test_automatic_choice_from_65_to_192_tokens(mbq, T, K, Ns):
+    """Above 64 tokens the automatic choice still takes the register-stationary kernel (one pass per 32 sorted
+    tokens, the tokens dealt evenly to the passes) up to 192 tokens for matrices that suit it, alone or as one launch for a group; the last shape mixes
+    it with the prefill kernel inside one group call.  Against the oracle, and the group against single calls."""
+    print(f"[case] automatic choice T={T} K={K} Ns={Ns}", flush=True)
+    xb = tokens(T, K, [T, K, 61])
+    X = dev_bf16(xb).reshape(T, K)
+    blobs, routing, refs = [], [], []
+    for i, N in enumerate(Ns):
+        W = make_weight(N, K, [61, N, K, i], 4.0)
+        codes, s0, z0 = O.encode(W)
+        prec = np.random.default_rng([T, K, i]).integers(0, 4, size=T).astype(np.int32)
+        perm, offsets = O.bucket(prec)
+        blobs.append(mbq.mbq_encode(dev(W)))
+        routing.append((dev(prec), dev(perm), dev(offsets)))
+        refs.append(O.linear(xb, codes, s0, z0, prec))
+    Ys = mbq.mbq_linear_group(X, blobs, list(Ns), K, routing)
+    torch.cuda.synchronize()
+    for i, N in enumerate(Ns):
+        assert_output_close(Ys[i].cpu().numpy(), refs[i], f"automatic choice matrix {i}")
+        single = mbq.mbq_linear(X, blobs[i], N, K, *routing[i])
+        assert torch.equal(single, Ys[i])
+
+
 def test_linear_zero_tokens_and_bad_arguments(mbq):
     N, K = 32, 256
     W = make_weight(N, K, [17], 4.0)
