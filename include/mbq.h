@@ -55,7 +55,7 @@ typedef enum mbq_status {
 } mbq_status;
 
 /* Which kernel family mbq_linear uses.  AUTO picks by token count and matrix size: the decode kernels up to 64
- * tokens, one of them (one pass over the weights per 32 precision-sorted tokens) on to 128 tokens, 192 for small
+ * tokens, one of them (one pass over the weights per 32 precision-sorted tokens) on to 128 tokens, 512 for small
  * matrices, where it still beats the tiled GEMM, then PREFILL. */
 typedef enum mbq_algo {
   MBQ_ALGO_AUTO = 0,

@@ -60,12 +60,13 @@ static bool takes_stationary_kernel(int64_t T, const Shape& sh) {
 
 // Above the decode limit the register-stationary kernel still beats the prefill kernel for a while: it walks the
 // weights once per 32 sorted tokens, the prefill kernel unpacks them once per bucket into 256-row tiles that are
-// mostly empty at these token counts (measured on 4096 x 4096, 14336 x 4096, 4096 x 14336: 17 / 42 / 48 us at 64
-// tokens against 98 / 102 / 121 us at 65 with the prefill kernel; at 128 tokens 28 / 71 / 83 us against 110 / 111 /
-// 132; at 192 tokens 48 / 114 / 153 against 110 / 111 / 139).  AUTO takes it up to 128 tokens, and up to 192 for
-// matrices of at most 8192 code blocks of 16 x 256.
-constexpr int kMaxStationaryTokens = 128, kMaxStationaryTokensSmall = 192;
-constexpr int64_t kSmallMatrixBlocks = 8192;
+// mostly empty at these token counts.  Measured, stationary / prefill in us per call:
+//   4096 x 4096: 31 / 36 at 65 tokens, 25 / 39 at 128, 49 / 43 at 192;  14336 x 4096: 80 / 98, 68 / 102, 116 / 111;
+//   4096 x 14336: 97 / 96, 82 / 106, 147 / 106;  28672 x 8192: 212 / 351, 237 / 370, 365 / 391;
+//   1024 x 4096: 12 / 29, 12 / 33, 16 / 34, and 25 / 52 at 512 tokens.
+// AUTO takes it up to 128 tokens, and up to 512 for matrices of at most 2048 code blocks of 16 x 256.
+constexpr int kMaxStationaryTokens = 128, kMaxStationaryTokensSmall = 512;
+constexpr int64_t kSmallMatrixBlocks = 2048;
 constexpr int kAlgoStationary = 100;  // internal: what AUTO resolves to in that range
 static int resolve_auto(int64_t T, const Shape& sh) {
   if (T <= kMaxDecodeTokens) return MBQ_ALGO_DECODE;

@@ -787,21 +787,24 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
   const int64_t ldT = prefill_ld(T);
   const int n_tiles_n = (int)((sh.N + kBN - 1) / kBN);
   const int64_t m_tiles_max = T / kBM + MBQ_N_PRECISIONS;
-  // K split: a launch with few tiles leaves compute units idle in its last round; when the K work per
-  // output is large (K >= 8192) the tiles are cut along K into S workgroups that add their partial sums
-  // into a zeroed Y.  S minimises the estimated makespan ceil(tiles S / compute units) / S, each further
-  // part priced at 5 % (its prologue and its atomic adds; measured on 4096 x 11008 and 8192 x 28672).
-  // knob 5 forces the split (1..8).
+  // K split: a launch with few tiles leaves compute units idle in its last round (a tile of K = 4096 holds its
+  // compute unit for about 110 us however few tiles there are), so tiles are cut along K into S workgroups that add
+  // their partial sums into a zeroed Y.  S (1..6) minimises the estimated makespan ceil(tiles S / compute units) / S,
+  // each further part priced at 5 % of a tile of K = 11008 (its prologue, its atomic adds: a fixed cost, so the
+  // price grows as K shrinks; measured on 4096 x 11008, 8192 x 28672, and on 4096 x 4096 .. 8192 x 4096 at 192..512
+  // tokens).  Tile rows: the full ones plus one ragged row per bucket, at least four.  knob 5 forces the split (1..8).
   constexpr int kComputeUnits = 256;
   int splits = 1;
   if (knob(5) >= 1 && knob(5) <= 8) {
     splits = knob(5);
-  } else if (sh.K >= 8192) {
-    const int64_t est_tiles = (T / kBM + 2) * n_tiles_n;
+  } else {
+    const int64_t est_rows = (T / kBM + 2 > 4) ? T / kBM + 2 : 4;
+    const int64_t est_tiles = est_rows * n_tiles_n;
+    const double per_part = 0.05 * 11008.0 / (double)sh.K;
     double best = 0.0;
     for (int s = 1; s <= 6; ++s) {
       const int64_t rounds = (est_tiles * s + kComputeUnits - 1) / kComputeUnits;
-      const double cost = (double)rounds / s * (1.0 + 0.05 * (s - 1));
+      const double cost = (double)rounds / s * (1.0 + per_part * (s - 1));
       if (s == 1 || cost < best) {
         best = cost;
         splits = s;

@@ -525,11 +525,12 @@ def test_prefill_on_drawn_shapes(mbq):
 
 @pytest.mark.parametrize("T,K,Ns", [(65, 4096, (130,)), (96, 2304, (48,)), (128, 4096, (272,)), (100, 1024, (40,)),
                                     (128, 4352, (2064,)), (96, 4096, (272, 130, 16)), (127, 512, (48, 300)),
-                                    (80, 4352, (2064, 16)), (192, 4096, (130, 272)), (161, 2304, (48,))])
-def test_automatic_choice_from_65_to_192_tokens(mbq, T, K, Ns):
+                                    (80, 4352, (2064, 16)), (192, 4096, (130, 272)), (161, 2304, (48,)), (500, 1024, (300,))])
+def test_automatic_choice_above_64_tokens(mbq, T, K, Ns):
     """Above 64 tokens the automatic choice still takes the register-stationary kernel (one pass per 32 sorted
-    tokens, the tokens dealt evenly to the passes) up to 192 tokens for matrices that suit it, alone or as one launch for a group; the last shape mixes
-    it with the prefill kernel inside one group call.  Against the oracle, and the group against single calls."""
+    tokens, the tokens dealt evenly to the passes) up to 128 tokens, 512 for small matrices, alone or as one launch
+    for a group; (80, 4352, (2064, 16)) mixes it with the prefill kernel inside one group call.  Group and single
+    calls against the oracle."""
     print(f"[case] automatic choice T={T} K={K} Ns={Ns}", flush=True)
     xb = tokens(T, K, [T, K, 61])
     X = dev_bf16(xb).reshape(T, K)
@@ -547,7 +548,9 @@ def test_automatic_choice_from_65_to_192_tokens(mbq, T, K, Ns):
     for i, N in enumerate(Ns):
         assert_output_close(Ys[i].cpu().numpy(), refs[i], f"automatic choice matrix {i}")
         single = mbq.mbq_linear(X, blobs[i], N, K, *routing[i])
-        assert torch.equal(single, Ys[i])
+        # (no bit-for-bit claim here: a matrix that goes to the prefill kernel may be cut into more than two parts
+        # along K, whose float atomic adds land in any order)
+        assert_output_close(single.cpu().numpy(), refs[i], f"automatic choice matrix {i}, single call")
 
 
 def test_linear_zero_tokens_and_bad_arguments(mbq):
