@@ -74,9 +74,40 @@ __device__ inline void bucket_by_workgroup(const int32_t* prec, int64_t T,
   }
 }
 
+// Cross-lane moves of a double through the data-parallel-primitive path of the vector ALU (no LDS
+// round trip as for a general shuffle): CTRL is a DPP control word, here a permutation inside each
+// group of four lanes (quad_perm) or a rotation inside each row of 16 lanes (row_ror).
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  const long long b = __builtin_bit_cast(long long, v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(b & 0xFFFFFFFFll), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
+  return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
+}
+constexpr int kDppQuadXor1 = 0xB1, kDppQuadXor2 = 0x4E;  // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kDppRowRor4 = 0x124, kDppRowRor8 = 0x128;
+
+// Sums four per-lane values over the wavefront.  The first two exchanges halve the number of values a
+// lane carries (lanes 1 apart split the four between them, then lanes 2 apart), so that seven moves of
+// a double do the work of twenty-four; afterwards lane l holds the total of value wave_sum4_index(l).
+__device__ __forceinline__ int wave_sum4_index(int lane) { return 2 * (lane & 1) + ((lane >> 1) & 1); }
+__device__ __forceinline__ double wave_sum4(const double (&acc)[4], int lane) {
+  const bool odd = (lane & 1) != 0, upper = (lane & 2) != 0;
+  double keep0 = odd ? acc[2] : acc[0], keep1 = odd ? acc[3] : acc[1];
+  keep0 += dpp_move<kDppQuadXor1>(odd ? acc[0] : acc[2]);
+  keep1 += dpp_move<kDppQuadXor1>(odd ? acc[1] : acc[3]);
+  double v = upper ? keep1 : keep0;
+  v += dpp_move<kDppQuadXor2>(upper ? keep0 : keep1);
+  v += dpp_move<kDppRowRor4>(v);
+  v += dpp_move<kDppRowRor8>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
 // One workgroup of 256 threads scores TPW consecutive tokens (Sec. 4.2 Eq. 4).  The K axis
 // is split over the threads in chunks of 8 columns; each thread keeps 4 x TPW fp64 partial
-// sums (bf16 x fp32 products are exact in fp64), reduced over the wavefront with shuffles and
+// sums (bf16 x fp32 products are exact in fp64), reduced over the wavefront (wave_sum4) and
 // over the four wavefronts through LDS.  The workgroup that finishes last (a ticket counter in
 // the workspace, left at zero again) then buckets all tokens, so routing is one launch.
 template <int TPW>
@@ -119,14 +150,10 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   __shared__ unsigned int s_ticket;
   const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
-  for (int t = 0; t < TPW; ++t)
-#pragma unroll
-    for (int q = 0; q < kP; ++q) {
-      double v = acc[t][q];
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
-      if (lane == 0) red[wave][t][q] = v;
-    }
+  for (int t = 0; t < TPW; ++t) {
+    const double v = wave_sum4(acc[t], lane);
+    if (lane < kP) red[wave][t][wave_sum4_index(lane)] = v;
+  }
   __syncthreads();
   if (tid < TPW && tok0 + tid < T) {
     double best = 0.0;
@@ -151,37 +178,6 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   __threadfence();
   bucket_by_workgroup<4>(prec, T, perm, offsets);
   if (tid == 0) *ticket = 0u;  // leave the counter ready for the next call
-}
-
-// Cross-lane moves of a double through the data-parallel-primitive path of the vector ALU (no LDS
-// round trip as for a general shuffle): CTRL is a DPP control word, here a permutation inside each
-// group of four lanes (quad_perm) or a rotation inside each row of 16 lanes (row_ror).
-template <int CTRL>
-__device__ __forceinline__ double dpp_move(double v) {
-  const long long b = __builtin_bit_cast(long long, v);
-  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(b & 0xFFFFFFFFll), CTRL, 0xF, 0xF, false);
-  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
-  return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
-}
-constexpr int kDppQuadXor1 = 0xB1, kDppQuadXor2 = 0x4E;  // quad_perm [1,0,3,2], [2,3,0,1]
-constexpr int kDppRowRor4 = 0x124, kDppRowRor8 = 0x128;
-
-// Sums four per-lane values over the wavefront.  The first two exchanges halve the number of values a
-// lane carries (lanes 1 apart split the four between them, then lanes 2 apart), so that seven moves of
-// a double do the work of twenty-four; afterwards lane l holds the total of value wave_sum4_index(l).
-__device__ __forceinline__ int wave_sum4_index(int lane) { return 2 * (lane & 1) + ((lane >> 1) & 1); }
-__device__ __forceinline__ double wave_sum4(const double (&acc)[4], int lane) {
-  const bool odd = (lane & 1) != 0, upper = (lane & 2) != 0;
-  double keep0 = odd ? acc[2] : acc[0], keep1 = odd ? acc[3] : acc[1];
-  keep0 += dpp_move<kDppQuadXor1>(odd ? acc[0] : acc[2]);
-  keep1 += dpp_move<kDppQuadXor1>(odd ? acc[1] : acc[3]);
-  double v = upper ? keep1 : keep0;
-  v += dpp_move<kDppQuadXor2>(upper ? keep0 : keep1);
-  v += dpp_move<kDppRowRor4>(v);
-  v += dpp_move<kDppRowRor8>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
 }
 
 // Small batches (T <= 64; the packed meeting word below up to kSmallRouteTokens), one or several routers over the same activations
