@@ -69,21 +69,38 @@ static bool takes_stationary_kernel(int64_t T, const Shape& sh) {
 // AUTO takes it up to 128 tokens, and up to 512 for matrices of at most 2048 code blocks of 16 x 256.
 constexpr int kMaxStationaryTokens = 128, kMaxStationaryTokensSmall = 512;
 constexpr int64_t kSmallMatrixBlocks = 2048;
-constexpr int kAlgoStationary = 100;  // internal: what AUTO resolves to in that range
+// From there to 256 tokens the better kernel depends on the precision mix (see mix_prefers_stationary): both are
+// launched and the device decides.
+constexpr int kMaxByMixTokens = 256;
+constexpr int kAlgoStationary = 100;  // internal: what AUTO resolves to in those ranges
+constexpr int kAlgoByMix = 101;
 static int resolve_auto(int64_t T, const Shape& sh) {
   if (T <= kMaxDecodeTokens) return MBQ_ALGO_DECODE;
   const int limit = (int64_t)sh.NT * sh.KB <= kSmallMatrixBlocks ? kMaxStationaryTokensSmall : kMaxStationaryTokens;
-  if (T <= limit && knob(3) == 0 && takes_stationary_kernel(T, sh)) return kAlgoStationary;
+  const bool can = knob(3) == 0 && takes_stationary_kernel(T, sh);
+  if (T <= limit && can) return kAlgoStationary;
+  // (up to 32 column blocks: with more, the stationary kernel's per-chunk prologues cost it the advantage - 8192 x
+  // 28672 at 256 tokens on the skewed mix 0.49 ms against 0.48)
+  if (T <= kMaxByMixTokens && can && sh.KB <= 32) return kAlgoByMix;
   return MBQ_ALGO_PREFILL;
 }
 
-// algo is DECODE (T <= 64), PREFILL, SIMPLE or kAlgoStationary here
+// algo is DECODE (T <= 64), PREFILL, SIMPLE, kAlgoStationary or kAlgoByMix here
 mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const Shape& sh, const int32_t* prec,
                            const int32_t* perm, const int32_t* offsets, float* Y, void* ws, int algo,
                            hipStream_t s) {
   switch (algo) {
     case MBQ_ALGO_SIMPLE:
       return launch_linear_simple(X, T, blob, sh, prec, Y, s);
+    case kAlgoByMix: {
+      ZeroList zl;
+      decode16_zero_list(T, 1, &sh, &Y, &zl);
+      mbq_status st = launch_zero_outputs(zl, s);
+      if (st != MBQ_OK) return st;
+      st = launch_linear_decode16_group(X, T, 1, &blob, &sh, &prec, &perm, &Y, s, nullptr, nullptr, &offsets);
+      if (st != MBQ_OK) return st;
+      return launch_linear_prefill(X, T, blob, sh, perm, offsets, Y, ws, s, true);
+    }
     case kAlgoStationary: {
       ZeroList zl;
       decode16_zero_list(T, 1, &sh, &Y, &zl);

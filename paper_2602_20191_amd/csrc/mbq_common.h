@@ -89,7 +89,7 @@ mbq_status launch_linear_decode(const uint16_t* X, int64_t T, const void* blob, 
                                 hipStream_t stream);
 mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                  const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
-                                 hipStream_t stream);
+                                 hipStream_t stream, bool mix_gate = false);
 mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                   const int32_t* prec, const int32_t* perm, float* Y, hipStream_t stream);
 // the same for up to MBQ_MAX_GROUP matrices over one X (one K), each with its own routing, in one launch
@@ -102,11 +102,27 @@ mbq_status launch_zero_outputs(const ZeroList& zl, hipStream_t stream);
 mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
                                         const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
                                         float* const* Y, hipStream_t stream, int32_t* const* sort_perm,
-                                        int32_t* const* sort_offsets);
+                                        int32_t* const* sort_offsets, const int32_t* const* gate_offsets = nullptr);
 bool decode_f4_supports(int64_t T, const Shape& sh);
 int decode_f4_k_parts(const Shape& sh);
 void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);
 // share `part` of `parts` of the clearing, done by `nthreads` threads of which this is `tid`
+// Between 129 and 256 tokens the better of the register-stationary kernel and the prefill kernel depends on the
+// precision mix, which only the device knows; both are launched and each asks this question about the bucket
+// offsets first, the one that is not wanted returns at once.  The stationary kernel walks the sorted tokens in
+// passes of at most 32 and reads slices 0..p of the pass's last token: it is taken when that is two slices per pass
+// or fewer on average (measured on the 70B-shaped linears at 256 tokens: {70,20,8,2}% mix 0.38 ms against 0.46 for
+// the prefill kernel, uniform mix 0.44 against 0.41).
+__device__ inline bool mix_prefers_stationary(const int32_t* __restrict__ offsets, int T) {
+  const int o1 = offsets[1], o2 = offsets[2], o3 = offsets[3];
+  const int passes = (T + 31) / 32, per_pass = (T + passes - 1) / passes;
+  int slices = 0;
+  for (int y = 0; y < passes; ++y) {
+    const int last = min(T, per_pass * (y + 1)) - 1;
+    slices += 1 + (last >= o1) + (last >= o2) + (last >= o3);
+  }
+  return slices <= 2 * passes;
+}
 // A 16-byte load of data that a launch reads once (packed weights in the decode kernels), with the
 // non-temporal hint: the stream then does not push the activations, router parameters and outputs that
 // the neighbouring launches share out of the caches.

@@ -127,6 +127,7 @@ struct Proj {
   // first workgroup writes perm and offsets out for the caller.
   int32_t* sort_perm;
   int32_t* sort_offsets;
+  const int32_t* gate_offsets;  // non-null: run only if mix_prefers_stationary says so (the prefill launch follows)
   float* Y;
   int wg_begin, wg_count;
   // 2: the K chunks are dealt to two workgroups per tile set (even / odd workgroup of the matrix take the first /
@@ -161,6 +162,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
   const int32_t* __restrict__ prec = P.prec;
   const int32_t* __restrict__ perm = P.perm;
   float* __restrict__ Y = P.Y;
+  if (P.gate_offsets != nullptr && !mix_prefers_stationary(P.gate_offsets, T)) return;
   const int halves = MULTI ? P.ksplit : 1;
   const int wg = ((int)blockIdx.x - P.wg_begin) / halves, wgs = P.wg_count / halves;
   const int half = ((int)blockIdx.x - P.wg_begin) % halves;
@@ -530,7 +532,7 @@ mbq_status launch_zero_outputs(const ZeroList& zl, hipStream_t stream) {
 mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
                                         const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
                                         float* const* Y, hipStream_t stream, int32_t* const* sort_perm,
-                                        int32_t* const* sort_offsets) {
+                                        int32_t* const* sort_offsets, const int32_t* const* gate_offsets) {
   const Shape& sh = shapes[0];
   const d16::Plan pl = d16::make_plan(T, n, shapes);
   const int waves = pl.waves, tt = pl.tt;
@@ -550,6 +552,7 @@ mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, con
     p.perm = (T > 16 && !sort_perm) ? perm[j] : nullptr;
     p.sort_perm = sort_perm ? sort_perm[j] : nullptr;
     p.sort_offsets = sort_perm ? sort_offsets[j] : nullptr;
+    p.gate_offsets = gate_offsets ? gate_offsets[j] : nullptr;
     p.Y = Y[j];
     p.ksplit = i < n ? pl.ksplit[i] : 1;
     p.wg_begin = grid;

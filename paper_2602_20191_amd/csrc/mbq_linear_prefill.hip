@@ -66,7 +66,10 @@ __host__ __device__ constexpr uint32_t rotl_c(uint32_t m, int r) {
 __global__ __launch_bounds__(256) void prefill_prep_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
                                                            const int32_t* __restrict__ perm,
                                                            uint16_t* __restrict__ Xs, float* __restrict__ SxT,
-                                                           int64_t ldT, float* __restrict__ Yzero, int64_t N) {
+                                                           int64_t ldT, float* __restrict__ Yzero, int64_t N,
+                                                           const int32_t* __restrict__ gate_offsets) {
+  // gate_offsets != null: the register-stationary kernel was launched first and has done the work if the mix suits it
+  if (gate_offsets != nullptr && mix_prefers_stationary(gate_offsets, (int)T)) return;
   const int64_t r = blockIdx.x;
   if (Yzero)
     for (int64_t n = threadIdx.x; n < N; n += 256) Yzero[r * N + n] = 0.f;
@@ -698,8 +701,10 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const uint16_t* __restr
                                                          const int32_t* __restrict__ perm,
                                                          const int32_t* __restrict__ offsets,
                                                          const float* __restrict__ SxT, int64_t ldT,
-                                                         float* __restrict__ Y, int n_tiles_n, int splits) {
+                                                         float* __restrict__ Y, int n_tiles_n, int splits,
+                                                         int mix_gate) {
   __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
+  if (mix_gate && mix_prefers_stationary(offsets, offsets[MBQ_N_PRECISIONS])) return;  // see prefill_prep_kernel
   // ---- which tile: full tiles of every bucket first, then the ragged last tile of each bucket ----
   // (tile row, tile column, K split): workgroups of one tile row are neighbours (they share activations)
   const int per_mt = n_tiles_n * splits;
@@ -778,7 +783,7 @@ size_t prefill_workspace_bytes(int64_t T, const Shape& sh) {
 
 mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                  const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
-                                 hipStream_t stream) {
+                                 hipStream_t stream, bool mix_gate) {
   const uint32_t* codes = reinterpret_cast<const uint32_t*>(blob);
   const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
   uint16_t* Xs = reinterpret_cast<uint16_t*>(ws);
@@ -813,12 +818,12 @@ mbq_status launch_linear_prefill(const uint16_t* X, int64_t T, const void* blob,
   }
   while (splits > 1 && sh.G / splits < 4) --splits;
   hipLaunchKernelGGL(prefill_prep_kernel, dim3((unsigned)T), dim3(256), 0, stream, X, T, sh.K, perm, Xs, SxT, ldT,
-                     splits > 1 ? Y : nullptr, sh.N);
+                     splits > 1 ? Y : nullptr, sh.N, mix_gate ? offsets : nullptr);
   mbq_status st = hip_status(hipGetLastError(), "prefill_prep_kernel launch");
   if (st != MBQ_OK) return st;
   hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)(m_tiles_max * n_tiles_n * splits)), dim3(512), 0, stream, Xs,
                      sh.K, codes, sh.slice_words, meta, sh.N, sh.NT, sh.KB, perm, offsets, SxT, ldT, Y, n_tiles_n,
-                     splits);
+                     splits, mix_gate ? 1 : 0);
   return hip_status(hipGetLastError(), "prefill_kernel launch");
 }
 

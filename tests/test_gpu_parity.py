@@ -553,6 +553,23 @@ def test_automatic_choice_above_64_tokens(mbq, T, K, Ns):
         assert_output_close(single.cpu().numpy(), refs[i], f"automatic choice matrix {i}, single call")
 
 
+@pytest.mark.parametrize("T", [129, 200, 256])
+@pytest.mark.parametrize("mix", [(0.8, 0.15, 0.05, 0.0), (0.25, 0.25, 0.25, 0.25), (0.0, 0.0, 0.1, 0.9)])
+def test_choice_by_precision_mix_from_129_to_256_tokens(mbq, T, mix):
+    """129..256 tokens on a matrix that is not small: the stationary kernel and the prefill kernel are both
+    launched and the device lets one of them work, by the slices the sorted passes would read; a skewed mix
+    takes the first, a uniform or high-precision mix the second.  Either way against the oracle."""
+    N, K = 2064, 4352
+    print(f"[case] choice by mix T={T} mix={mix}", flush=True)
+    W = make_weight(N, K, [67, T], 4.0)
+    xb = tokens(T, K, [67, T, 1])
+    prec = np.random.default_rng([67, T]).choice(4, size=T, p=mix).astype(np.int32)
+    codes, s0, z0 = O.encode(W)
+    Yref = O.linear(xb, codes, s0, z0, prec)
+    Y = run_linear(mbq, W, xb, prec, 0)
+    assert_output_close(Y, Yref, f"choice by mix T={T} mix={mix}")
+
+
 def test_linear_zero_tokens_and_bad_arguments(mbq):
     N, K = 32, 256
     W = make_weight(N, K, [17], 4.0)
