@@ -56,7 +56,8 @@ typedef enum mbq_status {
 
 /* Which kernel family mbq_linear uses.  AUTO picks by token count and matrix size: the decode kernels up to 64
  * tokens, one of them (one pass over the weights per 32 precision-sorted tokens) on to 128 tokens, 512 for small
- * matrices, where it still beats the tiled GEMM, then PREFILL. */
+ * matrices, where it still beats the tiled GEMM; from there to 256 tokens (K <= 8192) both are enqueued and the one
+ * that suits the precision mix, which only the device knows, does the work; then PREFILL. */
 typedef enum mbq_algo {
   MBQ_ALGO_AUTO = 0,
   MBQ_ALGO_SIMPLE = 1, /* one thread per output, fp64 accumulate: slow checker path   */
