@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   if (tid == 0) *ticket = 0u;  // leave the counter ready for the next call
 }
 
-// Small batches (T <= 64; the packed meeting word below up to kSmallRouteTokens), one or several routers over the same activations
+// Small batches (T <= 128; the packed meeting word below up to kSmallRouteTokens), one or several routers over the same activations
 // (the projections of a decoder block that share their input, Sec. 4.3, fused router launch).
 // blockIdx.x = token, blockIdx.y = router.  512 threads split the K axis in chunks of 8 columns,
 // two chunks in flight per thread.  Workgroups meet through ONE 64-bit atomic add per token: the
@@ -294,18 +294,22 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
     arrived = __shfl(arrived, 0, 64);
     if ((int)arrived != T) return;
     __threadfence();
+    // stable counting sort of up to 128 tokens by one wavefront: lane holds tokens lane and lane + 64
     const int p = (lane < T) ? __hip_atomic_load(out.prec + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
+    const int p2 = (lane + 64 < T) ? __hip_atomic_load(out.prec + lane + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
     const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int start = 0, my_pos = 0;
+    int start = 0, my_pos = 0, my_pos2 = 0;
 #pragma unroll
     for (int q = 0; q < kP; ++q) {
-      const uint64_t b = __ballot(p == q);
+      const uint64_t b = __ballot(p == q), b2 = __ballot(p2 == q);
       if (p == q) my_pos = start + __popcll(b & below);
+      if (p2 == q) my_pos2 = start + __popcll(b) + __popcll(b2 & below);
       if (lane == q) out.offsets[q] = start;
-      start += __popcll(b);
+      start += __popcll(b) + __popcll(b2);
     }
     if (lane == kP) out.offsets[kP] = start;
     if (p >= 0) out.perm[my_pos] = lane;
+    if (p2 >= 0) out.perm[my_pos2] = lane + 64;
     if (lane == 0) words[blockIdx.y] = 0ull;
     return;
   }
@@ -359,10 +363,11 @@ static mbq_status launch_route_one(const uint16_t* X, int64_t T, int64_t K, cons
 // Workspace: the ticket counter of the general kernels at byte 0, the per-router words of the
 // small-batch kernel from byte 64.
 bool route_can_carry_prep(int64_t T) { return T >= 1 && T <= kSmallRouteTokens && knob(4) != 1; }
-// one launch for all routers of a call: up to one wavefront of tokens
-static bool route_small_supports(int64_t T) { return T >= 1 && T <= 64 && knob(4) != 1; }
-// the one-launch kernel can leave the token sort to the consumer of the precisions (defer_bucket below)
-bool route_defers_sort(int64_t T) { return route_small_supports(T); }
+// one launch for all routers of a call: up to two tokens per lane of the sorting wavefront
+static bool route_small_supports(int64_t T) { return T >= 1 && T <= 128 && knob(4) != 1; }
+// the one-launch kernel can leave the token sort to the consumer of the precisions (defer_bucket below), which
+// sorts up to 64 tokens
+bool route_defers_sort(int64_t T) { return route_small_supports(T) && T <= 64; }
 
 // prep != nullptr (only when route_can_carry_prep(T)): the launch also prepares the activations
 // of the FP4-operand decode kernel, prep_blocks 256-column blocks, into prep.

@@ -72,7 +72,7 @@ def test_encode_with_external_parameters(mbq, N, K, keep):
 
 # ------------------------------------------------------------------------------ route
 @pytest.mark.parametrize("T,K", [(0, 256), (1, 128), (5, 384), (16, 4096), (16, 11008), (28, 8192), (29, 8320),
-                                 (32, 2048), (64, 4096), (65, 1024), (1023, 256), (1024, 256), (1025, 256),
+                                 (32, 2048), (64, 4096), (65, 1024), (100, 2304), (128, 4096), (129, 512), (1023, 256), (1024, 256), (1025, 256),
                                  (4100, 512)])
 def test_route_and_bucket_are_bit_exact(mbq, T, K):
     print(f"[case] route T={T} K={K}", flush=True)
@@ -160,7 +160,7 @@ def test_route_mlp_target_bits_and_linear(mbq):
         assert_output_close(Y.cpu().numpy(), O.linear(xb, codes, s0, z0, prec.cpu().numpy()), f"mlp-routed linear algo={algo}")
 
 
-@pytest.mark.parametrize("T,K,n", [(1, 4096, 3), (16, 4096, 3), (28, 1280, 4), (16, 11008, 1), (40, 512, 2),
+@pytest.mark.parametrize("T,K,n", [(1, 4096, 3), (16, 4096, 3), (28, 1280, 4), (16, 11008, 1), (40, 512, 2), (97, 4096, 2), (128, 1024, 3), (130, 512, 2),
                                    (0, 256, 2)])
 def test_route_group_equals_separate_calls(mbq, T, K, n):
     """Several routers over one X: against the oracle, and bit for bit against mbq_route; called
