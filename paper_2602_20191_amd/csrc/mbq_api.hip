@@ -350,11 +350,14 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
       return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream,
                                      perm_host, offsets_host);
     }
-    // up to 64 tokens with every matrix on the register-stationary kernel: the router launch only writes the
+    // up to 128 tokens with every matrix on the register-stationary kernel: the router launch only writes the
     // precisions (no meeting of its workgroups), the linear launch sorts the tokens itself
-    if (ok && T <= kMaxDecodeTokens && route_defers_sort(T)) {
+    const int64_t defer_limit = (algo == MBQ_ALGO_AUTO) ? kMaxStationaryTokens : kMaxDecodeTokens;
+    if (ok && T <= defer_limit && route_defers_sort(T)) {
       bool all = true;
-      for (int i = 0; i < n_proj; ++i) all = all && takes_stationary_kernel(T, sh[i]);
+      for (int i = 0; i < n_proj; ++i)
+        all = all && (T <= kMaxDecodeTokens ? takes_stationary_kernel(T, sh[i])
+                                            : resolve_auto(T, sh[i]) == kAlgoStationary);
       if (all) {
         ZeroList zl;  // outputs the linear launch adds into: cleared by a plane of the router launch
         decode16_zero_list(T, n_proj, sh, Y_host, &zl);

@@ -122,7 +122,7 @@ struct Proj {
   int NT;
   const int32_t* prec;
   const int32_t* perm;   // precision-sorted token order (read), or null: original order (one tile) / sorted here
-  // sort_perm != null (T <= 64): the tokens have not been sorted yet.  Every wavefront derives the order from
+  // sort_perm != null (T <= 128): the tokens have not been sorted yet.  Every wavefront derives the order from
   // the precisions itself (one load and a few ballots instead of two dependent loads), and the matrix's
   // first workgroup writes perm and offsets out for the caller.
   int32_t* sort_perm;
@@ -202,21 +202,25 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
     pl[tt] = (my_token[tt] >= 0 && P.sort_perm == nullptr) ? prec[my_token[tt]] : -1;
   }
   if (P.sort_perm != nullptr) {
-    // stable counting sort of all T_all <= 64 tokens by precision (Sec. 4.3, token permutation): lane = token
+    // stable counting sort of all T_all <= 128 tokens by precision (Sec. 4.3, token permutation): a lane holds
+    // tokens lane and lane + 64
     const int p_mine = lane < T_all ? min(max(prec[lane], 0), MBQ_N_PRECISIONS - 1) : -1;
+    const int p_two = lane + 64 < T_all ? min(max(prec[lane + 64], 0), MBQ_N_PRECISIONS - 1) : -1;
     const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int start = 0, my_pos = 0, off_mine = 0;
+    int start = 0, my_pos = 0, my_pos_two = 0, off_mine = 0;
 #pragma unroll
     for (int q = 0; q < MBQ_N_PRECISIONS; ++q) {
-      const uint64_t b = __ballot(p_mine == q);
+      const uint64_t b = __ballot(p_mine == q), b2 = __ballot(p_two == q);
       if (p_mine == q) my_pos = start + __popcll(b & below);
+      if (p_two == q) my_pos_two = start + __popcll(b) + __popcll(b2 & below);
       if (lane == q) off_mine = start;
-      start += __popcll(b);
+      start += __popcll(b) + __popcll(b2);
     }
     if (lane == MBQ_N_PRECISIONS) off_mine = start;
     // position -> (token, precision) through the wavefront's own LDS rows (in order within a wavefront)
     int* const order = reinterpret_cast<int*>(stage);
     if (p_mine >= 0) order[my_pos] = lane | (p_mine << 8);
+    if (p_two >= 0) order[my_pos_two] = (lane + 64) | (p_two << 8);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       const int r = 16 * tt + lane;
@@ -227,6 +231,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode16_kernel(const uint16_t* __
     asm volatile("" ::: "memory");  // the rows are reused below through another type: keep these reads in front
     if ((int)blockIdx.x == P.wg_begin && blockIdx.y == 0 && wave == 0) {
       if (p_mine >= 0) P.sort_perm[my_pos] = lane;
+      if (p_two >= 0) P.sort_perm[my_pos_two] = lane + 64;
       if (lane <= MBQ_N_PRECISIONS) P.sort_offsets[lane] = off_mine;
     }
   }

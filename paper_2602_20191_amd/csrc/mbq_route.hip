@@ -366,8 +366,8 @@ bool route_can_carry_prep(int64_t T) { return T >= 1 && T <= kSmallRouteTokens &
 // one launch for all routers of a call: up to two tokens per lane of the sorting wavefront
 static bool route_small_supports(int64_t T) { return T >= 1 && T <= 128 && knob(4) != 1; }
 // the one-launch kernel can leave the token sort to the consumer of the precisions (defer_bucket below), which
-// sorts up to 64 tokens
-bool route_defers_sort(int64_t T) { return route_small_supports(T) && T <= 64; }
+// sorts up to 128 tokens
+bool route_defers_sort(int64_t T) { return route_small_supports(T); }
 
 // prep != nullptr (only when route_can_carry_prep(T)): the launch also prepares the activations
 // of the FP4-operand decode kernel, prep_blocks 256-column blocks, into prep.

@@ -369,6 +369,8 @@ def test_linear_group_equals_separate_calls(mbq, K, T, Ns):
                                     # 29..64 tokens: the linear launch sorts the tokens; last shape: one matrix takes
                                     # another kernel, so the stage falls back to the two calls
                                     (4096, 64, (1040, 130)), (2304, 33, (272, 48, 16)), (512, 17, (40,)), (4352, 48, (2064, 16)),
+                                    # 65..128 tokens under the automatic choice: the same path, two tokens per sorting lane
+                                    (4096, 65, (272, 130)), (2304, 128, (1040, 48, 16)), (1024, 100, (40, 300)),
                                     # many row tiles: the whole chip takes part, K in one part, two parts and streamed
                                     (1024, 5, (1024, 528)), (4096, 16, (1040, 512, 512)), (9216, 3, (1600,)), (2304, 16, (640, 130))])
 def test_routed_linear_stage_equals_route_then_linear(mbq, K, T, Ns):
