@@ -58,10 +58,12 @@ def main() -> int:
                          "at once); the remainder of --steps runs from one-step graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the batch-1/4 and prefill side measurements")
-    ap.add_argument("--probe", choices=["decode", "prefill"], default=None,
+    ap.add_argument("--probe", choices=["decode", "prefill", "timeline"], default=None,
                     help="counter probe for rocprofv3 --pmc, nothing is timed.  decode: a plain 256 MiB device copy "
                          "(known size, calibrates the counters) then a few mbq_linear launches per linear of the "
-                         "block.  prefill: three mbq_linear launches of the BASELINE configs[2] gate linear")
+                         "block.  prefill: three mbq_linear launches of the BASELINE configs[2] gate linear.  "
+                         "timeline: where the time of the one-token-tile decode kernel goes, from the clock stamps of "
+                         "the library's timeline build of that kernel (prints a table per stage)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -127,6 +129,9 @@ def main() -> int:
             ws_r=mbq.route_workspace(T, K, dev), ws_l=mbq.linear_workspace(T, max(l["spec"].N for l in ls), K, dev)))
     print(f"[bench] inputs ready in {time.time() - t0:.1f}s "
           f"({sum(l['blobs'][0].numel() for l in layers) * RING / 1e6:.0f} MB of packed weights)", file=sys.stderr)
+
+    if args.probe == "timeline":
+        return timeline_probe(mbq, torch, dev, stages, T)
 
     if args.probe == "decode":
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -222,14 +227,13 @@ def main() -> int:
 
     # ------------------------------------- dominant kernel: per-launch duration (HIP events)
     # The linear kernel of every stage alone (activations already prepared in the workspace by the
-    # stage call above; knob 6 = 1 makes mbq_linear_group launch only that kernel), 24 launches per
+    # stage call above; mbq_bench_linear_group_prepared launches only that kernel), 24 launches per
     # HIP-graph replay over the rotating weight copies, timed with events on the launch stream.
     # Each stage rotates over enough copies of its own weights (>= 640 MB together) that no launch finds
     # them in the 256 MB last-level cache, as in the whole-step loop above.
     per_graph = 24
     kernel_us, kernel_bytes = [], []
-    mbq.set_knob(6, 1)
-    try:
+    if True:
         for st in stages:
             stage_mb = sum(l["blobs"][0].numel() for l in st["layers"]) / 1e6
             copies = max(RING, int(np.ceil(640.0 / stage_mb)))
@@ -237,8 +241,8 @@ def main() -> int:
             n_launch = max(per_graph, copies)
             def burst():
                 for i in range(n_launch):
-                    mbq.mbq_linear_group(st["X"], [pool[i % copies] for pool in pools], st["Ns"], st["K"],
-                                         st["routing"], Y=st["Y"], ws=st["ws_l"])
+                    mbq.bench_linear_group_prepared(T, st["K"], [pool[i % copies] for pool in pools], st["Ns"],
+                                                    st["routing"], st["Y"], st["ws_l"])
             burst()
             torch.cuda.synchronize()
             g = None
@@ -263,8 +267,6 @@ def main() -> int:
             kernel_bytes.append(sum(algorithmic_bytes(l["spec"].N, l["spec"].K, T, pm) - 2 * T * l["spec"].K
                                     for l, pm in zip(st["layers"], [pmaxes[layers.index(l)] for l in st["layers"]]))
                                 + 2 * T * st["K"])
-    finally:
-        mbq.set_knob(6, 0)
     avg_launch_us = float(np.mean(kernel_us))
     avg_launch_bytes = float(np.mean(kernel_bytes))
     achieved = avg_launch_bytes / (avg_launch_us * 1e-6) / 1e9
@@ -310,6 +312,59 @@ def main() -> int:
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layers, T)
     print(json.dumps(out))
+    return 0
+
+
+def timeline_probe(mbq, torch, dev, stages, T, dump_dir="gpurun_out"):
+    """Per stage (ring kernel only, K <= 8192): the stage call once (prepares the activations), the last-level cache
+    flushed by a 1 GiB fill, then the timeline build of the linear kernel on cold weights; repeated `reps` times.
+    Times are microseconds after the first wavefront of the launch entered the kernel (100 MHz clock: 0.01 us
+    steps), given as min / median / max over all wavefronts of the launch."""
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    reps = 5
+    names = ["entry", "precisions here", "first block requested", "activations + first block here"]
+    for st in stages:
+        if st["K"] > 8192:
+            continue
+        runs = []
+        for rep in range(reps):
+            blobs = [l["blobs"][rep % RING] for l in st["layers"]]
+            mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], blobs, st["Ns"], routing=st["routing"],
+                                        Y=st["Y"], ws_route=st["ws_r"], ws_linear=st["ws_l"])
+            flush.fill_(rep)
+            torch.cuda.synchronize()
+            stamps = mbq.bench_decode_timeline(T, st["K"], blobs, st["Ns"], st["routing"], st["Y"], st["ws_l"])
+            torch.cuda.synchronize()
+            runs.append(stamps.cpu().numpy())
+        a = runs[-1].astype(np.int64)                       # [workgroups, 8, 32]
+        live = a[:, :, 0] > 0
+        t0 = a[:, :, 0][live].min()
+        us = lambda x: (x - t0) / 100.0
+        tiles = int(((a[:, 0, 4:30:2] > 0).sum(axis=1)).max())
+        print(f"stage {'+'.join(st['names'])}: N {st['Ns']} K {st['K']} T {T}; {int(live[:, 0].sum())} workgroups, "
+              f"up to {tiles} tiles each")
+        spans = [(r[:, :, 30][r[:, :, 0] > 0].max() - r[:, :, 0][r[:, :, 0] > 0].min()) / 100.0 for r in runs]
+        print("  first entry -> last end, us, per repetition: " + " ".join(f"{x:.2f}" for x in spans))
+
+        def row(label, v):
+            v = v[v > 0]
+            if v.size:
+                print(f"  {label:<34s} {us(v.min()):7.2f} {us(np.median(v)):7.2f} {us(v.max()):7.2f}")
+        print(f"  {'phase (us after first entry)':<34s} {'min':>7s} {'median':>7s} {'max':>7s}")
+        for k, nm in enumerate(names):
+            row(nm, a[:, :, k][live])
+        for i in range(tiles):
+            row(f"tile {i}: MFMAs done", a[:, :, 4 + 2 * i][live])
+            row(f"tile {i}: outputs stored", a[:, :, 5 + 2 * i][live])
+        row("end", a[:, :, 30][live])
+        # per XCD: when its workgroups start and end
+        xcc = (a[:, 0, 31] >> 32) & 0xF
+        for x in sorted(set(xcc[live[:, 0]].tolist())):
+            sel = live[:, 0] & (xcc == x)
+            print(f"  XCD {x}: {int(sel.sum()):3d} workgroups, entry {us(a[sel, 0, 0].min()):.2f}..{us(a[sel, 0, 0].max()):.2f}"
+                  f", end {us(a[sel][:, :, 30].min()):.2f}..{us(a[sel][:, :, 30].max()):.2f}")
+        if dump_dir and os.path.isdir(dump_dir):
+            np.save(os.path.join(dump_dir, f"timeline_{'_'.join(st['names'])}_T{T}.npy"), np.stack(runs))
     return 0
 
 

@@ -12,9 +12,12 @@
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name ends in _host.
  *   - The caller owns every buffer.  The library allocates nothing, keeps no state
- *     between calls (apart from the tuning knobs below) and never synchronises:
- *     all work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
- *     default stream).  Outputs are valid once the stream reaches that point.
+ *     between calls and never synchronises: all work is enqueued on `stream` (a
+ *     hipStream_t passed as void*; NULL is the default stream).  Outputs are valid
+ *     once the stream reaches that point.  What a call launches depends on its
+ *     arguments alone (the test hooks of mbq_bench.h aside, which default to off);
+ *     calls may be made from several threads at once as long as they do not share a
+ *     workspace.
  *   - Every entry point returns an mbq_status.  On failure nothing has been
  *     enqueued and mbq_last_error() describes the cause (thread-local string).
  *   - bf16 values are passed as uint16_t bit patterns.
@@ -240,21 +243,6 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
                                    int32_t* const* offsets_host, float* const* Y_host, void* ws_route,
                                    size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
                                    int algo, void* stream);
-
-/*
- * Launch-shape knobs for experiments (process-global, not thread-safe; 0 = default).
- *   knob 0: waves per workgroup of the decode kernel (4, 8 or 16)
- *   knob 1: K-split (workgroups along K) of the multi-tile decode kernel, 0 = automatic
- *   knob 2: workgroups per compute unit of the single-tile decode kernel, 0 = automatic
- *   knob 5: K split of the prefill kernel (1..8 workgroups per tile, partial sums added into Y), 0 = automatic
- *   knob 3: decode kernel choice: 0 automatic, 1 multi-tile kernel, 2 single-matrix stationary kernel
- *   knob 4: 1 = route small batches with the general kernel too
- *   knob 7: 1 = the one-token-tile decode kernel works on the whole K axis per workgroup where it fits (no two-part split);
- *           3 = the 17..64-token kernel takes one token tile per workgroup
- *   knob 6: 1 = mbq_linear_group skips the activation preparation launch (the workspace must hold
- *           the result of an earlier call on the same X): for timing the linear kernel alone
- */
-mbq_status mbq_set_knob(int knob, int value);
 
 #ifdef __cplusplus
 }

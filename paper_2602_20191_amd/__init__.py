@@ -25,6 +25,9 @@ EXPORTS = (
     "mbq_linear_workspace_bytes", "mbq_encode", "mbq_encode_with_params", "mbq_unpack", "mbq_dequant", "mbq_route",
     "mbq_route_group", "mbq_linear", "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob",
     "mbq_route_mlp", "mbq_route_mlp_workspace_bytes", "mbq_threshold_quantile",
+    # include/mbq_bench.h: measurement and diagnostic entry points
+    "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop", "mbq_bench_linear_group_prepared",
+    "mbq_bench_decode_timeline", "mbq_bench_decode_timeline_bytes", "mbq_bench_decode_timeline_workgroups",
 )
 
 _lib = None
@@ -67,8 +70,19 @@ def load() -> ctypes.CDLL:
     lib.mbq_routed_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_p,
                                             c_p, c_sz, c_p, c_sz, c_int, c_p]
     lib.mbq_set_knob.argtypes = [c_int, c_int]
+    lib.mbq_bench_copy.argtypes = [c_p, c_p, c_sz, c_int, c_p]
+    lib.mbq_bench_read.argtypes = [c_p, c_sz, c_int, c_p, c_p]
+    lib.mbq_bench_mfma_loop.argtypes = [c_int, c_int, c_p, ctypes.POINTER(ctypes.c_double), c_p]
+    lib.mbq_bench_linear_group_prepared.argtypes = [c_i64, c_i64, c_int, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
+    lib.mbq_bench_decode_timeline.argtypes = [c_i64, c_i64, c_int, c_p, c_p, c_p, c_p, c_p, c_sz, c_p, c_sz, c_p]
+    lib.mbq_bench_decode_timeline_bytes.restype = c_sz
+    lib.mbq_bench_decode_timeline_bytes.argtypes = []
+    lib.mbq_bench_decode_timeline_workgroups.restype = c_int
+    lib.mbq_bench_decode_timeline_workgroups.argtypes = []
     for name in ("mbq_encode", "mbq_encode_with_params", "mbq_unpack", "mbq_dequant", "mbq_route", "mbq_route_group", "mbq_linear",
-                 "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob"):
+                 "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob", "mbq_route_mlp",
+                 "mbq_threshold_quantile", "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop",
+                 "mbq_bench_linear_group_prepared", "mbq_bench_decode_timeline"):
         getattr(lib, name).restype = c_int
     _lib = lib
     return lib
@@ -311,3 +325,51 @@ def mbq_routed_linear_group(X: torch.Tensor, Wr: Sequence[torch.Tensor], br: Seq
         _ptr_array([r[2] for r in routing]), _ptr_array(Y), _ptr(ws_route), ws_route.numel(), _ptr(ws_linear),
         ws_linear.numel(), algo, _stream()), "mbq_routed_linear_group")
     return [tuple(r) for r in routing], list(Y)
+
+
+# ---- measurement and diagnostic entry points (include/mbq_bench.h) ----------------------------------
+
+def bench_copy(src: torch.Tensor, dst: torch.Tensor, width: int = 1) -> None:
+    """dst = src by the library's plain streaming copy kernel (uint8 tensors of equal size)."""
+    assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    _check(load().mbq_bench_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), width, _stream()),
+           "mbq_bench_copy")
+
+
+def bench_read(src: torch.Tensor, sink: torch.Tensor, width: int = 1, nbytes: Optional[int] = None) -> None:
+    n = src.numel() * src.element_size() if nbytes is None else nbytes
+    _check(load().mbq_bench_read(_ptr(src), n, width, _ptr(sink), _stream()), "mbq_bench_read")
+
+
+def bench_mfma_loop(steps: int, with_barrier: bool, sink: torch.Tensor) -> float:
+    """Enqueues the LDS-fed MFMA loop; returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(load().mbq_bench_mfma_loop(steps, 1 if with_barrier else 0, _ptr(sink), ctypes.byref(flops), _stream()),
+           "mbq_bench_mfma_loop")
+    return flops.value
+
+
+def bench_linear_group_prepared(T: int, K: int, blobs: Sequence[torch.Tensor], Ns: Sequence[int],
+                                routing: Sequence[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]],
+                                Y: Sequence[torch.Tensor], ws: torch.Tensor) -> None:
+    """The T <= 16 linear kernel alone on a workspace prepared by an earlier call (timing only)."""
+    n_arr = (ctypes.c_int64 * len(Ns))(*[int(N) for N in Ns])
+    _check(load().mbq_bench_linear_group_prepared(T, K, len(Ns), _ptr_array(blobs), n_arr,
+                                                  _ptr_array([r[0] for r in routing]), _ptr_array(Y), _ptr(ws),
+                                                  ws.numel(), _stream()), "mbq_bench_linear_group_prepared")
+
+
+def bench_decode_timeline(T: int, K: int, blobs: Sequence[torch.Tensor], Ns: Sequence[int],
+                          routing: Sequence[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]],
+                          Y: Sequence[torch.Tensor], ws: torch.Tensor) -> torch.Tensor:
+    """The same launch from the timeline build; -> int64 tensor [workgroups, 8 wavefronts, 32 slots] of 100 MHz
+    clock stamps (layout in include/mbq_bench.h)."""
+    lib = load()
+    wgs = lib.mbq_bench_decode_timeline_workgroups()
+    nbytes = lib.mbq_bench_decode_timeline_bytes()
+    stamps = torch.zeros(nbytes // 8, dtype=torch.int64, device=ws.device)
+    n_arr = (ctypes.c_int64 * len(Ns))(*[int(N) for N in Ns])
+    _check(lib.mbq_bench_decode_timeline(T, K, len(Ns), _ptr_array(blobs), n_arr,
+                                         _ptr_array([r[0] for r in routing]), _ptr_array(Y), _ptr(ws), ws.numel(),
+                                         _ptr(stamps), nbytes, _stream()), "mbq_bench_decode_timeline")
+    return stamps.view(wgs, 8, -1)

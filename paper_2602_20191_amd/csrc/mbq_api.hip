@@ -2,12 +2,25 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <atomic>
+
+#include "mbq_bench.h"
 #include "mbq_common.h"
 
 namespace mbq {
 
 static thread_local char g_error[512] = "";
-static int g_knobs[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+// Test and experiment hooks (mbq_set_knob).  A call takes one snapshot of them when it enters the library and
+// dispatches on that snapshot only, so a change made by another thread never splits one call's decisions.
+constexpr int kKnobs = 8;
+static std::atomic<int> g_knobs[kKnobs];
+static thread_local int t_knobs[kKnobs] = {0, 0, 0, 0, 0, 0, 0, 0};
+static thread_local int t_depth = 0;
+ApiScope::ApiScope() {
+  if (t_depth++ == 0)
+    for (int i = 0; i < kKnobs; ++i) t_knobs[i] = g_knobs[i].load(std::memory_order_relaxed);
+}
+ApiScope::~ApiScope() { --t_depth; }
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -22,7 +35,7 @@ mbq_status hip_status(hipError_t e, const char* what) {
   return MBQ_ERR_HIP;
 }
 
-int knob(int index) { return (index >= 0 && index < 8) ? g_knobs[index] : 0; }
+int knob(int index) { return (index >= 0 && index < kKnobs) ? t_knobs[index] : 0; }
 
 bool make_shape(int64_t N, int64_t K, Shape* out) {
   if (N <= 0 || K <= 0) {
@@ -156,6 +169,7 @@ size_t mbq_route_workspace_bytes(int64_t T, int64_t K) {
 }
 
 size_t mbq_linear_workspace_bytes(int64_t T, int64_t N, int64_t K) {
+  ApiScope scope;
   Shape sh;
   if (T < 0 || !make_shape(N, K, &sh)) return 0;
   size_t a = decode_workspace_bytes(T, sh);
@@ -167,11 +181,11 @@ size_t mbq_linear_workspace_bytes(int64_t T, int64_t N, int64_t K) {
 }
 
 mbq_status mbq_set_knob(int k, int value) {
-  if (k < 0 || k >= 8) {
+  if (k < 0 || k >= kKnobs || k == 6) {
     set_error("unknown knob %d", k);
     return MBQ_ERR_INVALID_ARG;
   }
-  g_knobs[k] = value;
+  g_knobs[k].store(value, std::memory_order_relaxed);
   return MBQ_OK;
 }
 
@@ -220,6 +234,7 @@ mbq_status mbq_dequant(const void* blob, int64_t N, int64_t K, int p, float* Wha
 mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br, int P,
                      int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
                      size_t ws_bytes, void* stream) {
+  ApiScope scope;
   if (P != MBQ_N_PRECISIONS) {
     set_error("mbq_route: P=%d, only %d precisions are supported", P, MBQ_N_PRECISIONS);
     return MBQ_ERR_BAD_SHAPE;
@@ -243,6 +258,7 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
                            const float* const* br_host, int P, int32_t* const* prec_host,
                            int32_t* const* perm_host, int32_t* const* offsets_host, void* ws, size_t ws_bytes,
                            void* stream) {
+  ApiScope scope;
   if (P != MBQ_N_PRECISIONS) {
     set_error("mbq_route_group: P=%d, only %d precisions are supported", P, MBQ_N_PRECISIONS);
     return MBQ_ERR_BAD_SHAPE;
@@ -329,6 +345,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
                                    int32_t* const* perm_host, int32_t* const* offsets_host, float* const* Y_host,
                                    void* ws_route, size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
                                    int algo, void* stream) {
+  ApiScope scope;
   // the fused form: the router launch also prepares the activations of the decode kernel
   if (algo == MBQ_ALGO_AUTO || algo == MBQ_ALGO_DECODE) {
     Shape sh[MBQ_MAX_GROUP];
@@ -380,6 +397,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
 mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
                       const int32_t* prec, const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
                       size_t ws_bytes, int algo, void* stream) {
+  ApiScope scope;
   Shape sh;
   if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
   if (T < 0 || T > (int64_t)1 << 24) {
@@ -413,6 +431,7 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
                             const int64_t* N_host, const int32_t* const* prec_host,
                             const int32_t* const* perm_host, const int32_t* const* offsets_host,
                             float* const* Y_host, void* ws, size_t ws_bytes, int algo, void* stream) {
+  ApiScope scope;
   if (n_proj < 1 || n_proj > MBQ_MAX_GROUP) {
     set_error("mbq_linear_group: n_proj=%d outside 1..%d", n_proj, MBQ_MAX_GROUP);
     return MBQ_ERR_INVALID_ARG;
@@ -465,10 +484,9 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
   }
   hipStream_t s = (hipStream_t)stream;
   if (algo == MBQ_ALGO_DECODE && knob(3) == 0 && decode_f4_supports(T, sh[0])) {
-    // knob 6 = 1 (measurement only): the workspace already holds the prepared activations
     ZeroList zl;
     decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
-    mbq_status st = knob(6) == 1 ? MBQ_OK : launch_decode_f4_prep(X, T, K, sh[0].KB, ws, zl, s);
+    mbq_status st = launch_decode_f4_prep(X, T, K, sh[0].KB, ws, zl, s);
     if (st != MBQ_OK) return st;
     return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws, s, nullptr, nullptr);
   }

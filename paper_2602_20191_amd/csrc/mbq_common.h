@@ -30,7 +30,13 @@ struct Shape {
 bool make_shape(int64_t N, int64_t K, Shape* out);  // false (and error set) if invalid
 void set_error(const char* fmt, ...);
 mbq_status hip_status(hipError_t e, const char* what);
-int knob(int index);
+int knob(int index);  // the calling thread's snapshot of the hooks, taken by the outermost ApiScope
+// Every entry point that dispatches opens one; the outermost on a thread snapshots the test/experiment hooks, so
+// all decisions of one call (also of the calls it makes in turn) see the same values.
+struct ApiScope {
+  ApiScope();
+  ~ApiScope();
+};
 
 // ---- blob addressing (device + host) -------------------------------------------
 // Word index, inside one slice, of the dword holding weight (n, k).
@@ -146,7 +152,10 @@ mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB
 // perm/offsets (arrays of n, or null): the launch also sorts the tokens of every matrix by precision
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
                                    const int32_t* const* prec, float* const* Y, const void* ws, hipStream_t stream,
-                                   int32_t* const* perm, int32_t* const* offsets);
+                                   int32_t* const* perm, int32_t* const* offsets, unsigned long long* stamps = nullptr);
+// timeline build of the ring kernel: workgroups it launches at most, and 8-byte slots each of them writes
+int decode_f4_timeline_workgroups();
+int decode_f4_timeline_slots();
 size_t decode_workspace_bytes(int64_t T, const Shape& sh);
 size_t prefill_workspace_bytes(int64_t T, const Shape& sh);
 

@@ -57,6 +57,7 @@ struct Group {
   Proj p[MBQ_MAX_GROUP];
   int n;
   int tiles;
+  unsigned long long* stamps;  // timeline build of the kernel only (see decode_f4_ring_kernel): where the stamps go
 };
 
 template <int R>
@@ -194,11 +195,34 @@ static_assert(kPieces == 2, "slice_group picks the scale of a piece by piece == 
 static_assert(kRingDepth == 4 && kLoadsPerItem == 5, "ring_wait's constants are (kRingDepth - 1 .. 0) * kLoadsPerItem");
 }  // namespace f4
 
-template <int CPW, int S>
+// kStamp: the timeline build.  Lane 0 of every wavefront notes the 100 MHz wall clock at the phase boundaries in LDS
+// and the workgroup copies the notes to g.stamps when it is done: slot 0 entry, 1 precisions here, 2 first item
+// requested, 3 activations and first item here, 4 + 2 i tile i's MFMAs done, 5 + 2 i tile i's outputs stored,
+// kStampSlots - 2 end, kStampSlots - 1 the hardware id word (which XCD / compute unit ran the workgroup).
+namespace f4 {
+constexpr int kStampSlots = 32;
+}
+template <int CPW, int S, bool kStamp = false>
 __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restrict__ prep, int T, int KB,
                                                              const f4::Group g) {
   using namespace f4;
   constexpr int kWaves = 8;
+  __shared__ unsigned long long s_stamp[kStamp ? kWaves * kStampSlots : 1];
+  const uint32_t stamp_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)&s_stamp[0] +
+                              (uint32_t)(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) * kStampSlots * 8);
+  auto stamp = [&](int slot) {
+    if constexpr (kStamp) {
+      if (slot < kStampSlots - 2 && (threadIdx.x & 63) == 0) {
+        const unsigned long long now = __builtin_amdgcn_s_memrealtime();
+        asm volatile("ds_write_b64 %0, %1" ::"v"(stamp_addr + (uint32_t)slot * 8u), "v"(now) : "memory");
+      }
+    }
+  };
+  if constexpr (kStamp) {
+    for (int i = threadIdx.x; i < kWaves * kStampSlots; i += 512) s_stamp[i] = 0ull;
+    __syncthreads();
+  }
+  stamp(0);
   constexpr int kXaLoads = 2 * kPieces * 2 + 2 + 1;  // loads of one block's prepared activations
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -329,10 +353,13 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
 #pragma unroll
   for (int c = 0; c < CPW; ++c) load_activations(c);
   loads_arrived<CPW * kXaLoads>(pl[0], pl[1], pl[2], pl[3]);
+  stamp(1);
   find_pmax();
   for (int q = 0; q < CPW; ++q) request_routed(q);
   int next_request = CPW;
+  stamp(2);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the activations (and the first tile) have arrived
+  stamp(3);
   intx8 xa[CPW][2][kPieces];
 #pragma unroll
   for (int c = 0; c < CPW; ++c) {
@@ -449,6 +476,10 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
     }
     // sum the wavefronts' partial tiles; rows leave in token order
     const int buf = ti & 1;
+    if constexpr (kStamp) {
+      asm volatile("" ::"v"(acc[0]), "v"(acc[1]), "v"(acc[2]), "v"(acc[3]));
+      stamp(4 + 2 * ti);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) red[buf][rot][lane][i] = acc[i];  // filed by block, so the sum below does not depend on the rotation
     lds_barrier();
@@ -463,6 +494,18 @@ __global__ __launch_bounds__(512) void decode_f4_ring_kernel(const char* __restr
         else unsafeAtomicAdd(&Yj[(int64_t)r * Nj + col], sum);
       }
     }
+    stamp(5 + 2 * ti);
+  }
+  if constexpr (kStamp) {
+    if (lane == 0) {
+      s_stamp[wave * kStampSlots + kStampSlots - 2] = __builtin_amdgcn_s_memrealtime();
+      s_stamp[wave * kStampSlots + kStampSlots - 1] =
+          ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11)) << 32) |  // XCC_ID
+          (unsigned long long)__builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));             // HW_ID
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kWaves * kStampSlots; i += 512)
+      g.stamps[(size_t)blockIdx.x * (kWaves * kStampSlots) + i] = s_stamp[i];
   }
 }
 #undef MBQ_PICK
@@ -655,6 +698,8 @@ static int f4_compute_units() {
 }
 
 bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16; }
+int decode_f4_timeline_workgroups() { return f4_compute_units(); }
+int decode_f4_timeline_slots() { return 8 * f4::kStampSlots; }
 // Blocks per part, in units of 8: up to two blocks per wavefront (K <= 8192 in two parts); beyond
 // that the streaming kernel, which keeps nothing resident, is the faster one.
 static int f4_max_parts_blocks() { return 2; }
@@ -695,7 +740,7 @@ mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB
 // All matrices share K (the caller has checked); T <= 16; ws holds the prepared activations.
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
                                    const int32_t* const* prec, float* const* Y, const void* ws, hipStream_t stream,
-                                   int32_t* const* perm, int32_t* const* offsets) {
+                                   int32_t* const* perm, int32_t* const* offsets, unsigned long long* stamps) {
   f4::Group g;
   int tiles = 0;
   for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
@@ -715,10 +760,15 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
   }
   g.n = n;
   g.tiles = tiles;
+  g.stamps = stamps;
   const Shape& s0 = shapes[0];
   int grid = f4_compute_units();
   const char* prep = reinterpret_cast<const char*>(ws);
   if (s0.KB > 16 * f4_max_parts_blocks()) {
+    if (stamps) {
+      set_error("the timeline build exists for the ring kernel only (K <= 8192)");
+      return MBQ_ERR_BAD_SHAPE;
+    }
     if (grid > tiles) grid = tiles;
     hipLaunchKernelGGL(decode_f4_stream_kernel, dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g);
   } else {
@@ -726,11 +776,18 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
     grid = grid / S * S;
     if (grid > tiles * S) grid = tiles * S;
     const int cpw = (s0.KB + 8 * S - 1) / (8 * S);
-#define MBQ_RING(C, P) hipLaunchKernelGGL((decode_f4_ring_kernel<C, P>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g)
-    if (S == 1 && cpw == 1) MBQ_RING(1, 1);
-    else if (S == 1) MBQ_RING(2, 1);
-    else if (cpw == 1) MBQ_RING(1, 2);
-    else MBQ_RING(2, 2);
+#define MBQ_RING(C, P, ST) hipLaunchKernelGGL((decode_f4_ring_kernel<C, P, ST>), dim3(grid), dim3(512), 0, stream, prep, (int)T, s0.KB, g)
+    if (stamps) {
+      if (S == 1 && cpw == 1) MBQ_RING(1, 1, true);
+      else if (S == 1) MBQ_RING(2, 1, true);
+      else if (cpw == 1) MBQ_RING(1, 2, true);
+      else MBQ_RING(2, 2, true);
+    } else {
+      if (S == 1 && cpw == 1) MBQ_RING(1, 1, false);
+      else if (S == 1) MBQ_RING(2, 1, false);
+      else if (cpw == 1) MBQ_RING(1, 2, false);
+      else MBQ_RING(2, 2, false);
+    }
 #undef MBQ_RING
   }
   return hip_status(hipGetLastError(), "decode_f4_kernel launch");
