@@ -336,14 +336,15 @@ def timeline_probe(mbq, torch, dev, stages, T, dump_dir="gpurun_out"):
             stamps = mbq.bench_decode_timeline(T, st["K"], blobs, st["Ns"], st["routing"], st["Y"], st["ws_l"])
             torch.cuda.synchronize()
             runs.append(stamps.cpu().numpy())
-        a = runs[-1].astype(np.int64)                       # [workgroups, 8, 32]
+        full = runs[-1].astype(np.int64)                    # [workgroups, 9 wavefronts, 32]: 8 arithmetic + the loader
+        a, ld = full[:, :8, :], full[:, 8, :]
         live = a[:, :, 0] > 0
         t0 = a[:, :, 0][live].min()
         us = lambda x: (x - t0) / 100.0
         tiles = int(((a[:, 0, 4:30:2] > 0).sum(axis=1)).max())
         print(f"stage {'+'.join(st['names'])}: N {st['Ns']} K {st['K']} T {T}; {int(live[:, 0].sum())} workgroups, "
               f"up to {tiles} tiles each")
-        spans = [(r[:, :, 30][r[:, :, 0] > 0].max() - r[:, :, 0][r[:, :, 0] > 0].min()) / 100.0 for r in runs]
+        spans = [(r[:, :8, 30][r[:, :8, 0] > 0].max() - r[:, :, 0][r[:, :, 0] > 0].min()) / 100.0 for r in runs]
         print("  first entry -> last end, us, per repetition: " + " ".join(f"{x:.2f}" for x in spans))
 
         def row(label, v):
@@ -357,6 +358,12 @@ def timeline_probe(mbq, torch, dev, stages, T, dump_dir="gpurun_out"):
             row(f"tile {i}: MFMAs done", a[:, :, 4 + 2 * i][live])
             row(f"tile {i}: outputs stored", a[:, :, 5 + 2 * i][live])
         row("end", a[:, :, 30][live])
+        ldl = ld[:, 0] > 0
+        row("loader: precisions here", ld[:, 1][ldl])
+        row("loader: first block issued", ld[:, 2][ldl])
+        for i in (0, 1, 3, 7, 11, 15, 19, 23, 25):
+            row(f"loader: block {i} published", ld[:, 4 + i][ldl])
+        row("loader: end", ld[:, 30][ldl])
         # per XCD: when its workgroups start and end
         xcc = (a[:, 0, 31] >> 32) & 0xF
         for x in sorted(set(xcc[live[:, 0]].tolist())):

@@ -56,11 +56,14 @@ mbq_status mbq_bench_linear_group_prepared(int64_t T, int64_t K, int n_proj, con
 /*
  * mbq_bench_decode_timeline - the same launch (T <= 16, K <= 8192) from a build of the kernel
  * that notes the 100 MHz wall clock at its phase boundaries.  stamps receives, per workgroup b
- * (b < mbq_bench_decode_timeline_workgroups()) and wavefront w (w < 8), 32 words at
- * stamps[(8 b + w) 32 ...]:
- *   0 kernel entry, 1 precisions arrived, 2 first weight block requested, 3 activations and first
- *   block arrived, 4 + 2 i MFMAs of the workgroup's i-th tile done, 5 + 2 i its outputs stored
- *   (i < 13), 30 end, 31 hardware id (XCC_ID << 32 | HW_ID).  Unused words are zero.
+ * (b < mbq_bench_decode_timeline_workgroups()) and wavefront w (w < 9: eight arithmetic wavefronts,
+ * then the loader), 32 words at stamps[(9 b + w) 32 ...]:
+ *   arithmetic wavefronts: 0 kernel entry, 1 precisions and activations arrived, 4 + 2 i MFMAs of the
+ *   workgroup's i-th tile done, 5 + 2 i its partial tile filed (and, by the wavefront that came last,
+ *   the outputs stored) (i < 13), 30 end, 31 hardware id (XCC_ID << 32 | HW_ID);
+ *   loader: 0 entry, 1 precisions arrived, 2 first weight block issued, 4 + i block i published to
+ *   the arithmetic wavefronts (i < 26), 30 end, 31 hardware id.  Unused words are zero; the caller
+ *   clears the buffer (workgroups that the launch does not need write nothing).
  * stamps_bytes >= mbq_bench_decode_timeline_bytes().
  */
 size_t mbq_bench_decode_timeline_bytes(void);

@@ -362,7 +362,7 @@ def bench_linear_group_prepared(T: int, K: int, blobs: Sequence[torch.Tensor], N
 def bench_decode_timeline(T: int, K: int, blobs: Sequence[torch.Tensor], Ns: Sequence[int],
                           routing: Sequence[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]],
                           Y: Sequence[torch.Tensor], ws: torch.Tensor) -> torch.Tensor:
-    """The same launch from the timeline build; -> int64 tensor [workgroups, 8 wavefronts, 32 slots] of 100 MHz
+    """The same launch from the timeline build; -> int64 tensor [workgroups, wavefronts, 32 slots] of 100 MHz
     clock stamps (layout in include/mbq_bench.h)."""
     lib = load()
     wgs = lib.mbq_bench_decode_timeline_workgroups()
@@ -372,4 +372,4 @@ def bench_decode_timeline(T: int, K: int, blobs: Sequence[torch.Tensor], Ns: Seq
     _check(lib.mbq_bench_decode_timeline(T, K, len(Ns), _ptr_array(blobs), n_arr,
                                          _ptr_array([r[0] for r in routing]), _ptr_array(Y), _ptr(ws), ws.numel(),
                                          _ptr(stamps), nbytes, _stream()), "mbq_bench_decode_timeline")
-    return stamps.view(wgs, 8, -1)
+    return stamps.view(wgs, -1, 32)

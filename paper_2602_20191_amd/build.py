@@ -22,6 +22,7 @@ SOURCES = [
     ("mbq_linear_decode.hip", []),
     ("mbq_linear_decode16.hip", []),
     ("mbq_linear_decode_f4.hip", []),
+    ("mbq_linear_decode_f4_ws.hip", []),
     ("mbq_linear_prefill.hip", []),
     ("mbq_bench.hip", []),
 ]
