@@ -210,6 +210,24 @@ mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N,
                       void* ws, size_t ws_bytes, int algo, void* stream);
 
 /*
+ * mbq_linear_static - mbq_linear without a workspace argument, for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the workspace is a buffer of
+ * MBQ_STATIC_SCRATCH_BYTES that is part of the library image on every GPU (it costs that much device memory per
+ * GPU the library runs on, until the process ends).  The call allocates nothing and frees nothing.
+ *   - Same arguments, results and errors as mbq_linear otherwise; the kernels are the same.
+ *   - Shapes whose mbq_linear_workspace_bytes(T, N, K) exceeds the buffer are refused with MBQ_ERR_WORKSPACE
+ *     (nothing is enqueued); mbq_static_scratch_bytes() returns the size.
+ *   - All calls on one GPU share the one buffer (its contents are whatever the last call left; nothing in it has to
+ *     start at zero): two calls on the same GPU whose execution overlaps (different streams, different threads)
+ *     race.  Calls on one stream are ordered and safe.
+ */
+#define MBQ_STATIC_SCRATCH_BYTES (8u << 20)
+size_t mbq_static_scratch_bytes(void);
+mbq_status mbq_linear_static(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
+                             const int32_t* prec, const int32_t* perm, const int32_t* offsets, float* Y,
+                             int algo, void* stream);
+
+/*
  * mbq_linear_group - mbq_linear for n_proj weight matrices with the same K that read the SAME
  * activations (q/k/v, gate/up of a decoder block), each with its own routing; one launch and
  * one pass over X when T <= 16 and K <= 4096 (Sec. 4.3, fused launch for the projections of a

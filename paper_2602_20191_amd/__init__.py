@@ -25,6 +25,7 @@ EXPORTS = (
     "mbq_linear_workspace_bytes", "mbq_encode", "mbq_encode_with_params", "mbq_unpack", "mbq_dequant", "mbq_route",
     "mbq_route_group", "mbq_linear", "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob",
     "mbq_route_mlp", "mbq_route_mlp_workspace_bytes", "mbq_threshold_quantile",
+    "mbq_linear_static", "mbq_static_scratch_bytes",
     # include/mbq_bench.h: measurement and diagnostic entry points
     "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop", "mbq_bench_linear_group_prepared",
     "mbq_bench_decode_timeline", "mbq_bench_decode_timeline_bytes", "mbq_bench_decode_timeline_workgroups",
@@ -66,6 +67,10 @@ def load() -> ctypes.CDLL:
     lib.mbq_route_mlp_workspace_bytes.argtypes = [c_i64, c_i64, c_int]
     lib.mbq_threshold_quantile.argtypes = [c_p, c_i64, c_int, ctypes.c_double, c_p, c_p]
     lib.mbq_linear.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
+    lib.mbq_linear_static.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_p, c_p, c_int, c_p]
+    lib.mbq_linear_static.restype = c_int
+    lib.mbq_static_scratch_bytes.restype = c_sz
+    lib.mbq_static_scratch_bytes.argtypes = []
     lib.mbq_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_routed_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_p,
                                             c_p, c_sz, c_p, c_sz, c_int, c_p]
@@ -274,6 +279,15 @@ def mbq_linear(X: torch.Tensor, blob: torch.Tensor, N: int, K: int, prec: torch.
         ws = linear_workspace(T, N, K, X.device)
     _check(load().mbq_linear(_ptr(X), T, _ptr(blob), N, K, _ptr(prec), _ptr(perm), _ptr(offsets), _ptr(Y),
                              _ptr(ws), ws.numel(), algo, _stream()), "mbq_linear")
+    return Y
+
+
+def mbq_linear_static(X: torch.Tensor, blob: torch.Tensor, N: int, K: int, prec: torch.Tensor, perm: torch.Tensor,
+                      offsets: torch.Tensor, Y: torch.Tensor, algo: int = ALGO_AUTO) -> torch.Tensor:
+    """mbq_linear on the library's built-in scratch buffer: no allocation anywhere (Y is the caller's)."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.shape[1] == K
+    _check(load().mbq_linear_static(_ptr(X), X.shape[0], _ptr(blob), N, K, _ptr(prec), _ptr(perm), _ptr(offsets),
+                                    _ptr(Y), algo, _stream()), "mbq_linear_static")
     return Y
 
 

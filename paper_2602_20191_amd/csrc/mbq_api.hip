@@ -147,11 +147,68 @@ mbq_status dispatch_linear(const uint16_t* X, int64_t T, const void* blob, const
   }
 }
 
+// ---- scratch memory of mbq_linear_static ---------------------------------------------------------------------------
+// Device memory that belongs to the library image: every GPU the library runs on holds its own copy at its own address
+// until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[MBQ_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// the address of `scratch` on the current device (looked up once per device, with that device current)
+static mbq_status scratch_on_current_device(void** out) {
+  int dev = -1;
+  mbq_status st = hip_status(hipGetDevice(&dev), "hipGetDevice");
+  if (st != MBQ_OK) return st;
+  if (dev < 0 || dev >= kMaxDevices) {
+    set_error("mbq_linear_static: device index %d outside 0..%d", dev, kMaxDevices - 1);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    st = hip_status(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (st != MBQ_OK) return st;
+    if (ptr == nullptr) {
+      set_error("mbq_linear_static: hipGetSymbolAddress returned a null address");
+      return MBQ_ERR_HIP;
+    }
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // (a second thread may look it up too: same value)
+  }
+  *out = ptr;
+  return MBQ_OK;
+}
+
 }  // namespace mbq
 
 using namespace mbq;
 
 extern "C" {
+
+size_t mbq_static_scratch_bytes(void) { return MBQ_STATIC_SCRATCH_BYTES; }
+
+mbq_status mbq_linear_static(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
+                             const int32_t* prec, const int32_t* perm, const int32_t* offsets, float* Y, int algo,
+                             void* stream) {
+  ApiScope scope;
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (T < 0 || T > (int64_t)1 << 24) {
+    set_error("mbq_linear_static: bad token count %lld", (long long)T);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  const size_t need = mbq_linear_workspace_bytes(T, N, K);
+  if (need > (size_t)MBQ_STATIC_SCRATCH_BYTES) {
+    set_error("mbq_linear_static: T=%lld, N=%lld, K=%lld needs %zu bytes of scratch memory, the built-in buffer holds "
+              "%zu: use mbq_linear with a workspace of your own", (long long)T, (long long)N, (long long)K, need,
+              (size_t)MBQ_STATIC_SCRATCH_BYTES);
+    return MBQ_ERR_WORKSPACE;
+  }
+  if (T == 0) return mbq_linear(X, T, blob, N, K, prec, perm, offsets, Y, nullptr, 0, algo, stream);
+  void* ws = nullptr;
+  mbq_status st = scratch_on_current_device(&ws);
+  if (st != MBQ_OK) return st;
+  return mbq_linear(X, T, blob, N, K, prec, perm, offsets, Y, ws, (size_t)MBQ_STATIC_SCRATCH_BYTES, algo, stream);
+}
 
 const char* mbq_version(void) { return "mbq 0.1 (gfx950)"; }
 
