@@ -282,7 +282,9 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        # the arithmetic of the timed kernels (batch <= 16): bf16 activations split exactly into two FP8 (E4M3) pieces,
+        # 2-bit codes taken as FP4 (E2M1) operands, v_mfma_scale_f32_16x16x128_f8f6f4, fp32 accumulate and epilogue
+        "dtype": "fp8(e4m3) x2 x fp4(e2m1) scaled MFMA, fp32 accumulate",
         "data": "synthetic",
         "config": {
             "workload": f"BASELINE configs[1]: Llama-2-7B-shaped decoder block, 7 routed linears, decode batch {T}, "
@@ -294,7 +296,7 @@ def main() -> int:
         "hbm_gbps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "event_ms_per_step": ev_ms_per_step,
         "roofline": {
-            "bound": "hbm", "kernel": "the linear kernel of each stage: mbq::decode_f4_ring_kernel (q+k+v, o, gate+up), "
+            "bound": "hbm", "kernel": "the linear kernel of each stage: mbq::decode_f4_ws_kernel (q+k+v, o, gate+up), "
                                       "mbq::decode_f4_stream_kernel (down)",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
             "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(T),
@@ -306,7 +308,14 @@ def main() -> int:
     }
 
     if not args.no_extra:
+        peaks = measured_peaks(mbq, torch, dev)
+        out["measured_peaks"] = peaks
+        out["roofline"]["frac_of_measured_read"] = achieved / peaks["read_gbps"]
+        out["roofline"]["frac_of_measured_copy"] = achieved / peaks["copy_gbps"]
         out["extra"] = extra_measurements(mbq, torch, dev, cfg, layers, stages, T)
+        for key in ("prefill_mlp_2048tok", "prefill_70b_mlp_4096tok"):
+            r = out["extra"][key]["roofline"]
+            r["frac_of_measured_lds_fed_loop"] = r["achieved"] / peaks["mfma_bf16_lds_fed_tflops"]
 
     # ------------------------------------------------------------------ CPU baseline
     if not args.no_cpu_baseline:
@@ -647,34 +656,80 @@ def other_config_measurements(mbq, torch, dev):
 
 
 def cpu_baseline(cfg, layers, T):
-    """The oracle as it stands, timed on the host: full routing, and the routed linear on
-    the first 256 output rows of each linear, extrapolated linearly to all rows."""
-    import oracle as O
+    """The C oracle (oracle/mbq_oracle.c: plain fp64 loops, dequantise-then-dot, OpenMP over output rows) timed on
+    the host in full on the bench workload: routing, bucketing and the routed linear of all seven linears of the
+    block at batch T, once with every hardware thread and once with one.  Encoding is the offline step and is not
+    timed.  Also counts, per linear, the tokens whose top-2 router logits are closer than 1e-5 (reported apart by the
+    parity rule) and the tokens where the GPU's choice differs from the oracle's."""
+    from oracle import c_oracle as C
     from workloads import make_weight
 
-    try:
-        from threadpoolctl import threadpool_info
-
-        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    sample_rows = 256
-    total = 0.0
+    threads = C.max_threads()
+    t_all = t_one = 0.0
+    near_ties, differing = [], []
     for li, l in enumerate(layers):
         spec = l["spec"]
-        rows = np.arange(min(sample_rows, spec.N))
-        W = make_weight(spec.N, spec.K, [cfg.seed, li], cfg.weight_df, rows=rows)
-        codes, s0, z0 = O.encode(W)                      # offline step: not timed
-        t0 = time.perf_counter()
-        S, prec, gap = O.route(l["x_bits"], l["Wr_h"], l["br_h"])
-        perm, offsets = O.bucket(prec)
-        t1 = time.perf_counter()
-        O.linear(l["x_bits"], codes, s0, z0, prec)
-        t2 = time.perf_counter()
-        total += (t1 - t0) + (t2 - t1) * (spec.N / len(rows))
-    return {"value": T / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"routing in full; linear on the first {sample_rows} output rows of each of the 7 linears, "
-                      f"time scaled by N/{sample_rows} (numpy fp64, dequantise-then-matmul)"}
+        W = make_weight(spec.N, spec.K, [cfg.seed, li], cfg.weight_df)
+        codes, s0, z0 = C.encode(W)                      # offline step: not timed
+        del W
+        for n_threads in (threads, 1):
+            C.set_threads(n_threads)
+            t0 = time.perf_counter()
+            S, prec, gap = C.route(l["x_bits"], l["Wr_h"], l["br_h"])
+            perm, offsets = C.bucket(prec)
+            C.linear(l["x_bits"], codes, s0, z0, prec)
+            dt = time.perf_counter() - t0
+            if n_threads == 1:
+                t_one += dt
+            else:
+                t_all += dt
+        C.set_threads(threads)
+        gpu_prec = l["prec"].cpu().numpy()
+        near = gap < 1e-5
+        near_ties.append(int(near.sum()))
+        differing.append(int(((gpu_prec != prec) & ~near).sum()))
+        del codes
+    return {"value": T / t_all, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"the whole workload once (7 linears, batch {T}): routing + bucketing + routed linear by the C "
+                      f"oracle (fp64, plain loops, gcc -O2 -fopenmp); encode not timed",
+            "seconds": t_all, "value_1_thread": T / t_one, "seconds_1_thread": t_one,
+            "near_tie_tokens_per_linear": near_ties, "tokens_routed_differently_off_the_near_tie_list": differing}
+
+
+def measured_peaks(mbq, torch, dev):
+    """What this chip itself reaches, next to the published peaks: a plain streaming copy and a read-only stream over
+    1 GiB (HIP events, 5 launches each), and an MFMA loop fed from LDS (v_mfma_f32_32x32x16_bf16, one workgroup of 8
+    wavefronts per compute unit), with and without one workgroup barrier per 16 MFMAs."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    src.fill_(1)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps=5):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    t_copy = min(timed(lambda: mbq.bench_copy(src, dst, width=w)) for w in (4, 8))
+    t_read = min(timed(lambda: mbq.bench_read(src, sink, width=w)) for w in (1, 4))
+    out = {"copy_gbps": 2 * n / t_copy / 1e9, "read_gbps": n / t_read / 1e9}
+    steps = 20000
+    for name, barrier in (("mfma_bf16_lds_fed_tflops", False), ("mfma_bf16_lds_fed_barrier_per_16_tflops", True)):
+        flops = [0.0]
+
+        def run():
+            flops[0] = mbq.bench_mfma_loop(steps, barrier, sink)
+        t = timed(run, reps=3)
+        out[name] = flops[0] / t / 1e12
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":
