@@ -64,7 +64,7 @@ typedef enum mbq_status {
 typedef enum mbq_algo {
   MBQ_ALGO_AUTO = 0,
   MBQ_ALGO_SIMPLE = 1, /* one thread per output, fp64 accumulate: slow checker path   */
-  MBQ_ALGO_DECODE = 2, /* bandwidth-bound per-slice MFMA GEMV, T <= 64               */
+  MBQ_ALGO_DECODE = 2, /* the decode kernels; as a request: T <= 64 only             */
   MBQ_ALGO_PREFILL = 3 /* merged-code bf16 MFMA tiled GEMM, any T                     */
 } mbq_algo;
 
@@ -133,10 +133,10 @@ mbq_status mbq_dequant(const void* blob, int64_t N, int64_t K, int p, float* Wha
  *   X      : bf16 [T][K]           Wr : fp32 [P][K]        br : fp32 [P]
  *   prec   : int32 [T] (out)       perm : int32 [T] (out)  offsets : int32 [P+1] (out)
  *   logits : fp64 [T][P] (out, may be NULL)
- *   ws     : at least mbq_route_workspace_bytes(T, K) bytes, 256-byte aligned.  It holds a
- *            ticket counter: the bytes must be ZERO before the first call that uses this
- *            workspace; every call leaves them zero again.  Calls sharing one workspace
- *            must not overlap in time.
+ *   ws     : at least mbq_route_workspace_bytes(T, K) bytes, 256-byte aligned.  It holds the
+ *            counters by which the workgroups of the launch find out who is last; the call
+ *            clears them itself (a small launch ahead of the router's), so the contents before
+ *            the call do not matter.  Calls sharing one workspace must not overlap in time.
  * T = 0 is legal (offsets are zero-filled).
  */
 mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
@@ -146,8 +146,8 @@ mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, c
 /*
  * mbq_route_group - mbq_route for n_proj routers that read the SAME activations (the
  * projections of a decoder block that share their input: q/k/v, gate/up), in one launch
- * when T is small (Sec. 4.3, fused router launch for all projections of a layer).
- * Results are those of n_proj separate mbq_route calls.
+ * up to 128 tokens (Sec. 4.3, fused router launch for all projections of a layer).
+ * Results are those of n_proj separate mbq_route calls, bit for bit.
  *   Wr_host, br_host, prec_host, perm_host, offsets_host : HOST arrays of n_proj DEVICE
  *   pointers, each pointing to what the argument of the same name is in mbq_route; they are
  *   read before the call returns.  1 <= n_proj <= MBQ_MAX_GROUP.  ws as in mbq_route.
@@ -172,7 +172,7 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
  *   X : bf16 [T][K]   W1 : fp32 [H][K]   b1 : fp32 [H]   W2 : fp32 [E][H]   b2 : fp32 [E]
  *   1 <= H <= 512, E = 4;  prec, perm, offsets as in mbq_route;  scores : fp64 [T][E] (out, may be NULL)
  *   ws : at least mbq_route_mlp_workspace_bytes(T, K, H) bytes, 256-byte aligned; its first 256 bytes
- *        hold a ticket counter (ZERO before first use, left zero), the rest the hidden layer.
+ *        hold a ticket counter (cleared by the call itself), the rest the hidden layer.
  * T = 0 is legal.
  */
 size_t mbq_route_mlp_workspace_bytes(int64_t T, int64_t K, int H);
@@ -204,6 +204,17 @@ mbq_status mbq_threshold_quantile(const double* scores, int64_t T, int E, double
  *   ws   : at least mbq_linear_workspace_bytes(T, N, K) bytes, 256-byte aligned
  *   algo : an mbq_algo value
  * T = 0 is legal (no-op).
+ * Arithmetic.  Products of an activation and a code are exact everywhere and sums are fp32.  Up to 16 tokens the
+ * bf16 activations reach the matrix cores as two FP8 (E4M3) pieces per element under a power-of-two scale per
+ * (token, block of 256 columns): exact for every element within 13 binades of the block's largest, and off by at
+ * most 2^-21 of that largest element below (the piece that would carry it underflows) - a data-dependent error far
+ * inside the 1e-3 bar, none at all for blocks without such a spread.  The scale is an 8-bit exponent: a block whose
+ * largest element is under 2^-115 (bf16 subnormals and their neighbours) is scaled by 2^122 at most, and its elements
+ * are then rounded to multiples of 2^-135, an eighth of bf16's subnormal spacing.
+ * Reproducibility.  The decode kernels (up to 64 tokens, and on with AUTO while it keeps them) give the same bits on
+ * every call and in grouped and single calls.  The tiled GEMM does too unless a launch with few tiles splits K into
+ * more than two parts: those partial sums are added with float atomics in whatever order they arrive, and results
+ * then agree to rounding, not bit for bit.
  */
 mbq_status mbq_linear(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
                       const int32_t* prec, const int32_t* perm, const int32_t* offsets, float* Y,
@@ -229,9 +240,11 @@ mbq_status mbq_linear_static(const uint16_t* X, int64_t T, const void* blob, int
 
 /*
  * mbq_linear_group - mbq_linear for n_proj weight matrices with the same K that read the SAME
- * activations (q/k/v, gate/up of a decoder block), each with its own routing; one launch and
- * one pass over X when T <= 16 and K <= 4096 (Sec. 4.3, fused launch for the projections of a
- * layer).  Results are those of n_proj separate mbq_linear calls.
+ * activations (q/k/v, gate/up of a decoder block), each with its own routing; one launch for all
+ * of them while every matrix takes a decode kernel (up to 64 tokens, 128 with AUTO on matrices
+ * that keep the register-stationary kernel; Sec. 4.3, fused launch for the projections of a
+ * layer), otherwise one launch sequence per matrix.  Results are those of n_proj separate
+ * mbq_linear calls (bit for bit where mbq_linear is reproducible, see there).
  *   blob_host, prec_host, perm_host, offsets_host, Y_host : HOST arrays of n_proj DEVICE
  *   pointers (meaning as in mbq_linear); N_host : HOST array of the n_proj row counts.  The
  *   arrays are read before the call returns.  1 <= n_proj <= MBQ_MAX_GROUP.
@@ -247,9 +260,10 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
  * mbq_routed_linear_group - mbq_route_group followed by mbq_linear_group on the same
  * projections: one decoder-block stage (route the tokens for q/k/v, or gate/up, or one
  * projection alone, then compute their outputs).  Same results and the same outputs (prec,
- * perm, offsets, Y) as the two calls; for T <= 16 and K <= 4096 the router launch also carries
- * the decode kernel's activation preparation, so the stage is two launches.
- *   ws_route  : as ws in mbq_route (zero before first use, left zero)
+ * perm, offsets, Y) as the two calls.  Up to 16 tokens the router launch also carries the decode
+ * kernel's activation preparation, and up to 128 tokens (while every matrix takes a decode
+ * kernel) the token sort moves into the linear launch, so the stage is two launches.
+ *   ws_route  : as ws in mbq_route
  *   ws_linear : as ws in mbq_linear_group
  * const int32_t* and int32_t* arrays: prec_host etc. are written by the routing step and read
  * by the linear step.

@@ -83,8 +83,7 @@ mbq_status mbq_bench_decode_timeline(int64_t T, int64_t K, int n_proj, const voi
  *           FP4-operand kernels of T <= 16 off)
  *   knob 4: 1 = route small batches with the general router kernel too
  *   knob 5: K split of the prefill kernel (1..8 workgroups per tile, partial sums added into Y), 0 = automatic
- *   knob 7: 1 = the one-token-tile decode kernel works on the whole K axis per workgroup where it fits;
- *           3 = the 17..64-token kernel takes one token tile per workgroup
+ *   knob 7: 3 = the 17..64-token register-stationary kernel takes one token tile per workgroup
  */
 mbq_status mbq_set_knob(int knob, int value);
 

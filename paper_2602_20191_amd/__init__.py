@@ -165,8 +165,8 @@ def mbq_dequant(blob: torch.Tensor, N: int, K: int, p: int) -> torch.Tensor:
 
 
 def route_workspace(T: int, K: int, device) -> torch.Tensor:
-    # zero-filled: mbq_route keeps a ticket counter there (see include/mbq.h)
-    return torch.zeros(load().mbq_route_workspace_bytes(T, K), dtype=torch.uint8, device=device)
+    # the call clears the counters it keeps there itself: the contents do not matter
+    return torch.empty(load().mbq_route_workspace_bytes(T, K), dtype=torch.uint8, device=device)
 
 
 def linear_workspace(T: int, N: int, K: int, device) -> torch.Tensor:
@@ -196,9 +196,9 @@ def mbq_route(X: torch.Tensor, Wr: torch.Tensor, br: torch.Tensor, want_logits: 
 
 
 def route_mlp_workspace(T: int, K: int, H: int, device) -> torch.Tensor:
-    """Zeroed workspace of mbq_route_mlp (ticket counter + hidden layer)."""
+    """Workspace of mbq_route_mlp (ticket counter, cleared by the call, + hidden layer)."""
     n = load().mbq_route_mlp_workspace_bytes(T, K, H)
-    return torch.zeros(max(int(n), 256), dtype=torch.uint8, device=device)
+    return torch.empty(max(int(n), 256), dtype=torch.uint8, device=device)
 
 
 def mbq_route_mlp(X: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, W2: torch.Tensor, b2: torch.Tensor,

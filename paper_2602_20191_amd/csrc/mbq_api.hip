@@ -63,6 +63,19 @@ bool make_shape(int64_t N, int64_t K, Shape* out) {
   return true;
 }
 
+int device_compute_units() {
+  constexpr int kDevices = 64;
+  static std::atomic<int> cached[kDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kDevices) return 256;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 // 17..64 tokens (and one token tile when the FP4-operand kernels are switched off): the register-stationary
@@ -304,7 +317,7 @@ mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, c
     set_error("mbq_route: null or misaligned pointer (X and Wr need 16-byte alignment)");
     return MBQ_ERR_INVALID_ARG;
   }
-  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws || !aligned(ws, 8)) {
+  if (ws_bytes < mbq_route_workspace_bytes(T, K) || !ws || !aligned(ws, 256)) {
     set_error("mbq_route: workspace too small or misaligned (%zu < %zu)", ws_bytes, mbq_route_workspace_bytes(T, K));
     return MBQ_ERR_WORKSPACE;
   }

@@ -9,13 +9,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-static int bench_compute_units() {
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-    return n;
-  return 256;
-}
+static int bench_compute_units() { return device_compute_units(); }
 
 // four 16-byte loads in flight per lane and round
 __global__ __launch_bounds__(512) void bench_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,

@@ -33,6 +33,10 @@ mbq_status hip_status(hipError_t e, const char* what);
 int knob(int index);  // the calling thread's snapshot of the hooks, taken by the outermost ApiScope
 // Every entry point that dispatches opens one; the outermost on a thread snapshots the test/experiment hooks, so
 // all decisions of one call (also of the calls it makes in turn) see the same values.
+// Compute units of the CURRENT device (asked once per device; 256 if the query fails).  Launch shapes are sized
+// by it, so a process that drives several devices gets each device's own figure.
+int device_compute_units();
+
 struct ApiScope {
   ApiScope();
   ~ApiScope();
@@ -104,7 +108,7 @@ mbq_status launch_linear_decode16(const uint16_t* X, int64_t T, const void* blob
 void decode16_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);
 mbq_status launch_zero_outputs(const ZeroList& zl, hipStream_t stream);
 // sort_perm / sort_offsets (arrays of n, or null): the tokens are not sorted yet (perm is ignored); the launch sorts
-// them by the precisions itself and writes the order and the bucket offsets there (T <= 64)
+// them by the precisions itself and writes the order and the bucket offsets there (T <= 128)
 mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, const void* const* blobs,
                                         const Shape* shapes, const int32_t* const* prec, const int32_t* const* perm,
                                         float* const* Y, hipStream_t stream, int32_t* const* sort_perm,

@@ -444,19 +444,6 @@ static void launch_decode16(int grid, hipStream_t stream, const uint16_t* X, int
                      stream, X, T, K, KB, g);
 }
 
-static int compute_units() {
-  static int cached = 0;
-  if (cached == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cached = n;
-    else
-      cached = 256;
-  }
-  return cached;
-}
-
 namespace d16 {
 // Launch shape of a call (common K): kernel variant, workgroups per token pass and matrix, K split per matrix.
 struct Plan {
@@ -480,7 +467,7 @@ static Plan make_plan(int64_t T, int n, const Shape* shapes) {
   // tokens 39 us against 57 us, at 64 tokens 39 against 44; up to 32 tokens two one-tile passes side by side are as fast
   pl.tt = (T > 32 && pl.waves == 8 && knob(7) != 3) ? 2 : 1;
   pl.token_passes = (int)((T + 16 * pl.tt - 1) / (16 * pl.tt));
-  const int budget = (compute_units() * per_cu + pl.token_passes - 1) / pl.token_passes;  // workgroups per pass
+  const int budget = (device_compute_units() * per_cu + pl.token_passes - 1) / pl.token_passes;  // workgroups per pass
   // with several K chunks the per-tile partial sums live in LDS: bound the tiles per workgroup
   const int max_tiles = kMaxTilesMulti / pl.tt;
   int64_t all_tiles = 0;

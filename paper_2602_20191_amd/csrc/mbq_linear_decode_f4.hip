@@ -204,18 +204,7 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
   }
 }
 
-int f4_compute_units() {
-  static int cached = 0;
-  if (cached == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cached = n;
-    else
-      cached = 256;
-  }
-  return cached;
-}
+int f4_compute_units() { return device_compute_units(); }
 
 bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16; }
 int decode_f4_timeline_workgroups() { return f4_compute_units(); }

@@ -27,12 +27,6 @@
 
 #include "mbq_common.h"
 
-// 1: the packed-weight and scale loads of the K loop are issued behind the compiler's back and waited for
-// by hand (see load_dword_untracked); 0: ordinary loads, for comparison
-#ifndef MBQ_UNTRACKED
-#define MBQ_UNTRACKED 1
-#endif
-
 namespace mbq {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -107,9 +101,7 @@ __device__ __forceinline__ void vmem_outstanding_at_most() {  // s_waitcnt vmcnt
 // the same wait, needed only where registers are loaded behind the compiler's back
 template <int N>
 __device__ __forceinline__ void untracked_loads_outstanding_at_most() {
-#if MBQ_UNTRACKED
   vmem_outstanding_at_most<N>();
-#endif
 }
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (wave-uniform base).
 __device__ __forceinline__ void global_to_lds_16(const void* gptr, char* lds_base) {
@@ -122,33 +114,21 @@ __device__ __forceinline__ void global_to_lds_16(const void* gptr, char* lds_bas
 // would drain the activation loads that are meant to stay in flight for three steps).  Every use of
 // such a register comes after vmem_outstanding_at_most<N>() followed by settled(...) on it.
 __device__ __forceinline__ uint32_t load_dword_untracked(const uint32_t* p) {
-#if MBQ_UNTRACKED
   uint32_t r;
   asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
   return r;
-#else
-  return *p;
-#endif
 }
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ u32x2_t load_dwordx2_untracked(const uint32_t* p) {
-#if MBQ_UNTRACKED
   u32x2_t r;
   asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(r) : "v"(p) : "memory");
   return r;
-#else
-  return *reinterpret_cast<const u32x2_t*>(p);
-#endif
 }
 __device__ __forceinline__ void settled(u32x2_t& a) {
-#if MBQ_UNTRACKED
   asm volatile("" : "+v"(a));
-#endif
 }
 __device__ __forceinline__ void settled(uint32_t& a) {
-#if MBQ_UNTRACKED
   asm volatile("" : "+v"(a));
-#endif
 }
 // LDS fragment reads are ordinary loads; touching a fragment makes the compiler place its lgkmcnt wait here
 __device__ __forceinline__ void touch(u32x4& a) { asm volatile("" : "+v"(a)); }

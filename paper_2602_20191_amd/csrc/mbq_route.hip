@@ -109,7 +109,7 @@ __device__ __forceinline__ double wave_sum4(const double (&acc)[4], int lane) {
 // is split over the threads in chunks of 8 columns; each thread keeps 4 x TPW fp64 partial
 // sums (bf16 x fp32 products are exact in fp64), reduced over the wavefront (wave_sum4) and
 // over the four wavefronts through LDS.  The workgroup that finishes last (a ticket counter in
-// the workspace, left at zero again) then buckets all tokens, so routing is one launch.
+// the workspace, cleared ahead of the launch) then buckets all tokens.
 template <int TPW>
 __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ X, int64_t T, int64_t K,
                                                     const float* __restrict__ Wr, const float* __restrict__ br,
@@ -186,8 +186,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
 // two chunks in flight per thread.  Workgroups meet through ONE 64-bit atomic add per token: the
 // word carries 2 bits per token and an arrival count in its top byte, so the workgroup that
 // arrives last holds every token's precision in the returned value and buckets them with
-// wavefront ballots, without fences or a second pass over memory.  The word starts at zero and is
-// left at zero.
+// wavefront ballots, without fences or a second pass over memory.  The word is cleared ahead of the launch.
 constexpr int kSmallRouteTokens = 28;
 constexpr int kRouteGroupMax = MBQ_MAX_GROUP;
 
@@ -337,6 +336,16 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
   if (lane == 0) words[blockIdx.y] = 0ull;  // ready for the next call
 }
 
+// The arrival counters of a workspace (its first 256 bytes), cleared ahead of a launch that meets through them:
+// a caller's workspace may hold anything, for instance what a call that was cut short left behind.
+__global__ __launch_bounds__(64) void clear_counters_kernel(unsigned int* __restrict__ counters) {
+  counters[threadIdx.x] = 0u;
+}
+static mbq_status clear_counters(void* ws, hipStream_t stream) {
+  hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, stream, reinterpret_cast<unsigned int*>(ws));
+  return hip_status(hipGetLastError(), "clear_counters_kernel launch");
+}
+
 // T = 0: only the (all-zero) offsets have to be written.
 __global__ __launch_bounds__(64) void bucket_kernel(const int32_t* __restrict__ prec, int64_t T,
                                                     int32_t* __restrict__ perm, int32_t* __restrict__ offsets) {
@@ -376,6 +385,10 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
                               void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
+  if (T > 0 && !(defer_bucket && route_small_supports(T))) {  // a launch that sorts meets through the counters
+    mbq_status st = clear_counters(ws, stream);
+    if (st != MBQ_OK) return st;
+  }
   if (route_small_supports(T)) {
     if (!route_can_carry_prep(T)) prep = nullptr;
     RouteGroup g;
@@ -580,6 +593,8 @@ mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float
     hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(64), 0, stream, prec, T, perm, offsets);
     return hip_status(hipGetLastError(), "bucket_kernel launch");
   }
+  mbq_status st = clear_counters(ws, stream);
+  if (st != MBQ_OK) return st;
   const unsigned chunks = (unsigned)((H + kMlpHiddenChunk - 1) / kMlpHiddenChunk);
   if (T <= 256)
     hipLaunchKernelGGL(route_mlp_hidden_kernel<1>, dim3((unsigned)T, chunks), dim3(256), 0, stream, X, T, K, W1, b1,
@@ -587,7 +602,7 @@ mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float
   else
     hipLaunchKernelGGL(route_mlp_hidden_mfma_kernel, dim3((unsigned)((T + 15) / 16), (unsigned)((H + 15) / 16)),
                        dim3(256), 0, stream, X, T, K, W1, b1, H, hidden);
-  mbq_status st = hip_status(hipGetLastError(), "route_mlp_hidden_kernel launch");
+  st = hip_status(hipGetLastError(), "route_mlp_hidden_kernel launch");
   if (st != MBQ_OK) return st;
   hipLaunchKernelGGL(route_mlp_score_kernel, dim3((unsigned)((T + 63) / 64)), dim3(256), 0, stream, hidden, T, H, W2,
                      b2, delta, prec, perm, offsets, scores, ticket);

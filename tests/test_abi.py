@@ -77,3 +77,31 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.mbq_linear(None, 0, None, 16, 128, None, None, None, None, None, 0, 0, None) == 0   # T = 0: no-op
     assert lib.mbq_route(None, 4, 128, None, None, 3, None, None, None, None, None, 0, None) == 2
     assert lib.mbq_route(None, 4, 128, None, None, 4, None, None, None, None, None, 0, None) == 1
+
+
+def test_route_workspace_contract(lib):
+    """The workspace needs the documented 256-byte alignment (refused before any launch) and the headers no longer
+    ask the caller to clear it."""
+    lib.mbq_route.restype = ctypes.c_int
+    lib.mbq_route.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                              ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.mbq_last_error.restype = ctypes.c_char_p
+    fake = 0x10000                                            # never dereferenced: the call is refused first
+    for ws in (fake + 8, fake + 64, fake + 128):
+        assert lib.mbq_route(fake, 4, 128, fake, fake, 4, fake, fake, fake, None, ws, 256, None) == 3
+        assert b"misaligned" in lib.mbq_last_error()
+    assert lib.mbq_route(fake, 4, 128, fake, fake, 4, fake, fake, fake, None, fake, 255, None) == 3
+    for header in HEADERS:
+        text = open(header).read()
+        assert "ZERO before" not in text and "zero before first use" not in text
+
+
+def test_hooks_and_static_scratch(lib):
+    lib.mbq_set_knob.restype = ctypes.c_int
+    lib.mbq_set_knob.argtypes = [ctypes.c_int, ctypes.c_int]
+    assert lib.mbq_set_knob(6, 1) != 0                        # the old "skip the preparation" hook is gone
+    assert lib.mbq_set_knob(8, 1) != 0 and lib.mbq_set_knob(-1, 0) != 0
+    assert lib.mbq_set_knob(4, 0) == 0
+    lib.mbq_static_scratch_bytes.restype = ctypes.c_size_t
+    assert lib.mbq_static_scratch_bytes() == 8 << 20
