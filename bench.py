@@ -53,6 +53,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--batch", type=int, default=16, help="decode batch (tokens per step): 1, 4 or 16")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--warm", action="store_true",
+                    help="timeline probe: do not flush the last-level cache between the stage call and the timed launch")
     ap.add_argument("--steps-per-replay", type=int, default=32,
                     help="steps captured in one HIP graph (a decode step of a 32-layer model replays 32 blocks "
                          "at once); the remainder of --steps runs from one-step graphs")
@@ -131,7 +133,7 @@ def main() -> int:
           f"({sum(l['blobs'][0].numel() for l in layers) * RING / 1e6:.0f} MB of packed weights)", file=sys.stderr)
 
     if args.probe == "timeline":
-        return timeline_probe(mbq, torch, dev, stages, T)
+        return timeline_probe(mbq, torch, dev, stages, T, flush_cache=not args.warm)
 
     if args.probe == "decode":
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -324,7 +326,7 @@ def main() -> int:
     return 0
 
 
-def timeline_probe(mbq, torch, dev, stages, T, dump_dir="gpurun_out"):
+def timeline_probe(mbq, torch, dev, stages, T, dump_dir="gpurun_out", flush_cache=True):
     """Per stage (ring kernel only, K <= 8192): the stage call once (prepares the activations), the last-level cache
     flushed by a 1 GiB fill, then the timeline build of the linear kernel on cold weights; repeated `reps` times.
     Times are microseconds after the first wavefront of the launch entered the kernel (100 MHz clock: 0.01 us
@@ -340,7 +342,8 @@ def timeline_probe(mbq, torch, dev, stages, T, dump_dir="gpurun_out"):
             blobs = [l["blobs"][rep % RING] for l in st["layers"]]
             mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], blobs, st["Ns"], routing=st["routing"],
                                         Y=st["Y"], ws_route=st["ws_r"], ws_linear=st["ws_l"])
-            flush.fill_(rep)
+            if flush_cache:
+                flush.fill_(rep)
             torch.cuda.synchronize()
             stamps = mbq.bench_decode_timeline(T, st["K"], blobs, st["Ns"], st["routing"], st["Y"], st["ws_l"])
             torch.cuda.synchronize()
