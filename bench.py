@@ -37,7 +37,10 @@ STAGES = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))   # projections th
 # HBM bytes per linear-kernel launch at batch 16 (mean over the four stages) from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of `bench.py --probe decode`, scaled by what the same counters read for a plain 256 MiB copy
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/decode_linear_hbm_traffic_llama2_7b_batch16.txt
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 54.64e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 54.49e6}
+# HBM bytes per mbq_linear call (gather pre-kernel + tile kernel), mean over the three linears, same counters and scale
+# factors from `bench.py --probe prefill` / `--probe prefill70b`; see profiles/prefill_hbm_traffic.txt
+MEASURED_PREFILL_TRAFFIC_BYTES_PER_CALL = {"configs[2]": 653.8e6, "70b": 3498.4e6}
 
 
 def algorithmic_bytes(N, K, T, pmax):
@@ -60,10 +63,11 @@ def main() -> int:
                          "at once); the remainder of --steps runs from one-step graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the batch-1/4 and prefill side measurements")
-    ap.add_argument("--probe", choices=["decode", "prefill", "timeline"], default=None,
+    ap.add_argument("--probe", choices=["decode", "prefill", "prefill70b", "timeline"], default=None,
                     help="counter probe for rocprofv3 --pmc, nothing is timed.  decode: a plain 256 MiB device copy "
                          "(known size, calibrates the counters) then a few mbq_linear launches per linear of the "
-                         "block.  prefill: three mbq_linear launches of the BASELINE configs[2] gate linear.  "
+                         "block.  prefill / prefill70b: three mbq_linear launches of each linear of BASELINE configs[2] / of the "
+                         "70B-shaped linears at 4096 tokens.  "
                          "timeline: where the time of the one-token-tile decode kernel goes, from the clock stamps of "
                          "the library's timeline build of that kernel (prints a table per stage)")
     args = ap.parse_args()
@@ -82,20 +86,48 @@ def main() -> int:
     dev = torch.device("cuda:0")
     cfg = CONFIGS[1]
     T = args.batch
-    if args.probe == "prefill":
-        pcfg = CONFIGS[2]
-        Tp, spec = pcfg.token_counts[0], pcfg.linears[0]
-        case = make_case(pcfg, 0, Tp)
-        blob = mbq.mbq_encode(torch.from_numpy(case["W"]).to(dev))
-        X = torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev)
-        prec, perm, offsets = mbq.mbq_route(X, torch.from_numpy(case["Wr"]).to(dev), torch.from_numpy(case["br"]).to(dev))
-        Y = torch.empty((Tp, spec.N), dtype=torch.float32, device=dev)
-        ws = mbq.linear_workspace(Tp, spec.N, spec.K, dev)
-        for _ in range(3):
-            mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
-        torch.cuda.synchronize()
-        print(json.dumps({"probe": "prefill", "N": spec.N, "K": spec.K, "T": Tp,
-                          "mix": np.bincount(prec.cpu().numpy(), minlength=4).tolist()}))
+    if args.probe in ("prefill", "prefill70b"):
+        # counter probe: three mbq_linear calls per linear; configs[2] (2048 tokens) with the bench's inputs, or the
+        # 70B-shaped linears of configs[4] at 4096 tokens with the weights, activations and mix of the side measurement
+        done = []
+        if args.probe == "prefill":
+            pcfg = CONFIGS[2]
+            Tp = pcfg.token_counts[0]
+            jobs = []
+            for li, spec in enumerate(pcfg.linears):
+                case = make_case(pcfg, li, Tp)
+                blob = mbq.mbq_encode(torch.from_numpy(case["W"]).to(dev))
+                X = torch.from_numpy(case["X"].view(np.int16)).view(torch.bfloat16).to(dev)
+                routing = mbq.mbq_route(X, torch.from_numpy(case["Wr"]).to(dev), torch.from_numpy(case["br"]).to(dev))
+                jobs.append((spec, X, blob, routing))
+        else:
+            Tp = 4096
+            mix = torch.tensor([0.70, 0.20, 0.08, 0.02], device=dev)
+            jobs = []
+            for li, spec in enumerate(CONFIGS[4].linears):
+                g = torch.Generator(device=dev)
+                g.manual_seed(41 + li)
+                blob = mbq.mbq_encode(torch.randn((spec.N, spec.K), generator=g, device=dev) * 0.02)
+                g.manual_seed(100 + Tp)
+                X = torch.randn((Tp, spec.K), generator=g, device=dev).to(torch.bfloat16)
+                g.manual_seed(7 * Tp + li)
+                prec = torch.multinomial(mix, Tp, replacement=True, generator=g).to(torch.int32)
+                perm = torch.sort(prec, stable=True).indices.to(torch.int32)
+                counts = torch.bincount(prec, minlength=4)
+                offsets = torch.cat([torch.zeros(1, dtype=torch.int64, device=dev),
+                                     torch.cumsum(counts, 0)]).to(torch.int32)
+                jobs.append((spec, X, blob, (prec, perm, offsets)))
+                torch.cuda.synchronize()
+        for spec, X, blob, (prec, perm, offsets) in jobs:
+            Y = torch.empty((Tp, spec.N), dtype=torch.float32, device=dev)
+            ws = mbq.linear_workspace(Tp, spec.N, spec.K, dev)
+            for _ in range(3):
+                mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
+            torch.cuda.synchronize()
+            done.append({"name": spec.name, "N": spec.N, "K": spec.K, "T": Tp,
+                         "mix": np.bincount(prec.cpu().numpy(), minlength=4).tolist()})
+            del Y, ws
+        print(json.dumps({"probe": args.probe, "linears": done}))
         return 0
 
     # ------------------------------------------------------------------ inputs in HBM
@@ -496,7 +528,8 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         "ms_total": ms_sum, "tflops": tf, "route_ms_total": route_sum,
         "tflops_route_and_linear": flops_sum / ((ms_sum + route_sum) * 1e-3) / 1e12, "per_linear": per_linear,
         "roofline": {"bound": "mfma", "kernel": "mbq::prefill_kernel (+ mbq::prefill_prep_kernel)", "achieved": tf,
-                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0,
+                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES_PER_CALL["configs[2]"]}}
     # the paper's 2-layer router (hidden width 64) at the decode batch and at 2048 tokens, K = 4096
     from workloads import make_mlp_router, make_tokens
     Kr, Hr = 4096, 64
@@ -649,7 +682,8 @@ def other_config_measurements(mbq, torch, dev):
                     "(precisions drawn directly); useful flops 2 T N K over the whole mbq_linear call",
         "ms_total": ms_sum, "tflops": tf, "per_linear": pre,
         "roofline": {"bound": "mfma", "kernel": "mbq::prefill_kernel (+ mbq::prefill_prep_kernel)", "achieved": tf,
-                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0,
+                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES_PER_CALL["70b"]}}
     for v in dec.values():   # the mixed case: both fractions, graded against the larger of the two times
         v["hbm_frac"] = v["gbps"] / HBM_PEAK_GBPS
         v["mfma_frac"] = v["tflops"] / 2500.0
