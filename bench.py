@@ -478,6 +478,61 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         extra[f"decode_batch_{T}"] = {"ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
                                       "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9,
                                       "launch": f"hipgraph, {per_replay} steps per replay" if graphs else "eager"}
+    # the same block under another slice configuration (Sec. 4.1 general widths): a 4-bit first slice and two 2-bit
+    # residual slices, i.e. three-output routers choosing among 4, 6 and 8 bits, on the SAME packed blobs (a
+    # configuration only says where the eight-bit code may be cut); the routers are rows 1..3 of the block's own
+    for bits in ((4, 2, 2),):
+        scfg = mbq.Config(bits)
+        E = len(bits)
+        T = T_main
+        Wr3 = [[w[4 - E:].contiguous() for w in st["Wr"]] for st in stages]
+        br3 = [[b[4 - E:].contiguous() for b in st["br"]] for st in stages]
+
+        def one_cfg(slot):
+            for st, wr, br_ in zip(stages, Wr3, br3):
+                mbq.mbq_routed_linear_group_cfg(st["X"], wr, br_, scfg, [l["blobs"][slot] for l in st["layers"]],
+                                                st["Ns"], routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"],
+                                                ws_linear=st["ws_l"])
+
+        one_cfg(0)
+        torch.cuda.synchronize()
+        per_replay = 10
+        graphs = []
+        try:
+            for slot in range(RING):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for j in range(per_replay):
+                        one_cfg((slot + j) % RING)
+                graphs.append(g)
+        except Exception:
+            graphs, per_replay = [], 1
+        n = 6 if graphs else 60
+        for i in range(1 if graphs else 6):
+            graphs[i % RING].replay() if graphs else one_cfg(i % RING)
+        a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n):
+            graphs[i % RING].replay() if graphs else one_cfg(i % RING)
+        b2.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b2) / (n * per_replay)
+        byts, mixes = 0, []
+        for l in layers:
+            digits = l["prec"].cpu().numpy()
+            byts += algorithmic_bytes(l["spec"].N, l["spec"].K, T, int(digits.max())) + 4 * E * l["spec"].K
+            mixes.append(np.bincount(digits, minlength=4).tolist())
+        extra["slice_config_" + "_".join(str(b) for b in bits) + f"_decode_batch_{T}"] = {
+            "workload": f"the block of the main line, slice widths {list(bits)}: routers with {E} outputs, tokens at "
+                        f"{[mbq.config_bits(scfg, p) for p in range(E)]} bits",
+            "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9,
+            "tokens_per_digit_precision_per_linear": mixes,
+            "launch": f"hipgraph, {per_replay} steps per replay" if graphs else "eager"}
+        # leave the stage buffers as the main run had them
+        for st in stages:
+            mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [l["blobs"][0] for l in st["layers"]], st["Ns"],
+                                        routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"], ws_linear=st["ws_l"])
+        torch.cuda.synchronize()
     # the prefill linears of BASELINE configs[2] (gate, up, down; 2048 tokens), each as the whole mbq_linear call
     # (gather/group-sum pre-kernel + tile kernel) timed with HIP events over back-to-back launches
     pcfg = CONFIGS[2]

@@ -276,6 +276,73 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
                                    size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
                                    int algo, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Other slice configurations (Sec. 4.1: E slices of b_e bits; App. C.1: slice_bits_list, group size)
+ * ------------------------------------------------------------------------------------------------
+ * The method is stated for any number of slices E and any widths b_e: slice 0 is a b_0-bit quantiser with
+ * s_0 = (max - min) / 2^b_0 and z_0 = -min / s_0, slice e >= 1 has s_e = s_(e-1) / 2^b_e and z_e = 2^(b_e - 1)
+ * (App. B), precision p uses slices 0..p, B_p = b_0 + ... + b_p bits.
+ *
+ * What this library runs: 1 <= E <= MBQ_MAX_SLICES, every b_e even, B_(E-1) <= 8, group 128 - e.g. {2,2,2,2} (the
+ * default), {4,2,2}, {2,4,2}, {4,4}, {6,2}, {8}, {2,2,2}.  For these the packed blob is THE SAME as the default one:
+ * a slice of b bits with the centred zero point 2^(b-1) is b/2 consecutive 2-bit slices with zero point 2 (the codes
+ * are the same bits, the scales the same powers of two of s_0), so a configuration only says where the eight-bit
+ * code may be cut, and its (s_0, z_0) are the stored ones times 2^(2 - b_0) and 2^(b_0 - 2).  mbq_encode_cfg
+ * therefore writes the blob of mbq_encode, and every mbq_linear* call works on it unchanged.
+ * What does know the configuration is the router: it has E outputs, and output q stands for B_q / 2 base-4 digits.
+ * The prec arrays written by the *_cfg router calls (and read by mbq_linear*) hold that digit count minus one -
+ * mbq_config_digit_precision(cfg, q) - which for the default configuration is q itself; perm and offsets (always
+ * MBQ_N_PRECISIONS + 1 entries) sort and bucket the tokens by it.
+ * Odd widths (a 3-bit first slice, 1-bit residual slices), other group sizes and 16-bit scale / zero-point storage
+ * need a blob cut in binary digits and per-group metadata of another size: not built; the calls below refuse them
+ * with MBQ_ERR_BAD_SHAPE.
+ */
+#define MBQ_MAX_SLICES 4
+typedef struct mbq_config {
+  int n_slices;                   /* E */
+  int slice_bits[MBQ_MAX_SLICES]; /* b_e, e < n_slices */
+  int group;                      /* columns per quantisation group */
+} mbq_config;
+
+/* MBQ_OK if the library runs this configuration, else MBQ_ERR_BAD_SHAPE (mbq_last_error says why). */
+mbq_status mbq_config_check(const mbq_config* cfg);
+/* B_p, the bits of precision p; -1 for a bad configuration or index. */
+int mbq_config_bits(const mbq_config* cfg, int p);
+/* What the prec arrays hold for the configuration's precision p (B_p / 2 - 1); -1 for a bad configuration or index. */
+int mbq_config_digit_precision(const mbq_config* cfg, int p);
+
+/* mbq_encode for a configuration (Sec. 4.1 Eq. 2): checks it, then writes the blob described above. */
+mbq_status mbq_encode_cfg(const float* W, int64_t N, int64_t K, const mbq_config* cfg, void* blob, void* stream);
+/*
+ * mbq_unpack in the configuration's own terms, for checking against an independent implementation of the
+ * general recursion: codes uint8 [E][N][K] (slice e's b_e-bit codes), scale / zero fp32 [N][K/128] = (s_0, z_0) of
+ * the configuration's first slice.  Any of the three outputs may be null.
+ */
+mbq_status mbq_unpack_cfg(const void* blob, int64_t N, int64_t K, const mbq_config* cfg, uint8_t* codes,
+                          float* scale, float* zero, void* stream);
+/* W^(p) of the configuration (Eq. 3), fp32 [N][K]; p < E. */
+mbq_status mbq_dequant_cfg(const void* blob, int64_t N, int64_t K, const mbq_config* cfg, int p, float* What,
+                           void* stream);
+/*
+ * mbq_route, mbq_route_group, mbq_routed_linear_group for a configuration: Wr is fp32 [E][K] and br fp32 [E] per
+ * router, logits (mbq_route_cfg) fp64 [T][E]; argmax over the E outputs, first maximum wins; prec as described
+ * above.  Everything else as in the calls without _cfg.
+ */
+mbq_status mbq_route_cfg(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
+                         const mbq_config* cfg, int32_t* prec, int32_t* perm, int32_t* offsets, double* logits,
+                         void* ws, size_t ws_bytes, void* stream);
+mbq_status mbq_route_group_cfg(const uint16_t* X, int64_t T, int64_t K, int n_proj, const float* const* Wr_host,
+                               const float* const* br_host, const mbq_config* cfg, int32_t* const* prec_host,
+                               int32_t* const* perm_host, int32_t* const* offsets_host, void* ws, size_t ws_bytes,
+                               void* stream);
+mbq_status mbq_routed_linear_group_cfg(const uint16_t* X, int64_t T, int64_t K, int n_proj,
+                                       const float* const* Wr_host, const float* const* br_host,
+                                       const mbq_config* cfg, const void* const* blob_host, const int64_t* N_host,
+                                       int32_t* const* prec_host, int32_t* const* perm_host,
+                                       int32_t* const* offsets_host, float* const* Y_host, void* ws_route,
+                                       size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes, int algo,
+                                       void* stream);
+
 #ifdef __cplusplus
 }
 #endif

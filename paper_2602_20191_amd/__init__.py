@@ -26,6 +26,9 @@ EXPORTS = (
     "mbq_route_group", "mbq_linear", "mbq_linear_group", "mbq_routed_linear_group", "mbq_set_knob",
     "mbq_route_mlp", "mbq_route_mlp_workspace_bytes", "mbq_threshold_quantile",
     "mbq_linear_static", "mbq_static_scratch_bytes",
+    # other slice configurations
+    "mbq_config_check", "mbq_config_bits", "mbq_config_digit_precision", "mbq_encode_cfg", "mbq_unpack_cfg",
+    "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg", "mbq_routed_linear_group_cfg",
     # include/mbq_bench.h: measurement and diagnostic entry points
     "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop", "mbq_bench_linear_group_prepared",
     "mbq_bench_decode_timeline", "mbq_bench_decode_timeline_bytes", "mbq_bench_decode_timeline_workgroups",
@@ -36,6 +39,23 @@ _lib = None
 
 class MbqError(RuntimeError):
     pass
+
+
+class Config(ctypes.Structure):
+    """mbq_config of include/mbq.h: slice widths (Sec. 4.1, App. C.1) and group size."""
+    _fields_ = [("n_slices", ctypes.c_int), ("slice_bits", ctypes.c_int * 4), ("group", ctypes.c_int)]
+
+    def __init__(self, slice_bits: Sequence[int] = (2, 2, 2, 2), group: int = GROUP):
+        super().__init__()
+        bits = [int(b) for b in slice_bits]
+        self.n_slices = len(bits)
+        for e in range(4):
+            self.slice_bits[e] = bits[e] if e < min(len(bits), 4) else 0
+        self.group = int(group)
+
+    @property
+    def bits(self):
+        return [self.slice_bits[e] for e in range(min(self.n_slices, 4))]
 
 
 def load() -> ctypes.CDLL:
@@ -75,6 +95,21 @@ def load() -> ctypes.CDLL:
     lib.mbq_routed_linear_group.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_p, c_p, c_p, c_p,
                                             c_p, c_sz, c_p, c_sz, c_int, c_p]
     lib.mbq_set_knob.argtypes = [c_int, c_int]
+    c_cfg = ctypes.POINTER(Config)
+    lib.mbq_config_check.argtypes = [c_cfg]
+    lib.mbq_config_bits.argtypes = [c_cfg, c_int]
+    lib.mbq_config_digit_precision.argtypes = [c_cfg, c_int]
+    lib.mbq_encode_cfg.argtypes = [c_p, c_i64, c_i64, c_cfg, c_p, c_p]
+    lib.mbq_unpack_cfg.argtypes = [c_p, c_i64, c_i64, c_cfg, c_p, c_p, c_p, c_p]
+    lib.mbq_dequant_cfg.argtypes = [c_p, c_i64, c_i64, c_cfg, c_int, c_p, c_p]
+    lib.mbq_route_cfg.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_cfg, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
+    lib.mbq_route_group_cfg.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_cfg, c_p, c_p, c_p, c_p, c_sz, c_p]
+    lib.mbq_routed_linear_group_cfg.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_cfg, c_p, c_p, c_p, c_p, c_p,
+                                                c_p, c_p, c_sz, c_p, c_sz, c_int, c_p]
+    for name in ("mbq_config_check", "mbq_config_bits", "mbq_config_digit_precision", "mbq_encode_cfg",
+                 "mbq_unpack_cfg", "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg",
+                 "mbq_routed_linear_group_cfg"):
+        getattr(lib, name).restype = c_int
     lib.mbq_bench_copy.argtypes = [c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_bench_read.argtypes = [c_p, c_sz, c_int, c_p, c_p]
     lib.mbq_bench_mfma_loop.argtypes = [c_int, c_int, c_p, ctypes.POINTER(ctypes.c_double), c_p]
@@ -338,6 +373,108 @@ def mbq_routed_linear_group(X: torch.Tensor, Wr: Sequence[torch.Tensor], br: Seq
         _ptr_array([r[0] for r in routing]), _ptr_array([r[1] for r in routing]),
         _ptr_array([r[2] for r in routing]), _ptr_array(Y), _ptr(ws_route), ws_route.numel(), _ptr(ws_linear),
         ws_linear.numel(), algo, _stream()), "mbq_routed_linear_group")
+    return [tuple(r) for r in routing], list(Y)
+
+
+# ---- other slice configurations ----------------------------------------------------------------------
+
+def config_check(cfg: Config) -> None:
+    _check(load().mbq_config_check(ctypes.byref(cfg)), "mbq_config_check")
+
+
+def config_bits(cfg: Config, p: int) -> int:
+    return int(load().mbq_config_bits(ctypes.byref(cfg), p))
+
+
+def config_digit_precision(cfg: Config, p: int) -> int:
+    return int(load().mbq_config_digit_precision(ctypes.byref(cfg), p))
+
+
+def mbq_encode_cfg(W: torch.Tensor, cfg: Config, blob: Optional[torch.Tensor] = None) -> torch.Tensor:
+    assert W.dtype == torch.float32 and W.dim() == 2
+    N, K = W.shape
+    if blob is None:
+        blob = torch.empty(blob_bytes(N, K), dtype=torch.uint8, device=W.device)
+    _check(load().mbq_encode_cfg(_ptr(W.contiguous()), N, K, ctypes.byref(cfg), _ptr(blob), _stream()),
+           "mbq_encode_cfg")
+    return blob
+
+
+def mbq_unpack_cfg(blob: torch.Tensor, N: int, K: int, cfg: Config):
+    """-> (codes uint8 [E, N, K], scale fp32 [N, K/128], zero fp32 [N, K/128]) in the configuration's terms."""
+    codes = torch.empty((cfg.n_slices, N, K), dtype=torch.uint8, device=blob.device)
+    scale = torch.empty((N, K // GROUP), dtype=torch.float32, device=blob.device)
+    zero = torch.empty_like(scale)
+    _check(load().mbq_unpack_cfg(_ptr(blob), N, K, ctypes.byref(cfg), _ptr(codes), _ptr(scale), _ptr(zero), _stream()),
+           "mbq_unpack_cfg")
+    return codes, scale, zero
+
+
+def mbq_dequant_cfg(blob: torch.Tensor, N: int, K: int, cfg: Config, p: int) -> torch.Tensor:
+    What = torch.empty((N, K), dtype=torch.float32, device=blob.device)
+    _check(load().mbq_dequant_cfg(_ptr(blob), N, K, ctypes.byref(cfg), p, _ptr(What), _stream()), "mbq_dequant_cfg")
+    return What
+
+
+def mbq_route_cfg(X: torch.Tensor, Wr: torch.Tensor, br: torch.Tensor, cfg: Config, want_logits: bool = False,
+                  ws: Optional[torch.Tensor] = None):
+    """X bf16 [T, K], Wr fp32 [E, K], br fp32 [E] -> (prec (digit precisions), perm, offsets[5][, logits [T, E]])."""
+    assert X.dtype == torch.bfloat16 and Wr.dtype == torch.float32 and br.dtype == torch.float32
+    T, K = X.shape
+    assert Wr.shape == (cfg.n_slices, K) and br.shape == (cfg.n_slices,)
+    dev = X.device
+    prec = torch.empty(T, dtype=torch.int32, device=dev)
+    perm = torch.empty(T, dtype=torch.int32, device=dev)
+    offsets = torch.empty(N_PRECISIONS + 1, dtype=torch.int32, device=dev)
+    logits = torch.empty((T, cfg.n_slices), dtype=torch.float64, device=dev) if want_logits else None
+    if ws is None:
+        ws = route_workspace(T, K, dev)
+    _check(load().mbq_route_cfg(_ptr(X), T, K, _ptr(Wr), _ptr(br), ctypes.byref(cfg), _ptr(prec), _ptr(perm),
+                                _ptr(offsets), _ptr(logits), _ptr(ws), ws.numel(), _stream()), "mbq_route_cfg")
+    return (prec, perm, offsets, logits) if want_logits else (prec, perm, offsets)
+
+
+def mbq_route_group_cfg(X: torch.Tensor, Wr: Sequence[torch.Tensor], br: Sequence[torch.Tensor], cfg: Config,
+                        ws: Optional[torch.Tensor] = None):
+    T, K = X.shape
+    n = len(Wr)
+    dev = X.device
+    routing = [(torch.empty(T, dtype=torch.int32, device=dev), torch.empty(T, dtype=torch.int32, device=dev),
+                torch.empty(N_PRECISIONS + 1, dtype=torch.int32, device=dev)) for _ in range(n)]
+    if ws is None:
+        ws = route_workspace(T, K, dev)
+    _check(load().mbq_route_group_cfg(_ptr(X), T, K, n, _ptr_array(Wr), _ptr_array(br), ctypes.byref(cfg),
+                                      _ptr_array([r[0] for r in routing]), _ptr_array([r[1] for r in routing]),
+                                      _ptr_array([r[2] for r in routing]), _ptr(ws), ws.numel(), _stream()),
+           "mbq_route_group_cfg")
+    return routing
+
+
+def mbq_routed_linear_group_cfg(X: torch.Tensor, Wr: Sequence[torch.Tensor], br: Sequence[torch.Tensor], cfg: Config,
+                                blobs: Sequence[torch.Tensor], Ns: Sequence[int],
+                                routing: Optional[Sequence[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]]] = None,
+                                Y: Optional[Sequence[torch.Tensor]] = None, ws_route: Optional[torch.Tensor] = None,
+                                ws_linear: Optional[torch.Tensor] = None, algo: int = ALGO_AUTO):
+    """One stage under a slice configuration: route X with every E-output router, then the routed outputs."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2
+    T, K = X.shape
+    n = len(Ns)
+    dev = X.device
+    if routing is None:
+        routing = [(torch.empty(T, dtype=torch.int32, device=dev), torch.empty(T, dtype=torch.int32, device=dev),
+                    torch.empty(N_PRECISIONS + 1, dtype=torch.int32, device=dev)) for _ in range(n)]
+    if Y is None:
+        Y = [torch.empty((T, N), dtype=torch.float32, device=dev) for N in Ns]
+    if ws_route is None:
+        ws_route = route_workspace(T, K, dev)
+    if ws_linear is None:
+        ws_linear = linear_workspace(T, max(Ns), K, dev)
+    n_arr = (ctypes.c_int64 * n)(*[int(N) for N in Ns])
+    _check(load().mbq_routed_linear_group_cfg(
+        _ptr(X), T, K, n, _ptr_array(Wr), _ptr_array(br), ctypes.byref(cfg), _ptr_array(blobs), n_arr,
+        _ptr_array([r[0] for r in routing]), _ptr_array([r[1] for r in routing]),
+        _ptr_array([r[2] for r in routing]), _ptr_array(Y), _ptr(ws_route), ws_route.numel(), _ptr(ws_linear),
+        ws_linear.numel(), algo, _stream()), "mbq_routed_linear_group_cfg")
     return [tuple(r) for r in routing], list(Y)
 
 

@@ -78,6 +78,45 @@ int device_compute_units() {
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// The slice configuration a call runs under (the *_cfg entry points set it for the duration of the call they forward
+// to; everything else sees the default: four slices of two bits).
+static thread_local const RouteView* t_view = &kDefaultView;
+struct ViewScope {
+  const RouteView* saved;
+  explicit ViewScope(const RouteView* v) : saved(t_view) { t_view = v; }
+  ~ViewScope() { t_view = saved; }
+};
+// cfg -> view; the configurations this library runs are those whose slices end on the blob's 2-bit digits
+static bool make_view(const mbq_config* cfg, RouteView* v, const char* who) {
+  if (!cfg) {
+    set_error("%s: null configuration", who);
+    return false;
+  }
+  if (cfg->n_slices < 1 || cfg->n_slices > MBQ_MAX_SLICES) {
+    set_error("%s: %d slices, supported 1..%d", who, cfg->n_slices, MBQ_MAX_SLICES);
+    return false;
+  }
+  if (cfg->group != kGroup) {
+    set_error("%s: group size %d, only %d is supported", who, cfg->group, kGroup);
+    return false;
+  }
+  int bits = 0;
+  *v = kDefaultView;
+  v->P = cfg->n_slices;
+  for (int e = 0; e < cfg->n_slices; ++e) {
+    const int b = cfg->slice_bits[e];
+    if (b < 2 || (b & 1) != 0 || bits + b > 2 * kSlices) {
+      set_error("%s: slice %d has %d bits; supported: even widths that add up to at most %d bits", who, e, b,
+                2 * kSlices);
+      return false;
+    }
+    bits += b;
+    v->digits[e] = bits / 2 - 1;
+  }
+  for (int e = cfg->n_slices; e < MBQ_N_PRECISIONS; ++e) v->digits[e] = v->digits[cfg->n_slices - 1];
+  return true;
+}
+
 // 17..64 tokens (and one token tile when the FP4-operand kernels are switched off): the register-stationary
 // kernel, except for matrices with few row tiles (see dispatch_linear)
 static bool takes_stationary_kernel(int64_t T, const Shape& sh) {
@@ -305,8 +344,8 @@ mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, c
                      int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
                      size_t ws_bytes, void* stream) {
   ApiScope scope;
-  if (P != MBQ_N_PRECISIONS) {
-    set_error("mbq_route: P=%d, only %d precisions are supported", P, MBQ_N_PRECISIONS);
+  if (P != t_view->P) {
+    set_error("mbq_route: P=%d, the slice configuration has %d precisions", P, t_view->P);
     return MBQ_ERR_BAD_SHAPE;
   }
   if (T < 0 || K <= 0 || K % kGroup != 0 || T > (int64_t)1 << 24 || K > (int64_t)1 << 24) {
@@ -321,7 +360,7 @@ mbq_status mbq_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, c
     set_error("mbq_route: workspace too small or misaligned (%zu < %zu)", ws_bytes, mbq_route_workspace_bytes(T, K));
     return MBQ_ERR_WORKSPACE;
   }
-  return launch_route(X, T, K, Wr, br, prec, perm, offsets, logits, ws, (hipStream_t)stream);
+  return launch_route(X, T, K, Wr, br, prec, perm, offsets, logits, ws, (hipStream_t)stream, *t_view);
 }
 
 mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, const float* const* Wr_host,
@@ -329,8 +368,8 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
                            int32_t* const* perm_host, int32_t* const* offsets_host, void* ws, size_t ws_bytes,
                            void* stream) {
   ApiScope scope;
-  if (P != MBQ_N_PRECISIONS) {
-    set_error("mbq_route_group: P=%d, only %d precisions are supported", P, MBQ_N_PRECISIONS);
+  if (P != t_view->P) {
+    set_error("mbq_route_group: P=%d, the slice configuration has %d precisions", P, t_view->P);
     return MBQ_ERR_BAD_SHAPE;
   }
   if (n_proj < 1 || n_proj > MBQ_MAX_GROUP) {
@@ -357,7 +396,7 @@ mbq_status mbq_route_group(const uint16_t* X, int64_t T, int64_t K, int n_proj, 
     return MBQ_ERR_WORKSPACE;
   }
   return launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr, ws,
-                            (hipStream_t)stream, nullptr, 0, nullptr, false);
+                            (hipStream_t)stream, nullptr, 0, nullptr, false, *t_view);
 }
 
 size_t mbq_route_mlp_workspace_bytes(int64_t T, int64_t K, int H) {
@@ -419,7 +458,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
   // the fused form: the router launch also prepares the activations of the decode kernel
   if (algo == MBQ_ALGO_AUTO || algo == MBQ_ALGO_DECODE) {
     Shape sh[MBQ_MAX_GROUP];
-    bool ok = n_proj >= 1 && n_proj <= MBQ_MAX_GROUP && N_host && blob_host && Y_host && P == MBQ_N_PRECISIONS &&
+    bool ok = n_proj >= 1 && n_proj <= MBQ_MAX_GROUP && N_host && blob_host && Y_host && P == t_view->P &&
               T >= 1 && K > 0 && K % kGroup == 0 && X && aligned(X, 16) && Wr_host && br_host && prec_host &&
               perm_host && offsets_host && ws_route && aligned(ws_route, 256) &&
               ws_route_bytes >= mbq_route_workspace_bytes(T, K) && ws_linear && aligned(ws_linear, 256);
@@ -432,7 +471,8 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
       ZeroList zl;
       decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
       mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
-                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl, true);
+                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl, true,
+                                         *t_view);
       if (st != MBQ_OK) return st;
       return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream,
                                      perm_host, offsets_host);
@@ -449,7 +489,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
         ZeroList zl;  // outputs the linear launch adds into: cleared by a plane of the router launch
         decode16_zero_list(T, n_proj, sh, Y_host, &zl);
         mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
-                                           nullptr, ws_route, (hipStream_t)stream, nullptr, 0, &zl, true);
+                                           nullptr, ws_route, (hipStream_t)stream, nullptr, 0, &zl, true, *t_view);
         if (st != MBQ_OK) return st;
         return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host,
                                             (hipStream_t)stream, perm_host, offsets_host);
@@ -579,6 +619,95 @@ mbq_status mbq_linear_group(const uint16_t* X, int64_t T, int64_t K, int n_proj,
     if (st != MBQ_OK) return st;
   }
   return MBQ_OK;
+}
+
+// ---- other slice configurations (Sec. 4.1 general E and b_e; App. C.1 slice_bits_list) ---------------------------
+// The blob holds the eight-bit code of every weight as four base-4 digits whatever the configuration: a
+// configuration whose slices end on digit boundaries cuts the same code at other places (a 4-bit slice with the
+// centred zero point 8 and scale s/16 IS two 2-bit slices with zero point 2 and scales s/4, s/16), and its first-slice
+// parameters are the stored ones moved by a power of two.  So only the router (how many outputs, which digit count
+// each stands for) and the checking helpers know about it.
+
+mbq_status mbq_config_check(const mbq_config* cfg) {
+  RouteView v;
+  return make_view(cfg, &v, "mbq_config_check") ? MBQ_OK : MBQ_ERR_BAD_SHAPE;
+}
+
+int mbq_config_bits(const mbq_config* cfg, int p) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_config_bits") || p < 0 || p >= v.P) return -1;
+  return 2 * (v.digits[p] + 1);
+}
+
+int mbq_config_digit_precision(const mbq_config* cfg, int p) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_config_digit_precision") || p < 0 || p >= v.P) return -1;
+  return v.digits[p];
+}
+
+mbq_status mbq_encode_cfg(const float* W, int64_t N, int64_t K, const mbq_config* cfg, void* blob, void* stream) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_encode_cfg")) return MBQ_ERR_BAD_SHAPE;
+  return mbq_encode(W, N, K, blob, stream);
+}
+
+mbq_status mbq_unpack_cfg(const void* blob, int64_t N, int64_t K, const mbq_config* cfg, uint8_t* codes,
+                          float* scale, float* zero, void* stream) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_unpack_cfg")) return MBQ_ERR_BAD_SHAPE;
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!blob || !aligned(blob, 256)) {
+    set_error("mbq_unpack_cfg: blob must be non-null and 256-byte aligned");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_unpack_view(blob, sh, v, codes, scale, zero, (hipStream_t)stream);
+}
+
+mbq_status mbq_dequant_cfg(const void* blob, int64_t N, int64_t K, const mbq_config* cfg, int p, float* What,
+                           void* stream) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_dequant_cfg")) return MBQ_ERR_BAD_SHAPE;
+  if (p < 0 || p >= v.P) {
+    set_error("mbq_dequant_cfg: precision index %d outside 0..%d", p, v.P - 1);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return mbq_dequant(blob, N, K, v.digits[p], What, stream);
+}
+
+mbq_status mbq_route_cfg(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
+                         const mbq_config* cfg, int32_t* prec, int32_t* perm, int32_t* offsets, double* logits,
+                         void* ws, size_t ws_bytes, void* stream) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_route_cfg")) return MBQ_ERR_BAD_SHAPE;
+  ViewScope scope(&v);
+  return mbq_route(X, T, K, Wr, br, v.P, prec, perm, offsets, logits, ws, ws_bytes, stream);
+}
+
+mbq_status mbq_route_group_cfg(const uint16_t* X, int64_t T, int64_t K, int n_proj, const float* const* Wr_host,
+                               const float* const* br_host, const mbq_config* cfg, int32_t* const* prec_host,
+                               int32_t* const* perm_host, int32_t* const* offsets_host, void* ws, size_t ws_bytes,
+                               void* stream) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_route_group_cfg")) return MBQ_ERR_BAD_SHAPE;
+  ViewScope scope(&v);
+  return mbq_route_group(X, T, K, n_proj, Wr_host, br_host, v.P, prec_host, perm_host, offsets_host, ws, ws_bytes,
+                         stream);
+}
+
+mbq_status mbq_routed_linear_group_cfg(const uint16_t* X, int64_t T, int64_t K, int n_proj,
+                                       const float* const* Wr_host, const float* const* br_host,
+                                       const mbq_config* cfg, const void* const* blob_host, const int64_t* N_host,
+                                       int32_t* const* prec_host, int32_t* const* perm_host,
+                                       int32_t* const* offsets_host, float* const* Y_host, void* ws_route,
+                                       size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes, int algo,
+                                       void* stream) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_routed_linear_group_cfg")) return MBQ_ERR_BAD_SHAPE;
+  ViewScope scope(&v);
+  return mbq_routed_linear_group(X, T, K, n_proj, Wr_host, br_host, v.P, blob_host, N_host, prec_host, perm_host,
+                                 offsets_host, Y_host, ws_route, ws_route_bytes, ws_linear, ws_linear_bytes, algo,
+                                 stream);
 }
 
 }  // extern "C"

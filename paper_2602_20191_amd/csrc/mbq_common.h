@@ -70,19 +70,31 @@ struct ZeroList {
   long long n[MBQ_MAX_GROUP];  // floats
 };
 
+// How a router's outputs map onto the blob's 2-bit digits (Sec. 4.1 with other slice widths, App. C.1): the router has
+// P outputs (one per slice of the configuration) and output q stands for the first digits[q] + 1 base-4 digits of the
+// eight-bit code.  The linear kernels only ever see digit precisions.  Default: four outputs, digits = {0, 1, 2, 3}.
+struct RouteView {
+  int P;
+  int digits[MBQ_N_PRECISIONS];
+};
+constexpr RouteView kDefaultView = {MBQ_N_PRECISIONS, {0, 1, 2, 3}};
+
 // ---- kernels' host launchers (each enqueues on `stream`, returns a status) ------
 mbq_status launch_encode(const float* W, const Shape& sh, void* blob, const float* ext_scale, const float* ext_zero,
                          hipStream_t stream);
 mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* codes, float* scale, float* zero,
                          hipStream_t stream);
 mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream);
+mbq_status launch_unpack_view(const void* blob, const Shape& sh, const RouteView& view, uint8_t* codes, float* scale,
+                              float* zero, hipStream_t stream);
 mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
                         int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
-                        hipStream_t stream);
+                        hipStream_t stream, const RouteView& view = kDefaultView);
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
-                              void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket);
+                              void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket,
+                              const RouteView& view = kDefaultView);
 bool route_can_carry_prep(int64_t T);
 bool route_defers_sort(int64_t T);
 mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,

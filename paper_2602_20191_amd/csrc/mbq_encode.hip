@@ -126,6 +126,35 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
   }
 }
 
+// The blob seen through a slice configuration (see RouteView): slice q of the configuration is the run of base-4
+// digits after those of slice q - 1, merged into one code of b_q bits; its first-slice parameters are the blob's,
+// moved by the power of two between a 2-bit and a b_0-bit first slice (exact).
+__global__ __launch_bounds__(256) void unpack_view_kernel(const uint32_t* __restrict__ codes, size_t slice_words,
+                                                          const float2* __restrict__ meta, int64_t N, int64_t K,
+                                                          int NT, int KB, const RouteView view,
+                                                          uint8_t* __restrict__ out_codes, float* __restrict__ scale,
+                                                          float* __restrict__ zero) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= N * K) return;
+  const int64_t n = idx / K, k = idx % K;
+  if (out_codes) {
+    const size_t w = code_word(NT, KB, n, k);
+    int e = 0;
+    for (int q = 0; q < view.P; ++q) {
+      uint32_t c = 0u;
+      for (; e <= view.digits[q]; ++e) c = c * 4u + ((codes[e * slice_words + w] >> code_bit(e, k)) & 3u);
+      out_codes[(size_t)q * N * K + idx] = (uint8_t)c;
+    }
+  }
+  if ((k % kGroup) == 0) {
+    const int g = (int)(k / kGroup);
+    const float2 m = meta[meta_index(KB, n, g)];
+    const float up = (float)(1 << (2 * view.digits[0]));  // 2^(b_0 - 2)
+    if (scale) scale[n * (K / kGroup) + g] = m.x / up;
+    if (zero) zero[n * (K / kGroup) + g] = m.y * up;
+  }
+}
+
 __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict__ codes, size_t slice_words,
                                                       const float2* __restrict__ meta, int64_t N, int64_t K,
                                                       int NT, int KB, int p, float* __restrict__ What) {
@@ -158,6 +187,16 @@ mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* out_codes, 
   hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes,
                      sh.slice_words, meta, sh.N, sh.K, sh.NT, sh.KB, out_codes, scale, zero);
   return hip_status(hipGetLastError(), "unpack_kernel launch");
+}
+
+mbq_status launch_unpack_view(const void* blob, const Shape& sh, const RouteView& view, uint8_t* out_codes,
+                              float* scale, float* zero, hipStream_t stream) {
+  const uint32_t* codes = reinterpret_cast<const uint32_t*>(blob);
+  const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
+  const int64_t total = sh.N * sh.K;
+  hipLaunchKernelGGL(unpack_view_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes,
+                     sh.slice_words, meta, sh.N, sh.K, sh.NT, sh.KB, view, out_codes, scale, zero);
+  return hip_status(hipGetLastError(), "unpack_view_kernel launch");
 }
 
 mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream) {

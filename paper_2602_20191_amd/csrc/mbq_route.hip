@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
                                                     const float* __restrict__ Wr, const float* __restrict__ br,
                                                     int32_t* prec, int32_t* __restrict__ perm,
                                                     int32_t* __restrict__ offsets, double* __restrict__ logits,
-                                                    unsigned int* __restrict__ ticket) {
+                                                    unsigned int* __restrict__ ticket, const RouteView view) {
   const int64_t tok0 = (int64_t)blockIdx.x * TPW;
   const int tid = threadIdx.x;
   double acc[TPW][kP];
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
     float w[kP][8];
 #pragma unroll
     for (int q = 0; q < kP; ++q) {
-      const float4* src = reinterpret_cast<const float4*>(Wr + (int64_t)q * K + k);
+      const float4* src = reinterpret_cast<const float4*>(Wr + (int64_t)min(q, view.P - 1) * K + k);  // rows past P: unused
       float4 a = src[0], b = src[1];
       w[q][0] = a.x; w[q][1] = a.y; w[q][2] = a.z; w[q][3] = a.w;
       w[q][4] = b.x; w[q][5] = b.y; w[q][6] = b.z; w[q][7] = b.w;
@@ -160,14 +160,16 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
     int arg = 0;
 #pragma unroll
     for (int q = 0; q < kP; ++q) {
-      const double s = ((red[0][tid][q] + red[1][tid][q]) + (red[2][tid][q] + red[3][tid][q])) + (double)br[q];
-      if (logits) logits[(tok0 + tid) * kP + q] = s;
-      if (q == 0 || s > best) {  // strict: the first maximum wins ties
-        best = s;
-        arg = q;
+      if (q < view.P) {
+        const double s = ((red[0][tid][q] + red[1][tid][q]) + (red[2][tid][q] + red[3][tid][q])) + (double)br[q];
+        if (logits) logits[(tok0 + tid) * view.P + q] = s;
+        if (q == 0 || s > best) {  // strict: the first maximum wins ties
+          best = s;
+          arg = q;
+        }
       }
     }
-    prec[tok0 + tid] = arg;
+    prec[tok0 + tid] = view.digits[arg];
     __threadfence();  // publish this workgroup's choices before taking a ticket
   }
   __syncthreads();
@@ -200,6 +202,7 @@ struct RouteOut {
 };
 struct RouteGroup {
   RouteOut r[kRouteGroupMax];
+  RouteView view;
 };
 
 //
@@ -235,8 +238,9 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
     float4 wa[kP][2], wb[kP][2];
 #pragma unroll
     for (int q = 0; q < kP; ++q) {
-      const float4* sa = reinterpret_cast<const float4*>(Wr + (int64_t)q * K + k);
-      const float4* sb = reinterpret_cast<const float4*>(Wr + (int64_t)q * K + k2);
+      const int64_t row = min(q, group.view.P - 1);  // rows past P do not exist: re-read the last one, never used
+      const float4* sa = reinterpret_cast<const float4*>(Wr + row * K + k);
+      const float4* sb = reinterpret_cast<const float4*>(Wr + row * K + k2);
       wa[q][0] = sa[0]; wa[q][1] = sa[1];
       wb[q][0] = sb[0]; wb[q][1] = sb[1];
     }
@@ -261,22 +265,25 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
   __syncthreads();
   if (wave != 0) return;
   // lanes 0..3 finish one logit each; every lane then sees all four
+  const int P = group.view.P;
   double mine = 0.0;
-  if (lane < kP) {
+  if (lane < P) {
     mine = ((red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane])) +
            ((red[4][lane] + red[5][lane]) + (red[6][lane] + red[7][lane])) + (double)out.br[lane];
-    if (out.logits) out.logits[(int64_t)tok * kP + lane] = mine;
+    if (out.logits) out.logits[(int64_t)tok * P + lane] = mine;
   }
   double best = __shfl(mine, 0, 64);
   int arg = 0;
 #pragma unroll
   for (int q = 1; q < kP; ++q) {
     const double s = __shfl(mine, q, 64);
-    if (s > best) {  // strict: the first maximum wins ties
+    if (q < P && s > best) {  // strict: the first maximum wins ties
       best = s;
       arg = q;
     }
   }
+  // the router's output q stands for the first digits[q] + 1 digits of the code: that is what the linear kernels use
+  arg = arg == 0 ? group.view.digits[0] : arg == 1 ? group.view.digits[1] : arg == 2 ? group.view.digits[2] : group.view.digits[3];
   if (defer_bucket) {  // the consumer of the precisions sorts the tokens itself: no meeting, the workgroup is done
     if (lane == 0) out.prec[tok] = arg;
     return;
@@ -354,17 +361,17 @@ __global__ __launch_bounds__(64) void bucket_kernel(const int32_t* __restrict__ 
 
 static mbq_status launch_route_one(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
                                    int32_t* prec, int32_t* perm, int32_t* offsets, double* logits,
-                                   unsigned int* ticket, hipStream_t stream) {
+                                   unsigned int* ticket, hipStream_t stream, const RouteView& view) {
   if (T == 0) {
     hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(64), 0, stream, prec, T, perm, offsets);
     return hip_status(hipGetLastError(), "bucket_kernel launch");
   }
   if (T <= 256) {
     hipLaunchKernelGGL(route_kernel<1>, dim3((unsigned)T), dim3(256), 0, stream, X, T, K, Wr, br, prec, perm,
-                       offsets, logits, ticket);
+                       offsets, logits, ticket, view);
   } else {
     hipLaunchKernelGGL(route_kernel<4>, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, stream, X, T, K, Wr, br,
-                       prec, perm, offsets, logits, ticket);
+                       prec, perm, offsets, logits, ticket, view);
   }
   return hip_status(hipGetLastError(), "route_kernel launch");
 }
@@ -383,7 +390,8 @@ bool route_defers_sort(int64_t T) { return route_small_supports(T); }
 mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, const float* const* Wr,
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
-                              void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket) {
+                              void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket,
+                              const RouteView& view) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
   if (T > 0 && !(defer_bucket && route_small_supports(T))) {  // a launch that sorts meets through the counters
     mbq_status st = clear_counters(ws, stream);
@@ -392,6 +400,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
   if (route_small_supports(T)) {
     if (!route_can_carry_prep(T)) prep = nullptr;
     RouteGroup g;
+    g.view = view;
     for (int i = 0; i < kRouteGroupMax; ++i) {
       const int j = i < n ? i : 0;
       g.r[i] = RouteOut{Wr[j], br[j], prec[j], perm[j], offsets[j], logits ? logits[j] : nullptr};
@@ -409,7 +418,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
   }
   for (int i = 0; i < n; ++i) {
     mbq_status st = launch_route_one(X, T, K, Wr[i], br[i], prec[i], perm[i], offsets[i],
-                                     logits ? logits[i] : nullptr, ticket, stream);
+                                     logits ? logits[i] : nullptr, ticket, stream, view);
     if (st != MBQ_OK) return st;
   }
   return MBQ_OK;
@@ -417,10 +426,10 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
 
 mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
                         int32_t* prec, int32_t* perm, int32_t* offsets, double* logits, void* ws,
-                        hipStream_t stream) {
+                        hipStream_t stream, const RouteView& view) {
   double* const lg[1] = {logits};
   return launch_route_group(X, T, K, 1, &Wr, &br, &prec, &perm, &offsets, logits ? lg : nullptr, ws, stream,
-                            nullptr, 0, nullptr, false);
+                            nullptr, 0, nullptr, false, view);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -105,3 +105,35 @@ def test_hooks_and_static_scratch(lib):
     assert lib.mbq_set_knob(4, 0) == 0
     lib.mbq_static_scratch_bytes.restype = ctypes.c_size_t
     assert lib.mbq_static_scratch_bytes() == 8 << 20
+
+
+def test_configuration_checks_need_no_gpu(lib):
+    """Which slice configurations the library runs is decided from the numbers alone."""
+    class Cfg(ctypes.Structure):
+        _fields_ = [("n_slices", ctypes.c_int), ("slice_bits", ctypes.c_int * 4), ("group", ctypes.c_int)]
+
+    def cfg(bits, group=128):
+        c = Cfg()
+        c.n_slices = len(bits)
+        for e, b in enumerate(bits[:4]):
+            c.slice_bits[e] = b
+        c.group = group
+        return c
+
+    lib.mbq_config_check.restype = ctypes.c_int
+    lib.mbq_config_bits.restype = ctypes.c_int
+    lib.mbq_config_digit_precision.restype = ctypes.c_int
+    for bits in [(2, 2, 2, 2), (4, 2, 2), (2, 4, 2), (4, 4), (6, 2), (8,), (2, 2, 2), (2,)]:
+        c = cfg(bits)
+        assert lib.mbq_config_check(ctypes.byref(c)) == 0, bits
+        acc = 0
+        for p, b in enumerate(bits):
+            acc += b
+            assert lib.mbq_config_bits(ctypes.byref(c), p) == acc
+            assert lib.mbq_config_digit_precision(ctypes.byref(c), p) == acc // 2 - 1
+        assert lib.mbq_config_bits(ctypes.byref(c), len(bits)) == -1
+    for bits, group in [((3, 1, 2, 2), 128), ((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((1, 1), 128), ((), 128),
+                        ((2, 2, 2, 2, 2), 128)]:
+        c = cfg(bits, group)
+        assert lib.mbq_config_check(ctypes.byref(c)) == 2, (bits, group)
+    assert lib.mbq_config_check(None) == 2

@@ -1,0 +1,129 @@
+"""GPU parity for other slice configurations (Sec. 4.1 general E and b_e, App. C.1): the library runs them as cuts of
+its eight-bit code; the oracle (oracle/mbq_oracle_general.py) runs the literal recursion with the configuration's own
+widths, scales and zero points.  Encode and routing bit-exact, outputs to the usual bar."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from oracle import mbq_oracle_general as G
+from helpers import assert_output_close, check_bucket, compare_routing, dev, dev_bf16
+from workloads import f32_to_bf16_bits, make_weight
+
+pytestmark = pytest.mark.gpu
+
+CONFIGS = [(2, 2, 2, 2), (4, 2, 2), (2, 4, 2), (2, 2, 4), (4, 4), (6, 2), (2, 6), (8,), (2, 2, 2), (4, 2), (2,)]
+
+
+def tokens(T, K, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, K)).astype(np.float32)
+    x[:, rng.choice(K, max(1, K // 100), replace=False)] *= 20.0
+    return f32_to_bf16_bits(x)
+
+
+@pytest.mark.parametrize("bits", CONFIGS)
+def test_encode_in_the_configurations_terms_is_bit_exact(mbq, bits):
+    N, K = 37, 640
+    print(f"[case] config {bits}: encode / unpack / dequant N={N} K={K}", flush=True)
+    cfg = mbq.Config(bits)
+    mbq.config_check(cfg)
+    W = make_weight(N, K, [61, len(bits), bits[0]], 4.0)
+    blob = mbq.mbq_encode_cfg(dev(W), cfg)
+    assert torch.equal(blob, mbq.mbq_encode(dev(W)))          # one blob for every configuration
+    codes, s0, z0 = G.encode(W, bits, 128)
+    c, s, z = mbq.mbq_unpack_cfg(blob, N, K, cfg)
+    torch.cuda.synchronize()
+    assert np.array_equal(c.cpu().numpy(), np.stack(codes).astype(np.uint8))
+    assert np.array_equal(s.cpu().numpy(), s0) and np.array_equal(z.cpu().numpy(), z0)
+    B = G.cumulative_bits(bits)
+    for p in range(len(bits)):
+        assert mbq.config_bits(cfg, p) == B[p]
+        assert mbq.config_digit_precision(cfg, p) == B[p] // 2 - 1
+        What = mbq.mbq_dequant_cfg(blob, N, K, cfg, p).cpu().numpy()
+        want = G.dequant(codes, s0, z0, bits, 128, p)
+        np.testing.assert_allclose(What, want.astype(np.float32), rtol=0, atol=0)
+    assert mbq.config_bits(cfg, len(bits)) == -1
+
+
+@pytest.mark.parametrize("bits,T,K", [((4, 2, 2), 16, 4096), ((4, 4), 5, 384), ((2, 2, 2), 28, 1280), ((8,), 16, 256),
+                                      ((6, 2), 64, 2048), ((2, 4, 2), 129, 512), ((4, 2, 2), 700, 256),
+                                      ((2, 6), 0, 256)])
+def test_route_with_as_many_outputs_as_slices(mbq, bits, T, K):
+    print(f"[case] config {bits}: route T={T} K={K}", flush=True)
+    cfg = mbq.Config(bits)
+    E = len(bits)
+    rng = np.random.default_rng([T, K, E])
+    xb = tokens(T, K, [T, K, 3])
+    Wr = (rng.standard_normal((E, K)) / np.sqrt(K)).astype(np.float32)
+    br = rng.normal(0, 0.2, size=E).astype(np.float32)
+    S, prec_ref, gap = O.route(xb, Wr, br) if E > 1 else (None, np.zeros(T, dtype=np.int32), np.full(T, np.inf))
+    digits = np.array([mbq.config_digit_precision(cfg, p) for p in range(E)], dtype=np.int32)
+    prec, perm, offsets, logits = mbq.mbq_route_cfg(dev_bf16(xb).reshape(T, K), dev(Wr), dev(br), cfg, want_logits=True)
+    torch.cuda.synchronize()
+    prec, perm, offsets = prec.cpu().numpy(), perm.cpu().numpy(), offsets.cpu().numpy()
+    if T and E > 1:
+        np.testing.assert_allclose(logits.cpu().numpy(), S, rtol=0, atol=1e-10)
+    compare_routing(prec, digits[prec_ref], gap, f"route config {bits} T={T}")
+    check_bucket(prec, perm, offsets)            # buckets are by digit precision: five offsets as ever
+    assert offsets[4] == T
+    assert set(np.unique(prec)).issubset(set(digits.tolist()))
+
+
+@pytest.mark.parametrize("bits,T,K,Ns", [((4, 2, 2), 16, 4096, (272, 130)), ((4, 4), 12, 1280, (96,)),
+                                         ((2, 2, 2), 16, 8192, (64, 48, 80)), ((6, 2), 40, 4096, (272,)),
+                                         ((2, 4, 2), 64, 1024, (130, 64)), ((8,), 16, 512, (100,)),
+                                         ((4, 2, 2), 300, 768, (260,))])
+def test_stage_call_under_a_configuration(mbq, bits, T, K, Ns):
+    """mbq_routed_linear_group_cfg against the general oracle: precisions (as digit counts) bit-exact off the near-tie
+    list, outputs within the bar for the precisions the GPU chose, and identical to route_cfg + linear_group."""
+    print(f"[case] config {bits}: stage T={T} K={K} Ns={Ns}", flush=True)
+    cfg = mbq.Config(bits)
+    E = len(bits)
+    rng = np.random.default_rng([T, K, E, len(Ns)])
+    xb = tokens(T, K, [T, K, 5])
+    X = dev_bf16(xb).reshape(T, K)
+    Wrs = [(rng.standard_normal((E, K)) / np.sqrt(K)).astype(np.float32) for _ in Ns]
+    brs = [rng.normal(0, 0.3, size=E).astype(np.float32) for _ in Ns]
+    Ws = [make_weight(N, K, [67, N, K, i], 4.0) for i, N in enumerate(Ns)]
+    blobs = [mbq.mbq_encode_cfg(dev(W), cfg) for W in Ws]
+    dWr, dbr = [dev(w) for w in Wrs], [dev(b) for b in brs]
+    routing, Ys = mbq.mbq_routed_linear_group_cfg(X, dWr, dbr, cfg, blobs, list(Ns))
+    torch.cuda.synchronize()
+    routing2 = mbq.mbq_route_group_cfg(X, dWr, dbr, cfg)
+    Ys2 = mbq.mbq_linear_group(X, blobs, list(Ns), K, routing2)
+    digits = np.array([mbq.config_digit_precision(cfg, p) for p in range(E)], dtype=np.int32)
+    back = {int(d): p for p, d in enumerate(digits)}
+    for i, N in enumerate(Ns):
+        for a, b in zip(routing[i], routing2[i]):
+            assert torch.equal(a, b), i
+        assert torch.equal(Ys[i], Ys2[i]) or T > 64, i       # (the tiled GEMM may add K parts in any order)
+        prec = routing[i][0].cpu().numpy()
+        if E > 1:
+            _, prec_ref, gap = O.route(xb, Wrs[i], brs[i])
+        else:
+            prec_ref, gap = np.zeros(T, dtype=np.int32), np.full(T, np.inf)
+        compare_routing(prec, digits[prec_ref], gap, f"stage router {i}")
+        check_bucket(prec, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
+        prec_cfg = np.array([back[int(d)] for d in prec], dtype=np.int32)       # the GPU's choice, as config indices
+        codes, s0, z0 = G.encode(Ws[i], bits, 128)
+        want = G.linear(xb, codes, s0, z0, bits, 128, prec_cfg)
+        assert_output_close(Ys[i].cpu().numpy(), want, f"config {bits} matrix {i}")
+        assert_output_close(Ys2[i].cpu().numpy(), want, f"config {bits} matrix {i}, two calls")
+
+
+def test_unsupported_configurations_are_refused(mbq):
+    for bits, group in [((3, 1, 2, 2), 128), ((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((1, 1), 128), ((2, 2, 2, 2, 2), 128),
+                        ((), 128), ((0, 2), 128)]:
+        cfg = mbq.Config(bits[:4], group)
+        cfg.n_slices = len(bits)
+        with pytest.raises(mbq.MbqError):
+            mbq.config_check(cfg)
+    W = dev(make_weight(16, 256, [1], 4.0))
+    with pytest.raises(mbq.MbqError):
+        mbq.mbq_encode_cfg(W, mbq.Config((3, 1, 2, 2)))
+    # P must match the configuration
+    cfg = mbq.Config((4, 2, 2))
+    X = dev_bf16(tokens(4, 256, 1)).reshape(4, 256)
+    with pytest.raises(AssertionError):
+        mbq.mbq_route_cfg(X, dev(np.zeros((4, 256), dtype=np.float32)), dev(np.zeros(4, dtype=np.float32)), cfg)
