@@ -478,10 +478,12 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         extra[f"decode_batch_{T}"] = {"ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
                                       "hbm_gbps_whole_step": byts / (ms * 1e-3) / 1e9,
                                       "launch": f"hipgraph, {per_replay} steps per replay" if graphs else "eager"}
-    # the same block under another slice configuration (Sec. 4.1 general widths): a 4-bit first slice and two 2-bit
-    # residual slices, i.e. three-output routers choosing among 4, 6 and 8 bits, on the SAME packed blobs (a
-    # configuration only says where the eight-bit code may be cut); the routers are rows 1..3 of the block's own
-    for bits in ((4, 2, 2),):
+    # the same block under other slice configurations (Sec. 4.1 general widths), on the SAME packed blobs (a configuration
+    # only says where the eight-bit code may be cut): a 4-bit first slice and two 2-bit residual slices (three-output
+    # routers choosing among 4, 6 and 8 bits; the routers are rows 1..3 of the block's own), and a 3-bit first slice with
+    # residual slices of 1, 2 and 2 bits (tokens at 3, 4, 6 and 8 bits: the decode kernels then feed the two bits of every
+    # code to the matrix cores separately)
+    for bits in ((4, 2, 2), (3, 1, 2, 2)):
         scfg = mbq.Config(bits)
         E = len(bits)
         T = T_main
@@ -519,7 +521,7 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         ms = a.elapsed_time(b2) / (n * per_replay)
         byts, mixes = 0, []
         for l in layers:
-            digits = l["prec"].cpu().numpy()
+            digits = l["prec"].cpu().numpy() >> (1 if mbq.config_counts_bits(scfg) else 0)
             byts += algorithmic_bytes(l["spec"].N, l["spec"].K, T, int(digits.max())) + 4 * E * l["spec"].K
             mixes.append(np.bincount(digits, minlength=4).tolist())
         extra["slice_config_" + "_".join(str(b) for b in bits) + f"_decode_batch_{T}"] = {

@@ -283,19 +283,26 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
  * s_0 = (max - min) / 2^b_0 and z_0 = -min / s_0, slice e >= 1 has s_e = s_(e-1) / 2^b_e and z_e = 2^(b_e - 1)
  * (App. B), precision p uses slices 0..p, B_p = b_0 + ... + b_p bits.
  *
- * What this library runs: 1 <= E <= MBQ_MAX_SLICES, every b_e even, B_(E-1) <= 8, group 128 - e.g. {2,2,2,2} (the
- * default), {4,2,2}, {2,4,2}, {4,4}, {6,2}, {8}, {2,2,2}.  For these the packed blob is THE SAME as the default one:
- * a slice of b bits with the centred zero point 2^(b-1) is b/2 consecutive 2-bit slices with zero point 2 (the codes
- * are the same bits, the scales the same powers of two of s_0), so a configuration only says where the eight-bit
- * code may be cut, and its (s_0, z_0) are the stored ones times 2^(2 - b_0) and 2^(b_0 - 2).  mbq_encode_cfg
- * therefore writes the blob of mbq_encode, and every mbq_linear* call works on it unchanged.
- * What does know the configuration is the router: it has E outputs, and output q stands for B_q / 2 base-4 digits.
- * The prec arrays written by the *_cfg router calls (and read by mbq_linear*) hold that digit count minus one -
- * mbq_config_digit_precision(cfg, q) - which for the default configuration is q itself; perm and offsets (always
- * MBQ_N_PRECISIONS + 1 entries) sort and bucket the tokens by it.
- * Odd widths (a 3-bit first slice, 1-bit residual slices), other group sizes and 16-bit scale / zero-point storage
- * need a blob cut in binary digits and per-group metadata of another size: not built; the calls below refuse them
- * with MBQ_ERR_BAD_SHAPE.
+ * What this library runs: 1 <= E <= MBQ_MAX_SLICES, b_e >= 1, B_(E-1) <= 8, group 128 - e.g. {2,2,2,2} (the default),
+ * {4,2,2}, {4,4}, {6,2}, {8}, {2,2,2}, {3,1,2,2}, {3,2,1}, {4,1,1,2}.  For all of these the packed blob is THE SAME
+ * as the default one: a slice of b bits with the centred zero point 2^(b-1) splits into narrower slices with their
+ * centred zero points without changing a bit (the codes are runs of bits of one eight-bit code, the scales powers of
+ * two of s_0), so a configuration only says where that code may be cut, and its (s_0, z_0) are the stored ones times
+ * 2^(2 - b_0) and 2^(b_0 - 2).  mbq_encode_cfg therefore writes the blob of mbq_encode.
+ * What does know the configuration is the router: it has E outputs, and output q stands for the first B_q bits.
+ *   - Every B_q even ("digit configurations"): the prec arrays written by the *_cfg router calls hold B_q / 2 - 1,
+ *     the number of 2-bit digits minus one, which is what every mbq_linear* call reads (for the default configuration
+ *     that is q itself): all linear kernels run unchanged and at full speed.
+ *   - Some B_q odd ("bit configurations"): the prec arrays hold B_q - 1, and only mbq_linear_cfg and
+ *     mbq_routed_linear_group_cfg understand them.  Up to 16 tokens the decode kernels run them (it hands
+ *     the two bits of every 2-bit code to the matrix cores separately, gated per token: twice the MFMAs, the same
+ *     memory traffic); every other shape takes the one-thread-per-output kernel of MBQ_ALGO_SIMPLE, which is correct
+ *     and slow.
+ * mbq_config_precision_value(cfg, q) is what a prec array holds for the configuration's precision q, and
+ * mbq_config_counts_bits(cfg) says which of the two cases it is.  perm and offsets (always MBQ_N_PRECISIONS + 1
+ * entries) sort and bucket the tokens by the number of 2-bit digits they touch, ceil(B_q / 2) - 1, in both cases.
+ * Other group sizes and 16-bit scale / zero-point storage need per-group metadata of another size: not built; the
+ * calls below refuse them with MBQ_ERR_BAD_SHAPE.
  */
 #define MBQ_MAX_SLICES 4
 typedef struct mbq_config {
@@ -308,8 +315,10 @@ typedef struct mbq_config {
 mbq_status mbq_config_check(const mbq_config* cfg);
 /* B_p, the bits of precision p; -1 for a bad configuration or index. */
 int mbq_config_bits(const mbq_config* cfg, int p);
-/* What the prec arrays hold for the configuration's precision p (B_p / 2 - 1); -1 for a bad configuration or index. */
-int mbq_config_digit_precision(const mbq_config* cfg, int p);
+/* What the prec arrays hold for the configuration's precision p; -1 for a bad configuration or index. */
+int mbq_config_precision_value(const mbq_config* cfg, int p);
+/* 1 if the configuration's prec arrays count bits (some B_p is odd), 0 if digits, -1 for a bad configuration. */
+int mbq_config_counts_bits(const mbq_config* cfg);
 
 /* mbq_encode for a configuration (Sec. 4.1 Eq. 2): checks it, then writes the blob described above. */
 mbq_status mbq_encode_cfg(const float* W, int64_t N, int64_t K, const mbq_config* cfg, void* blob, void* stream);
@@ -328,6 +337,14 @@ mbq_status mbq_dequant_cfg(const void* blob, int64_t N, int64_t K, const mbq_con
  * router, logits (mbq_route_cfg) fp64 [T][E]; argmax over the E outputs, first maximum wins; prec as described
  * above.  Everything else as in the calls without _cfg.
  */
+/*
+ * mbq_linear on precision arrays written under a configuration (see above): a digit configuration is mbq_linear
+ * itself; a bit configuration takes the decode kernels (T <= 16, algo AUTO or DECODE) or the slow checker
+ * kernel.  perm and offsets may be null for a bit configuration (neither kernel reads them).
+ */
+mbq_status mbq_linear_cfg(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
+                          const mbq_config* cfg, const int32_t* prec, const int32_t* perm, const int32_t* offsets,
+                          float* Y, void* ws, size_t ws_bytes, int algo, void* stream);
 mbq_status mbq_route_cfg(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
                          const mbq_config* cfg, int32_t* prec, int32_t* perm, int32_t* offsets, double* logits,
                          void* ws, size_t ws_bytes, void* stream);

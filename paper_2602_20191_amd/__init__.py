@@ -27,7 +27,7 @@ EXPORTS = (
     "mbq_route_mlp", "mbq_route_mlp_workspace_bytes", "mbq_threshold_quantile",
     "mbq_linear_static", "mbq_static_scratch_bytes",
     # other slice configurations
-    "mbq_config_check", "mbq_config_bits", "mbq_config_digit_precision", "mbq_encode_cfg", "mbq_unpack_cfg",
+    "mbq_config_check", "mbq_config_bits", "mbq_config_precision_value", "mbq_config_counts_bits", "mbq_linear_cfg", "mbq_encode_cfg", "mbq_unpack_cfg",
     "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg", "mbq_routed_linear_group_cfg",
     # include/mbq_bench.h: measurement and diagnostic entry points
     "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop", "mbq_bench_linear_group_prepared",
@@ -98,7 +98,9 @@ def load() -> ctypes.CDLL:
     c_cfg = ctypes.POINTER(Config)
     lib.mbq_config_check.argtypes = [c_cfg]
     lib.mbq_config_bits.argtypes = [c_cfg, c_int]
-    lib.mbq_config_digit_precision.argtypes = [c_cfg, c_int]
+    lib.mbq_config_precision_value.argtypes = [c_cfg, c_int]
+    lib.mbq_config_counts_bits.argtypes = [c_cfg]
+    lib.mbq_linear_cfg.argtypes = [c_p, c_i64, c_p, c_i64, c_i64, c_cfg, c_p, c_p, c_p, c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_encode_cfg.argtypes = [c_p, c_i64, c_i64, c_cfg, c_p, c_p]
     lib.mbq_unpack_cfg.argtypes = [c_p, c_i64, c_i64, c_cfg, c_p, c_p, c_p, c_p]
     lib.mbq_dequant_cfg.argtypes = [c_p, c_i64, c_i64, c_cfg, c_int, c_p, c_p]
@@ -106,7 +108,7 @@ def load() -> ctypes.CDLL:
     lib.mbq_route_group_cfg.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_cfg, c_p, c_p, c_p, c_p, c_sz, c_p]
     lib.mbq_routed_linear_group_cfg.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_cfg, c_p, c_p, c_p, c_p, c_p,
                                                 c_p, c_p, c_sz, c_p, c_sz, c_int, c_p]
-    for name in ("mbq_config_check", "mbq_config_bits", "mbq_config_digit_precision", "mbq_encode_cfg",
+    for name in ("mbq_config_check", "mbq_config_bits", "mbq_config_precision_value", "mbq_config_counts_bits", "mbq_linear_cfg", "mbq_encode_cfg",
                  "mbq_unpack_cfg", "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg",
                  "mbq_routed_linear_group_cfg"):
         getattr(lib, name).restype = c_int
@@ -386,8 +388,28 @@ def config_bits(cfg: Config, p: int) -> int:
     return int(load().mbq_config_bits(ctypes.byref(cfg), p))
 
 
-def config_digit_precision(cfg: Config, p: int) -> int:
-    return int(load().mbq_config_digit_precision(ctypes.byref(cfg), p))
+def config_precision_value(cfg: Config, p: int) -> int:
+    """What a prec array holds for the configuration's precision p."""
+    return int(load().mbq_config_precision_value(ctypes.byref(cfg), p))
+
+
+def config_counts_bits(cfg: Config) -> bool:
+    return int(load().mbq_config_counts_bits(ctypes.byref(cfg))) == 1
+
+
+def mbq_linear_cfg(X: torch.Tensor, blob: torch.Tensor, N: int, K: int, cfg: Config, prec: torch.Tensor,
+                   perm: Optional[torch.Tensor] = None, offsets: Optional[torch.Tensor] = None,
+                   Y: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                   algo: int = ALGO_AUTO) -> torch.Tensor:
+    """mbq_linear on precision arrays written under a configuration."""
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, N), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = linear_workspace(T, N, K, X.device)
+    _check(load().mbq_linear_cfg(_ptr(X), T, _ptr(blob), N, K, ctypes.byref(cfg), _ptr(prec), _ptr(perm),
+                                 _ptr(offsets), _ptr(Y), _ptr(ws), ws.numel(), algo, _stream()), "mbq_linear_cfg")
+    return Y
 
 
 def mbq_encode_cfg(W: torch.Tensor, cfg: Config, blob: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -86,7 +86,7 @@ struct ViewScope {
   explicit ViewScope(const RouteView* v) : saved(t_view) { t_view = v; }
   ~ViewScope() { t_view = saved; }
 };
-// cfg -> view; the configurations this library runs are those whose slices end on the blob's 2-bit digits
+// cfg -> view; the configurations this library runs are those that cut the blob's eight-bit code
 static bool make_view(const mbq_config* cfg, RouteView* v, const char* who) {
   if (!cfg) {
     set_error("%s: null configuration", who);
@@ -101,19 +101,27 @@ static bool make_view(const mbq_config* cfg, RouteView* v, const char* who) {
     return false;
   }
   int bits = 0;
+  bool odd = false;
   *v = kDefaultView;
   v->P = cfg->n_slices;
   for (int e = 0; e < cfg->n_slices; ++e) {
     const int b = cfg->slice_bits[e];
-    if (b < 2 || (b & 1) != 0 || bits + b > 2 * kSlices) {
-      set_error("%s: slice %d has %d bits; supported: even widths that add up to at most %d bits", who, e, b,
+    if (b < 1 || bits + b > 2 * kSlices) {
+      set_error("%s: slice %d has %d bits; supported: widths of at least 1 bit that add up to at most %d bits", who, e, b,
                 2 * kSlices);
       return false;
     }
     bits += b;
-    v->digits[e] = bits / 2 - 1;
+    v->bits[e] = bits;
+    v->digits[e] = (bits + 1) / 2 - 1;
+    odd = odd || (bits & 1) != 0;
   }
-  for (int e = cfg->n_slices; e < MBQ_N_PRECISIONS; ++e) v->digits[e] = v->digits[cfg->n_slices - 1];
+  for (int e = cfg->n_slices; e < MBQ_N_PRECISIONS; ++e) {
+    v->bits[e] = v->bits[cfg->n_slices - 1];
+    v->digits[e] = v->digits[cfg->n_slices - 1];
+  }
+  v->shift = odd ? 1 : 0;
+  for (int e = 0; e < MBQ_N_PRECISIONS; ++e) v->value[e] = odd ? v->bits[e] - 1 : v->digits[e];
   return true;
 }
 
@@ -455,6 +463,62 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
                                    void* ws_route, size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
                                    int algo, void* stream) {
   ApiScope scope;
+  if (t_view->shift != 0) {
+    // A configuration with an odd cumulative width: the precision arrays count bits.  The loader-wavefront decode
+    // kernels understand that (one token tile); every other shape goes through the slow
+    // one-thread-per-output kernel.  (T = 0: the routing call writes the empty offsets.)
+    if (T == 0)  // the routing call checks its arguments and writes the empty offsets; there is nothing to multiply
+      return mbq_route_group(X, T, K, n_proj, Wr_host, br_host, P, prec_host, perm_host, offsets_host, ws_route,
+                             ws_route_bytes, stream);
+    if (P != t_view->P || n_proj < 1 || n_proj > MBQ_MAX_GROUP || T < 0 || T > (int64_t)1 << 24 || K <= 0 ||
+        K % kGroup != 0 || K > (int64_t)1 << 24) {
+      set_error("mbq_routed_linear_group_cfg: bad sizes (P=%d, n_proj=%d, T=%lld, K=%lld)", P, n_proj, (long long)T,
+                (long long)K);
+      return MBQ_ERR_BAD_SHAPE;
+    }
+    if (algo < MBQ_ALGO_AUTO || algo > MBQ_ALGO_PREFILL || !N_host || !blob_host || !Y_host || !Wr_host || !br_host ||
+        !prec_host || !perm_host || !offsets_host) {
+      set_error("mbq_routed_linear_group_cfg: bad algo or null pointer array");
+      return MBQ_ERR_INVALID_ARG;
+    }
+    for (int i = 0; i < n_proj; ++i)
+      if (!Wr_host[i] || !aligned(Wr_host[i], 16) || !br_host[i] || !prec_host[i] || !perm_host[i] || !offsets_host[i]) {
+        set_error("mbq_routed_linear_group_cfg: null or misaligned router pointer for projection %d", i);
+        return MBQ_ERR_INVALID_ARG;
+      }
+    if (!ws_route || !aligned(ws_route, 256) || ws_route_bytes < mbq_route_workspace_bytes(T, K)) {
+      set_error("mbq_routed_linear_group_cfg: route workspace too small or misaligned");
+      return MBQ_ERR_WORKSPACE;
+    }
+    Shape sh[MBQ_MAX_GROUP];
+    for (int i = 0; i < n_proj; ++i) {
+      if (!make_shape(N_host[i], K, &sh[i])) return MBQ_ERR_BAD_SHAPE;
+      if (!blob_host[i] || !aligned(blob_host[i], 256) || !Y_host[i] || !X || !aligned(X, 16)) {
+        set_error("mbq_routed_linear_group_cfg: null or misaligned pointer for projection %d", i);
+        return MBQ_ERR_INVALID_ARG;
+      }
+      if (!ws_linear || !aligned(ws_linear, 256) || ws_linear_bytes < mbq_linear_workspace_bytes(T, N_host[i], K)) {
+        set_error("mbq_routed_linear_group_cfg: linear workspace too small or misaligned");
+        return MBQ_ERR_WORKSPACE;
+      }
+    }
+    if (algo != MBQ_ALGO_SIMPLE && algo != MBQ_ALGO_PREFILL && knob(3) == 0 && decode_f4_takes_bit_view(T, sh[0]) &&
+        route_can_carry_prep(T)) {
+      ZeroList zl;
+      decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
+      mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
+                                         nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl, true,
+                                         *t_view);
+      if (st != MBQ_OK) return st;
+      return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream,
+                                     perm_host, offsets_host, nullptr, true);
+    }
+    mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr,
+                                       ws_route, (hipStream_t)stream, nullptr, 0, nullptr, false, *t_view);
+    for (int i = 0; st == MBQ_OK && i < n_proj; ++i)
+      st = launch_linear_simple(X, T, blob_host[i], sh[i], prec_host[i], Y_host[i], (hipStream_t)stream, true);
+    return st;
+  }
   // the fused form: the router launch also prepares the activations of the decode kernel
   if (algo == MBQ_ALGO_AUTO || algo == MBQ_ALGO_DECODE) {
     Shape sh[MBQ_MAX_GROUP];
@@ -636,13 +700,19 @@ mbq_status mbq_config_check(const mbq_config* cfg) {
 int mbq_config_bits(const mbq_config* cfg, int p) {
   RouteView v;
   if (!make_view(cfg, &v, "mbq_config_bits") || p < 0 || p >= v.P) return -1;
-  return 2 * (v.digits[p] + 1);
+  return v.bits[p];
 }
 
-int mbq_config_digit_precision(const mbq_config* cfg, int p) {
+int mbq_config_precision_value(const mbq_config* cfg, int p) {
   RouteView v;
-  if (!make_view(cfg, &v, "mbq_config_digit_precision") || p < 0 || p >= v.P) return -1;
-  return v.digits[p];
+  if (!make_view(cfg, &v, "mbq_config_precision_value") || p < 0 || p >= v.P) return -1;
+  return v.value[p];
+}
+
+int mbq_config_counts_bits(const mbq_config* cfg) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_config_counts_bits")) return -1;
+  return v.shift;
 }
 
 mbq_status mbq_encode_cfg(const float* W, int64_t N, int64_t K, const mbq_config* cfg, void* blob, void* stream) {
@@ -672,7 +742,51 @@ mbq_status mbq_dequant_cfg(const void* blob, int64_t N, int64_t K, const mbq_con
     set_error("mbq_dequant_cfg: precision index %d outside 0..%d", p, v.P - 1);
     return MBQ_ERR_INVALID_ARG;
   }
-  return mbq_dequant(blob, N, K, v.digits[p], What, stream);
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!blob || !What || !aligned(blob, 256)) {
+    set_error("mbq_dequant_cfg: null or misaligned pointer");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_dequant_bits(blob, sh, v.bits[p], What, (hipStream_t)stream);
+}
+
+mbq_status mbq_linear_cfg(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
+                          const mbq_config* cfg, const int32_t* prec, const int32_t* perm, const int32_t* offsets,
+                          float* Y, void* ws, size_t ws_bytes, int algo, void* stream) {
+  RouteView v;
+  if (!make_view(cfg, &v, "mbq_linear_cfg")) return MBQ_ERR_BAD_SHAPE;
+  if (v.shift == 0) return mbq_linear(X, T, blob, N, K, prec, perm, offsets, Y, ws, ws_bytes, algo, stream);
+  ApiScope scope;
+  Shape sh;
+  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (T < 0 || T > (int64_t)1 << 24) {
+    set_error("mbq_linear_cfg: bad token count %lld", (long long)T);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (algo < MBQ_ALGO_AUTO || algo > MBQ_ALGO_PREFILL) {
+    set_error("mbq_linear_cfg: unknown algo %d", algo);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (T == 0) return MBQ_OK;
+  if (!X || !blob || !prec || !Y || !aligned(blob, 256) || !aligned(X, 16)) {
+    set_error("mbq_linear_cfg: null or misaligned pointer (X 16-byte, blob 256-byte alignment)");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (!ws || !aligned(ws, 256) || ws_bytes < mbq_linear_workspace_bytes(T, N, K)) {
+    set_error("mbq_linear_cfg: workspace too small or misaligned (%zu < %zu)", ws_bytes,
+              mbq_linear_workspace_bytes(T, N, K));
+    return MBQ_ERR_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (algo != MBQ_ALGO_SIMPLE && algo != MBQ_ALGO_PREFILL && knob(3) == 0 && decode_f4_takes_bit_view(T, sh)) {
+    ZeroList zl;
+    decode_f4_zero_list(T, 1, &sh, &Y, &zl);
+    mbq_status st = launch_decode_f4_prep(X, T, sh.K, sh.KB, ws, zl, s);
+    if (st != MBQ_OK) return st;
+    return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s, nullptr, nullptr, nullptr, true);
+  }
+  return launch_linear_simple(X, T, blob, sh, prec, Y, s, true);
 }
 
 mbq_status mbq_route_cfg(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,

@@ -70,14 +70,21 @@ struct ZeroList {
   long long n[MBQ_MAX_GROUP];  // floats
 };
 
-// How a router's outputs map onto the blob's 2-bit digits (Sec. 4.1 with other slice widths, App. C.1): the router has
-// P outputs (one per slice of the configuration) and output q stands for the first digits[q] + 1 base-4 digits of the
-// eight-bit code.  The linear kernels only ever see digit precisions.  Default: four outputs, digits = {0, 1, 2, 3}.
+// How a router's outputs map onto the blob's eight-bit code (Sec. 4.1 with other slice widths, App. C.1): the router
+// has P outputs (one per slice of the configuration) and output q stands for the first bits[q] bits of the code.
+// digits[q] = base-4 digits that precision touches, minus one (what the tokens are sorted and bucketed by, and what the
+// weight loaders go by).  A precision array holds value[q]: digits[q] when every bits[q] is even (the linear kernels'
+// native precision), bits[q] - 1 otherwise (a token may then stop at the high bit of its last digit; only the kernels
+// that say so understand that); shift = 0 / 1 turns a stored value back into digits.
+// Default: four outputs of 2, 4, 6, 8 bits.
 struct RouteView {
   int P;
+  int bits[MBQ_N_PRECISIONS];
   int digits[MBQ_N_PRECISIONS];
+  int value[MBQ_N_PRECISIONS];
+  int shift;
 };
-constexpr RouteView kDefaultView = {MBQ_N_PRECISIONS, {0, 1, 2, 3}};
+constexpr RouteView kDefaultView = {MBQ_N_PRECISIONS, {2, 4, 6, 8}, {0, 1, 2, 3}, {0, 1, 2, 3}, 0};
 
 // ---- kernels' host launchers (each enqueues on `stream`, returns a status) ------
 mbq_status launch_encode(const float* W, const Shape& sh, void* blob, const float* ext_scale, const float* ext_zero,
@@ -85,6 +92,7 @@ mbq_status launch_encode(const float* W, const Shape& sh, void* blob, const floa
 mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* codes, float* scale, float* zero,
                          hipStream_t stream);
 mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream);
+mbq_status launch_dequant_bits(const void* blob, const Shape& sh, int bits, float* What, hipStream_t stream);
 mbq_status launch_unpack_view(const void* blob, const Shape& sh, const RouteView& view, uint8_t* codes, float* scale,
                               float* zero, hipStream_t stream);
 mbq_status launch_route(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,
@@ -105,7 +113,7 @@ size_t route_mlp_workspace_bytes(int64_t T, int H);
 mbq_status launch_threshold_quantile(const double* scores, int64_t T, long long k, double* delta_out,
                                      hipStream_t stream);
 mbq_status launch_linear_simple(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
-                                const int32_t* prec, float* Y, hipStream_t stream);
+                                const int32_t* prec, float* Y, hipStream_t stream, bool bit_view = false);
 mbq_status launch_linear_decode(const uint16_t* X, int64_t T, const void* blob, const Shape& sh,
                                 const int32_t* perm, const int32_t* offsets, float* Y, void* ws,
                                 hipStream_t stream);
@@ -168,7 +176,10 @@ mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB
 // perm/offsets (arrays of n, or null): the launch also sorts the tokens of every matrix by precision
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
                                    const int32_t* const* prec, float* const* Y, const void* ws, hipStream_t stream,
-                                   int32_t* const* perm, int32_t* const* offsets, unsigned long long* stamps = nullptr);
+                                   int32_t* const* perm, int32_t* const* offsets, unsigned long long* stamps = nullptr,
+                                   bool bit_view = false);
+// bit_view (the precision arrays hold bits - 1, see RouteView) is understood by the one-token-tile kernels only
+bool decode_f4_takes_bit_view(int64_t T, const Shape& sh);
 // timeline build of the ring kernel: workgroups it launches at most, and 8-byte slots each of them writes
 int decode_f4_timeline_workgroups();
 int decode_f4_timeline_slots();

@@ -126,9 +126,9 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
   }
 }
 
-// The blob seen through a slice configuration (see RouteView): slice q of the configuration is the run of base-4
-// digits after those of slice q - 1, merged into one code of b_q bits; its first-slice parameters are the blob's,
-// moved by the power of two between a 2-bit and a b_0-bit first slice (exact).
+// The blob seen through a slice configuration (see RouteView): slice q of the configuration is the run of bits of the
+// eight-bit code after those of slice q - 1; its first-slice parameters are the blob's, moved by the power of two
+// between a 2-bit and a b_0-bit first slice (exact).
 __global__ __launch_bounds__(256) void unpack_view_kernel(const uint32_t* __restrict__ codes, size_t slice_words,
                                                           const float2* __restrict__ meta, int64_t N, int64_t K,
                                                           int NT, int KB, const RouteView view,
@@ -139,33 +139,37 @@ __global__ __launch_bounds__(256) void unpack_view_kernel(const uint32_t* __rest
   const int64_t n = idx / K, k = idx % K;
   if (out_codes) {
     const size_t w = code_word(NT, KB, n, k);
-    int e = 0;
+    uint32_t I = 0u;  // the eight-bit code
+#pragma unroll
+    for (int e = 0; e < kSlices; ++e) I = I * 4u + ((codes[e * slice_words + w] >> code_bit(e, k)) & 3u);
+    int before = 0;
     for (int q = 0; q < view.P; ++q) {
-      uint32_t c = 0u;
-      for (; e <= view.digits[q]; ++e) c = c * 4u + ((codes[e * slice_words + w] >> code_bit(e, k)) & 3u);
-      out_codes[(size_t)q * N * K + idx] = (uint8_t)c;
+      const int width = view.bits[q] - before;
+      out_codes[(size_t)q * N * K + idx] = (uint8_t)((I >> (2 * kSlices - view.bits[q])) & ((1u << width) - 1u));
+      before = view.bits[q];
     }
   }
   if ((k % kGroup) == 0) {
     const int g = (int)(k / kGroup);
     const float2 m = meta[meta_index(KB, n, g)];
-    const float up = (float)(1 << (2 * view.digits[0]));  // 2^(b_0 - 2)
-    if (scale) scale[n * (K / kGroup) + g] = m.x / up;
-    if (zero) zero[n * (K / kGroup) + g] = m.y * up;
+    if (scale) scale[n * (K / kGroup) + g] = __builtin_ldexpf(m.x, 2 - view.bits[0]);
+    if (zero) zero[n * (K / kGroup) + g] = __builtin_ldexpf(m.y, view.bits[0] - 2);
   }
 }
 
 __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict__ codes, size_t slice_words,
                                                       const float2* __restrict__ meta, int64_t N, int64_t K,
-                                                      int NT, int KB, int p, float* __restrict__ What) {
+                                                      int NT, int KB, int bits, float* __restrict__ What) {
+  // the first `bits` bits of the eight-bit code: W = s0 / 2^(bits - 2) ((I - 2^(bits - 2) z0) + 0.5)
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= N * K) return;
   const int64_t n = idx / K, k = idx % K;
   const size_t w = code_word(NT, KB, n, k);
   int I = 0;
-  for (int e = 0; e <= p; ++e) I = I * 4 + (int)((codes[e * slice_words + w] >> code_bit(e, k)) & 3u);
+  for (int e = 0; e < kSlices; ++e) I = I * 4 + (int)((codes[e * slice_words + w] >> code_bit(e, k)) & 3u);
+  I >>= 2 * kSlices - bits;
   const float2 m = meta[meta_index(KB, n, (int)(k / kGroup))];
-  const double pw = (double)(1 << (2 * p));
+  const double pw = __builtin_ldexp(1.0, bits - 2);
   What[idx] = (float)(((double)m.x / pw) * (((double)I - pw * (double)m.y) + 0.5));
 }
 
@@ -200,11 +204,15 @@ mbq_status launch_unpack_view(const void* blob, const Shape& sh, const RouteView
 }
 
 mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream) {
+  return launch_dequant_bits(blob, sh, 2 * (p + 1), What, stream);
+}
+
+mbq_status launch_dequant_bits(const void* blob, const Shape& sh, int bits, float* What, hipStream_t stream) {
   const uint32_t* codes = reinterpret_cast<const uint32_t*>(blob);
   const float2* meta = reinterpret_cast<const float2*>(reinterpret_cast<const char*>(blob) + sh.meta_offset);
   const int64_t total = sh.N * sh.K;
   hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes,
-                     sh.slice_words, meta, sh.N, sh.K, sh.NT, sh.KB, p, What);
+                     sh.slice_words, meta, sh.N, sh.K, sh.NT, sh.KB, bits, What);
   return hip_status(hipGetLastError(), "dequant_kernel launch");
 }
 

@@ -30,7 +30,8 @@ struct Group {
   Proj p[MBQ_MAX_GROUP];
   int n;
   int tiles;
-  unsigned long long* stamps;  // timeline build of the kernel only (see decode_f4_ring_kernel): where the stamps go
+  unsigned long long* stamps;  // timeline build of the kernel only: where the stamps go
+  int bit_view;                // the precision arrays hold bits - 1 instead of digit precisions (see RouteView)
 };
 
 template <int R>

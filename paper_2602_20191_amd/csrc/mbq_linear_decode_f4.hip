@@ -27,6 +27,8 @@
 // the packed weights into an LDS ring, eight wavefronts with the activations in registers do the arithmetic);
 // beyond, decode_f4_stream_kernel below, which streams the activations along with the weights.  This file also
 // holds the activation preparation launch and the launcher that picks the kernel.
+#include <type_traits>
+
 #include "mbq_f4_kernel.h"
 
 namespace mbq {
@@ -46,6 +48,9 @@ struct StreamItem {
 };
 }  // namespace f4
 
+// kBits: the precision arrays hold bits - 1 (see RouteView); as in the loader-wavefront kernel the two bits of a code
+// then go to the matrix cores as two operands with their own gates.
+template <bool kBits>
 __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __restrict__ prep, int T, int KB,
                                                                const f4::Group g) {
   using namespace f4;
@@ -106,15 +111,18 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
   load_first((int)blockIdx.x, wave, A);
 
   int pmax[MBQ_MAX_GROUP];
+  auto digits_of = [](int stored) { return kBits ? (stored >> 1) : stored; };  // (-1 stays -1)
 #pragma unroll
-  for (int j = 0; j < MBQ_MAX_GROUP; ++j)
-    pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
+  for (int j = 0; j < MBQ_MAX_GROUP; ++j) {
+    const int d = digits_of(pl[j]);
+    pmax[j] = (__ballot(d == 3) != 0ull) ? 3 : (__ballot(d == 2) != 0ull) ? 2 : (__ballot(d == 1) != 0ull) ? 1 : 0;
+  }
   auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
   load_rest((int)blockIdx.x, wave, pmax_of(proj_of((int)blockIdx.x)), A);
   if (blockIdx.x == 0 && wave == 0) {
 #pragma unroll
     for (int j = 0; j < MBQ_MAX_GROUP; ++j)
-      if (j < g.n && g.p[j].perm != nullptr) bucket_by_wave(pl[j], lane, g.p[j].perm, g.p[j].offsets);
+      if (j < g.n && g.p[j].perm != nullptr) bucket_by_wave(digits_of(pl[j]), lane, g.p[j].perm, g.p[j].offsets);
   }
 
   uint32_t nib_mask = 0x33333333u;
@@ -144,30 +152,54 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
     const int pm = pmax_of(j);
     const int plv = j == 0 ? pl[0] : j == 1 ? pl[1] : j == 2 ? pl[2] : pl[3];
     const int pa = __shfl(plv, m, 64);
-    const uint32_t gate = (pa >= 3) ? 0xFFFFFFFFu : (pa == 2) ? 0x00FFFFFFu : (pa == 1) ? 0x0000FFFFu
-                          : (pa == 0) ? 0x000000FFu : 0u;
+    auto gate_of = [](int d) {  // slices 0..d
+      return (d >= 3) ? 0xFFFFFFFFu : (d == 2) ? 0x00FFFFFFu : (d == 1) ? 0x0000FFFFu : (d == 0) ? 0x000000FFu : 0u;
+    };
+    // kBits: pa + 1 bits; the high bit of digit e counts from 2 e + 1 bits on, its low bit from 2 e + 2
+    const uint32_t gate = kBits ? gate_of(pa >= 0 ? pa >> 1 : -1) : gate_of(pa);
+    const uint32_t gate_lo = kBits ? gate_of(pa >= 0 ? ((pa + 1) >> 1) - 1 : -1) : 0u;
     float kp[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int p = __shfl(plv, 4 * kq + i, 64);
-      kp[i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
+      if constexpr (kBits) kp[i] = __builtin_ldexpf(1.f, -max(p, 0));  // 2^(1 - bits)
+      else kp[i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
     }
     const Item& I = cu.w;
     const int sa = (int)(((uint32_t)cu.scale * 0x01010101u) & gate);
     const int sa2 = (int)(((uint32_t)max(cu.scale - kPieceShift, 0) * 0x01010101u) & gate);
-    floatx4 D0 = slice_group<0>(cu.xa[0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
-    floatx4 D1 = slice_group<0>(cu.xa[1], I.w[0].z, I.w[0].w, nib_mask, sa, sa2, sb, zero4);
-    if (pm >= 1) {
-      D0 = slice_group<1>(cu.xa[0], I.w[1].x, I.w[1].y, nib_mask, sa, sa2, sb, D0);
-      D1 = slice_group<1>(cu.xa[1], I.w[1].z, I.w[1].w, nib_mask, sa, sa2, sb, D1);
-    }
-    if (pm >= 2) {
-      D0 = slice_group<2>(cu.xa[0], I.w[2].x, I.w[2].y, nib_mask, sa, sa2, sb, D0);
-      D1 = slice_group<2>(cu.xa[1], I.w[2].z, I.w[2].w, nib_mask, sa, sa2, sb, D1);
-    }
-    if (pm >= 3) {
-      D0 = slice_group<3>(cu.xa[0], I.w[3].x, I.w[3].y, nib_mask, sa, sa2, sb, D0);
-      D1 = slice_group<3>(cu.xa[1], I.w[3].z, I.w[3].w, nib_mask, sa, sa2, sb, D1);
+    floatx4 D0 = zero4, D1 = zero4;
+    if constexpr (kBits) {
+      const int sl = (int)(((uint32_t)cu.scale * 0x01010101u) & gate_lo);
+      const int sl2 = (int)(((uint32_t)max(cu.scale - kPieceShift, 0) * 0x01010101u) & gate_lo);
+      const uint32_t mask_hi = nib_mask & 0xAAAAAAAAu, mask_lo = nib_mask & 0x55555555u;
+      auto planes = [&](auto e_tag) {
+        constexpr int E = decltype(e_tag)::value;
+        if (E > pm) return;
+        D0 = slice_group<E>(cu.xa[0], I.w[E].x, I.w[E].y, mask_hi, sa, sa2, sb, D0);
+        D1 = slice_group<E>(cu.xa[1], I.w[E].z, I.w[E].w, mask_hi, sa, sa2, sb, D1);
+        D0 = slice_group<E>(cu.xa[0], I.w[E].x, I.w[E].y, mask_lo, sl, sl2, sb, D0);
+        D1 = slice_group<E>(cu.xa[1], I.w[E].z, I.w[E].w, mask_lo, sl, sl2, sb, D1);
+      };
+      planes(std::integral_constant<int, 0>{});
+      planes(std::integral_constant<int, 1>{});
+      planes(std::integral_constant<int, 2>{});
+      planes(std::integral_constant<int, 3>{});
+    } else {
+      D0 = slice_group<0>(cu.xa[0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
+      D1 = slice_group<0>(cu.xa[1], I.w[0].z, I.w[0].w, nib_mask, sa, sa2, sb, zero4);
+      if (pm >= 1) {
+        D0 = slice_group<1>(cu.xa[0], I.w[1].x, I.w[1].y, nib_mask, sa, sa2, sb, D0);
+        D1 = slice_group<1>(cu.xa[1], I.w[1].z, I.w[1].w, nib_mask, sa, sa2, sb, D1);
+      }
+      if (pm >= 2) {
+        D0 = slice_group<2>(cu.xa[0], I.w[2].x, I.w[2].y, nib_mask, sa, sa2, sb, D0);
+        D1 = slice_group<2>(cu.xa[1], I.w[2].z, I.w[2].w, nib_mask, sa, sa2, sb, D1);
+      }
+      if (pm >= 3) {
+        D0 = slice_group<3>(cu.xa[0], I.w[3].x, I.w[3].y, nib_mask, sa, sa2, sb, D0);
+        D1 = slice_group<3>(cu.xa[1], I.w[3].z, I.w[3].w, nib_mask, sa, sa2, sb, D1);
+      }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -207,6 +239,7 @@ __global__ __launch_bounds__(512) void decode_f4_stream_kernel(const char* __res
 int f4_compute_units() { return device_compute_units(); }
 
 bool decode_f4_supports(int64_t T, const Shape& sh) { return T >= 1 && T <= 16; }
+bool decode_f4_takes_bit_view(int64_t T, const Shape& sh) { return decode_f4_supports(T, sh); }
 int decode_f4_timeline_workgroups() { return f4_compute_units(); }
 int decode_f4_timeline_slots() { return decode_f4_ws_stamp_wavefronts() * 32; }
 // Parts of the K axis the linear kernel works in (2: it adds into Y, which must be zero when it starts; see
@@ -243,7 +276,8 @@ mbq_status launch_decode_f4_prep(const uint16_t* X, int64_t T, int64_t K, int KB
 // All matrices share K (the caller has checked); T <= 16; ws holds the prepared activations.
 mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, const Shape* shapes,
                                    const int32_t* const* prec, float* const* Y, const void* ws, hipStream_t stream,
-                                   int32_t* const* perm, int32_t* const* offsets, unsigned long long* stamps) {
+                                   int32_t* const* perm, int32_t* const* offsets, unsigned long long* stamps,
+                                   bool bit_view) {
   f4::Group g;
   int tiles = 0;
   for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
@@ -264,6 +298,7 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
   g.n = n;
   g.tiles = tiles;
   g.stamps = stamps;
+  g.bit_view = bit_view ? 1 : 0;
   const Shape& s0 = shapes[0];
   if (decode_f4_ws_supports(s0.KB)) return launch_linear_decode_f4_ws(T, g, s0.KB, ws, stream);
   if (stamps) {
@@ -272,8 +307,12 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
   }
   int grid = f4_compute_units();
   if (grid > tiles) grid = tiles;
-  hipLaunchKernelGGL(decode_f4_stream_kernel, dim3(grid), dim3(512), 0, stream, reinterpret_cast<const char*>(ws), (int)T,
-                     s0.KB, g);
+  if (bit_view)
+    hipLaunchKernelGGL(decode_f4_stream_kernel<true>, dim3(grid), dim3(512), 0, stream,
+                       reinterpret_cast<const char*>(ws), (int)T, s0.KB, g);
+  else
+    hipLaunchKernelGGL(decode_f4_stream_kernel<false>, dim3(grid), dim3(512), 0, stream,
+                       reinterpret_cast<const char*>(ws), (int)T, s0.KB, g);
   return hip_status(hipGetLastError(), "decode_f4_kernel launch");
 }
 

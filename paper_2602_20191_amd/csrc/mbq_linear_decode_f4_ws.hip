@@ -25,6 +25,8 @@
 // Arithmetic, operand layout and the A/B block scales: see mbq_linear_decode_f4.hip.  Paper: Sec. 4.2 Eq. 6 slice by
 // slice; Sec. 4.3 (on-demand slice access: a tile fetches slices 0..max precision of its matrix; fused launch for the
 // projections of a layer).
+#include <type_traits>
+
 #include "mbq_f4_kernel.h"
 
 namespace mbq {
@@ -111,7 +113,11 @@ static_assert(kWsDepth <= 12 && kWsDepth < kWsRing, "60 loads in flight at most;
 static_assert(kWsRing % 8 == 0, "the loader checks the slots in groups of eight");
 }  // namespace f4
 
-template <int CPW, int S, bool kStamp>
+// kBits: the precision arrays hold bits - 1 (1 to 8 bits, see RouteView) instead of digit precisions: a token may stop
+// at the high bit of its last digit, so the two bits of every 2-bit code go to the matrix cores as two operands (the
+// high bit as the FP4 number (c & 2) / 2, the low bit as (c & 1) / 2), each gated by its own A scale byte: twice the
+// MFMAs, same loads.
+template <int CPW, int S, bool kStamp, bool kBits = false>
 __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restrict__ prep, int T, int KB,
                                                            const f4::Group g) {
   using namespace f4;
@@ -195,12 +201,15 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
     return b;
   };
   int pmax[MBQ_MAX_GROUP];
+  auto digits_of = [](int stored) { return kBits ? (stored >> 1) : stored; };  // (-1 stays -1)
   auto find_pmax = [&]() {
 #pragma unroll
     for (int j = 0; j < MBQ_MAX_GROUP; ++j) pl[j] = lane < T ? pl[j] : -1;
 #pragma unroll
-    for (int j = 0; j < MBQ_MAX_GROUP; ++j)
-      pmax[j] = (__ballot(pl[j] == 3) != 0ull) ? 3 : (__ballot(pl[j] == 2) != 0ull) ? 2 : (__ballot(pl[j] == 1) != 0ull) ? 1 : 0;
+    for (int j = 0; j < MBQ_MAX_GROUP; ++j) {
+      const int d = digits_of(pl[j]);
+      pmax[j] = (__ballot(d == 3) != 0ull) ? 3 : (__ballot(d == 2) != 0ull) ? 2 : (__ballot(d == 1) != 0ull) ? 1 : 0;
+    }
   };
   auto pmax_of = [&](int j) { return j == 0 ? pmax[0] : j == 1 ? pmax[1] : j == 2 ? pmax[2] : pmax[3]; };
 
@@ -353,7 +362,7 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
     if (blockIdx.x == 0 && wave == 0) {  // one wavefront of the launch sorts the tokens, where the caller wants them sorted
 #pragma unroll
       for (int j = 0; j < MBQ_MAX_GROUP; ++j)
-        if (j < g.n && g.p[j].perm != nullptr) bucket_by_wave(pl[j], lane, g.p[j].perm, g.p[j].offsets);
+        if (j < g.n && g.p[j].perm != nullptr) bucket_by_wave(digits_of(pl[j]), lane, g.p[j].perm, g.p[j].offsets);
     }
     if (has_work) {
       uint32_t nib_mask = 0x33333333u;
@@ -364,6 +373,7 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
       int cs_t = bid, cs_next_begin = 0, cs_pm = 0, cs_N = 0, cs_col0 = 0;
       float* cs_Y = nullptr;
       uint32_t cs_gate = 0u;  // A scale gate of this lane's token (row m of the A operand): slice e counts iff e <= its precision
+      uint32_t cs_gate_lo = 0u;  // kBits: cs_gate gates the high bits of the codes, this one the low bits
       floatx4 cs_kp = zero4;  // 0.5 - 1.5 q_p of the output rows 4 kq + i
       auto cs_enter = [&]() {
         const int j = proj_of(cs_t);
@@ -374,11 +384,22 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
         cs_next_begin = uniform(next_begin_of(j));
         const int plj = j == 0 ? pl[0] : j == 1 ? pl[1] : j == 2 ? pl[2] : pl[3];
         const int pa = __shfl(plj, m, 64);
-        cs_gate = (pa >= 3) ? 0xFFFFFFFFu : (pa == 2) ? 0x00FFFFFFu : (pa == 1) ? 0x0000FFFFu : (pa == 0) ? 0x000000FFu : 0u;
+        auto gate_of = [](int d) {  // slices 0..d
+          return (d >= 3) ? 0xFFFFFFFFu : (d == 2) ? 0x00FFFFFFu : (d == 1) ? 0x0000FFFFu : (d == 0) ? 0x000000FFu : 0u;
+        };
+        if constexpr (kBits) {
+          // pa + 1 bits: the high bit of digit e counts from 2 e + 1 bits on, its low bit from 2 e + 2
+          cs_gate = gate_of(pa >= 0 ? pa >> 1 : -1);
+          cs_gate_lo = gate_of(pa >= 0 ? ((pa + 1) >> 1) - 1 : -1);
+        } else {
+          cs_gate = gate_of(pa);
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int p = __shfl(plj, 4 * kq + i, 64);
-          cs_kp[i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
+          // the constant of the reconstruction: 2^(1 - bits)
+          if constexpr (kBits) cs_kp[i] = __builtin_ldexpf(1.f, -max(p, 0));
+          else cs_kp[i] = (p >= 3) ? 0.0078125f : (p == 2) ? 0.03125f : (p == 1) ? 0.125f : 0.5f;
         }
       };
       cs_enter();
@@ -419,7 +440,26 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
             const int sa = (int)(((uint32_t)tok_scale[c] * 0x01010101u) & cs_gate);
             const int sa2 = (int)(((uint32_t)max(tok_scale[c] - kPieceShift, 0) * 0x01010101u) & cs_gate);  // second piece is stored 2^kPieceShift times larger
             floatx4 D0, D1;
-            if (pm >= 3) {
+            if constexpr (kBits) {
+              const int sl = (int)(((uint32_t)tok_scale[c] * 0x01010101u) & cs_gate_lo);
+              const int sl2 = (int)(((uint32_t)max(tok_scale[c] - kPieceShift, 0) * 0x01010101u) & cs_gate_lo);
+              uint32_t mask_hi = 0x22222222u, mask_lo = 0x11111111u;
+              asm volatile("" : "+s"(mask_hi), "+s"(mask_lo));
+              D0 = zero4;
+              D1 = zero4;
+              auto planes = [&](auto e_tag) {
+                constexpr int E = decltype(e_tag)::value;
+                if (E > pm) return;
+                D0 = slice_group<E>(xa[c][0], I.w[E].x, I.w[E].y, mask_hi, sa, sa2, sb, D0);
+                D1 = slice_group<E>(xa[c][1], I.w[E].z, I.w[E].w, mask_hi, sa, sa2, sb, D1);
+                D0 = slice_group<E>(xa[c][0], I.w[E].x, I.w[E].y, mask_lo, sl, sl2, sb, D0);
+                D1 = slice_group<E>(xa[c][1], I.w[E].z, I.w[E].w, mask_lo, sl, sl2, sb, D1);
+              };
+              planes(std::integral_constant<int, 0>{});
+              planes(std::integral_constant<int, 1>{});
+              planes(std::integral_constant<int, 2>{});
+              planes(std::integral_constant<int, 3>{});
+            } else if (pm >= 3) {
               // all four slices (the usual case at 16 tokens) as one straight run of code: the operands of a slice are
               // built while the MFMAs of the slice before occupy the matrix core
               D0 = slice_group<0>(xa[c][0], I.w[0].x, I.w[0].y, nib_mask, sa, sa2, sb, zero4);
@@ -548,7 +588,18 @@ mbq_status launch_linear_decode_f4_ws(int64_t T, const f4::Group& g, int KB, con
   const char* prep = reinterpret_cast<const char*>(ws);
 #define MBQ_WS(C, P, ST) \
   hipLaunchKernelGGL((decode_f4_ws_kernel<C, P, ST>), dim3(grid), dim3(576), 0, stream, prep, (int)T, KB, g)
-  if (g.stamps) {
+  if (g.bit_view) {  // (no timeline build of this variant)
+    if (g.stamps) {
+      set_error("the timeline build exists for digit precisions only");
+      return MBQ_ERR_BAD_SHAPE;
+    }
+    if (S == 1 && cpw == 1)
+      hipLaunchKernelGGL((decode_f4_ws_kernel<1, 1, false, true>), dim3(grid), dim3(576), 0, stream, prep, (int)T, KB, g);
+    else if (S == 1)
+      hipLaunchKernelGGL((decode_f4_ws_kernel<2, 1, false, true>), dim3(grid), dim3(576), 0, stream, prep, (int)T, KB, g);
+    else
+      hipLaunchKernelGGL((decode_f4_ws_kernel<2, 2, false, true>), dim3(grid), dim3(576), 0, stream, prep, (int)T, KB, g);
+  } else if (g.stamps) {
     if (S == 1 && cpw == 1) MBQ_WS(1, 1, true);
     else if (S == 1) MBQ_WS(2, 1, true);
     else MBQ_WS(2, 2, true);

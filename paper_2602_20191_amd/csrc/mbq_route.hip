@@ -15,7 +15,7 @@ __device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0
 // inside its wavefront is the population count of the ballot below its lane.
 template <int NW>
 __device__ inline void bucket_by_workgroup(const int32_t* prec, int64_t T,
-                                           int32_t* __restrict__ perm, int32_t* __restrict__ offsets) {
+                                           int32_t* __restrict__ perm, int32_t* __restrict__ offsets, int shift = 0) {
   __shared__ int s_wave[NW][kP];  // per-wavefront counts of the current pass
   __shared__ int s_run[kP];       // running write position of each precision
   constexpr int NT = NW * 64;
@@ -26,7 +26,7 @@ __device__ inline void bucket_by_workgroup(const int32_t* prec, int64_t T,
   int cnt[kP] = {0, 0, 0, 0};
   for (int64_t base = 0; base < T; base += NT) {
     const int64_t i = base + tid;
-    const int p = (i < T) ? prec[i] : -1;
+    const int p = (i < T) ? (prec[i] >> shift) : -1;
 #pragma unroll
     for (int q = 0; q < kP; ++q) cnt[q] += __popcll(__ballot(p == q));
   }
@@ -50,7 +50,7 @@ __device__ inline void bucket_by_workgroup(const int32_t* prec, int64_t T,
   // pass 2: stable placement, NT tokens at a time in token order
   for (int64_t base = 0; base < T; base += NT) {
     const int64_t i = base + tid;
-    const int p = (i < T) ? prec[i] : -1;
+    const int p = (i < T) ? (prec[i] >> shift) : -1;
     int rank_in_wave = 0;
 #pragma unroll
     for (int q = 0; q < kP; ++q) {
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
         }
       }
     }
-    prec[tok0 + tid] = view.digits[arg];
+    prec[tok0 + tid] = view.value[arg];
     __threadfence();  // publish this workgroup's choices before taking a ticket
   }
   __syncthreads();
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
   if (s_ticket != gridDim.x - 1) return;
   // last workgroup: every token's precision is visible now
   __threadfence();
-  bucket_by_workgroup<4>(prec, T, perm, offsets);
+  bucket_by_workgroup<4>(prec, T, perm, offsets, view.shift);
   if (tid == 0) *ticket = 0u;  // leave the counter ready for the next call
 }
 
@@ -282,10 +282,13 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
       arg = q;
     }
   }
-  // the router's output q stands for the first digits[q] + 1 digits of the code: that is what the linear kernels use
-  arg = arg == 0 ? group.view.digits[0] : arg == 1 ? group.view.digits[1] : arg == 2 ? group.view.digits[2] : group.view.digits[3];
+  // the router's output q stands for the first bits[q] bits of the code: `value` is what the precision array holds,
+  // `arg` from here on the digit count minus one that tokens are sorted by
+  const RouteView& vw = group.view;
+  const int value = arg == 0 ? vw.value[0] : arg == 1 ? vw.value[1] : arg == 2 ? vw.value[2] : vw.value[3];
+  arg = arg == 0 ? vw.digits[0] : arg == 1 ? vw.digits[1] : arg == 2 ? vw.digits[2] : vw.digits[3];
   if (defer_bucket) {  // the consumer of the precisions sorts the tokens itself: no meeting, the workgroup is done
-    if (lane == 0) out.prec[tok] = arg;
+    if (lane == 0) out.prec[tok] = value;
     return;
   }
   if (T > kSmallRouteTokens) {
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
     // (store, fence, count; the last to arrive fences and reads them back) and one wavefront sorts them.
     unsigned long long arrived = 0ull;
     if (lane == 0) {
-      out.prec[tok] = arg;
+      out.prec[tok] = value;
       __threadfence();
       arrived = atomicAdd(words + blockIdx.y, 1ull) + 1ull;
     }
@@ -301,8 +304,8 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
     if ((int)arrived != T) return;
     __threadfence();
     // stable counting sort of up to 128 tokens by one wavefront: lane holds tokens lane and lane + 64
-    const int p = (lane < T) ? __hip_atomic_load(out.prec + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
-    const int p2 = (lane + 64 < T) ? __hip_atomic_load(out.prec + lane + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
+    const int p = (lane < T) ? (__hip_atomic_load(out.prec + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> vw.shift) : -1;
+    const int p2 = (lane + 64 < T) ? (__hip_atomic_load(out.prec + lane + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> vw.shift) : -1;
     const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
     int start = 0, my_pos = 0, my_pos2 = 0;
 #pragma unroll
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __rest
   }
   unsigned long long all = 0ull;
   if (lane == 0) {
-    out.prec[tok] = arg;
+    out.prec[tok] = value;
     const unsigned long long inc = ((unsigned long long)arg << (2 * tok)) + (1ull << 56);
     all = atomicAdd(words + blockIdx.y, inc) + inc;
   }

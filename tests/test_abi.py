@@ -122,7 +122,8 @@ def test_configuration_checks_need_no_gpu(lib):
 
     lib.mbq_config_check.restype = ctypes.c_int
     lib.mbq_config_bits.restype = ctypes.c_int
-    lib.mbq_config_digit_precision.restype = ctypes.c_int
+    lib.mbq_config_precision_value.restype = ctypes.c_int
+    lib.mbq_config_counts_bits.restype = ctypes.c_int
     for bits in [(2, 2, 2, 2), (4, 2, 2), (2, 4, 2), (4, 4), (6, 2), (8,), (2, 2, 2), (2,)]:
         c = cfg(bits)
         assert lib.mbq_config_check(ctypes.byref(c)) == 0, bits
@@ -130,9 +131,19 @@ def test_configuration_checks_need_no_gpu(lib):
         for p, b in enumerate(bits):
             acc += b
             assert lib.mbq_config_bits(ctypes.byref(c), p) == acc
-            assert lib.mbq_config_digit_precision(ctypes.byref(c), p) == acc // 2 - 1
+            assert lib.mbq_config_precision_value(ctypes.byref(c), p) == acc // 2 - 1
+        assert lib.mbq_config_counts_bits(ctypes.byref(c)) == 0
         assert lib.mbq_config_bits(ctypes.byref(c), len(bits)) == -1
-    for bits, group in [((3, 1, 2, 2), 128), ((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((1, 1), 128), ((), 128),
+    for bits in [(3, 1, 2, 2), (3, 2, 1), (1, 1), (4, 1, 1, 2), (5,), (1, 2, 2, 2)]:     # an odd cumulative width
+        c = cfg(bits)
+        assert lib.mbq_config_check(ctypes.byref(c)) == 0, bits
+        assert lib.mbq_config_counts_bits(ctypes.byref(c)) == 1
+        acc = 0
+        for p, b in enumerate(bits):
+            acc += b
+            assert lib.mbq_config_bits(ctypes.byref(c), p) == acc
+            assert lib.mbq_config_precision_value(ctypes.byref(c), p) == acc - 1
+    for bits, group in [((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((3, 3, 3), 128), ((), 128), ((0, 2), 128),
                         ((2, 2, 2, 2, 2), 128)]:
         c = cfg(bits, group)
         assert lib.mbq_config_check(ctypes.byref(c)) == 2, (bits, group)

@@ -12,7 +12,15 @@ from workloads import f32_to_bf16_bits, make_weight
 
 pytestmark = pytest.mark.gpu
 
-CONFIGS = [(2, 2, 2, 2), (4, 2, 2), (2, 4, 2), (2, 2, 4), (4, 4), (6, 2), (2, 6), (8,), (2, 2, 2), (4, 2), (2,)]
+CONFIGS = [(2, 2, 2, 2), (4, 2, 2), (2, 4, 2), (2, 2, 4), (4, 4), (6, 2), (2, 6), (8,), (2, 2, 2), (4, 2), (2,),
+           (3, 1, 2, 2), (3, 2, 1), (4, 1, 1, 2), (1, 1, 1, 1), (5, 3), (1, 2, 2, 2), (7,)]       # the last row: bit configurations
+
+
+def stored_values(mbq, cfg, E):
+    """What the precision arrays hold for the configuration's precisions, and the digits tokens are bucketed by."""
+    values = np.array([mbq.config_precision_value(cfg, p) for p in range(E)], dtype=np.int32)
+    bits = np.array([mbq.config_bits(cfg, p) for p in range(E)], dtype=np.int32)
+    return values, (bits + 1) // 2 - 1
 
 
 def tokens(T, K, seed):
@@ -39,7 +47,7 @@ def test_encode_in_the_configurations_terms_is_bit_exact(mbq, bits):
     B = G.cumulative_bits(bits)
     for p in range(len(bits)):
         assert mbq.config_bits(cfg, p) == B[p]
-        assert mbq.config_digit_precision(cfg, p) == B[p] // 2 - 1
+        assert mbq.config_precision_value(cfg, p) == (B[p] - 1 if mbq.config_counts_bits(cfg) else B[p] // 2 - 1)
         What = mbq.mbq_dequant_cfg(blob, N, K, cfg, p).cpu().numpy()
         want = G.dequant(codes, s0, z0, bits, 128, p)
         np.testing.assert_allclose(What, want.astype(np.float32), rtol=0, atol=0)
@@ -48,7 +56,8 @@ def test_encode_in_the_configurations_terms_is_bit_exact(mbq, bits):
 
 @pytest.mark.parametrize("bits,T,K", [((4, 2, 2), 16, 4096), ((4, 4), 5, 384), ((2, 2, 2), 28, 1280), ((8,), 16, 256),
                                       ((6, 2), 64, 2048), ((2, 4, 2), 129, 512), ((4, 2, 2), 700, 256),
-                                      ((2, 6), 0, 256)])
+                                      ((2, 6), 0, 256), ((3, 1, 2, 2), 16, 4096), ((3, 2, 1), 40, 512),
+                                      ((1, 1, 1, 1), 100, 384), ((4, 1, 1, 2), 300, 256), ((5, 3), 0, 128)])
 def test_route_with_as_many_outputs_as_slices(mbq, bits, T, K):
     print(f"[case] config {bits}: route T={T} K={K}", flush=True)
     cfg = mbq.Config(bits)
@@ -58,22 +67,29 @@ def test_route_with_as_many_outputs_as_slices(mbq, bits, T, K):
     Wr = (rng.standard_normal((E, K)) / np.sqrt(K)).astype(np.float32)
     br = rng.normal(0, 0.2, size=E).astype(np.float32)
     S, prec_ref, gap = O.route(xb, Wr, br) if E > 1 else (None, np.zeros(T, dtype=np.int32), np.full(T, np.inf))
-    digits = np.array([mbq.config_digit_precision(cfg, p) for p in range(E)], dtype=np.int32)
+    values, digits = stored_values(mbq, cfg, E)
     prec, perm, offsets, logits = mbq.mbq_route_cfg(dev_bf16(xb).reshape(T, K), dev(Wr), dev(br), cfg, want_logits=True)
     torch.cuda.synchronize()
     prec, perm, offsets = prec.cpu().numpy(), perm.cpu().numpy(), offsets.cpu().numpy()
     if T and E > 1:
         np.testing.assert_allclose(logits.cpu().numpy(), S, rtol=0, atol=1e-10)
-    compare_routing(prec, digits[prec_ref], gap, f"route config {bits} T={T}")
-    check_bucket(prec, perm, offsets)            # buckets are by digit precision: five offsets as ever
+    compare_routing(prec, values[prec_ref], gap, f"route config {bits} T={T}")
+    shift = 1 if mbq.config_counts_bits(cfg) else 0
+    check_bucket(prec >> shift, perm, offsets)   # buckets are by the digits a token touches: five offsets as ever
     assert offsets[4] == T
-    assert set(np.unique(prec)).issubset(set(digits.tolist()))
+    assert set(np.unique(prec)).issubset(set(values.tolist()))
 
 
 @pytest.mark.parametrize("bits,T,K,Ns", [((4, 2, 2), 16, 4096, (272, 130)), ((4, 4), 12, 1280, (96,)),
                                          ((2, 2, 2), 16, 8192, (64, 48, 80)), ((6, 2), 40, 4096, (272,)),
                                          ((2, 4, 2), 64, 1024, (130, 64)), ((8,), 16, 512, (100,)),
-                                         ((4, 2, 2), 300, 768, (260,))])
+                                         ((4, 2, 2), 300, 768, (260,)),
+                                         # bit configurations: the decode kernel up to 16 tokens and K <= 8192 ...
+                                         ((3, 1, 2, 2), 16, 4096, (272, 130)), ((3, 2, 1), 12, 1280, (96, 40, 64)),
+                                         ((1, 1, 1, 1), 16, 8192, (48,)), ((4, 1, 1, 2), 7, 2304, (130, 66)),
+                                         ((1, 2, 2, 2), 16, 768, (100,)), ((7,), 3, 512, (64,)),
+                                         # ... and the checker kernel beyond
+                                         ((3, 1, 2, 2), 40, 512, (72,)), ((5, 3), 16, 8448, (32,))])
 def test_stage_call_under_a_configuration(mbq, bits, T, K, Ns):
     """mbq_routed_linear_group_cfg against the general oracle: precisions (as digit counts) bit-exact off the near-tie
     list, outputs within the bar for the precisions the GPU chose, and identical to route_cfg + linear_group."""
@@ -91,9 +107,13 @@ def test_stage_call_under_a_configuration(mbq, bits, T, K, Ns):
     routing, Ys = mbq.mbq_routed_linear_group_cfg(X, dWr, dbr, cfg, blobs, list(Ns))
     torch.cuda.synchronize()
     routing2 = mbq.mbq_route_group_cfg(X, dWr, dbr, cfg)
-    Ys2 = mbq.mbq_linear_group(X, blobs, list(Ns), K, routing2)
-    digits = np.array([mbq.config_digit_precision(cfg, p) for p in range(E)], dtype=np.int32)
-    back = {int(d): p for p, d in enumerate(digits)}
+    if mbq.config_counts_bits(cfg):
+        Ys2 = [mbq.mbq_linear_cfg(X, blobs[i], N, K, cfg, *routing2[i]) for i, N in enumerate(Ns)]
+    else:
+        Ys2 = mbq.mbq_linear_group(X, blobs, list(Ns), K, routing2)
+    values, digits = stored_values(mbq, cfg, E)
+    shift = 1 if mbq.config_counts_bits(cfg) else 0
+    back = {int(d): p for p, d in enumerate(values)}
     for i, N in enumerate(Ns):
         for a, b in zip(routing[i], routing2[i]):
             assert torch.equal(a, b), i
@@ -103,8 +123,8 @@ def test_stage_call_under_a_configuration(mbq, bits, T, K, Ns):
             _, prec_ref, gap = O.route(xb, Wrs[i], brs[i])
         else:
             prec_ref, gap = np.zeros(T, dtype=np.int32), np.full(T, np.inf)
-        compare_routing(prec, digits[prec_ref], gap, f"stage router {i}")
-        check_bucket(prec, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
+        compare_routing(prec, values[prec_ref], gap, f"stage router {i}")
+        check_bucket(prec >> shift, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
         prec_cfg = np.array([back[int(d)] for d in prec], dtype=np.int32)       # the GPU's choice, as config indices
         codes, s0, z0 = G.encode(Ws[i], bits, 128)
         want = G.linear(xb, codes, s0, z0, bits, 128, prec_cfg)
@@ -113,7 +133,7 @@ def test_stage_call_under_a_configuration(mbq, bits, T, K, Ns):
 
 
 def test_unsupported_configurations_are_refused(mbq):
-    for bits, group in [((3, 1, 2, 2), 128), ((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((1, 1), 128), ((2, 2, 2, 2, 2), 128),
+    for bits, group in [((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((3, 3, 3), 128), ((2, 2, 2, 2, 2), 128),
                         ((), 128), ((0, 2), 128)]:
         cfg = mbq.Config(bits[:4], group)
         cfg.n_slices = len(bits)
@@ -121,7 +141,7 @@ def test_unsupported_configurations_are_refused(mbq):
             mbq.config_check(cfg)
     W = dev(make_weight(16, 256, [1], 4.0))
     with pytest.raises(mbq.MbqError):
-        mbq.mbq_encode_cfg(W, mbq.Config((3, 1, 2, 2)))
+        mbq.mbq_encode_cfg(W, mbq.Config((2, 2, 2, 2), 64))
     # P must match the configuration
     cfg = mbq.Config((4, 2, 2))
     X = dev_bf16(tokens(4, 256, 1)).reshape(4, 256)
