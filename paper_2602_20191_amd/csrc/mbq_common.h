@@ -134,7 +134,7 @@ mbq_status launch_linear_decode16_group(const uint16_t* X, int64_t T, int n, con
                                         float* const* Y, hipStream_t stream, int32_t* const* sort_perm,
                                         int32_t* const* sort_offsets, const int32_t* const* gate_offsets = nullptr);
 bool decode_f4_supports(int64_t T, const Shape& sh);
-int decode_f4_k_parts(const Shape& sh);
+int decode_f4_k_parts(int n, const Shape* shapes);
 void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl);
 // share `part` of `parts` of the clearing, done by `nthreads` threads of which this is `tid`
 // Between 129 and 256 tokens the better of the register-stationary kernel and the prefill kernel depends on the

@@ -102,8 +102,9 @@ struct Item {  // one 16 x 256 block: four slices and the {s0, z0} of its two gr
 
 // launch geometry shared by the kernels' launchers
 int f4_compute_units();
-// T <= 16 and at most 32 column blocks (K <= 8192): a loader wavefront and eight arithmetic wavefronts per workgroup
-bool decode_f4_ws_supports(int KB);
+// T <= 16 and at most 32 column blocks (K <= 8192), or up to 64 when the call has few enough row tiles (`tiles` = row
+// tiles of all matrices of the call): a loader wavefront and eight arithmetic wavefronts per workgroup
+bool decode_f4_ws_supports(int KB, int tiles);
 int decode_f4_ws_parts(int KB);  // 2: the launch adds into outputs that must be zero when it starts
 int decode_f4_ws_stamp_wavefronts();
 mbq_status launch_linear_decode_f4_ws(int64_t T, const f4::Group& g, int KB, const void* ws, hipStream_t stream);

@@ -244,13 +244,20 @@ int decode_f4_timeline_workgroups() { return f4_compute_units(); }
 int decode_f4_timeline_slots() { return decode_f4_ws_stamp_wavefronts() * 32; }
 // Parts of the K axis the linear kernel works in (2: it adds into Y, which must be zero when it starts; see
 // decode_f4_zero_list).
-int decode_f4_k_parts(const Shape& sh) { return decode_f4_ws_supports(sh.KB) ? decode_f4_ws_parts(sh.KB) : 1; }
+static int call_tiles(int n, const Shape* shapes) {
+  int tiles = 0;
+  for (int i = 0; i < n; ++i) tiles += shapes[i].NT;
+  return tiles;
+}
+int decode_f4_k_parts(int n, const Shape* shapes) {
+  return decode_f4_ws_supports(shapes[0].KB, call_tiles(n, shapes)) ? decode_f4_ws_parts(shapes[0].KB) : 1;
+}
 void decode_f4_zero_list(int64_t T, int n, const Shape* shapes, float* const* Y, ZeroList* zl) {
   for (int i = 0; i < MBQ_MAX_GROUP; ++i) {
     zl->p[i] = nullptr;
     zl->n[i] = 0;
   }
-  if (decode_f4_k_parts(shapes[0]) != 2) return;
+  if (decode_f4_k_parts(n, shapes) != 2) return;
   for (int i = 0; i < n; ++i) {
     zl->p[i] = Y[i];
     zl->n[i] = (long long)T * shapes[i].N;
@@ -300,7 +307,7 @@ mbq_status launch_linear_decode_f4(int64_t T, int n, const void* const* blobs, c
   g.stamps = stamps;
   g.bit_view = bit_view ? 1 : 0;
   const Shape& s0 = shapes[0];
-  if (decode_f4_ws_supports(s0.KB)) return launch_linear_decode_f4_ws(T, g, s0.KB, ws, stream);
+  if (decode_f4_ws_supports(s0.KB, tiles)) return launch_linear_decode_f4_ws(T, g, s0.KB, ws, stream);
   if (stamps) {
     set_error("the timeline build exists for K <= 8192 only");
     return MBQ_ERR_BAD_SHAPE;

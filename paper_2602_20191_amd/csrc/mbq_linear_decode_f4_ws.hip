@@ -35,6 +35,7 @@ namespace f4 {
 constexpr int kWsRing = 32;        // ring slots (items of 4352 bytes), four groups of eight
 constexpr int kWsDepth = 12;       // items in flight at most: 60 loads, the wavefront's counter holds 63
 constexpr int kWsRed = 2;          // partial-tile buffers: a wavefront may run this many tiles ahead of the slowest
+constexpr int kWsChunkTiles = 8;   // kChunks > 1: tiles per workgroup at most (their sums wait in LDS between chunks)
 constexpr int kWsPollCap = 1 << 17;  // x ~0.1 us: three orders of magnitude above any real wait
 constexpr int kWsSlotBytes = 4 * 1024 + 256;
 constexpr int kWsStampSlots = 32;  // timeline build, slots as documented in mbq_bench.h (wavefront 8 = loader: slot 1
@@ -117,16 +118,23 @@ static_assert(kWsRing % 8 == 0, "the loader checks the slots in groups of eight"
 // at the high bit of its last digit, so the two bits of every 2-bit code go to the matrix cores as two operands (the
 // high bit as the FP4 number (c & 2) / 2, the low bit as (c & 1) / 2), each gated by its own A scale byte: twice the
 // MFMAs, same loads.
-template <int CPW, int S, bool kStamp, bool kBits = false>
+// kChunks > 1 (8192 < K <= 16384): a part of the K axis is more than the registers hold, so a workgroup works through
+// it in kChunks chunks of at most 16 blocks - all its tiles for the first chunk, then the activations of the second
+// chunk, all its tiles again - and keeps the tiles' sums of the earlier chunks in LDS (at most kWsChunkTiles tiles per
+// workgroup; the ring gives up a quarter of its slots for them).  The parts still meet by adding two addends.
+template <int CPW, int S, bool kStamp, bool kBits = false, int kChunks = 1>
 __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restrict__ prep, int T, int KB,
                                                            const f4::Group g) {
   using namespace f4;
   constexpr int kWaves = 8;  // arithmetic wavefronts; wavefront 8 loads
   static_assert(S == 1 || S == 2, "one or two parts");
   static_assert(CPW == 1 || CPW == 2, "one or two blocks per wavefront");
-  __shared__ __attribute__((aligned(1024))) char ring[kWsRing * kWsSlotBytes];
+  static_assert(kChunks == 1 || (CPW == 2 && S == 2 && !kStamp), "the chunked variant: two parts, two blocks per wavefront");
+  constexpr int kRing = kChunks > 1 ? kWsRing - 8 : kWsRing;
+  __shared__ __attribute__((aligned(16))) float s_held[kChunks > 1 ? kWsChunkTiles : 1][64][4];  // sums of earlier chunks
+  __shared__ __attribute__((aligned(1024))) char ring[kRing * kWsSlotBytes];
   __shared__ __attribute__((aligned(16))) float red[kWsRed][kWaves][64][4];
-  __shared__ __attribute__((aligned(16))) uint32_t s_done[kWsRing], s_cnt[kWsRed], s_fin[kWsRed];
+  __shared__ __attribute__((aligned(16))) uint32_t s_done[kRing], s_cnt[kWsRed], s_fin[kWsRed];
   __shared__ uint32_t s_count;  // items that have landed in the ring (they land in issue order)
   __shared__ unsigned long long s_stamp[kStamp ? (kWaves + 1) * kWsStampSlots : 1];
   constexpr int kThreads = 64 * (kWaves + 1);
@@ -146,7 +154,7 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
       }
     }
   };
-  for (int i = threadIdx.x; i < kWsRing; i += kThreads) s_done[i] = 0u;
+  for (int i = threadIdx.x; i < kRing; i += kThreads) s_done[i] = 0u;
   if (threadIdx.x < kWsRed) {
     s_cnt[threadIdx.x] = 0u;
     s_fin[threadIdx.x] = 0u;
@@ -165,6 +173,7 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
   const int kb_first = part * nbp;
   const int nb = min(KB - kb_first, nbp);  // blocks of this part (the launcher makes sure it is positive)
   const bool has_work = my_tiles > 0 && nb > 0;
+  const int nbc = (nb + kChunks - 1) / kChunks;  // blocks per chunk (<= 8 CPW); chunk c: blocks c nbc .. of the part
 
   int pl[MBQ_MAX_GROUP];  // precisions of every matrix (arithmetic wavefronts; the loader is told the highest ones)
 
@@ -222,6 +231,8 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
     stamp(1);
     if (has_work) {
       const int total = my_tiles * nb;
+      const uint32_t held_addr = lds_addr(s_held);
+      (void)held_addr;
       const size_t code_step = (size_t)stride * (size_t)KB * 1024u;  // from one of this workgroup's tiles to the next
       const size_t meta_step = (size_t)stride * (size_t)KB * 256u;
       // wave-uniform pointers to block kb_first of the current row of tiles; a slice the matrix does not need at this
@@ -230,18 +241,19 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
       size_t step[4];
       const char* pmeta;
       int t = bid, next_begin = 0;
+      int chunk_first = kb_first;  // first block of the chunk being loaded
       auto enter = [&]() {
         const int j = proj_of(t);
         const int nt = t - MBQ_PICK(m_begin, j);
         const int pm = pmax_of(j);
-        const char* row = MBQ_PICK(m_codes, j) + ((size_t)nt * (size_t)KB + (size_t)kb_first) * 1024u;
+        const char* row = MBQ_PICK(m_codes, j) + ((size_t)nt * (size_t)KB + (size_t)chunk_first) * 1024u;
         const size_t slice_bytes = MBQ_PICK(m_slice_bytes, j);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           p[e] = uniform((e <= pm) ? row + (size_t)e * slice_bytes : prep);
           step[e] = uniform((e <= pm) ? code_step : (size_t)0);
         }
-        pmeta = uniform(MBQ_PICK(m_meta, j) + ((size_t)nt * (size_t)KB + (size_t)kb_first) * 256u);
+        pmeta = uniform(MBQ_PICK(m_meta, j) + ((size_t)nt * (size_t)KB + (size_t)chunk_first) * 256u);
         next_begin = uniform(next_begin_of(j));
       };
       auto next_tile = [&]() {
@@ -252,7 +264,7 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
         if (t >= next_begin && t < g.tiles) enter();
       };
       enter();
-      int slot = 0, lap = 0;     // ring position of the next item: q = lap kWsRing + slot
+      int slot = 0, lap = 0;     // ring position of the next item: q = lap kRing + slot
       uint32_t landed = 0u;      // items published so far (they land, and are published, in order)
       const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u;
       // five loads of the item that is block b of the cursor's tile, into ring slot sl
@@ -275,7 +287,33 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
       };
       stamp(2);
       const int issued = total;
-      if ((nb & 7) == 0) {
+      if constexpr (kChunks > 1) {
+        int q = 0;
+#pragma unroll 1
+        for (int c = 0; c < kChunks; ++c) {
+          const int nb_c = min(nbc, nb - c * nbc);
+          chunk_first = kb_first + c * nbc;
+          t = bid;
+          enter();
+          int b = 0;
+#pragma unroll 1
+          for (int n = my_tiles * nb_c; n > 0; --n, ++q) {
+            asm volatile("" : "+s"(p[0]), "+s"(p[1]), "+s"(p[2]), "+s"(p[3]), "+s"(pmeta), "+s"(b), "+s"(slot), "+s"(lap),
+                         "+s"(t), "+s"(next_begin), "+s"(q));
+            if (lap > 0 && (slot & 7) == 0) wait_flags8(done_addr + (uint32_t)slot * 4u, (uint32_t)lap);
+            issue(b, slot);
+            publish_behind(q);
+            if (++slot == kRing) {
+              slot = 0;
+              ++lap;
+            }
+            if (++b == nb_c) {
+              b = 0;
+              next_tile();
+            }
+          }
+        }
+      } else if ((nb & 7) == 0) {
         // The usual shapes (8 or 16 blocks per part): eight items at a time, no bookkeeping between them.  The loader is
         // a single wavefront and every instruction it spends per item comes off the stream's rate.
         const int groups = nb >> 3;
@@ -295,7 +333,7 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
             }
             q += 8;
             slot += 8;
-            if (slot == kWsRing) {
+            if (slot == kRing) {
               slot = 0;
               ++lap;
             }
@@ -311,7 +349,7 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
           if (lap > 0 && (slot & 7) == 0) wait_flags8(done_addr + (uint32_t)slot * 4u, (uint32_t)lap);
           issue(b, slot);
           publish_behind(q);
-          if (++slot == kWsRing) {
+          if (++slot == kRing) {
             slot = 0;
             ++lap;
           }
@@ -340,10 +378,12 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
     intx8 xa[CPW][2][kPieces];
     floatx4 sx[CPW][2];
     int tok_scale[CPW];
+    // (chunked variant: blocks first .. first + count - 1 of the K axis; called once per chunk)
+    auto load_activations = [&](int first, int count) {
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
       const int b = wave + kWaves * c;
-      const char* base = prep + (size_t)(b < nb ? kb_first + b : 0) * kPrepBytesPerBlock;
+      const char* base = prep + (size_t)(b < count ? first + b : 0) * kPrepBytesPerBlock;
       const uint4* src = reinterpret_cast<const uint4*>(base);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
@@ -357,6 +397,8 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
       }
       tok_scale[c] = reinterpret_cast<const int*>(base + kPrepVecPerBlock * 16 + 2 * 16 * 4)[m];
     }
+    };
+    load_activations(kb_first, kChunks > 1 ? min(nbc, nb) : nb);
     find_pmax();
     stamp(1);
     if (blockIdx.x == 0 && wave == 0) {  // one wavefront of the launch sorts the tokens, where the caller wants them sorted
@@ -403,7 +445,17 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
         }
       };
       cs_enter();
-      int rb = 0, rlap = 0;  // partial-tile buffer of the current tile: ti = rlap kWsRed + rb
+      int rb = 0, rlap = 0;  // partial-tile buffer of the current tile: (chunk my_tiles + ti) = rlap kWsRed + rb
+      int q_base = 0;        // items of the chunks before this one
+      const uint32_t held_addr = lds_addr(s_held);
+#pragma unroll 1
+      for (int chunk = 0; chunk < kChunks; ++chunk) {
+      const int nb_c = kChunks > 1 ? min(nbc, nb - chunk * nbc) : nb;  // blocks of this chunk
+      if (kChunks > 1 && chunk > 0) {
+        load_activations(kb_first + chunk * nbc, nb_c);
+        cs_t = bid;
+        cs_enter();
+      }
 #pragma unroll 1
       for (int ti = 0; ti < my_tiles; ++ti) {
         asm volatile("" : "+s"(cs_t), "+s"(cs_next_begin), "+s"(cs_pm), "+s"(cs_N), "+s"(cs_col0), "+s"(cs_Y), "+s"(rb),
@@ -413,10 +465,10 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
           const int b = wave + kWaves * c;
-          if (b < nb) {
-            const int q = ti * nb + b;  // position in the ring's sequence of items
+          if (b < nb_c) {
+            const int q = q_base + ti * nb_c + b;  // position in the ring's sequence of items
             wait_count(count_addr, (uint32_t)q + 1u);
-            const int qlap = q / kWsRing, qslot = q - qlap * kWsRing;
+            const int qlap = q / kRing, qslot = q - qlap * kRing;
             const uint32_t slot = ring_addr + (uint32_t)(qslot * kWsSlotBytes);
             u32x4 wv[4];
             f32x2 mv[2];
@@ -530,8 +582,21 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
           lds_store_u32(fin_addr + (uint32_t)rb * 4u, (uint32_t)(rlap + 1));
 #pragma unroll
           for (int w = 0; w < kWaves; ++w) sum += part[w];
+          bool last_chunk = true;
+          if constexpr (kChunks > 1) {
+            // sums of the earlier chunks of this tile wait in LDS (written by whichever wavefront summed then: it filed
+            // its later partial tiles after that write, and all eight have been counted in here)
+            const uint32_t held = held_addr + (uint32_t)((ti * 64 + lane) * 16);
+            if (chunk > 0) {
+              floatx4 before;
+              asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(before) : "v"(held) : "memory");
+              sum = before + sum;
+            }
+            last_chunk = chunk == kChunks - 1;
+            if (!last_chunk) asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(held), "v"(sum) : "memory");
+          }
           const int col = cs_col0 + m;
-          if (col < cs_N) {
+          if (last_chunk && col < cs_N) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const int r = 4 * kq + i;
@@ -552,6 +617,8 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
         cs_t += stride;
         cs_col0 += stride * kTileN;
         if (cs_t >= cs_next_begin && cs_t < g.tiles) cs_enter();
+      }
+      q_base += my_tiles * nb_c;
       }
     }
   }
@@ -574,7 +641,13 @@ __global__ __launch_bounds__(576) void decode_f4_ws_kernel(const char* __restric
 
 #undef MBQ_PICK
 
-bool decode_f4_ws_supports(int KB) { return KB >= 1 && KB <= 32; }
+// one to 32 column blocks: activations of a part in registers; up to 64: two chunks per part, if the workgroups'
+// tile lists are short enough for the sums to wait in LDS
+bool decode_f4_ws_supports(int KB, int tiles) {
+  if (KB >= 1 && KB <= 32) return true;
+  const int per_part = f4_compute_units() / 2;
+  return KB <= 64 && per_part >= 1 && (tiles + per_part - 1) / per_part <= f4::kWsChunkTiles && knob(7) != 1;
+}
 int decode_f4_ws_parts(int KB) { return KB <= 16 ? 1 : 2; }
 int decode_f4_ws_stamp_wavefronts() { return 9; }
 
@@ -586,6 +659,17 @@ mbq_status launch_linear_decode_f4_ws(int64_t T, const f4::Group& g, int KB, con
   if (grid > g.tiles * S) grid = g.tiles * S;
   const int cpw = ((KB + S - 1) / S + 7) / 8;
   const char* prep = reinterpret_cast<const char*>(ws);
+  if (KB > 32) {  // two chunks per part
+    if (g.stamps) {
+      set_error("the timeline build exists for K <= 8192 only");
+      return MBQ_ERR_BAD_SHAPE;
+    }
+    if (g.bit_view)
+      hipLaunchKernelGGL((decode_f4_ws_kernel<2, 2, false, true, 2>), dim3(grid), dim3(576), 0, stream, prep, (int)T, KB, g);
+    else
+      hipLaunchKernelGGL((decode_f4_ws_kernel<2, 2, false, false, 2>), dim3(grid), dim3(576), 0, stream, prep, (int)T, KB, g);
+    return hip_status(hipGetLastError(), "decode_f4_ws_kernel launch");
+  }
 #define MBQ_WS(C, P, ST) \
   hipLaunchKernelGGL((decode_f4_ws_kernel<C, P, ST>), dim3(grid), dim3(576), 0, stream, prep, (int)T, KB, g)
   if (g.bit_view) {  // (no timeline build of this variant)

@@ -349,6 +349,30 @@ def test_decode_every_highest_precision(mbq, K, pmax, T):
     assert_output_close(Y, Yref, f"decode pmax={pmax} K={K} T={T}")
 
 
+@pytest.mark.parametrize("K,N,T,pmax", [(8448, 80, 16, 3), (11008, 272, 16, 3), (11008, 4096, 13, 2), (14336, 130, 1, 3),
+                                        (16384, 64, 16, 1), (9216, 2064, 7, 3), (12288, 16, 16, 0), (16384, 16500, 5, 3)])
+def test_decode_one_token_tile_long_rows(mbq, K, N, T, pmax):
+    """8192 < K <= 16384 at up to 16 tokens: the loader kernel works through each of its two parts in two chunks and
+    keeps the tiles' sums of the first chunk in LDS (few enough tiles per workgroup), else the kernel that streams the
+    activations with the weights takes over (the last case: 1032 row tiles); outputs also identical from call to call."""
+    print(f"[case] decode long rows K={K} N={N} T={T} pmax={pmax}", flush=True)
+    W = make_weight(N, K, [53, N, K], 4.0)
+    xb = tokens(T, K, [K, N, T])
+    prec = np.random.default_rng([K, N, T]).integers(0, pmax + 1, size=T).astype(np.int32)
+    prec[T // 2] = pmax
+    blob = mbq.mbq_encode(dev(W))
+    perm, offsets = O.bucket(prec)
+    X = dev_bf16(xb).reshape(T, K)
+    args = (X, blob, N, K, dev(prec), dev(perm), dev(offsets))
+    Y = mbq.mbq_linear(*args, algo=ALGOS["decode"])
+    Y2 = mbq.mbq_linear(*args, algo=ALGOS["decode"])
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    rows = np.arange(N) if N <= 4096 else np.random.default_rng(3).choice(N, 2048, replace=False)
+    codes, s0, z0 = O.encode(W[rows])
+    assert_output_close(Y.cpu().numpy()[:, rows], O.linear(xb, codes, s0, z0, prec), f"long rows K={K} N={N} T={T}")
+
+
 @pytest.mark.parametrize("T,K,N", [(17, 4096, 130), (31, 2304, 48), (32, 4096, 64), (33, 1024, 272), (48, 4096, 40),
                                    (49, 2048, 130), (64, 4096, 2064), (64, 256, 16)])
 def test_decode_several_token_tiles(mbq, T, K, N):
