@@ -37,7 +37,7 @@ STAGES = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))   # projections th
 # HBM bytes per linear-kernel launch at batch 16 (mean over the four stages) from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of `bench.py --probe decode`, scaled by what the same counters read for a plain 256 MiB copy
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/decode_linear_hbm_traffic_llama2_7b_batch16.txt
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 54.49e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {16: 53.10e6}
 # HBM bytes per mbq_linear call (gather pre-kernel + tile kernel), mean over the three linears, same counters and scale
 # factors from `bench.py --probe prefill` / `--probe prefill70b`; see profiles/prefill_hbm_traffic.txt
 MEASURED_PREFILL_TRAFFIC_BYTES_PER_CALL = {"configs[2]": 653.8e6, "70b": 3498.4e6}
@@ -330,8 +330,8 @@ def main() -> int:
         "hbm_gbps_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "event_ms_per_step": ev_ms_per_step,
         "roofline": {
-            "bound": "hbm", "kernel": "the linear kernel of each stage: mbq::decode_f4_ws_kernel (q+k+v, o, gate+up), "
-                                      "mbq::decode_f4_stream_kernel (down)",
+            "bound": "hbm", "kernel": "the linear kernel of each stage: mbq::decode_f4_ws_kernel, K in one part "
+                                      "(q+k+v, o, gate+up) and in two parts of two chunks (down)",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
             "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(T),
             "avg_launch_us": avg_launch_us, "avg_launch_bytes": avg_launch_bytes,
