@@ -21,8 +21,9 @@
  *   - Every entry point returns an mbq_status.  On failure nothing has been
  *     enqueued and mbq_last_error() describes the cause (thread-local string).
  *   - bf16 values are passed as uint16_t bit patterns.
- *   - Only the paper's default configuration is supported: group size 128 along K,
- *     four slices of two bits (App. C.1).  K must be a multiple of 128.
+ *   - The calls without _cfg in their names run the paper's default configuration: group
+ *     size 128 along K, four slices of two bits (App. C.1).  Other slice widths and groups of
+ *     64 or 32: the *_cfg calls at the end of this file.  K must be a multiple of 128.
  *
  * Packed weight blob (written by mbq_encode, read by every other call)
  *   Let NT = ceil(N/16), KB = ceil(K/256); rows and columns beyond N, K are padded
@@ -283,9 +284,9 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
  * s_0 = (max - min) / 2^b_0 and z_0 = -min / s_0, slice e >= 1 has s_e = s_(e-1) / 2^b_e and z_e = 2^(b_e - 1)
  * (App. B), precision p uses slices 0..p, B_p = b_0 + ... + b_p bits.
  *
- * What this library runs: 1 <= E <= MBQ_MAX_SLICES, b_e >= 1, B_(E-1) <= 8, group 128 - e.g. {2,2,2,2} (the default),
- * {4,2,2}, {4,4}, {6,2}, {8}, {2,2,2}, {3,1,2,2}, {3,2,1}, {4,1,1,2}.  For all of these the packed blob is THE SAME
- * as the default one: a slice of b bits with the centred zero point 2^(b-1) splits into narrower slices with their
+ * What this library runs: 1 <= E <= MBQ_MAX_SLICES, b_e >= 1, B_(E-1) <= 8, group 128, 64 or 32 - e.g. {2,2,2,2}
+ * (the default), {4,2,2}, {4,4}, {6,2}, {8}, {2,2,2}, {3,1,2,2}, {3,2,1}, {4,1,1,2}.  For all of these at group 128 the
+ * packed blob is THE SAME as the default one: a slice of b bits with the centred zero point 2^(b-1) splits into narrower slices with their
  * centred zero points without changing a bit (the codes are runs of bits of one eight-bit code, the scales powers of
  * two of s_0), so a configuration only says where that code may be cut, and its (s_0, z_0) are the stored ones times
  * 2^(2 - b_0) and 2^(b_0 - 2).  mbq_encode_cfg therefore writes the blob of mbq_encode.
@@ -301,8 +302,15 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
  * mbq_config_precision_value(cfg, q) is what a prec array holds for the configuration's precision q, and
  * mbq_config_counts_bits(cfg) says which of the two cases it is.  perm and offsets (always MBQ_N_PRECISIONS + 1
  * entries) sort and bucket the tokens by the number of 2-bit digits they touch, ceil(B_q / 2) - 1, in both cases.
- * Other group sizes and 16-bit scale / zero-point storage need per-group metadata of another size: not built; the
- * calls below refuse them with MBQ_ERR_BAD_SHAPE.
+ * Groups of 64 or 32 columns (K still a multiple of 128): the code section of the blob is laid out as for 128, the
+ * {s0, z0} section holds 256 / group pairs per row and 256-column tile instead of two (pair of group g of row n at
+ * index ((n / 16) * (256 / group) * KB + g) * 16 + n % 16), so the blob is larger: size it with mbq_blob_bytes_cfg,
+ * write it with mbq_encode_cfg and hand it ONLY to the *_cfg calls with the same configuration (nothing in the blob
+ * records its group size).  mbq_linear_cfg and mbq_routed_linear_group_cfg run these blobs through the
+ * one-thread-per-output kernel of MBQ_ALGO_SIMPLE at every token count: correct and slow; none of the fast kernels
+ * reads the larger metadata section.  scale / zero of mbq_unpack_cfg are then fp32 [N][K/group].
+ * Other group sizes and 16-bit scale / zero-point storage: not built; the calls below refuse them with
+ * MBQ_ERR_BAD_SHAPE.
  */
 #define MBQ_MAX_SLICES 4
 typedef struct mbq_config {
@@ -320,11 +328,13 @@ int mbq_config_precision_value(const mbq_config* cfg, int p);
 /* 1 if the configuration's prec arrays count bits (some B_p is odd), 0 if digits, -1 for a bad configuration. */
 int mbq_config_counts_bits(const mbq_config* cfg);
 
+/* Blob bytes under the configuration (= mbq_blob_bytes at group 128); 0 for a bad configuration or shape. */
+size_t mbq_blob_bytes_cfg(const mbq_config* cfg, int64_t N, int64_t K);
 /* mbq_encode for a configuration (Sec. 4.1 Eq. 2): checks it, then writes the blob described above. */
 mbq_status mbq_encode_cfg(const float* W, int64_t N, int64_t K, const mbq_config* cfg, void* blob, void* stream);
 /*
  * mbq_unpack in the configuration's own terms, for checking against an independent implementation of the
- * general recursion: codes uint8 [E][N][K] (slice e's b_e-bit codes), scale / zero fp32 [N][K/128] = (s_0, z_0) of
+ * general recursion: codes uint8 [E][N][K] (slice e's b_e-bit codes), scale / zero fp32 [N][K/group] = (s_0, z_0) of
  * the configuration's first slice.  Any of the three outputs may be null.
  */
 mbq_status mbq_unpack_cfg(const void* blob, int64_t N, int64_t K, const mbq_config* cfg, uint8_t* codes,

@@ -27,7 +27,7 @@ EXPORTS = (
     "mbq_route_mlp", "mbq_route_mlp_workspace_bytes", "mbq_threshold_quantile",
     "mbq_linear_static", "mbq_static_scratch_bytes",
     # other slice configurations
-    "mbq_config_check", "mbq_config_bits", "mbq_config_precision_value", "mbq_config_counts_bits", "mbq_linear_cfg", "mbq_encode_cfg", "mbq_unpack_cfg",
+    "mbq_config_check", "mbq_config_bits", "mbq_config_precision_value", "mbq_config_counts_bits", "mbq_linear_cfg", "mbq_encode_cfg", "mbq_unpack_cfg", "mbq_blob_bytes_cfg",
     "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg", "mbq_routed_linear_group_cfg",
     # include/mbq_bench.h: measurement and diagnostic entry points
     "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop", "mbq_bench_linear_group_prepared",
@@ -97,6 +97,8 @@ def load() -> ctypes.CDLL:
     lib.mbq_set_knob.argtypes = [c_int, c_int]
     c_cfg = ctypes.POINTER(Config)
     lib.mbq_config_check.argtypes = [c_cfg]
+    lib.mbq_blob_bytes_cfg.argtypes = [c_cfg, c_i64, c_i64]
+    lib.mbq_blob_bytes_cfg.restype = c_sz
     lib.mbq_config_bits.argtypes = [c_cfg, c_int]
     lib.mbq_config_precision_value.argtypes = [c_cfg, c_int]
     lib.mbq_config_counts_bits.argtypes = [c_cfg]
@@ -412,20 +414,27 @@ def mbq_linear_cfg(X: torch.Tensor, blob: torch.Tensor, N: int, K: int, cfg: Con
     return Y
 
 
+def blob_bytes_cfg(cfg: Config, N: int, K: int) -> int:
+    n = int(load().mbq_blob_bytes_cfg(ctypes.byref(cfg), N, K))
+    if n == 0:
+        raise MbqError(f"mbq_blob_bytes_cfg: {load().mbq_last_error().decode()}")
+    return n
+
+
 def mbq_encode_cfg(W: torch.Tensor, cfg: Config, blob: Optional[torch.Tensor] = None) -> torch.Tensor:
     assert W.dtype == torch.float32 and W.dim() == 2
     N, K = W.shape
     if blob is None:
-        blob = torch.empty(blob_bytes(N, K), dtype=torch.uint8, device=W.device)
+        blob = torch.empty(blob_bytes_cfg(cfg, N, K), dtype=torch.uint8, device=W.device)
     _check(load().mbq_encode_cfg(_ptr(W.contiguous()), N, K, ctypes.byref(cfg), _ptr(blob), _stream()),
            "mbq_encode_cfg")
     return blob
 
 
 def mbq_unpack_cfg(blob: torch.Tensor, N: int, K: int, cfg: Config):
-    """-> (codes uint8 [E, N, K], scale fp32 [N, K/128], zero fp32 [N, K/128]) in the configuration's terms."""
+    """-> (codes uint8 [E, N, K], scale fp32 [N, K/group], zero fp32 [N, K/group]) in the configuration's terms."""
     codes = torch.empty((cfg.n_slices, N, K), dtype=torch.uint8, device=blob.device)
-    scale = torch.empty((N, K // GROUP), dtype=torch.float32, device=blob.device)
+    scale = torch.empty((N, K // cfg.group), dtype=torch.float32, device=blob.device)
     zero = torch.empty_like(scale)
     _check(load().mbq_unpack_cfg(_ptr(blob), N, K, ctypes.byref(cfg), _ptr(codes), _ptr(scale), _ptr(zero), _stream()),
            "mbq_unpack_cfg")

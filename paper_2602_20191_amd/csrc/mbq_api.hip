@@ -37,7 +37,7 @@ mbq_status hip_status(hipError_t e, const char* what) {
 
 int knob(int index) { return (index >= 0 && index < kKnobs) ? t_knobs[index] : 0; }
 
-bool make_shape(int64_t N, int64_t K, Shape* out) {
+bool make_shape(int64_t N, int64_t K, Shape* out, int group) {
   if (N <= 0 || K <= 0) {
     set_error("N and K must be positive (N=%lld, K=%lld)", (long long)N, (long long)K);
     return false;
@@ -55,10 +55,12 @@ bool make_shape(int64_t N, int64_t K, Shape* out) {
   s.K = K;
   s.NT = (int)((N + kTileN - 1) / kTileN);
   s.KB = (int)((K + kTileK - 1) / kTileK);
-  s.G = (int)(K / kGroup);
+  s.group = group;
+  s.gshift = group == 128 ? 7 : (group == 64 ? 6 : 5);
+  s.G = (int)(K / group);
   s.slice_words = (size_t)s.NT * s.KB * kTileWords;
   s.meta_offset = (size_t)kSlices * s.slice_words * 4;
-  s.bytes = s.meta_offset + (size_t)s.NT * (2 * s.KB) * kTileN * 8;
+  s.bytes = s.meta_offset + (size_t)s.NT * ((kTileK / group) * s.KB) * kTileN * 8;
   *out = s;
   return true;
 }
@@ -96,8 +98,8 @@ static bool make_view(const mbq_config* cfg, RouteView* v, const char* who) {
     set_error("%s: %d slices, supported 1..%d", who, cfg->n_slices, MBQ_MAX_SLICES);
     return false;
   }
-  if (cfg->group != kGroup) {
-    set_error("%s: group size %d, only %d is supported", who, cfg->group, kGroup);
+  if (cfg->group != kGroup && cfg->group != 64 && cfg->group != 32) {
+    set_error("%s: group size %d, supported: %d, 64, 32", who, cfg->group, kGroup);
     return false;
   }
   int bits = 0;
@@ -121,6 +123,7 @@ static bool make_view(const mbq_config* cfg, RouteView* v, const char* who) {
     v->digits[e] = v->digits[cfg->n_slices - 1];
   }
   v->shift = odd ? 1 : 0;
+  v->group = cfg->group;
   for (int e = 0; e < MBQ_N_PRECISIONS; ++e) v->value[e] = odd ? v->bits[e] - 1 : v->digits[e];
   return true;
 }
@@ -463,10 +466,12 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
                                    void* ws_route, size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
                                    int algo, void* stream) {
   ApiScope scope;
-  if (t_view->shift != 0) {
+  if (t_view->shift != 0 || t_view->group != kGroup) {
     // A configuration with an odd cumulative width: the precision arrays count bits.  The loader-wavefront decode
     // kernels understand that (one token tile); every other shape goes through the slow
-    // one-thread-per-output kernel.  (T = 0: the routing call writes the empty offsets.)
+    // one-thread-per-output kernel, and so does every shape of a configuration with groups of 64 or 32 columns.
+    // (T = 0: the routing call writes the empty offsets.)
+    const bool bit_view = t_view->shift != 0;
     if (T == 0)  // the routing call checks its arguments and writes the empty offsets; there is nothing to multiply
       return mbq_route_group(X, T, K, n_proj, Wr_host, br_host, P, prec_host, perm_host, offsets_host, ws_route,
                              ws_route_bytes, stream);
@@ -492,7 +497,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
     }
     Shape sh[MBQ_MAX_GROUP];
     for (int i = 0; i < n_proj; ++i) {
-      if (!make_shape(N_host[i], K, &sh[i])) return MBQ_ERR_BAD_SHAPE;
+      if (!make_shape(N_host[i], K, &sh[i], t_view->group)) return MBQ_ERR_BAD_SHAPE;
       if (!blob_host[i] || !aligned(blob_host[i], 256) || !Y_host[i] || !X || !aligned(X, 16)) {
         set_error("mbq_routed_linear_group_cfg: null or misaligned pointer for projection %d", i);
         return MBQ_ERR_INVALID_ARG;
@@ -502,8 +507,8 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
         return MBQ_ERR_WORKSPACE;
       }
     }
-    if (algo != MBQ_ALGO_SIMPLE && algo != MBQ_ALGO_PREFILL && knob(3) == 0 && decode_f4_takes_bit_view(T, sh[0]) &&
-        route_can_carry_prep(T)) {
+    if (bit_view && t_view->group == kGroup && algo != MBQ_ALGO_SIMPLE && algo != MBQ_ALGO_PREFILL && knob(3) == 0 &&
+        decode_f4_takes_bit_view(T, sh[0]) && route_can_carry_prep(T)) {
       ZeroList zl;
       decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
       mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
@@ -516,7 +521,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
     mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr,
                                        ws_route, (hipStream_t)stream, nullptr, 0, nullptr, false, *t_view);
     for (int i = 0; st == MBQ_OK && i < n_proj; ++i)
-      st = launch_linear_simple(X, T, blob_host[i], sh[i], prec_host[i], Y_host[i], (hipStream_t)stream, true);
+      st = launch_linear_simple(X, T, blob_host[i], sh[i], prec_host[i], Y_host[i], (hipStream_t)stream, bit_view);
     return st;
   }
   // the fused form: the router launch also prepares the activations of the decode kernel
@@ -715,10 +720,23 @@ int mbq_config_counts_bits(const mbq_config* cfg) {
   return v.shift;
 }
 
+size_t mbq_blob_bytes_cfg(const mbq_config* cfg, int64_t N, int64_t K) {
+  RouteView v;
+  Shape sh;
+  return make_view(cfg, &v, "mbq_blob_bytes_cfg") && make_shape(N, K, &sh, v.group) ? sh.bytes : 0;
+}
+
 mbq_status mbq_encode_cfg(const float* W, int64_t N, int64_t K, const mbq_config* cfg, void* blob, void* stream) {
   RouteView v;
   if (!make_view(cfg, &v, "mbq_encode_cfg")) return MBQ_ERR_BAD_SHAPE;
-  return mbq_encode(W, N, K, blob, stream);
+  if (v.group == kGroup) return mbq_encode(W, N, K, blob, stream);
+  Shape sh;
+  if (!make_shape(N, K, &sh, v.group)) return MBQ_ERR_BAD_SHAPE;
+  if (!W || !blob || !aligned(blob, 256) || !aligned(W, 16)) {
+    set_error("mbq_encode_cfg: W must be 16-byte and blob 256-byte aligned and non-null");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_encode_small_group(W, sh, blob, (hipStream_t)stream);
 }
 
 mbq_status mbq_unpack_cfg(const void* blob, int64_t N, int64_t K, const mbq_config* cfg, uint8_t* codes,
@@ -726,7 +744,7 @@ mbq_status mbq_unpack_cfg(const void* blob, int64_t N, int64_t K, const mbq_conf
   RouteView v;
   if (!make_view(cfg, &v, "mbq_unpack_cfg")) return MBQ_ERR_BAD_SHAPE;
   Shape sh;
-  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!make_shape(N, K, &sh, v.group)) return MBQ_ERR_BAD_SHAPE;
   if (!blob || !aligned(blob, 256)) {
     set_error("mbq_unpack_cfg: blob must be non-null and 256-byte aligned");
     return MBQ_ERR_INVALID_ARG;
@@ -743,7 +761,7 @@ mbq_status mbq_dequant_cfg(const void* blob, int64_t N, int64_t K, const mbq_con
     return MBQ_ERR_INVALID_ARG;
   }
   Shape sh;
-  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!make_shape(N, K, &sh, v.group)) return MBQ_ERR_BAD_SHAPE;
   if (!blob || !What || !aligned(blob, 256)) {
     set_error("mbq_dequant_cfg: null or misaligned pointer");
     return MBQ_ERR_INVALID_ARG;
@@ -756,10 +774,11 @@ mbq_status mbq_linear_cfg(const uint16_t* X, int64_t T, const void* blob, int64_
                           float* Y, void* ws, size_t ws_bytes, int algo, void* stream) {
   RouteView v;
   if (!make_view(cfg, &v, "mbq_linear_cfg")) return MBQ_ERR_BAD_SHAPE;
-  if (v.shift == 0) return mbq_linear(X, T, blob, N, K, prec, perm, offsets, Y, ws, ws_bytes, algo, stream);
+  if (v.shift == 0 && v.group == kGroup)
+    return mbq_linear(X, T, blob, N, K, prec, perm, offsets, Y, ws, ws_bytes, algo, stream);
   ApiScope scope;
   Shape sh;
-  if (!make_shape(N, K, &sh)) return MBQ_ERR_BAD_SHAPE;
+  if (!make_shape(N, K, &sh, v.group)) return MBQ_ERR_BAD_SHAPE;
   if (T < 0 || T > (int64_t)1 << 24) {
     set_error("mbq_linear_cfg: bad token count %lld", (long long)T);
     return MBQ_ERR_BAD_SHAPE;
@@ -779,14 +798,15 @@ mbq_status mbq_linear_cfg(const uint16_t* X, int64_t T, const void* blob, int64_
     return MBQ_ERR_WORKSPACE;
   }
   hipStream_t s = (hipStream_t)stream;
-  if (algo != MBQ_ALGO_SIMPLE && algo != MBQ_ALGO_PREFILL && knob(3) == 0 && decode_f4_takes_bit_view(T, sh)) {
+  if (v.group == kGroup && algo != MBQ_ALGO_SIMPLE && algo != MBQ_ALGO_PREFILL && knob(3) == 0 &&
+      decode_f4_takes_bit_view(T, sh)) {
     ZeroList zl;
     decode_f4_zero_list(T, 1, &sh, &Y, &zl);
     mbq_status st = launch_decode_f4_prep(X, T, sh.K, sh.KB, ws, zl, s);
     if (st != MBQ_OK) return st;
     return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s, nullptr, nullptr, nullptr, true);
   }
-  return launch_linear_simple(X, T, blob, sh, prec, Y, s, true);
+  return launch_linear_simple(X, T, blob, sh, prec, Y, s, v.shift != 0);
 }
 
 mbq_status mbq_route_cfg(const uint16_t* X, int64_t T, int64_t K, const float* Wr, const float* br,

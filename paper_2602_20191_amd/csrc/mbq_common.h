@@ -21,13 +21,16 @@ struct Shape {
   int64_t N, K;
   int NT;               // row tiles, ceil(N / 16)
   int KB;               // column tiles, ceil(K / 256)
-  int G;                // real groups per row, K / 128
+  int G;                // real groups per row, K / group
   size_t slice_words;   // uint32 words of one slice = NT * KB * 256
   size_t meta_offset;   // byte offset of the {s0, z0} section
   size_t bytes;         // total blob bytes
+  int group;            // columns per quantisation group: 128, or 64 / 32 (configurations; slow kernels only)
+  int gshift;           // log2(group)
 };
 
-bool make_shape(int64_t N, int64_t K, Shape* out);  // false (and error set) if invalid
+// false (and error set) if invalid
+bool make_shape(int64_t N, int64_t K, Shape* out, int group = kGroup);
 void set_error(const char* fmt, ...);
 mbq_status hip_status(hipError_t e, const char* what);
 int knob(int index);  // the calling thread's snapshot of the hooks, taken by the outermost ApiScope
@@ -58,9 +61,9 @@ __host__ __device__ inline int code_bit(int e, int64_t k) {
   const int s = r & 7;
   return (16 * (s & 1) + 4 * (s >> 1) + 2 * step + 2 - 2 * e) & 31;
 }
-// Index of the float2 {s0, z0} of (row n, group g) inside the meta section.
-__host__ __device__ inline size_t meta_index(int KB, int64_t n, int g) {
-  return ((size_t)(n >> 4) * (2 * KB) + g) * kTileN + (size_t)(n & 15);
+// Index of the float2 {s0, z0} of (row n, group g) inside the meta section; per_tile = groups per 256 columns.
+__host__ __device__ inline size_t meta_index(int KB, int64_t n, int g, int per_tile = 2) {
+  return ((size_t)(n >> 4) * (per_tile * KB) + g) * kTileN + (size_t)(n & 15);
 }
 
 // Output arrays that the activation-preparation launch clears for a linear kernel that adds into
@@ -83,12 +86,15 @@ struct RouteView {
   int digits[MBQ_N_PRECISIONS];
   int value[MBQ_N_PRECISIONS];
   int shift;
+  int group;  // columns per quantisation group (the routers do not care; the blob's metadata section does)
 };
-constexpr RouteView kDefaultView = {MBQ_N_PRECISIONS, {2, 4, 6, 8}, {0, 1, 2, 3}, {0, 1, 2, 3}, 0};
+constexpr RouteView kDefaultView = {MBQ_N_PRECISIONS, {2, 4, 6, 8}, {0, 1, 2, 3}, {0, 1, 2, 3}, 0, kGroup};
 
 // ---- kernels' host launchers (each enqueues on `stream`, returns a status) ------
 mbq_status launch_encode(const float* W, const Shape& sh, void* blob, const float* ext_scale, const float* ext_zero,
                          hipStream_t stream);
+// groups of 64 or 32 columns (sh.group): same code section, a metadata section of 256 / group pairs per tile row
+mbq_status launch_encode_small_group(const float* W, const Shape& sh, void* blob, hipStream_t stream);
 mbq_status launch_unpack(const void* blob, const Shape& sh, uint8_t* codes, float* scale, float* zero,
                          hipStream_t stream);
 mbq_status launch_dequant(const void* blob, const Shape& sh, int p, float* What, hipStream_t stream);

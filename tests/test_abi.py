@@ -143,8 +143,22 @@ def test_configuration_checks_need_no_gpu(lib):
             acc += b
             assert lib.mbq_config_bits(ctypes.byref(c), p) == acc
             assert lib.mbq_config_precision_value(ctypes.byref(c), p) == acc - 1
-    for bits, group in [((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((3, 3, 3), 128), ((), 128), ((0, 2), 128),
-                        ((2, 2, 2, 2, 2), 128)]:
+    for bits, group in [((2, 2, 2, 2), 16), ((2, 2, 2, 2), 96), ((2, 2, 2, 2), 256), ((4, 4, 2), 128), ((3, 3, 3), 128),
+                        ((), 128), ((0, 2), 128), ((2, 2, 2, 2, 2), 128)]:
         c = cfg(bits, group)
         assert lib.mbq_config_check(ctypes.byref(c)) == 2, (bits, group)
     assert lib.mbq_config_check(None) == 2
+    # groups of 64 and 32 columns: same code section, 256 / group {s0, z0} pairs per row and 256-column tile
+    lib.mbq_blob_bytes_cfg.restype = ctypes.c_size_t
+    lib.mbq_blob_bytes_cfg.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64]
+    lib.mbq_blob_bytes.restype = ctypes.c_size_t
+    lib.mbq_blob_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+    N, K = 37, 640                                                   # 3 row tiles x 3 column tiles
+    code_bytes = 4 * 3 * 3 * 1024
+    for group, per_tile in ((128, 2), (64, 4), (32, 8)):
+        c = cfg((3, 2, 1), group)
+        assert lib.mbq_config_check(ctypes.byref(c)) == 0
+        assert lib.mbq_blob_bytes_cfg(ctypes.byref(c), N, K) == code_bytes + 3 * 3 * per_tile * 16 * 8
+    assert lib.mbq_blob_bytes_cfg(ctypes.byref(cfg((2, 2, 2, 2))), N, K) == lib.mbq_blob_bytes(N, K)
+    assert lib.mbq_blob_bytes_cfg(ctypes.byref(cfg((2, 2, 2, 2), 48)), N, K) == 0
+    assert lib.mbq_blob_bytes_cfg(ctypes.byref(cfg((2, 2, 2, 2), 64)), N, 192) == 0      # K stays a multiple of 128

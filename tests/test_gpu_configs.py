@@ -132,16 +132,91 @@ def test_stage_call_under_a_configuration(mbq, bits, T, K, Ns):
         assert_output_close(Ys2[i].cpu().numpy(), want, f"config {bits} matrix {i}, two calls")
 
 
+SMALL_GROUPS = [((2, 2, 2, 2), 64), ((4, 2, 2), 64), ((3, 2, 1), 64), ((2, 2, 2, 2), 32), ((4, 1, 1, 2), 32),
+                ((8,), 32), ((2, 3), 64)]
+
+
+@pytest.mark.parametrize("bits,group", SMALL_GROUPS)
+def test_groups_of_64_and_32_columns_encode_bit_exact(mbq, bits, group):
+    """App. C.1 lists the group size among the settings: codes, (s_0, z_0) per group and every W^(p) against the
+    general oracle at that group size; the blob has the documented size and is written in full."""
+    N, K = 37, 640
+    print(f"[case] config {bits} group {group}: encode / unpack / dequant N={N} K={K}", flush=True)
+    cfg = mbq.Config(bits, group)
+    mbq.config_check(cfg)
+    W = make_weight(N, K, [71, len(bits), bits[0], group], 4.0)
+    blob = mbq.mbq_encode_cfg(dev(W), cfg)
+    assert blob.numel() == mbq.blob_bytes_cfg(cfg, N, K) > mbq.blob_bytes(N, K)
+    codes, s0, z0 = G.encode(W, bits, group)
+    c, s, z = mbq.mbq_unpack_cfg(blob, N, K, cfg)
+    torch.cuda.synchronize()
+    assert s.shape == (N, K // group)
+    assert np.array_equal(c.cpu().numpy(), np.stack(codes).astype(np.uint8))
+    assert np.array_equal(s.cpu().numpy(), s0) and np.array_equal(z.cpu().numpy(), z0)
+    for p in range(len(bits)):
+        What = mbq.mbq_dequant_cfg(blob, N, K, cfg, p).cpu().numpy()
+        np.testing.assert_allclose(What, G.dequant(codes, s0, z0, bits, group, p).astype(np.float32), rtol=0, atol=0)
+    # rows and groups of the padding hold zeros: the blob is written in full, whatever the buffer held before
+    blob2 = torch.full_like(blob, 0xA5)
+    mbq.mbq_encode_cfg(dev(W), cfg, blob2)
+    assert torch.equal(blob, blob2)
+
+
+@pytest.mark.parametrize("bits,group,T,K,Ns", [((2, 2, 2, 2), 64, 16, 1024, (100, 48)), ((4, 2, 2), 64, 40, 512, (72,)),
+                                               ((3, 2, 1), 64, 9, 768, (64, 33)), ((2, 2, 2, 2), 32, 70, 256, (96,)),
+                                               ((4, 1, 1, 2), 32, 16, 640, (40,)), ((8,), 32, 3, 384, (50,)),
+                                               ((2, 2, 2, 2), 64, 0, 256, (16,))])
+def test_stage_call_with_groups_of_64_and_32_columns(mbq, bits, group, T, K, Ns):
+    """The routed stage and route_cfg + linear_cfg on blobs with smaller groups (the one-thread-per-output kernel at
+    every token count) against the general oracle at that group size."""
+    print(f"[case] config {bits} group {group}: stage T={T} K={K} Ns={Ns}", flush=True)
+    cfg = mbq.Config(bits, group)
+    E = len(bits)
+    rng = np.random.default_rng([T, K, E, group])
+    xb = tokens(T, K, [T, K, 9])
+    X = dev_bf16(xb).reshape(T, K)
+    Wrs = [(rng.standard_normal((E, K)) / np.sqrt(K)).astype(np.float32) for _ in Ns]
+    brs = [rng.normal(0, 0.3, size=E).astype(np.float32) for _ in Ns]
+    Ws = [make_weight(N, K, [73, N, K, i], 4.0) for i, N in enumerate(Ns)]
+    blobs = [mbq.mbq_encode_cfg(dev(W), cfg) for W in Ws]
+    dWr, dbr = [dev(w) for w in Wrs], [dev(b) for b in brs]
+    routing, Ys = mbq.mbq_routed_linear_group_cfg(X, dWr, dbr, cfg, blobs, list(Ns))
+    torch.cuda.synchronize()
+    routing2 = mbq.mbq_route_group_cfg(X, dWr, dbr, cfg)
+    values, digits = stored_values(mbq, cfg, E)
+    shift = 1 if mbq.config_counts_bits(cfg) else 0
+    back = {int(d): p for p, d in enumerate(values)}
+    for i, N in enumerate(Ns):
+        for a, b in zip(routing[i], routing2[i]):
+            assert torch.equal(a, b), i
+        Y2 = mbq.mbq_linear_cfg(X, blobs[i], N, K, cfg, *routing2[i])
+        assert torch.equal(Ys[i], Y2), i
+        assert Ys[i].shape == (T, N)
+        if T == 0:
+            continue
+        prec = routing[i][0].cpu().numpy()
+        if E > 1:
+            _, prec_ref, gap = O.route(xb, Wrs[i], brs[i])
+        else:
+            prec_ref, gap = np.zeros(T, dtype=np.int32), np.full(T, np.inf)
+        compare_routing(prec, values[prec_ref], gap, f"stage router {i}")
+        check_bucket(prec >> shift, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
+        prec_cfg = np.array([back[int(d)] for d in prec], dtype=np.int32)
+        codes, s0, z0 = G.encode(Ws[i], bits, group)
+        want = G.linear(xb, codes, s0, z0, bits, group, prec_cfg)
+        assert_output_close(Ys[i].cpu().numpy(), want, f"config {bits} group {group} matrix {i}")
+
+
 def test_unsupported_configurations_are_refused(mbq):
-    for bits, group in [((2, 2, 2, 2), 64), ((4, 4, 2), 128), ((3, 3, 3), 128), ((2, 2, 2, 2, 2), 128),
-                        ((), 128), ((0, 2), 128)]:
+    for bits, group in [((2, 2, 2, 2), 16), ((2, 2, 2, 2), 96), ((4, 4, 2), 128), ((3, 3, 3), 128),
+                        ((2, 2, 2, 2, 2), 128), ((), 128), ((0, 2), 128)]:
         cfg = mbq.Config(bits[:4], group)
         cfg.n_slices = len(bits)
         with pytest.raises(mbq.MbqError):
             mbq.config_check(cfg)
     W = dev(make_weight(16, 256, [1], 4.0))
     with pytest.raises(mbq.MbqError):
-        mbq.mbq_encode_cfg(W, mbq.Config((2, 2, 2, 2), 64))
+        mbq.mbq_encode_cfg(W, mbq.Config((2, 2, 2, 2), 16))
     # P must match the configuration
     cfg = mbq.Config((4, 2, 2))
     X = dev_bf16(tokens(4, 256, 1)).reshape(4, 256)
