@@ -535,6 +535,66 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
             mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [l["blobs"][0] for l in st["layers"]], st["Ns"],
                                         routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"], ws_linear=st["ws_l"])
         torch.cuda.synchronize()
+    # the same block with 4-bit activations (App. E.4): per stage mbq_act_quant (transform, per-token quantiser, router
+    # input rebuilt in the original space), mbq_route_group on that input, mbq_linear_group on the integer activations,
+    # mbq_scale_rows per projection - the plain composition of the calls, nothing fused across them.  The block's own
+    # weights stand in for the transformed ones, the transform's shift and scale are drawn at random, the bias is zero.
+    if True:
+        T = T_main
+        rng_a = np.random.default_rng(2602)
+        act = []
+        for st in stages:
+            K = st["X"].shape[1]
+            act.append({
+                "shift": torch.from_numpy(rng_a.normal(0, 0.1, size=K).astype(np.float32)).to(dev),
+                "scale": torch.from_numpy(np.exp2(rng_a.uniform(-1, 1, size=K)).astype(np.float32)).to(dev),
+                "out": (torch.empty_like(st["X"]), torch.empty((T,), dtype=torch.float32, device=dev),
+                        torch.empty_like(st["X"])),
+                "bias": [torch.zeros((N,), dtype=torch.float32, device=dev) for N in st["Ns"]]})
+
+        def one_act(slot):
+            for st, a_ in zip(stages, act):
+                K = st["X"].shape[1]
+                xi, rs, xr = mbq.mbq_act_quant(st["X"], 4, a_["shift"], a_["scale"], out=a_["out"])
+                mbq.mbq_route_group(xr, st["Wr"], st["br"], out=st["routing"], ws=st["ws_r"])
+                mbq.mbq_linear_group(xi, [l["blobs"][slot] for l in st["layers"]], st["Ns"], K, st["routing"],
+                                     Y=st["Y"], ws=st["ws_l"])
+                for y, b_ in zip(st["Y"], a_["bias"]):
+                    mbq.mbq_scale_rows(y, rs, b_)
+
+        one_act(0)
+        torch.cuda.synchronize()
+        per_replay = 10
+        graphs = []
+        try:
+            for slot in range(RING):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for j in range(per_replay):
+                        one_act((slot + j) % RING)
+                graphs.append(g)
+        except Exception:
+            graphs, per_replay = [], 1
+        n = 6 if graphs else 60
+        for i in range(1 if graphs else 6):
+            graphs[i % RING].replay() if graphs else one_act(i % RING)
+        a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n):
+            graphs[i % RING].replay() if graphs else one_act(i % RING)
+        b2.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b2) / (n * per_replay)
+        extra[f"activations_4bit_decode_batch_{T}"] = {
+            "workload": "the block of the main line with 4-bit per-token activations: quantise, route on the rebuilt "
+                        "activations, routed linears on the integers, row scaling; separate calls, nothing fused",
+            "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
+            "launches_per_step": sum(5 + len(st["Ns"]) for st in stages),
+            "launch": f"hipgraph, {per_replay} steps per replay" if graphs else "eager"}
+        for st in stages:
+            mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [l["blobs"][0] for l in st["layers"]], st["Ns"],
+                                        routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"], ws_linear=st["ws_l"])
+        torch.cuda.synchronize()
     # the prefill linears of BASELINE configs[2] (gate, up, down; 2048 tokens), each as the whole mbq_linear call
     # (gather/group-sum pre-kernel + tile kernel) timed with HIP events over back-to-back launches
     pcfg = CONFIGS[2]

@@ -370,6 +370,41 @@ mbq_status mbq_routed_linear_group_cfg(const uint16_t* X, int64_t T, int64_t K, 
                                        size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes, int algo,
                                        void* stream);
 
+/*
+ * Activation-quantised variant (App. E.4; `abits` of App. C.1: the paper's W3A4 / W4A4 / W5A4 runs use abits = 4)
+ * -------------------------------------------------------------------------------------------------------------
+ * App. E.4 keeps the sliced weights and the routers and changes what they are fed.  With a per-input-channel shift
+ * delta and scale s (the equivalent transform of the pipeline the paper builds on),
+ *     X~ = (X - delta) / s,   W~ = s (.) W,   B~ = B + delta W      so that  X~ W~ + B~ = X W + B,
+ * the main path multiplies the QUANTISED X~ with the slices of W~ (encode W~ with mbq_encode; folding s and delta into
+ * the weights and the bias is the caller's offline step), and the router reads the same quantised activations taken
+ * back to the original space, X_r = X~ (.) s + delta, so that it keeps working in the space it was trained in.
+ * The quantiser is not spelled out by the paper; this library takes the usual dynamic per-token asymmetric one with
+ * an integer zero point, every step ONE fp32 operation in this order: for a token's row t = X~[i][:],
+ *     lo = min(min t, 0), hi = max(max t, 0), scale = max(hi - lo, 2^-100) / (2^abits - 1),
+ *     zp = clamp(rint(-lo / scale), 0, 2^abits - 1),  q = clamp(rint(t / scale) + zp, 0, 2^abits - 1)
+ * (rint: to nearest, ties to even; inputs must be finite).
+ *
+ * mbq_act_quant writes, for T tokens,
+ *   Xint      : bf16 [T][K], the integers q - zp (|q - zp| <= 2^abits - 1: exact in bf16).  This is the X of the
+ *               linear calls: they multiply it exactly (also the decode kernels, whose two-piece split holds eight
+ *               bits), and Y[i][:] = row_scale[i] * (Xint[i][:] W~^(p_i)^T) + B~ is the layer's output;
+ *   row_scale : fp32 [T], the token's scale;
+ *   Xr        : bf16 [T][K] (may be NULL), the router's input ((q - zp) * scale) * s + delta, each step one fp32
+ *               operation, then rounded to nearest even - pass it as X to the mbq_route* calls.
+ *   X         : bf16 [T][K] (read) - the activations in the ORIGINAL space when let_shift / let_scale (fp32 [K]
+ *               each, both or neither) are given: the call applies (x - delta) / s itself; with both NULL, X is
+ *               taken as X~ and Xr is the dequantised X~.
+ * 2 <= abits <= 8; K a multiple of 128; X, Xint, Xr, let_shift, let_scale 16-byte aligned.
+ * mbq_scale_rows finishes the main path in place: Y[i][n] = Y[i][n] * row_scale[i] (+ bias[n] if bias is not NULL;
+ * fp32 [N]), one multiplication and one addition.
+ * Both are plain streaming launches (one workgroup per token / one thread per output); a stage of the variant is
+ * mbq_act_quant, mbq_route_group on Xr, mbq_linear_group on Xint, mbq_scale_rows per projection.
+ */
+mbq_status mbq_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
+                         const float* let_scale, uint16_t* Xint, float* row_scale, uint16_t* Xr, void* stream);
+mbq_status mbq_scale_rows(float* Y, int64_t T, int64_t N, const float* row_scale, const float* bias, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

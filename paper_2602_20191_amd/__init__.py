@@ -29,6 +29,8 @@ EXPORTS = (
     # other slice configurations
     "mbq_config_check", "mbq_config_bits", "mbq_config_precision_value", "mbq_config_counts_bits", "mbq_linear_cfg", "mbq_encode_cfg", "mbq_unpack_cfg", "mbq_blob_bytes_cfg",
     "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg", "mbq_routed_linear_group_cfg",
+    # activation-quantised variant
+    "mbq_act_quant", "mbq_scale_rows",
     # include/mbq_bench.h: measurement and diagnostic entry points
     "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop", "mbq_bench_linear_group_prepared",
     "mbq_bench_decode_timeline", "mbq_bench_decode_timeline_bytes", "mbq_bench_decode_timeline_workgroups",
@@ -114,6 +116,10 @@ def load() -> ctypes.CDLL:
                  "mbq_unpack_cfg", "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg",
                  "mbq_routed_linear_group_cfg"):
         getattr(lib, name).restype = c_int
+    lib.mbq_act_quant.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_p, c_p, c_p, c_p]
+    lib.mbq_act_quant.restype = c_int
+    lib.mbq_scale_rows.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_p]
+    lib.mbq_scale_rows.restype = c_int
     lib.mbq_bench_copy.argtypes = [c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_bench_read.argtypes = [c_p, c_sz, c_int, c_p, c_p]
     lib.mbq_bench_mfma_loop.argtypes = [c_int, c_int, c_p, ctypes.POINTER(ctypes.c_double), c_p]
@@ -555,3 +561,28 @@ def bench_decode_timeline(T: int, K: int, blobs: Sequence[torch.Tensor], Ns: Seq
                                          _ptr_array([r[0] for r in routing]), _ptr_array(Y), _ptr(ws), ws.numel(),
                                          _ptr(stamps), nbytes, _stream()), "mbq_bench_decode_timeline")
     return stamps.view(wgs, -1, 32)
+
+
+def mbq_act_quant(X: torch.Tensor, abits: int = 4, let_shift: Optional[torch.Tensor] = None,
+                  let_scale: Optional[torch.Tensor] = None, want_router_input: bool = True, out=None):
+    """X bf16 [T, K] -> (Xint bf16 [T, K] integers, row_scale fp32 [T], Xr bf16 [T, K] or None); App. E.4.
+    out: (Xint, row_scale, Xr) buffers to write into instead of new ones."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.is_contiguous()
+    T, K = X.shape
+    if out is not None:
+        Xint, row_scale, Xr = out
+    else:
+        Xint = torch.empty_like(X)
+        row_scale = torch.empty((T,), dtype=torch.float32, device=X.device)
+        Xr = torch.empty_like(X) if want_router_input else None
+    _check(load().mbq_act_quant(_ptr(X), T, K, abits, _ptr(let_shift), _ptr(let_scale), _ptr(Xint), _ptr(row_scale),
+                                _ptr(Xr), _stream()), "mbq_act_quant")
+    return Xint, row_scale, Xr
+
+
+def mbq_scale_rows(Y: torch.Tensor, row_scale: torch.Tensor, bias: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """In place: Y[i, n] = Y[i, n] * row_scale[i] (+ bias[n])."""
+    assert Y.dtype == torch.float32 and Y.dim() == 2 and Y.is_contiguous()
+    T, N = Y.shape
+    _check(load().mbq_scale_rows(_ptr(Y), T, N, _ptr(row_scale), _ptr(bias), _stream()), "mbq_scale_rows")
+    return Y

@@ -18,6 +18,7 @@ SOURCES = [
     ("mbq_api.hip", []),
     ("mbq_encode.hip", ["-ffp-contract=off"]),   # the code recursion is specified unfused
     ("mbq_route.hip", ["-ffp-contract=off"]),
+    ("mbq_act.hip", ["-ffp-contract=off"]),      # every step of the activation quantiser is one fp32 operation
     ("mbq_linear_simple.hip", []),
     ("mbq_linear_decode.hip", []),
     ("mbq_linear_decode16.hip", []),

@@ -844,4 +844,41 @@ mbq_status mbq_routed_linear_group_cfg(const uint16_t* X, int64_t T, int64_t K, 
                                  stream);
 }
 
+mbq_status mbq_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
+                         const float* let_scale, uint16_t* Xint, float* row_scale, uint16_t* Xr, void* stream) {
+  if (T < 0 || K <= 0 || K % kGroup != 0 || T > (int64_t)1 << 24 || K > (int64_t)1 << 24) {
+    set_error("mbq_act_quant: bad sizes (T=%lld, K=%lld; K must be a multiple of %d)", (long long)T, (long long)K,
+              kGroup);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (abits < 2 || abits > 8) {
+    set_error("mbq_act_quant: abits = %d, supported 2..8", abits);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if ((let_shift == nullptr) != (let_scale == nullptr)) {
+    set_error("mbq_act_quant: pass both the shift and the scale of the transform, or neither");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (T == 0) return MBQ_OK;
+  if (!X || !Xint || !row_scale || !aligned(X, 16) || !aligned(Xint, 16) || !aligned(Xr, 16) ||
+      !aligned(let_shift, 16) || !aligned(let_scale, 16)) {
+    set_error("mbq_act_quant: null or misaligned pointer (16-byte alignment for X, Xint, Xr, shift and scale)");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_act_quant(X, T, K, abits, let_shift, let_scale, Xint, row_scale, Xr, (hipStream_t)stream);
+}
+
+mbq_status mbq_scale_rows(float* Y, int64_t T, int64_t N, const float* row_scale, const float* bias, void* stream) {
+  if (T < 0 || N <= 0 || T > (int64_t)1 << 24 || N > (int64_t)1 << 24) {
+    set_error("mbq_scale_rows: bad sizes (T=%lld, N=%lld)", (long long)T, (long long)N);
+    return MBQ_ERR_BAD_SHAPE;
+  }
+  if (T == 0) return MBQ_OK;
+  if (!Y || !row_scale) {
+    set_error("mbq_scale_rows: null pointer");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  return launch_scale_rows(Y, T, N, row_scale, bias, (hipStream_t)stream);
+}
+
 }  // extern "C"

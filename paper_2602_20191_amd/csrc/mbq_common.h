@@ -189,6 +189,12 @@ bool decode_f4_takes_bit_view(int64_t T, const Shape& sh);
 // timeline build of the ring kernel: workgroups it launches at most, and 8-byte slots each of them writes
 int decode_f4_timeline_workgroups();
 int decode_f4_timeline_slots();
+// activation-quantised variant (App. E.4): per-token quantiser and the row scaling that finishes the main path
+mbq_status launch_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
+                            const float* let_scale, uint16_t* Xint, float* row_scale, uint16_t* Xr,
+                            hipStream_t stream);
+mbq_status launch_scale_rows(float* Y, int64_t T, int64_t N, const float* row_scale, const float* bias,
+                             hipStream_t stream);
 size_t decode_workspace_bytes(int64_t T, const Shape& sh);
 size_t prefill_workspace_bytes(int64_t T, const Shape& sh);
 

@@ -162,3 +162,21 @@ def test_configuration_checks_need_no_gpu(lib):
     assert lib.mbq_blob_bytes_cfg(ctypes.byref(cfg((2, 2, 2, 2))), N, K) == lib.mbq_blob_bytes(N, K)
     assert lib.mbq_blob_bytes_cfg(ctypes.byref(cfg((2, 2, 2, 2), 48)), N, K) == 0
     assert lib.mbq_blob_bytes_cfg(ctypes.byref(cfg((2, 2, 2, 2), 64)), N, 192) == 0      # K stays a multiple of 128
+
+
+def test_activation_quantiser_arguments_are_checked_without_a_gpu(lib):
+    lib.mbq_act_quant.restype = ctypes.c_int
+    lib.mbq_act_quant.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int] + [ctypes.c_void_p] * 6
+    lib.mbq_scale_rows.restype = ctypes.c_int
+    lib.mbq_scale_rows.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64] + [ctypes.c_void_p] * 3
+    fake = 0x10000                                            # never dereferenced: the calls are refused first
+    assert lib.mbq_act_quant(fake, 4, 100, 4, None, None, fake, fake, None, None) == 2      # K not a multiple of 128
+    assert lib.mbq_act_quant(fake, 4, 128, 1, None, None, fake, fake, None, None) == 1      # abits
+    assert lib.mbq_act_quant(fake, 4, 128, 9, None, None, fake, fake, None, None) == 1
+    assert lib.mbq_act_quant(fake, 4, 128, 4, fake, None, fake, fake, None, None) == 1      # shift without scale
+    assert lib.mbq_act_quant(fake + 2, 4, 128, 4, None, None, fake, fake, None, None) == 1  # misaligned X
+    assert lib.mbq_act_quant(None, 4, 128, 4, None, None, fake, fake, None, None) == 1
+    assert lib.mbq_act_quant(None, 0, 128, 4, None, None, None, None, None, None) == 0      # no tokens: nothing to do
+    assert lib.mbq_scale_rows(None, 4, 16, fake, None, None) == 1
+    assert lib.mbq_scale_rows(fake, 4, 0, fake, None, None) == 2
+    assert lib.mbq_scale_rows(None, 0, 16, None, None, None) == 0

@@ -1,0 +1,120 @@
+"""GPU parity for the activation-quantised variant (App. E.4): quantiser outputs bit for bit against the oracle, and
+the whole stage - quantise, route on the rebuilt activations, routed linears on the integers, row scaling and bias -
+against the oracle to the usual bar."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from oracle import mbq_oracle_act as A
+from helpers import assert_output_close, check_bucket, compare_routing, dev, dev_bf16
+from workloads import f32_to_bf16_bits, make_weight
+
+pytestmark = pytest.mark.gpu
+
+
+def activations(T, K, seed, offset=0.0):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, K)).astype(np.float32) + np.float32(offset)
+    if K:
+        x[:, rng.choice(K, max(1, K // 100), replace=False)] *= 15.0
+    return f32_to_bf16_bits(x)
+
+
+def let_params(K, seed):
+    rng = np.random.default_rng(seed)
+    s = np.exp2(rng.uniform(-1.5, 1.5, size=K)).astype(np.float32)
+    delta = rng.normal(0, 0.5, size=K).astype(np.float32)
+    return delta, s
+
+
+def bf16_tensor_bits(t: torch.Tensor) -> np.ndarray:
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("abits", [2, 4, 5, 8])
+@pytest.mark.parametrize("T,K,let,offset", [(1, 128, True, 0.0), (16, 4096, True, 0.0), (70, 640, False, 0.0),
+                                            (5, 11008, True, 2.0), (33, 2304, False, -30.0), (300, 256, True, 0.0)])
+def test_quantiser_is_bit_exact(mbq, abits, T, K, let, offset):
+    print(f"[case] act_quant abits={abits} T={T} K={K} let={let} offset={offset}", flush=True)
+    xb = activations(T, K, [abits, T, K], offset)
+    xb[0, : min(K, 128)] = 0                                     # a stretch of zeros; with T = 1, K = 128: an all-zero row
+    delta, s = let_params(K, [K, 7])
+    if let:
+        Xt = A.let_transform(xb, delta, s)
+        got = mbq.mbq_act_quant(dev_bf16(xb).reshape(T, K), abits, dev(delta), dev(s))
+    else:
+        Xt = A.bf16_bits_to_f32(xb)
+        got = mbq.mbq_act_quant(dev_bf16(xb).reshape(T, K), abits)
+    torch.cuda.synchronize()
+    xint, scale, zp, q = A.act_quant(Xt, abits)
+    assert np.array_equal(got[1].cpu().numpy(), scale)
+    assert np.array_equal(got[0].float().cpu().numpy().astype(np.int32), xint)
+    if let:
+        want_xr = A.router_input_bits(xint, scale, delta, s)
+    else:
+        want_xr = A.f32_to_bf16_bits_rne((xint.astype(np.float32) * scale[:, None]).astype(np.float32))
+    assert np.array_equal(bf16_tensor_bits(got[2]), want_xr)
+    # without the router input asked for, the rest is the same
+    again = mbq.mbq_act_quant(dev_bf16(xb).reshape(T, K), abits, dev(delta) if let else None, dev(s) if let else None,
+                              want_router_input=False)
+    assert again[2] is None and torch.equal(again[0], got[0]) and torch.equal(again[1], got[1])
+
+
+@pytest.mark.parametrize("abits,T,K,Ns", [(4, 16, 4096, (272, 130)), (4, 7, 11008, (64,)), (8, 16, 1280, (96, 40, 64)),
+                                          (4, 40, 2048, (130,)), (4, 64, 4096, (272,)), (6, 300, 768, (260, 100)),
+                                          (4, 1, 256, (16,))])
+def test_stage_of_the_variant(mbq, abits, T, K, Ns):
+    """mbq_act_quant -> mbq_route_group on the rebuilt activations -> mbq_linear_group on the integers ->
+    mbq_scale_rows with the folded bias, against Y = scale_i ((q - zp) W~^(p_i)^T) + B~ of the oracle."""
+    print(f"[case] W-A stage abits={abits} T={T} K={K} Ns={Ns}", flush=True)
+    rng = np.random.default_rng([abits, T, K, len(Ns)])
+    xb = activations(T, K, [T, K, 17])
+    delta, s = let_params(K, [K, 19])
+    Ws = [make_weight(N, K, [83, N, K, i], 4.0) for i, N in enumerate(Ns)]
+    Bs = [rng.standard_normal(N).astype(np.float32) for N in Ns]
+    folded = [A.let_fold(W, B, delta, s) for W, B in zip(Ws, Bs)]
+    Wt = [f[0].astype(np.float32) for f in folded]               # what gets encoded: W~ in fp32
+    Bt = [f[1].astype(np.float32) for f in folded]
+    Wrs = [(rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32) for _ in Ns]
+    brs = [rng.normal(0, 0.3, size=4).astype(np.float32) for _ in Ns]
+    # GPU
+    X = dev_bf16(xb).reshape(T, K)
+    Xint, row_scale, Xr = mbq.mbq_act_quant(X, abits, dev(delta), dev(s))
+    blobs = [mbq.mbq_encode(dev(W)) for W in Wt]
+    routing = mbq.mbq_route_group(Xr, [dev(w) for w in Wrs], [dev(b) for b in brs])
+    Ys = mbq.mbq_linear_group(Xint, blobs, list(Ns), K, routing)
+    for Y, B in zip(Ys, Bt):
+        mbq.mbq_scale_rows(Y, row_scale, dev(B))
+    torch.cuda.synchronize()
+    # oracle
+    xint, scale, zp, q = A.act_quant(A.let_transform(xb, delta, s), abits)
+    xr_bits = A.router_input_bits(xint, scale, delta, s)
+    assert np.array_equal(bf16_tensor_bits(Xr), xr_bits)
+    for i, N in enumerate(Ns):
+        prec = routing[i][0].cpu().numpy()
+        _, prec_ref, gap = O.route(xr_bits, Wrs[i], brs[i])
+        compare_routing(prec, prec_ref, gap, f"router {i} on the rebuilt activations")
+        check_bucket(prec, routing[i][1].cpu().numpy(), routing[i][2].cpu().numpy())
+        codes, s0, z0 = O.encode(Wt[i])
+        Wp = [O.dequant(codes, s0, z0, p) for p in range(4)]
+        want = A.w_a_linear(xint, scale, lambda t: Wp[int(prec[t])], Bt[i])
+        assert_output_close(Ys[i].cpu().numpy(), want, f"W-A stage abits={abits} matrix {i}")
+
+
+def test_scale_rows_alone_and_empty_inputs(mbq):
+    rng = np.random.default_rng(3)
+    Y = rng.standard_normal((37, 130)).astype(np.float32)
+    sc = np.exp2(rng.uniform(-4, 4, size=37)).astype(np.float32)
+    b = rng.standard_normal(130).astype(np.float32)
+    got = mbq.mbq_scale_rows(dev(Y.copy()), dev(sc), dev(b)).cpu().numpy()
+    assert np.array_equal(got, ((Y * sc[:, None]).astype(np.float32) + b[None, :]).astype(np.float32))
+    got = mbq.mbq_scale_rows(dev(Y.copy()), dev(sc)).cpu().numpy()
+    assert np.array_equal(got, (Y * sc[:, None]).astype(np.float32))
+    empty = torch.empty((0, 256), dtype=torch.bfloat16, device="cuda")
+    xi, rs, xr = mbq.mbq_act_quant(empty, 4)
+    assert xi.shape == (0, 256) and rs.shape == (0,)
+    with pytest.raises(mbq.MbqError):
+        mbq.mbq_act_quant(torch.zeros((2, 256), dtype=torch.bfloat16, device="cuda"), 9)
+    with pytest.raises(mbq.MbqError):
+        mbq.mbq_act_quant(torch.zeros((2, 192), dtype=torch.bfloat16, device="cuda"), 4)
