@@ -535,10 +535,11 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
             mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [l["blobs"][0] for l in st["layers"]], st["Ns"],
                                         routing=st["routing"], Y=st["Y"], ws_route=st["ws_r"], ws_linear=st["ws_l"])
         torch.cuda.synchronize()
-    # the same block with 4-bit activations (App. E.4): per stage mbq_act_quant (transform, per-token quantiser, router
-    # input rebuilt in the original space), mbq_route_group on that input, mbq_linear_group on the integer activations,
-    # mbq_scale_rows per projection - the plain composition of the calls, nothing fused across them.  The block's own
-    # weights stand in for the transformed ones, the transform's shift and scale are drawn at random, the bias is zero.
+    # the same block with 4-bit activations (App. E.4), one mbq_routed_linear_group_act call per stage: the quantiser
+    # launch (transform, per-token quantiser, router input rebuilt in the original space), the router launch on that
+    # input (which also prepares the integer activations for the decode kernel), the linear launch, one launch for the
+    # row scaling and bias of the stage's projections.  The block's own weights stand in for the transformed ones, the
+    # transform's shift and scale are drawn at random, the bias is zero.
     if True:
         T = T_main
         rng_a = np.random.default_rng(2602)
@@ -554,13 +555,10 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
 
         def one_act(slot):
             for st, a_ in zip(stages, act):
-                K = st["X"].shape[1]
-                xi, rs, xr = mbq.mbq_act_quant(st["X"], 4, a_["shift"], a_["scale"], out=a_["out"])
-                mbq.mbq_route_group(xr, st["Wr"], st["br"], out=st["routing"], ws=st["ws_r"])
-                mbq.mbq_linear_group(xi, [l["blobs"][slot] for l in st["layers"]], st["Ns"], K, st["routing"],
-                                     Y=st["Y"], ws=st["ws_l"])
-                for y, b_ in zip(st["Y"], a_["bias"]):
-                    mbq.mbq_scale_rows(y, rs, b_)
+                mbq.mbq_routed_linear_group_act(st["X"], 4, a_["shift"], a_["scale"], st["Wr"], st["br"],
+                                                [l["blobs"][slot] for l in st["layers"]], st["Ns"], bias=a_["bias"],
+                                                routing=st["routing"], Y=st["Y"], act=a_["out"], ws_route=st["ws_r"],
+                                                ws_linear=st["ws_l"])
 
         one_act(0)
         torch.cuda.synchronize()
@@ -587,9 +585,9 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         ms = a.elapsed_time(b2) / (n * per_replay)
         extra[f"activations_4bit_decode_batch_{T}"] = {
             "workload": "the block of the main line with 4-bit per-token activations: quantise, route on the rebuilt "
-                        "activations, routed linears on the integers, row scaling; separate calls, nothing fused",
+                        "activations, routed linears on the integers, row scaling; one stage call each",
             "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
-            "launches_per_step": sum(5 + len(st["Ns"]) for st in stages),
+            "launches_per_step": 4 * len(stages),
             "launch": f"hipgraph, {per_replay} steps per replay" if graphs else "eager"}
         for st in stages:
             mbq.mbq_routed_linear_group(st["X"], st["Wr"], st["br"], [l["blobs"][0] for l in st["layers"]], st["Ns"],

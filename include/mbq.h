@@ -309,8 +309,9 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
  * records its group size).  mbq_linear_cfg and mbq_routed_linear_group_cfg run these blobs through the
  * one-thread-per-output kernel of MBQ_ALGO_SIMPLE at every token count: correct and slow; none of the fast kernels
  * reads the larger metadata section.  scale / zero of mbq_unpack_cfg are then fp32 [N][K/group].
- * Other group sizes and 16-bit scale / zero-point storage: not built; the calls below refuse them with
- * MBQ_ERR_BAD_SHAPE.
+ * Other group sizes: not built; the calls below refuse them with MBQ_ERR_BAD_SHAPE.  Scale and zero point are
+ * stored as fp32 whatever the configuration; a pipeline that keeps them in 16 bits hands its rounded values to
+ * mbq_encode_with_params and gets the codes that belong to them.
  */
 #define MBQ_MAX_SLICES 4
 typedef struct mbq_config {
@@ -404,6 +405,24 @@ mbq_status mbq_routed_linear_group_cfg(const uint16_t* X, int64_t T, int64_t K, 
 mbq_status mbq_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
                          const float* let_scale, uint16_t* Xint, float* row_scale, uint16_t* Xr, void* stream);
 mbq_status mbq_scale_rows(float* Y, int64_t T, int64_t N, const float* row_scale, const float* bias, void* stream);
+/*
+ * One stage of the variant in one call: mbq_act_quant on X, mbq_routed_linear_group with the routers reading Xr and
+ * the linear kernels Xint (up to 16 tokens the router launch prepares Xint for the decode kernel as it prepares X in
+ * the weight-only stage), then the row scaling and bias of all projections in one launch - four launches where the
+ * weight-only stage has two.  Same results as the separate calls, bit for bit.
+ *   bias_host : host array of n_proj device pointers, fp32 [N_i] each; the array or any entry may be NULL
+ *   Xint, row_scale, Xr : as in mbq_act_quant, all three required (T > 0); they are outputs the caller may read
+ *   everything else as in mbq_act_quant and mbq_routed_linear_group; on failure some launches may already have been
+ *   enqueued (the calls it is made of check their own arguments in turn).
+ */
+mbq_status mbq_routed_linear_group_act(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
+                                       const float* let_scale, int n_proj, const float* const* Wr_host,
+                                       const float* const* br_host, int P, const void* const* blob_host,
+                                       const int64_t* N_host, const float* const* bias_host,
+                                       int32_t* const* prec_host, int32_t* const* perm_host,
+                                       int32_t* const* offsets_host, float* const* Y_host, uint16_t* Xint,
+                                       float* row_scale, uint16_t* Xr, void* ws_route, size_t ws_route_bytes,
+                                       void* ws_linear, size_t ws_linear_bytes, int algo, void* stream);
 
 #ifdef __cplusplus
 }

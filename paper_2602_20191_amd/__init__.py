@@ -30,7 +30,7 @@ EXPORTS = (
     "mbq_config_check", "mbq_config_bits", "mbq_config_precision_value", "mbq_config_counts_bits", "mbq_linear_cfg", "mbq_encode_cfg", "mbq_unpack_cfg", "mbq_blob_bytes_cfg",
     "mbq_dequant_cfg", "mbq_route_cfg", "mbq_route_group_cfg", "mbq_routed_linear_group_cfg",
     # activation-quantised variant
-    "mbq_act_quant", "mbq_scale_rows",
+    "mbq_act_quant", "mbq_scale_rows", "mbq_routed_linear_group_act",
     # include/mbq_bench.h: measurement and diagnostic entry points
     "mbq_bench_copy", "mbq_bench_read", "mbq_bench_mfma_loop", "mbq_bench_linear_group_prepared",
     "mbq_bench_decode_timeline", "mbq_bench_decode_timeline_bytes", "mbq_bench_decode_timeline_workgroups",
@@ -120,6 +120,10 @@ def load() -> ctypes.CDLL:
     lib.mbq_act_quant.restype = c_int
     lib.mbq_scale_rows.argtypes = [c_p, c_i64, c_i64, c_p, c_p, c_p]
     lib.mbq_scale_rows.restype = c_int
+    lib.mbq_routed_linear_group_act.argtypes = [c_p, c_i64, c_i64, c_int, c_p, c_p, c_int, c_p, c_p, c_int, c_p, c_p,
+                                                c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_sz, c_p, c_sz, c_int,
+                                                c_p]
+    lib.mbq_routed_linear_group_act.restype = c_int
     lib.mbq_bench_copy.argtypes = [c_p, c_p, c_sz, c_int, c_p]
     lib.mbq_bench_read.argtypes = [c_p, c_sz, c_int, c_p, c_p]
     lib.mbq_bench_mfma_loop.argtypes = [c_int, c_int, c_p, ctypes.POINTER(ctypes.c_double), c_p]
@@ -586,3 +590,36 @@ def mbq_scale_rows(Y: torch.Tensor, row_scale: torch.Tensor, bias: Optional[torc
     T, N = Y.shape
     _check(load().mbq_scale_rows(_ptr(Y), T, N, _ptr(row_scale), _ptr(bias), _stream()), "mbq_scale_rows")
     return Y
+
+
+def mbq_routed_linear_group_act(X: torch.Tensor, abits: int, let_shift: Optional[torch.Tensor],
+                                let_scale: Optional[torch.Tensor], Wr: Sequence[torch.Tensor],
+                                br: Sequence[torch.Tensor], blobs: Sequence[torch.Tensor], Ns: Sequence[int],
+                                bias: Optional[Sequence[Optional[torch.Tensor]]] = None, routing=None, Y=None, act=None,
+                                ws_route: Optional[torch.Tensor] = None, ws_linear: Optional[torch.Tensor] = None,
+                                algo: int = ALGO_AUTO):
+    """One stage of the activation-quantised variant (App. E.4) -> (routing, Y, (Xint, row_scale, Xr))."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.is_contiguous()
+    T, K = X.shape
+    n = len(Ns)
+    dev = X.device
+    P = Wr[0].shape[0]
+    if routing is None:
+        routing = [(torch.empty(T, dtype=torch.int32, device=dev), torch.empty(T, dtype=torch.int32, device=dev),
+                    torch.empty(P + 1, dtype=torch.int32, device=dev)) for _ in range(n)]
+    if Y is None:
+        Y = [torch.empty((T, N), dtype=torch.float32, device=dev) for N in Ns]
+    if act is None:
+        act = (torch.empty_like(X), torch.empty((T,), dtype=torch.float32, device=dev), torch.empty_like(X))
+    if ws_route is None:
+        ws_route = route_workspace(T, K, dev)
+    if ws_linear is None:
+        ws_linear = linear_workspace(T, max(Ns), K, dev)
+    n_arr = (ctypes.c_int64 * n)(*[int(N) for N in Ns])
+    bias_arr = None if bias is None else (ctypes.c_void_p * n)(*[_ptr(b) for b in bias])
+    _check(load().mbq_routed_linear_group_act(
+        _ptr(X), T, K, abits, _ptr(let_shift), _ptr(let_scale), n, _ptr_array(Wr), _ptr_array(br), P,
+        _ptr_array(blobs), n_arr, bias_arr, _ptr_array([r[0] for r in routing]), _ptr_array([r[1] for r in routing]),
+        _ptr_array([r[2] for r in routing]), _ptr_array(Y), _ptr(act[0]), _ptr(act[1]), _ptr(act[2]), _ptr(ws_route),
+        ws_route.numel(), _ptr(ws_linear), ws_linear.numel(), algo, _stream()), "mbq_routed_linear_group_act")
+    return [tuple(r) for r in routing], list(Y), act

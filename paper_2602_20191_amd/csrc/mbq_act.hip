@@ -134,6 +134,46 @@ __global__ __launch_bounds__(256) void scale_rows_kernel(float* __restrict__ Y, 
   Y[idx] = y;
 }
 
+struct ScaleList {
+  float* Y[MBQ_MAX_GROUP];
+  const float* bias[MBQ_MAX_GROUP];
+  long long total[MBQ_MAX_GROUP];  // T * N
+  int N[MBQ_MAX_GROUP];
+};
+__global__ __launch_bounds__(256) void scale_rows_group_kernel(const ScaleList list,
+                                                               const float* __restrict__ row_scale) {
+#pragma clang fp contract(off)
+  const int j = blockIdx.y;
+  float* __restrict__ Y = list.Y[j];
+  const float* __restrict__ bias = list.bias[j];
+  const long long total = list.total[j];
+  const int N = list.N[j];
+  for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
+    const long long i = idx / N;
+    float y = Y[idx] * row_scale[i];
+    if (bias) y = y + bias[idx - i * N];
+    Y[idx] = y;
+  }
+}
+
+mbq_status launch_scale_rows_group(int n, float* const* Y, int64_t T, const int64_t* N, const float* row_scale,
+                                   const float* const* bias, hipStream_t stream) {
+  ScaleList list = {};
+  long long most = 0;
+  for (int j = 0; j < n; ++j) {
+    list.Y[j] = Y[j];
+    list.bias[j] = bias ? bias[j] : nullptr;
+    list.total[j] = (long long)T * N[j];
+    list.N[j] = (int)N[j];
+    if (list.total[j] > most) most = list.total[j];
+  }
+  long long blocks = (most + 255) / 256;
+  if (blocks > 65536) blocks = 65536;  // the kernel strides
+  hipLaunchKernelGGL(scale_rows_group_kernel, dim3((unsigned)blocks, (unsigned)n), dim3(256), 0, stream, list,
+                     row_scale);
+  return hip_status(hipGetLastError(), "scale_rows_group_kernel launch");
+}
+
 mbq_status launch_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
                             const float* let_scale, uint16_t* Xint, float* row_scale, uint16_t* Xr,
                             hipStream_t stream) {

@@ -88,6 +88,13 @@ struct ViewScope {
   explicit ViewScope(const RouteView* v) : saved(t_view) { t_view = v; }
   ~ViewScope() { t_view = saved; }
 };
+// The activations the linear kernels of a routed stage multiply when they are not the router's input (the
+// activation-quantised stage call sets it for the duration of the call it forwards to; null: the router's input).
+static thread_local const uint16_t* t_linear_X = nullptr;
+struct LinearInputScope {
+  explicit LinearInputScope(const uint16_t* x) { t_linear_X = x; }
+  ~LinearInputScope() { t_linear_X = nullptr; }
+};
 // cfg -> view; the configurations this library runs are those that cut the blob's eight-bit code
 static bool make_view(const mbq_config* cfg, RouteView* v, const char* who) {
   if (!cfg) {
@@ -466,6 +473,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
                                    void* ws_route, size_t ws_route_bytes, void* ws_linear, size_t ws_linear_bytes,
                                    int algo, void* stream) {
   ApiScope scope;
+  const uint16_t* XL = t_linear_X ? t_linear_X : X;  // what the linear kernels multiply
   if (t_view->shift != 0 || t_view->group != kGroup) {
     // A configuration with an odd cumulative width: the precision arrays count bits.  The loader-wavefront decode
     // kernels understand that (one token tile); every other shape goes through the slow
@@ -513,7 +521,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
       decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
       mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
                                          nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl, true,
-                                         *t_view);
+                                         *t_view, XL);
       if (st != MBQ_OK) return st;
       return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream,
                                      perm_host, offsets_host, nullptr, true);
@@ -521,7 +529,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
     mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr,
                                        ws_route, (hipStream_t)stream, nullptr, 0, nullptr, false, *t_view);
     for (int i = 0; st == MBQ_OK && i < n_proj; ++i)
-      st = launch_linear_simple(X, T, blob_host[i], sh[i], prec_host[i], Y_host[i], (hipStream_t)stream, bit_view);
+      st = launch_linear_simple(XL, T, blob_host[i], sh[i], prec_host[i], Y_host[i], (hipStream_t)stream, bit_view);
     return st;
   }
   // the fused form: the router launch also prepares the activations of the decode kernel
@@ -541,7 +549,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
       decode_f4_zero_list(T, n_proj, sh, Y_host, &zl);
       mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
                                          nullptr, ws_route, (hipStream_t)stream, ws_linear, sh[0].KB, &zl, true,
-                                         *t_view);
+                                         *t_view, XL);
       if (st != MBQ_OK) return st;
       return launch_linear_decode_f4(T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream,
                                      perm_host, offsets_host);
@@ -560,7 +568,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
         mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host,
                                            nullptr, ws_route, (hipStream_t)stream, nullptr, 0, &zl, true, *t_view);
         if (st != MBQ_OK) return st;
-        return launch_linear_decode16_group(X, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host,
+        return launch_linear_decode16_group(XL, T, n_proj, blob_host, sh, prec_host, perm_host, Y_host,
                                             (hipStream_t)stream, perm_host, offsets_host);
       }
     }
@@ -569,7 +577,7 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
   mbq_status st = mbq_route_group(X, T, K, n_proj, Wr_host, br_host, P, prec_host, perm_host, offsets_host,
                                   ws_route, ws_route_bytes, stream);
   if (st != MBQ_OK) return st;
-  return mbq_linear_group(X, T, K, n_proj, blob_host, N_host, prec_host, perm_host, offsets_host, Y_host, ws_linear,
+  return mbq_linear_group(XL, T, K, n_proj, blob_host, N_host, prec_host, perm_host, offsets_host, Y_host, ws_linear,
                           ws_linear_bytes, algo, stream);
 }
 
@@ -866,6 +874,40 @@ mbq_status mbq_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, con
     return MBQ_ERR_INVALID_ARG;
   }
   return launch_act_quant(X, T, K, abits, let_shift, let_scale, Xint, row_scale, Xr, (hipStream_t)stream);
+}
+
+mbq_status mbq_routed_linear_group_act(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
+                                       const float* let_scale, int n_proj, const float* const* Wr_host,
+                                       const float* const* br_host, int P, const void* const* blob_host,
+                                       const int64_t* N_host, const float* const* bias_host,
+                                       int32_t* const* prec_host, int32_t* const* perm_host,
+                                       int32_t* const* offsets_host, float* const* Y_host, uint16_t* Xint,
+                                       float* row_scale, uint16_t* Xr, void* ws_route, size_t ws_route_bytes,
+                                       void* ws_linear, size_t ws_linear_bytes, int algo, void* stream) {
+  ApiScope scope;
+  if (n_proj < 1 || n_proj > MBQ_MAX_GROUP || !N_host || !Y_host) {
+    set_error("mbq_routed_linear_group_act: n_proj = %d (1..%d) or a null N / Y array", n_proj, MBQ_MAX_GROUP);
+    return MBQ_ERR_INVALID_ARG;
+  }
+  if (T > 0 && !Xr) {
+    set_error("mbq_routed_linear_group_act: the buffer for the router's input is null");
+    return MBQ_ERR_INVALID_ARG;
+  }
+  for (int i = 0; i < n_proj; ++i)
+    if (N_host[i] <= 0 || N_host[i] > (int64_t)1 << 24 || (T > 0 && !Y_host[i])) {
+      set_error("mbq_routed_linear_group_act: bad N or null Y for projection %d", i);
+      return MBQ_ERR_INVALID_ARG;
+    }
+  mbq_status st = mbq_act_quant(X, T, K, abits, let_shift, let_scale, Xint, row_scale, Xr, stream);
+  if (st != MBQ_OK) return st;
+  {
+    LinearInputScope linear_input(Xint);
+    st = mbq_routed_linear_group(Xr, T, K, n_proj, Wr_host, br_host, P, blob_host, N_host, prec_host, perm_host,
+                                 offsets_host, Y_host, ws_route, ws_route_bytes, ws_linear, ws_linear_bytes, algo,
+                                 stream);
+  }
+  if (st != MBQ_OK || T == 0) return st;
+  return launch_scale_rows_group(n_proj, Y_host, T, N_host, row_scale, bias_host, (hipStream_t)stream);
 }
 
 mbq_status mbq_scale_rows(float* Y, int64_t T, int64_t N, const float* row_scale, const float* bias, void* stream) {

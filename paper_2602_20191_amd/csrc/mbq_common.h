@@ -108,7 +108,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
                               void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket,
-                              const RouteView& view = kDefaultView);
+                              const RouteView& view = kDefaultView, const uint16_t* Xprep = nullptr);
 bool route_can_carry_prep(int64_t T);
 bool route_defers_sort(int64_t T);
 mbq_status launch_route_mlp(const uint16_t* X, int64_t T, int64_t K, const float* W1, const float* b1, int H,
@@ -195,6 +195,9 @@ mbq_status launch_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, 
                             hipStream_t stream);
 mbq_status launch_scale_rows(float* Y, int64_t T, int64_t N, const float* row_scale, const float* bias,
                              hipStream_t stream);
+// the same for the outputs of up to MBQ_MAX_GROUP projections in one launch (bias: array of n, entries may be null)
+mbq_status launch_scale_rows_group(int n, float* const* Y, int64_t T, const int64_t* N, const float* row_scale,
+                                   const float* const* bias, hipStream_t stream);
 size_t decode_workspace_bytes(int64_t T, const Shape& sh);
 size_t prefill_workspace_bytes(int64_t T, const Shape& sh);
 

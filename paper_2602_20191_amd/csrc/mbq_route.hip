@@ -214,11 +214,14 @@ struct RouteGroup {
 __global__ __launch_bounds__(512) void route_small_kernel(const uint16_t* __restrict__ X, int T, int64_t K,
                                                           RouteGroup group, int n_routers,
                                                           unsigned long long* words, char* prep, int prep_blocks,
-                                                          const ZeroList zl, int defer_bucket) {
+                                                          const ZeroList zl, int defer_bucket,
+                                                          const uint16_t* __restrict__ Xprep) {
+  // Xprep: the activations the linear kernel multiplies (X itself, except in the activation-quantised variant,
+  // where the routers read the rebuilt activations and the linear kernel the integers)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if ((int)blockIdx.y == n_routers) {
     if (wave == 0) {
-      if ((int)blockIdx.x < prep_blocks) f4::prep_block(X, T, K, prep, (int)blockIdx.x, lane);
+      if ((int)blockIdx.x < prep_blocks) f4::prep_block(Xprep, T, K, prep, (int)blockIdx.x, lane);
     } else {
       zero_share(zl, (int)blockIdx.x, (int)gridDim.x, tid - 64, 448);  // outputs a split-K linear kernel adds into
     }
@@ -394,7 +397,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
                               const float* const* br, int32_t* const* prec, int32_t* const* perm,
                               int32_t* const* offsets, double* const* logits, void* ws, hipStream_t stream,
                               void* prep, int prep_blocks, const ZeroList* zl, bool defer_bucket,
-                              const RouteView& view) {
+                              const RouteView& view, const uint16_t* Xprep) {
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ws);
   if (T > 0 && !(defer_bucket && route_small_supports(T))) {  // a launch that sorts meets through the counters
     mbq_status st = clear_counters(ws, stream);
@@ -416,7 +419,7 @@ mbq_status launch_route_group(const uint16_t* X, int64_t T, int64_t K, int n, co
     const unsigned gx = (prep && prep_blocks > (int)T) ? (unsigned)prep_blocks : (unsigned)T;
     hipLaunchKernelGGL(route_small_kernel, dim3(gx, (unsigned)n + (plane ? 1u : 0u)), dim3(512), 0, stream, X, (int)T,
                        K, g, n, words, reinterpret_cast<char*>(prep), prep ? prep_blocks : 0,
-                       (plane && zl) ? *zl : ZeroList{}, defer_bucket ? 1 : 0);
+                       (plane && zl) ? *zl : ZeroList{}, defer_bucket ? 1 : 0, Xprep ? Xprep : X);
     return hip_status(hipGetLastError(), "route_small_kernel launch");
   }
   for (int i = 0; i < n; ++i) {

@@ -87,6 +87,19 @@ def test_stage_of_the_variant(mbq, abits, T, K, Ns):
     for Y, B in zip(Ys, Bt):
         mbq.mbq_scale_rows(Y, row_scale, dev(B))
     torch.cuda.synchronize()
+    # the stage as one call: the same numbers, bit for bit (above 64 tokens the tiled GEMM may add K parts in any order)
+    routing1, Ys1, act1 = mbq.mbq_routed_linear_group_act(X, abits, dev(delta), dev(s), [dev(w) for w in Wrs],
+                                                          [dev(b) for b in brs], blobs, list(Ns),
+                                                          bias=[dev(B) for B in Bt])
+    torch.cuda.synchronize()
+    assert torch.equal(act1[0], Xint) and torch.equal(act1[1], row_scale) and torch.equal(act1[2], Xr)
+    for i in range(len(Ns)):
+        for a_, b_ in zip(routing1[i], routing[i]):
+            assert torch.equal(a_, b_), i
+        if T <= 64:
+            assert torch.equal(Ys1[i], Ys[i]), i
+        else:
+            assert_output_close(Ys1[i].cpu().numpy(), Ys[i].double().cpu().numpy(), f"one call vs separate calls {i}")
     # oracle
     xint, scale, zp, q = A.act_quant(A.let_transform(xb, delta, s), abits)
     xr_bits = A.router_input_bits(xint, scale, delta, s)
@@ -118,3 +131,16 @@ def test_scale_rows_alone_and_empty_inputs(mbq):
         mbq.mbq_act_quant(torch.zeros((2, 256), dtype=torch.bfloat16, device="cuda"), 9)
     with pytest.raises(mbq.MbqError):
         mbq.mbq_act_quant(torch.zeros((2, 192), dtype=torch.bfloat16, device="cuda"), 4)
+    # the stage call without tokens, without a transform and without biases
+    W = dev(make_weight(32, 256, [1], 4.0))
+    Wr, br = dev(np.zeros((4, 256), dtype=np.float32)), dev(np.zeros(4, dtype=np.float32))
+    routing, Ys, act = mbq.mbq_routed_linear_group_act(empty, 4, None, None, [Wr], [br], [mbq.mbq_encode(W)], [32])
+    torch.cuda.synchronize()
+    assert Ys[0].shape == (0, 32) and routing[0][2].cpu().tolist() == [0, 0, 0, 0, 0]
+    xb = activations(9, 256, 5)
+    routing, Ys, act = mbq.mbq_routed_linear_group_act(dev_bf16(xb).reshape(9, 256), 4, None, None, [Wr], [br],
+                                                       [mbq.mbq_encode(W)], [32])
+    xint, scale, zp, q = A.act_quant(A.bf16_bits_to_f32(xb), 4)
+    codes, s0, z0 = O.encode(make_weight(32, 256, [1], 4.0))
+    want = A.w_a_linear(xint, scale, lambda t: O.dequant(codes, s0, z0, 0))     # zero routers: first maximum, p = 0
+    assert_output_close(Ys[0].cpu().numpy(), want, "stage call, no transform, no bias")

@@ -70,6 +70,36 @@ def test_encode_with_external_parameters(mbq, N, K, keep):
     assert_output_close(Y.cpu().numpy(), O.linear(xb, codes, s0, z0, prec), f"linear over clipped blob N={N} K={K}")
 
 
+@pytest.mark.parametrize("meta", ["float16", "bfloat16"])
+def test_sixteen_bit_parameter_values_through_external_parameters(mbq, meta):
+    """App. C.1's pipeline may keep the per-group scale and zero point in 16 bits.  The blob stores fp32 pairs, but the
+    NUMBERS of such a setting pass through unchanged: parameters rounded to fp16 / bf16 before they are handed in give
+    the oracle's codes for exactly those parameters, and every stored value is a 16-bit number."""
+    N, K, T = 70, 1024, 16
+    print(f"[case] encode with {meta} parameter values N={N} K={K}", flush=True)
+    W = make_weight(N, K, [57, N, K], 4.0)
+    _, s_fit, z_fit = O.encode(W)
+    if meta == "float16":
+        s0, z0 = s_fit.astype(np.float16).astype(np.float32), z_fit.astype(np.float16).astype(np.float32)
+    else:
+        def to_bf16(a):
+            u = a.view(np.uint32).astype(np.uint64)
+            u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+            return u.astype(np.uint32).view(np.float32)
+        s0, z0 = to_bf16(s_fit), to_bf16(z_fit)
+    codes, _, _ = O.encode(W, s0, z0)
+    blob = mbq.mbq_encode_with_params(dev(W), dev(s0), dev(z0))
+    torch.cuda.synchronize()
+    assert np.array_equal(blob.cpu().numpy(), O.pack_blob(codes, s0, z0))
+    c, s, z = mbq.mbq_unpack(blob, N, K)
+    assert np.array_equal(s.cpu().numpy(), s0) and np.array_equal(z.cpu().numpy(), z0)
+    xb = tokens(T, K, [N, K, 61])
+    prec = np.random.default_rng([N, K, 3]).integers(0, 4, size=T).astype(np.int32)
+    perm, offsets = O.bucket(prec)
+    Y = mbq.mbq_linear(dev_bf16(xb).reshape(T, K), blob, N, K, dev(prec), dev(perm), dev(offsets))
+    assert_output_close(Y.cpu().numpy(), O.linear(xb, codes, s0, z0, prec), f"linear, {meta} parameter values")
+
+
 # ------------------------------------------------------------------------------ route
 @pytest.mark.parametrize("T,K", [(0, 256), (1, 128), (5, 384), (16, 4096), (16, 11008), (28, 8192), (29, 8320),
                                  (32, 2048), (64, 4096), (65, 1024), (100, 2304), (128, 4096), (129, 512), (1023, 256), (1024, 256), (1025, 256),
