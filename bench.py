@@ -419,6 +419,22 @@ def timeline_probe(mbq, torch, dev, stages, T, dump_dir="gpurun_out", flush_cach
     return 0
 
 
+def warm_until_steady(torch, fn, batch=5, budget_ms=50.0):
+    """Untimed launches of fn(i) for budget_ms of GPU time: after host-side set-up the GPU needs some tens of
+    milliseconds of work before its launches reach their sustained duration (measured: the 2048-token gate linear
+    328 us over the first 20 calls, 278 us from the sixtieth on)."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    spent, i = 0.0, 0
+    while spent < budget_ms:
+        a.record()
+        for _ in range(batch):
+            fn(i)
+            i += 1
+        b.record()
+        torch.cuda.synchronize()
+        spent += a.elapsed_time(b)
+
+
 def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
     """Side figures, each timed with HIP events over eager back-to-back launches:
     the same block at the other decode batches of the config, and the three prefill linears of
@@ -608,8 +624,7 @@ def extra_measurements(mbq, torch, dev, cfg, layers, stages, T_main):
         prec, perm, offsets = mbq.mbq_route(X, Wr, br)
         Y = torch.empty((T, spec.N), dtype=torch.float32, device=dev)
         ws = mbq.linear_workspace(T, spec.N, spec.K, dev)
-        for _ in range(3):
-            mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws)
+        warm_until_steady(torch, lambda i: mbq.mbq_linear(X, blob, spec.N, spec.K, prec, perm, offsets, Y=Y, ws=ws))
         a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         n = 20
         a.record()
@@ -691,6 +706,7 @@ def other_config_measurements(mbq, torch, dev):
     def timed(fn, n, warm=2):
         for i in range(warm):
             fn(i)
+        warm_until_steady(torch, fn, batch=max(2, n // 3))
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for i in range(n):
