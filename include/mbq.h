@@ -295,10 +295,12 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
  *     the number of 2-bit digits minus one, which is what every mbq_linear* call reads (for the default configuration
  *     that is q itself): all linear kernels run unchanged and at full speed.
  *   - Some B_q odd ("bit configurations"): the prec arrays hold B_q - 1, and only mbq_linear_cfg and
- *     mbq_routed_linear_group_cfg understand them.  Up to 16 tokens the decode kernels run them (it hands
+ *     mbq_routed_linear_group_cfg understand them.  The one-token-tile decode kernels run them (they hand
  *     the two bits of every 2-bit code to the matrix cores separately, gated per token: twice the MFMAs, the same
- *     memory traffic); every other shape takes the one-thread-per-output kernel of MBQ_ALGO_SIMPLE, which is correct
- *     and slow.
+ *     memory traffic): one launch up to 16 tokens, and beyond, with algo AUTO or DECODE, one launch per 16 tokens -
+ *     a pass over the weights each, so a long prompt under a bit configuration costs a multiple of what it costs
+ *     under a digit configuration.  MBQ_ALGO_SIMPLE and MBQ_ALGO_PREFILL take the one-thread-per-output kernel,
+ *     which is correct and very slow.
  * mbq_config_precision_value(cfg, q) is what a prec array holds for the configuration's precision q, and
  * mbq_config_counts_bits(cfg) says which of the two cases it is.  perm and offsets (always MBQ_N_PRECISIONS + 1
  * entries) sort and bucket the tokens by the number of 2-bit digits they touch, ceil(B_q / 2) - 1, in both cases.
@@ -350,8 +352,8 @@ mbq_status mbq_dequant_cfg(const void* blob, int64_t N, int64_t K, const mbq_con
  */
 /*
  * mbq_linear on precision arrays written under a configuration (see above): a digit configuration is mbq_linear
- * itself; a bit configuration takes the decode kernels (T <= 16, algo AUTO or DECODE) or the slow checker
- * kernel.  perm and offsets may be null for a bit configuration (neither kernel reads them).
+ * itself; a bit configuration takes the one-token-tile decode kernels (algo AUTO or DECODE; 16 tokens per launch)
+ * or the slow checker kernel.  perm and offsets may be null for a bit configuration (neither kernel reads them).
  */
 mbq_status mbq_linear_cfg(const uint16_t* X, int64_t T, const void* blob, int64_t N, int64_t K,
                           const mbq_config* cfg, const int32_t* prec, const int32_t* perm, const int32_t* offsets,

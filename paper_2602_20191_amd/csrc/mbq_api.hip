@@ -135,6 +135,30 @@ static bool make_view(const mbq_config* cfg, RouteView* v, const char* who) {
   return true;
 }
 
+// Precision arrays that count bits (see RouteView) above one token tile: the one-token-tile decode kernels, which
+// understand them, run once per 16 tokens - a pass over the weights each, far from the kernels of the digit
+// configurations at these token counts, and three to four orders of magnitude from the one-thread-per-output kernel
+// that would run otherwise.  The chunks follow each other on the stream and share the prepared-activation area.
+static mbq_status bit_view_in_chunks(const uint16_t* X, int64_t T, int n, const void* const* blobs, const Shape* sh,
+                                     const int32_t* const* prec, float* const* Y, void* ws, hipStream_t s) {
+  for (int64_t t0 = 0; t0 < T; t0 += 16) {
+    const int64_t tc = T - t0 < 16 ? T - t0 : 16;
+    const int32_t* pc[MBQ_MAX_GROUP];
+    float* yc[MBQ_MAX_GROUP];
+    for (int i = 0; i < n; ++i) {
+      pc[i] = prec[i] + t0;
+      yc[i] = Y[i] + t0 * sh[i].N;
+    }
+    ZeroList zl;
+    decode_f4_zero_list(tc, n, sh, yc, &zl);
+    mbq_status st = launch_decode_f4_prep(X + t0 * sh[0].K, tc, sh[0].K, sh[0].KB, ws, zl, s);
+    if (st != MBQ_OK) return st;
+    st = launch_linear_decode_f4(tc, n, blobs, sh, pc, yc, ws, s, nullptr, nullptr, nullptr, true);
+    if (st != MBQ_OK) return st;
+  }
+  return MBQ_OK;
+}
+
 // 17..64 tokens (and one token tile when the FP4-operand kernels are switched off): the register-stationary
 // kernel, except for matrices with few row tiles (see dispatch_linear)
 static bool takes_stationary_kernel(int64_t T, const Shape& sh) {
@@ -528,6 +552,9 @@ mbq_status mbq_routed_linear_group(const uint16_t* X, int64_t T, int64_t K, int 
     }
     mbq_status st = launch_route_group(X, T, K, n_proj, Wr_host, br_host, prec_host, perm_host, offsets_host, nullptr,
                                        ws_route, (hipStream_t)stream, nullptr, 0, nullptr, false, *t_view);
+    if (st == MBQ_OK && bit_view && t_view->group == kGroup && (algo == MBQ_ALGO_AUTO || algo == MBQ_ALGO_DECODE) &&
+        knob(3) == 0 && decode_f4_takes_bit_view(16, sh[0]))
+      return bit_view_in_chunks(XL, T, n_proj, blob_host, sh, prec_host, Y_host, ws_linear, (hipStream_t)stream);
     for (int i = 0; st == MBQ_OK && i < n_proj; ++i)
       st = launch_linear_simple(XL, T, blob_host[i], sh[i], prec_host[i], Y_host[i], (hipStream_t)stream, bit_view);
     return st;
@@ -814,6 +841,9 @@ mbq_status mbq_linear_cfg(const uint16_t* X, int64_t T, const void* blob, int64_
     if (st != MBQ_OK) return st;
     return launch_linear_decode_f4(T, 1, &blob, &sh, &prec, &Y, ws, s, nullptr, nullptr, nullptr, true);
   }
+  if (v.shift != 0 && v.group == kGroup && (algo == MBQ_ALGO_AUTO || algo == MBQ_ALGO_DECODE) && knob(3) == 0 &&
+      decode_f4_takes_bit_view(16, sh))
+    return bit_view_in_chunks(X, T, 1, &blob, &sh, &prec, &Y, ws, s);
   return launch_linear_simple(X, T, blob, sh, prec, Y, s, v.shift != 0);
 }
 

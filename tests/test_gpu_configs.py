@@ -88,8 +88,10 @@ def test_route_with_as_many_outputs_as_slices(mbq, bits, T, K):
                                          ((3, 1, 2, 2), 16, 4096, (272, 130)), ((3, 2, 1), 12, 1280, (96, 40, 64)),
                                          ((1, 1, 1, 1), 16, 8192, (48,)), ((4, 1, 1, 2), 7, 2304, (130, 66)),
                                          ((1, 2, 2, 2), 16, 768, (100,)), ((7,), 3, 512, (64,)),
-                                         # ... and the checker kernel beyond
-                                         ((3, 1, 2, 2), 40, 512, (72,)), ((5, 3), 16, 8448, (32,))])
+                                         # ... 16 tokens per launch beyond
+                                         ((3, 1, 2, 2), 40, 512, (72,)), ((5, 3), 16, 8448, (32,)),
+                                         ((3, 2, 1), 300, 768, (130, 64)), ((1, 2, 2, 2), 17, 4096, (272,)),
+                                         ((4, 1, 1, 2), 33, 11008, (48,))])
 def test_stage_call_under_a_configuration(mbq, bits, T, K, Ns):
     """mbq_routed_linear_group_cfg against the general oracle: precisions (as digit counts) bit-exact off the near-tie
     list, outputs within the bar for the precisions the GPU chose, and identical to route_cfg + linear_group."""
