@@ -16,9 +16,12 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
   return u >> 16;
 }
 
-// One workgroup per token.  Pass 1 finds the row's extremes (zero included), pass 2 re-reads the row (it is in
-// cache) and writes the codes; both passes compute the transformed value with the same two operations.
-__global__ __launch_bounds__(256) void act_quant_kernel(const uint16_t* __restrict__ X, int64_t K, int abits,
+// One workgroup per token.  Pass 1 finds the row's extremes (zero included), pass 2 writes the codes.  kHold > 0: the
+// row fits in kHold chunks of eight values per thread and the transformed values of pass 1 stay in registers;
+// kHold = 0: pass 2 re-reads the row (it is in cache) and computes the transformed values again with the same two
+// operations.
+template <int kThreads, int kHold>
+__global__ __launch_bounds__(kThreads) void act_quant_kernel(const uint16_t* __restrict__ X, int64_t K, int abits,
                                                         const float* __restrict__ let_shift,
                                                         const float* __restrict__ let_scale,
                                                         uint16_t* __restrict__ Xint, float* __restrict__ row_scale,
@@ -51,13 +54,29 @@ __global__ __launch_bounds__(256) void act_quant_kernel(const uint16_t* __restri
   };
 
   float lo = 0.f, hi = 0.f;
-  for (int j = tid; j < n8; j += 256) {
-    float t[8];
-    transformed(j, t);
+  float held[kHold > 0 ? kHold : 1][8];
+  if constexpr (kHold > 0) {
 #pragma unroll
-    for (int h = 0; h < 8; ++h) {
-      lo = fminf(lo, t[h]);
-      hi = fmaxf(hi, t[h]);
+    for (int c = 0; c < kHold; ++c) {
+      const int j = tid + c * kThreads;
+      if (j < n8) {
+        transformed(j, held[c]);
+#pragma unroll
+        for (int h = 0; h < 8; ++h) {
+          lo = fminf(lo, held[c][h]);
+          hi = fmaxf(hi, held[c][h]);
+        }
+      }
+    }
+  } else {
+    for (int j = tid; j < n8; j += kThreads) {
+      float t[8];
+      transformed(j, t);
+#pragma unroll
+      for (int h = 0; h < 8; ++h) {
+        lo = fminf(lo, t[h]);
+        hi = fmaxf(hi, t[h]);
+      }
     }
   }
 #pragma unroll
@@ -65,14 +84,18 @@ __global__ __launch_bounds__(256) void act_quant_kernel(const uint16_t* __restri
     lo = fminf(lo, __shfl_xor(lo, off));
     hi = fmaxf(hi, __shfl_xor(hi, off));
   }
-  __shared__ float s_lo[4], s_hi[4];
+  constexpr int kWavefronts = kThreads / 64;
+  __shared__ float s_lo[kWavefronts], s_hi[kWavefronts];
   if ((tid & 63) == 0) {
     s_lo[tid >> 6] = lo;
     s_hi[tid >> 6] = hi;
   }
   __syncthreads();
-  lo = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
-  hi = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
+#pragma unroll
+  for (int w = 0; w < kWavefronts; ++w) {
+    lo = fminf(lo, s_lo[w]);
+    hi = fmaxf(hi, s_hi[w]);
+  }
 
   const float top = (float)((1 << abits) - 1);
   const float rng = fmaxf(hi - lo, 0x1p-100f);
@@ -82,9 +105,7 @@ __global__ __launch_bounds__(256) void act_quant_kernel(const uint16_t* __restri
 
   uint4* out8 = reinterpret_cast<uint4*>(Xint + row * K);
   uint4* xr8 = Xr ? reinterpret_cast<uint4*>(Xr + row * K) : nullptr;
-  for (int j = tid; j < n8; j += 256) {
-    float t[8];
-    transformed(j, t);
+  auto write_chunk = [&](int j, const float t[8]) {
     float xi[8];
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
@@ -117,6 +138,19 @@ __global__ __launch_bounds__(256) void act_quant_kernel(const uint16_t* __restri
       p.z = bf16_bits(r[4]) | (bf16_bits(r[5]) << 16);
       p.w = bf16_bits(r[6]) | (bf16_bits(r[7]) << 16);
       xr8[j] = p;
+    }
+  };
+  if constexpr (kHold > 0) {
+#pragma unroll
+    for (int c = 0; c < kHold; ++c) {
+      const int j = tid + c * kThreads;
+      if (j < n8) write_chunk(j, held[c]);
+    }
+  } else {
+    for (int j = tid; j < n8; j += kThreads) {
+      float t[8];
+      transformed(j, t);
+      write_chunk(j, t);
     }
   }
 }
@@ -177,8 +211,13 @@ mbq_status launch_scale_rows_group(int n, float* const* Y, int64_t T, const int6
 mbq_status launch_act_quant(const uint16_t* X, int64_t T, int64_t K, int abits, const float* let_shift,
                             const float* let_scale, uint16_t* Xint, float* row_scale, uint16_t* Xr,
                             hipStream_t stream) {
-  hipLaunchKernelGGL(act_quant_kernel, dim3((unsigned)T), dim3(256), 0, stream, X, K, abits, let_shift, let_scale,
-                     Xint, row_scale, Xr);
+  // up to 16384 columns a row is held in registers by 512 threads (four chunks of eight values each)
+  if (K <= 512 * 4 * 8)
+    hipLaunchKernelGGL((act_quant_kernel<512, 4>), dim3((unsigned)T), dim3(512), 0, stream, X, K, abits, let_shift,
+                       let_scale, Xint, row_scale, Xr);
+  else
+    hipLaunchKernelGGL((act_quant_kernel<256, 0>), dim3((unsigned)T), dim3(256), 0, stream, X, K, abits, let_shift,
+                       let_scale, Xint, row_scale, Xr);
   return hip_status(hipGetLastError(), "act_quant_kernel launch");
 }
 
