@@ -144,3 +144,54 @@ def test_scale_rows_alone_and_empty_inputs(mbq):
     codes, s0, z0 = O.encode(make_weight(32, 256, [1], 4.0))
     want = A.w_a_linear(xint, scale, lambda t: O.dequant(codes, s0, z0, 0))     # zero routers: first maximum, p = 0
     assert_output_close(Ys[0].cpu().numpy(), want, "stage call, no transform, no bias")
+
+
+@pytest.mark.parametrize("T", [16, 40])
+def test_stage_of_the_variant_replays_from_a_hip_graph(mbq, T):
+    """The one-call stage captured once and replayed with new activations in the same buffers (eager work and
+    synchronisation between the replays): every replay equals the eager call bit for bit."""
+    K, Ns, abits = 4096, (272, 130), 4
+    print(f"[case] W-A stage under graph replay T={T}", flush=True)
+    rng = np.random.default_rng(53)
+    delta, s = let_params(K, 53)
+    d_delta, d_s = dev(delta), dev(s)
+    Wrs = [dev((rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32)) for _ in Ns]
+    brs = [dev(rng.normal(0, 0.3, size=4).astype(np.float32)) for _ in Ns]
+    bias = [dev(rng.standard_normal(N).astype(np.float32)) for N in Ns]
+    blobs = [mbq.mbq_encode(dev(make_weight(N, K, [53, N], 4.0))) for N in Ns]
+    X = dev_bf16(activations(T, K, [53, 0])).reshape(T, K)
+    ws_r = mbq.route_workspace(T, K, "cuda")
+    ws_l = mbq.linear_workspace(T, max(Ns), K, "cuda")
+    routing = [(torch.empty(T, dtype=torch.int32, device="cuda"), torch.empty(T, dtype=torch.int32, device="cuda"),
+                torch.empty(5, dtype=torch.int32, device="cuda")) for _ in Ns]
+    Ys = [torch.empty((T, N), dtype=torch.float32, device="cuda") for N in Ns]
+    act = (torch.empty_like(X), torch.empty((T,), dtype=torch.float32, device="cuda"), torch.empty_like(X))
+
+    def call():
+        mbq.mbq_routed_linear_group_act(X, abits, d_delta, d_s, Wrs, brs, blobs, list(Ns), bias=bias, routing=routing,
+                                        Y=Ys, act=act, ws_route=ws_r, ws_linear=ws_l)
+
+    call()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    for rep in range(3):
+        X.copy_(dev_bf16(activations(T, K, [53, rep + 1])).reshape(T, K))
+        call()
+        torch.cuda.synchronize()
+        want = [[t.clone() for t in r] for r in routing], [y.clone() for y in Ys], [t.clone() for t in act]
+        for y in Ys:
+            y.fill_(float("nan"))
+        for r in routing:
+            for t in r:
+                t.fill_(-7)
+        act[1].fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for i in range(len(Ns)):
+            for a, b in zip(want[0][i], routing[i]):
+                assert torch.equal(a, b), (rep, i)
+            assert torch.equal(want[1][i], Ys[i]), (rep, i)
+        for a, b in zip(want[2], act):
+            assert torch.equal(a, b), rep
