@@ -195,3 +195,56 @@ def test_stage_of_the_variant_replays_from_a_hip_graph(mbq, T):
             assert torch.equal(want[1][i], Ys[i]), (rep, i)
         for a, b in zip(want[2], act):
             assert torch.equal(a, b), rep
+
+
+def test_calls_from_two_threads_do_not_disturb_each_other(mbq):
+    """The header allows calls from several threads as long as they share no workspace.  One thread runs stage calls
+    under the slice configuration {3,1,2,2}, the other the activation-quantised stage, each on a stream of its own
+    (default priority) with its own buffers; every result equals what the same call gave alone.  (What a call runs
+    under - configuration, linear operand, test hooks - is per thread inside the library.)"""
+    import threading
+
+    T, K, Ns = 16, 4096, (272, 130)
+    rng = np.random.default_rng(71)
+    Wr4 = [dev((rng.standard_normal((4, K)) / np.sqrt(K)).astype(np.float32)) for _ in Ns]
+    br4 = [dev(rng.normal(0, 0.3, size=4).astype(np.float32)) for _ in Ns]
+    blobs = [mbq.mbq_encode(dev(make_weight(N, K, [71, N], 4.0))) for N in Ns]
+    delta, s = let_params(K, 71)
+    d_delta, d_s = dev(delta), dev(s)
+    cfg = mbq.Config((3, 1, 2, 2))
+    Xs = [dev_bf16(activations(T, K, [71, i])).reshape(T, K) for i in range(6)]
+
+    def run_cfg(X):
+        routing, Ys = mbq.mbq_routed_linear_group_cfg(X, Wr4, br4, cfg, blobs, list(Ns))
+        return [t for r in routing for t in r] + list(Ys)
+
+    def run_act(X):
+        routing, Ys, act = mbq.mbq_routed_linear_group_act(X, 4, d_delta, d_s, Wr4, br4, blobs, list(Ns))
+        return [t for r in routing for t in r] + list(Ys) + list(act)
+
+    want = {"cfg": [run_cfg(X) for X in Xs], "act": [run_act(X) for X in Xs]}
+    torch.cuda.synchronize()
+    failures = []
+
+    def worker(name, fn):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(20):
+                    i = rep % len(Xs)
+                    got = fn(Xs[i])
+                    stream.synchronize()
+                    for a, b in zip(got, want[name][i]):
+                        if not torch.equal(a, b):
+                            failures.append((name, rep))
+                            return
+        except Exception as e:                      # noqa: BLE001 - reported to the main thread
+            failures.append((name, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=("cfg", run_cfg)), threading.Thread(target=worker, args=("act", run_act))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not failures, failures
